@@ -1,0 +1,225 @@
+"""Pins for the CPU oracle: closed forms, loop-level brute force and special cases.
+
+No value in the paper fixes a float, so the oracle's arithmetic is pinned to mathematics instead:
+each primitive against a closed form or a scalar-loop evaluation written independently here, and
+the block against a pure-Python scalar transformer on a very small model.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from ht_inputs import make_weights, counter_normal, counter_u64_reference, counter_tokens, prune_tree, \
+    random_tree, tree_depths
+from ht_inputs.generators import counter_token_reference
+from oracle import ht_oracle as O
+from helpers import small_workload, oracle_model, oracle_config
+
+
+# ------------------------------------------------------------------ input generators (host side)
+def test_counter_generator_matches_python_integers():
+    t = counter_normal(11, 1003, (7, 9), 0.02)
+    for i in (0, 1, 8, 9, 62):
+        s = counter_u64_reference(11, 1003, i)
+        want = np.float32(np.float32(s - 393210) / np.float32(65536.0)) * np.float32(0.02)
+        assert t.view(-1)[i].item() == want
+    g = counter_normal(11, 2, (64,), 0.02, mean=1.0)
+    s = counter_u64_reference(11, 2, 5)
+    want = np.float32(np.float32((s - 393210) / 65536.0) * np.float32(0.02)) + np.float32(1.0)
+    assert g[5].item() == want
+
+
+def test_counter_generator_chunking_and_moments():
+    a = counter_normal(3, 5, (1000, 37), 1.0, chunk=1 << 24)
+    b = counter_normal(3, 5, (1000, 37), 1.0, chunk=4099)
+    assert torch.equal(a, b)
+    assert abs(a.mean().item()) < 0.02 and abs(a.std().item() - 1.0) < 0.02
+    toks = counter_tokens(3, 7, 50, 1024)
+    assert [int(x) for x in toks] == [counter_token_reference(3, 7, i, 1024) for i in range(50)]
+    assert toks.min() >= 0 and toks.max() < 1024
+
+
+def test_prune_tree_shapes():
+    for br, size, levels in [((10, 3, 2), 64, [1, 10, 21, 32]), ((10, 3, 2), 16, [1, 4, 5, 6]),
+                             ((10, 3, 2), 32, [1, 6, 11, 14]), ((2, 2), 8, [1, 3, 4]), ((2, 2), 7, [1, 2, 4]),
+                             ((2, 2, 1), 8, [1, 2, 3, 2]), ((10, 3, 2), 1, [1])]:
+        parent, rank = prune_tree(br, size)
+        depth = tree_depths(parent)
+        assert [depth.count(e) for e in range(max(depth) + 1)] == levels
+        assert parent[0] == -1 and all(0 <= parent[v] < v for v in range(1, size))
+        sib = {(parent[v], rank[v]) for v in range(1, size)}
+        assert len(sib) == size - 1                      # distinct rank among siblings
+        for v in range(1, size):                          # rank-closed: a rank-r child implies rank r-1 sibling
+            assert rank[v] == 0 or (parent[v], rank[v] - 1) in sib
+
+
+# ------------------------------------------------------------------ primitives: closed forms
+def test_rms_norm_closed_forms():
+    g = np.array([2.0, -1.0])
+    out = O.rms_norm(np.array([[3.0, 4.0]]), g, 0.0)
+    assert np.allclose(out, [[3.0 / math.sqrt(12.5) * 2.0, -4.0 / math.sqrt(12.5)]], rtol=0, atol=1e-15)
+    c = np.full((1, 8), 0.5)
+    assert np.allclose(O.rms_norm(c, np.ones(8), 1e-5), 0.5 / math.sqrt(0.25 + 1e-5), atol=1e-15)
+    x = np.random.default_rng(0).normal(size=(3, 32))
+    y = O.rms_norm(x, np.ones(32), 0.0)
+    assert np.allclose((y * y).mean(axis=1), 1.0, atol=1e-12)
+    assert np.allclose(O.rms_norm(7.0 * x, np.ones(32), 0.0), y, atol=1e-12)       # scale invariant when eps = 0
+
+
+def test_rope_closed_forms():
+    # hd = 2: one pair, frequency base^0 = 1, so position p is a plain rotation by p radians
+    x = np.array([[[1.0, 0.0]], [[0.3, -0.7]]])
+    out = O.rope(x, np.array([2, 5]), 10000.0)
+    assert np.allclose(out[0, 0], [math.cos(2.0), math.sin(2.0)], atol=1e-15)
+    assert np.allclose(out[1, 0], [0.3 * math.cos(5) + 0.7 * math.sin(5), -0.7 * math.cos(5) + 0.3 * math.sin(5)],
+                       atol=1e-15)
+    # hd = 4: pairs (0,2) and (1,3); second pair turns at base^(-2/4)
+    y = O.rope(np.array([[[1.0, 1.0, 0.0, 0.0]]]), np.array([3]), 100.0)
+    assert np.allclose(y[0, 0], [math.cos(3.0), math.cos(0.3), math.sin(3.0), math.sin(0.3)], atol=1e-15)
+    rng = np.random.default_rng(1)
+    q, k = rng.normal(size=(1, 2, 16)), rng.normal(size=(1, 2, 16))
+    assert np.allclose(O.rope(q, np.array([0]), 10000.0), q, atol=0)                # position 0 is the identity
+    assert np.allclose(np.linalg.norm(O.rope(q, np.array([17]), 10000.0)), np.linalg.norm(q), atol=1e-12)
+    dots = [np.sum(O.rope(q, np.array([a]), 1e4) * O.rope(k, np.array([a - 4]), 1e4), axis=-1) for a in (4, 9, 300)]
+    assert np.allclose(dots[0], dots[1], atol=1e-12) and np.allclose(dots[0], dots[2], atol=1e-11)
+
+
+def test_silu_closed_forms():
+    x = np.array([-30.0, -1.0, 0.0, 1.0, 30.0])
+    s = O.silu(x)
+    assert s[2] == 0.0 and np.allclose(s - O.silu(-x), x, atol=1e-12)
+    assert abs(s[3] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15 and abs(s[4] - 30.0) < 1e-10
+
+
+def _attention_loops(q, keys, values, visible):
+    r, hq, hd = q.shape
+    group = hq // keys.shape[1]
+    out = np.zeros_like(q)
+    for a in range(r):
+        for h in range(hq):
+            js = [j for j in range(keys.shape[0]) if visible[a][j]]
+            sc = [sum(q[a, h, e] * keys[j, h // group, e] for e in range(hd)) / math.sqrt(hd) for j in js]
+            mx = max(sc)
+            w = [math.exp(s - mx) for s in sc]
+            tot = sum(w)
+            for e in range(hd):
+                out[a, h, e] = sum(wj * values[j, h // group, e] for wj, j in zip(w, js)) / tot
+    return out
+
+
+def test_masked_attention_against_loops_and_limits():
+    rng = np.random.default_rng(2)
+    q, keys, vals = rng.normal(size=(5, 4, 6)), rng.normal(size=(9, 2, 6)), rng.normal(size=(9, 2, 6))
+    vis = rng.random((5, 9)) < 0.6
+    vis[:, 0] = True
+    assert np.allclose(O.masked_attention(q, keys, vals, vis), _attention_loops(q, keys, vals, vis), atol=1e-13)
+    # q = 0 -> uniform weights -> mean of the visible values (GQA: head h reads kv head h // 2)
+    out = O.masked_attention(np.zeros_like(q), keys, vals, vis)
+    for a in range(5):
+        for h in range(4):
+            assert np.allclose(out[a, h], vals[vis[a], h // 2].mean(axis=0), atol=1e-13)
+    one = np.zeros((5, 9), dtype=bool)
+    one[np.arange(5), [3, 1, 4, 1, 5]] = True                                      # a single visible key
+    out = O.masked_attention(q, keys, vals, one)
+    assert np.allclose(out[2, 3], vals[4, 1], atol=1e-13)
+
+
+def test_top_candidates_order_and_ties():
+    row = np.array([0.5, 2.0, 2.0, -1.0, 2.0, 0.5, 3.0])
+    assert O.top_candidates(row, 5) == [6, 1, 2, 4, 0]
+    rng = np.random.default_rng(3)
+    r = np.round(rng.normal(size=200), 1)                                           # many exact ties
+    want = sorted(range(200), key=lambda j: (-r[j], j))[:17]
+    assert O.top_candidates(r, 17) == want
+    assert O.top_candidates(r, 1)[0] == int(np.argmax(r))                           # argmax tie -> lowest id
+
+
+# ------------------------------------------------------------------ whole block vs scalar Python
+def _scalar_forward(cfg, w, tokens):
+    """Pure-Python scalar causal transformer (independent of the numpy code path)."""
+    L, d, hq, hkv, hd, f = cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn
+    n = len(tokens)
+    xs = [[float(w.tok_emb[t][c]) for c in range(d)] for t in tokens]
+
+    def matvec(mat, vec):
+        return [sum(float(mat[o][i]) * vec[i] for i in range(len(vec))) for o in range(len(mat))]
+
+    def norm(vec, gain):
+        ms = sum(a * a for a in vec) / len(vec)
+        return [a / math.sqrt(ms + cfg.rms_eps) * float(gg) for a, gg in zip(vec, gain)]
+
+    def rot(vec, p):
+        out = list(vec)
+        for h in range(len(vec) // hd):
+            for j in range(hd // 2):
+                ang = p * cfg.rope_base ** (-2.0 * j / hd)
+                a, b = vec[h * hd + j], vec[h * hd + j + hd // 2]
+                out[h * hd + j] = a * math.cos(ang) - b * math.sin(ang)
+                out[h * hd + j + hd // 2] = b * math.cos(ang) + a * math.sin(ang)
+        return out
+
+    for layer in range(L):
+        us = [norm(x, w.attn_norm[layer]) for x in xs]
+        qs = [rot(matvec(w.wq[layer], u), p) for p, u in enumerate(us)]
+        ks = [rot(matvec(w.wk[layer], u), p) for p, u in enumerate(us)]
+        vs = [matvec(w.wv[layer], u) for u in us]
+        new = []
+        for p in range(n):
+            att = []
+            for h in range(hq):
+                g = h // (hq // hkv)
+                sc = [sum(qs[p][h * hd + e] * ks[j][g * hd + e] for e in range(hd)) / math.sqrt(hd) for j in range(p + 1)]
+                mx = max(sc)
+                ex = [math.exp(s - mx) for s in sc]
+                tot = sum(ex)
+                att += [sum(ex[j] * vs[j][g * hd + e] for j in range(p + 1)) / tot for e in range(hd)]
+            x = [a + b for a, b in zip(xs[p], matvec(w.wo[layer], att))]
+            u2 = norm(x, w.ffn_norm[layer])
+            gate, up = matvec(w.w_gate[layer], u2), matvec(w.w_up[layer], u2)
+            act = [gg / (1.0 + math.exp(-gg)) * uu for gg, uu in zip(gate, up)]
+            new.append([a + b for a, b in zip(x, matvec(w.w_down[layer], act))])
+        xs = new
+    return [matvec(w.lm_head, norm(x, w.final_norm)) for x in xs]
+
+
+def test_causal_forward_against_scalar_python():
+    wl = small_workload()
+    model = oracle_model(wl, make_weights(wl, wl.seed, sigma=0.4))
+    tokens = [3, 17, 5, 39, 0, 22, 8]
+    z, hidden, ks, vs = model.causal_forward(tokens)
+    want = np.array(_scalar_forward(model.cfg, model.w, tokens))
+    assert np.max(np.abs(z - want)) < 1e-11
+    assert np.std(want) > 0.05                                                     # not a vacuous comparison
+
+
+def test_causality_and_degenerate_blocks():
+    wl = small_workload()
+    tensors = make_weights(wl, wl.seed, sigma=0.4)
+    model = oracle_model(wl, tensors)
+    a, _, _, _ = model.causal_forward([1, 2, 3, 4, 5])
+    b, _, _, _ = model.causal_forward([1, 2, 3, 9, 7])
+    assert np.allclose(a[:3], b[:3], atol=1e-13) and not np.allclose(a[3], b[3])
+    # zero output projections switch both sub-layers off: logits = rms(E[tok]) @ W_lm^T
+    for layer in range(wl.n_layers):
+        tensors["wo"][layer] = torch.zeros_like(tensors["wo"][layer])
+        tensors["w_down"][layer] = torch.zeros_like(tensors["w_down"][layer])
+    off = oracle_model(wl, tensors)
+    z, _, _, _ = off.causal_forward([4, 4, 11])
+    e = off.w.tok_emb[[4, 4, 11]]
+    want = (e / np.sqrt((e * e).mean(axis=1, keepdims=True) + wl.rms_eps) * off.w.final_norm) @ off.w.lm_head.T
+    assert np.allclose(z, want, atol=1e-14) and np.allclose(z[0], z[1], atol=0)
+
+
+def test_transfer_is_a_bare_matrix_product():
+    wl = small_workload(k=3, transfer_layers=(1, 1, 2), n_layers=3)
+    model = oracle_model(wl, make_weights(wl, wl.seed, sigma=0.4))
+    dec = O.HiddenTransferOracle(model, [-1, 0], [0, 0], 32)
+    prompt = [5, 6, 7, 8]
+    dec.prefill(prompt)
+    _, hidden, _, _ = model.causal_forward(prompt)
+    ps = dec.transfer()
+    for i, t in enumerate(wl.transfer_layers):
+        h = hidden[t][-1]
+        want = [sum(model.w.w_transfer[i][o, c] * h[c] for c in range(wl.d_model)) for o in range(wl.d_model)]
+        assert np.allclose(ps[i], want, atol=1e-13)
