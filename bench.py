@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the Hidden Transfer tree-verify decode step on one MI355X.
+
+A "step" is one pass of the whole hot path on the Llama-2-7B-shaped workload (bf16, batch 1, 512-token
+cache, 64-node tree): hidden transfer -> draft pass of the k pseudo rows -> top-k -> tree build ->
+tree-verify forward -> greedy acceptance -> KV compaction.  Weights and prompt are seeded synthetic data
+already resident in HBM when timing starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def model_bytes(wl, T, n):
+    """Algorithmic HBM bytes of one verify pass: every weight once, KV cache read once, new KV written."""
+    es = 2 if wl.dtype == "bf16" else 4
+    d, qd, kvd, f, v = wl.d_model, wl.n_heads * wl.head_dim, wl.n_kv_heads * wl.head_dim, wl.d_ffn, wl.vocab
+    per_layer = (d * (qd + 2 * kvd) + qd * d + 3 * d * f + 2 * d) * es
+    weights = wl.n_layers * per_layer + (v * d + d) * es + T * d * es        # + embedding rows actually read
+    kv_read = wl.n_layers * 2 * (n + T) * kvd * es
+    kv_write = wl.n_layers * 2 * T * kvd * es
+    return weights + kv_read + kv_write
+
+
+def cpu_baseline(wl, T, n, weights):
+    """Times the fp64 oracle on one decoder block + the LM head at the real shape and extrapolates.
+    `weights` are the seeded tensors already generated on the GPU; layer 0 and the head are copied to the host."""
+    import numpy as np
+    from oracle import ht_oracle as O
+    tens = {}
+    for name, val in weights.items():
+        tens[name] = [val[0].cpu(), val[0].cpu()] if isinstance(val, list) and name != "w_transfer" else (
+            [t.cpu() for t in val] if isinstance(val, list) else val.cpu())
+    cfg = O.OracleConfig(2, wl.d_model, wl.n_heads, wl.n_kv_heads, wl.head_dim, wl.d_ffn, wl.vocab, wl.k,
+                         tuple(1 for _ in range(wl.k)), wl.rms_eps, wl.rope_base)
+    model = O.OracleModel(cfg, O.OracleWeights(tens))
+    rng = np.random.default_rng(0)
+    x = rng.normal(size=(T, wl.d_model))
+    kc = rng.normal(size=(n, wl.n_kv_heads, wl.head_dim))
+    vc = rng.normal(size=(n, wl.n_kv_heads, wl.head_dim))
+    pos = np.full(T, n)
+    vis_old = np.ones((T, n), dtype=bool)
+    vis_new = np.tril(np.ones((T, T), dtype=bool))
+    model.block(0, x[:2], pos[:2], kc, vc, vis_old[:2], vis_new[:2, :2])      # warm the BLAS threads
+    t0 = time.perf_counter()
+    y, _, _ = model.block(0, x, pos, kc, vc, vis_old, vis_new)
+    t_block = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    model.logits(y)
+    t_head = time.perf_counter() - t0
+    kx = x[:wl.k]
+    t0 = time.perf_counter()
+    model.block(0, kx, pos[:wl.k], kc, vc, vis_old[:wl.k], vis_new[:wl.k, :wl.k])
+    t_dblock = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    model.logits(kx)
+    t_dhead = time.perf_counter() - t0
+    est = wl.n_layers * t_block + t_head + (wl.n_layers - wl.transfer_layers[0]) * t_dblock + t_dhead
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": round(est * 1e3, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
+            "sample": (f"fp64 numpy oracle, one of {wl.n_layers} decoder blocks at T={T} rows and n={n} cached keys plus "
+                       f"the LM head, and one draft block at {wl.k} rows, each timed once "
+                       f"({t_block + t_head + t_dblock + t_dhead:.1f} s of CPU work) and extrapolated to a full step "
+                       f"({wl.n_layers} verify blocks + head + {wl.n_layers - wl.transfer_layers[0]} draft blocks + head)")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from ht_inputs import WORKLOADS, make_weights, counter_tokens, prune_tree, counter_normal
+    from ht_inputs.generators import PROMPT_STREAM
+    import paper_2404_12022_amd.binding as B
+
+    dev = "cuda:0"
+    wl = WORKLOADS[args.workload]
+    headroom = (args.steps + args.warmup + 4) * (wl.k + 1) + wl.tree_size
+    wl = wl.with_(max_cache=(wl.prompt_len + headroom + 7) // 8 * 8)
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    T, n0 = wl.tree_size, wl.prompt_len
+    parent, rank = prune_tree(wl.branching, T)
+    prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n0, wl.vocab)]
+    weights = make_weights(wl, wl.seed, dev, tdt)
+    model = B.HTModel(B.make_config(wl), weights, dev)
+    model.ht_set_tree(parent, rank)
+    model.ht_prefill(prompt)
+    stream = torch.cuda.current_stream()
+
+    def full_step():
+        model.ht_transfer()
+        model.ht_tree_verify_step()
+        return model.ht_accept_and_compact()
+
+    # ---- whole hot path, K steps, wall clock bracketed by synchronisation
+    accepted = 0
+    for _ in range(args.warmup):
+        full_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        accepted += full_step()[0]
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- verify pass alone (explicit tokens, no draft) and the one-token step, HIP events on the launch stream
+    def time_verify(tree_parent, tree_rank, reps):
+        model.ht_set_tree(tree_parent, tree_rank)
+        toks = torch.tensor(prompt[:len(tree_parent)], dtype=torch.int32, device=dev)
+        for _ in range(3):
+            model.ht_tree_verify_step(toks)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            model.ht_tree_verify_step(toks)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    n_now = model.ht_cache_len()
+    reps = max(5, args.steps)
+    ms_verify = time_verify(parent, rank, reps)
+    ms_one = time_verify([-1], [0], reps)
+    model.ht_set_tree(parent, rank)
+
+    # ---- dominant kernel: the gate/up projection [T,d] x [2f,d]^T, timed alone over rotating weight copies
+    M, N, K = T, 2 * wl.d_ffn, wl.d_model
+    copies = 4                                   # 4 x 180 MB > 256 MB of last-level cache
+    wbufs = [counter_normal(wl.seed, 900 + i, (N, K), 0.02, device=dev, dtype=tdt) for i in range(copies)]
+    a = counter_normal(wl.seed, 899, (B.ht_padded_rows(M), K), 1.0, device=dev, dtype=tdt)
+    out = torch.empty(M, N, dtype=torch.float32, device=dev)
+    for i in range(copies):
+        B.ht_skinny_gemm(a, wbufs[i], M, N, K, B.HT_BF16, out)
+    launches = 40
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(launches):
+        B.ht_skinny_gemm(a, wbufs[i % copies], M, N, K, B.HT_BF16, out)
+    e1.record(stream)
+    e1.synchronize()
+    ms_kernel = e0.elapsed_time(e1) / launches
+    es = 2
+    kernel_bytes = N * K * es + M * K * es + M * N * 4
+    achieved = kernel_bytes / (ms_kernel * 1e-3) / 1e9
+
+    verify_bytes = model_bytes(wl, T, n_now)
+    one_bytes = model_bytes(wl, 1, n_now)
+    res = {
+        "metric": "tree_verify_step_latency_ms", "value": round(ms_step, 4), "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_layers} layers d={wl.d_model} {wl.n_heads}x{wl.head_dim} heads "
+                               f"ffn={wl.d_ffn} vocab={wl.vocab}, batch 1, cache {n0}, tree T={T} {list(wl.branching)}, "
+                               f"k={wl.k} transfer after layer {wl.transfer_layers[0]}; step = transfer + draft pass + "
+                               f"top-k + tree build + verify + accept + compact"},
+        "verify_pass_ms": round(ms_verify, 4), "one_token_step_ms": round(ms_one, 4),
+        "verify_over_one_token": round(ms_verify / ms_one, 4),
+        "candidate_tokens_per_s": round(T / (ms_verify * 1e-3), 1),
+        "accepted_tokens_per_step": round(accepted / args.steps, 3),
+        "verify_hbm_GBps": round(verify_bytes / (ms_verify * 1e-3) / 1e9, 1),
+        "verify_hbm_frac_of_peak": round(verify_bytes / (ms_verify * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "one_token_hbm_GBps": round(one_bytes / (ms_one * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": f"gemm_mfma_kernel<4,2> gate/up projection M={M} N={N} K={K}",
+                     "bytes_per_launch": kernel_bytes, "ms_per_launch": round(ms_kernel, 5)},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

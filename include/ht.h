@@ -1,0 +1,162 @@
+/*
+ * ht.h — C ABI of the Hidden Transfer tree-verify decoding library for AMD MI355X (gfx950).
+ *
+ * The library computes, at batch 1 on one GPU, the decode step of "Parallel Decoding via Hidden
+ * Transfer for Lossless Large Language Model Acceleration" (arXiv 2404.12022):
+ *
+ *   transfer  : pseudo hidden states p_i = W_i h  for the next k positions        (Sec. 3.2, eq. of Sec. 3.3)
+ *   draft     : the pseudo rows run through the remaining blocks and the original
+ *               LM head; their top candidates fill a static tree                   (Sec. 1, 3.2, 3.4)
+ *   verify    : one forward of the flattened tree with ancestor-only attention and
+ *               original positional indices over the KV cache                      (Sec. 3.4, 3.4.1)
+ *   accept    : last accepted position under greedy decoding, next token, and the
+ *               KV cache keeps only the accepted rows                              (Fig. 2, Sec. 3.4, 4.1)
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked "host".  The library
+ *     allocates no device memory: all of its device state lives in the caller's `workspace`.
+ *   - Matrices are row-major [out_features, in_features]; y = x W^T.  No biases.
+ *   - `stream` is a hipStream_t passed as void*.  Calls enqueue on it and return without waiting unless
+ *     stated otherwise.  One model is used from one stream at a time; calls are not re-entrant.
+ *   - Positions are 0-based: the cache holds positions 0..n-1, the tree root sits at position n and a
+ *     node of depth e at n+e.  "Layer t" is the residual stream after t complete blocks.
+ *   - Return value: HT_OK (0) or a negative error; on error nothing has been enqueued and no state
+ *     changed.  `ht_last_error()` gives a thread-local message.  No exception crosses this boundary.
+ */
+#ifndef HT_H_
+#define HT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ht_model ht_model; /* opaque, host side, owned by the library */
+
+enum { HT_OK = 0, HT_EINVAL = -1, HT_ECAPACITY = -2, HT_ETREE = -3, HT_ESTATE = -4, HT_EHIP = -5,
+       HT_EUNSUPPORTED = -6 };
+enum { HT_F32 = 0, HT_BF16 = 1 };
+enum { HT_MAX_TRANSFER = 8, HT_MAX_TREE = 128, HT_MAX_TOPK = 64 };
+
+/* Llama-style decoder shape plus the hidden-transfer hyper-parameters (Sec. 3.3: the number of
+ * transfer steps k and the transfer layers t_i).  This build requires t_1 = ... = t_k. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype;                             /* HT_F32 or HT_BF16: storage type of weights, activations, KV */
+  int32_t k;                                 /* 1..HT_MAX_TRANSFER */
+  int32_t transfer_layer[HT_MAX_TRANSFER];   /* 1 <= t_i < n_layers */
+  int32_t max_cache;                         /* KV slots per layer (multiple of 8) */
+  int32_t max_tree;                          /* largest tree, root included; <= HT_MAX_TREE */
+} ht_config;
+
+/* Borrowed weight pointers (device).  They must outlive the model.  Per-layer arrays are host arrays
+ * of n_layers device pointers; w_transfer is a host array of k device pointers. */
+typedef struct {
+  const void *tok_emb;                       /* [vocab, d] */
+  const void *final_norm;                    /* [d] */
+  const void *lm_head;                       /* [vocab, d] */
+  const void *const *attn_norm;              /* [d] */
+  const void *const *wq;                     /* [n_heads*head_dim, d] */
+  const void *const *wk, *const *wv;         /* [n_kv_heads*head_dim, d] */
+  const void *const *wo;                     /* [d, n_heads*head_dim] */
+  const void *const *ffn_norm;               /* [d] */
+  const void *const *w_gate, *const *w_up;   /* [d_ffn, d] */
+  const void *const *w_down;                 /* [d, d_ffn] */
+  const void *const *w_transfer;             /* k x [d, d] */
+} ht_weights;
+
+/* Bytes of device workspace `ht_init_model` needs for this configuration (KV cache, activations,
+ * tree tables, decoder state). */
+int ht_workspace_bytes(const ht_config *cfg, size_t *out_bytes);
+
+/* Validates cfg, carves `workspace` (device, 256-byte aligned, >= ht_workspace_bytes) and clears it on
+ * `stream`.  The returned model starts with an empty cache and no tree. */
+int ht_init_model(const ht_config *cfg, const ht_weights *weights, void *workspace, size_t workspace_bytes,
+                  void *stream, ht_model **out);
+int ht_free_model(ht_model *m);
+
+/* Static candidate tree (Sec. 3.4.1 "pre-defined tree structure"): T nodes, root included.
+ * parent[0] = -1, 0 <= parent[v] < v, depth <= k; rank[v] (v >= 1) selects the rank-th best candidate
+ * of pseudo position depth[v], 0 <= rank < HT_MAX_TOPK, distinct among siblings.  Host arrays, copied
+ * before return.  HT_ETREE if malformed. */
+int ht_set_tree(ht_model *m, int32_t T, const int32_t *parent /*host*/, const int32_t *rank /*host*/, void *stream);
+
+/* Runs the prompt (host array of n token ids, n >= 1) through the model in chunks with plain causal
+ * attention, fills the KV cache, sets the pending root token to the greedy next token and keeps the
+ * layer-t residual of the last prompt token as the transfer source.  Resets any previous cache. */
+int ht_prefill(ht_model *m, const int32_t *tokens /*host*/, int32_t n, void *stream);
+
+/* Hidden transfer (Sec. 3.2; equation of Sec. 3.3): pseudo[i] = W_i h, i = 0..k-1, a bare matrix
+ * product.  h_src: [d] in the model dtype, or NULL to use the saved layer-t residual of the last
+ * accepted token.  pseudo_out: [k, d] float32, or NULL; the result is also kept inside the model for
+ * the next `ht_tree_verify_step`. */
+int ht_transfer(ht_model *m, const void *h_src, float *pseudo_out, void *stream);
+
+/* One tree-verify step (Sec. 3.4).
+ *   tree_tokens == NULL: draft first — the pseudo rows of the last `ht_transfer` run through blocks
+ *     t+1..L at positions n, n+1, .. seeing the cache, earlier pseudo rows and themselves, the LM head
+ *     gives D[k, vocab], top candidates by (logit desc, id asc) fill the tree under the pending root.
+ *   tree_tokens != NULL: device [T] token ids used as the tree (external drafter / forced trees);
+ *     tree_tokens[0] should be the pending root for the result to be a greedy continuation.
+ * Then the T rows are verified in one forward: row v at position n + depth[v] attends to cache[0, n)
+ * and its ancestors-or-self; K/V go to cache slot n+v; the layer-t residuals are saved.
+ * argmax_out: device [T] int32 or NULL, greedy token after each node (ties -> lowest id).
+ * logits_out: device [T, vocab] float32 or NULL.
+ * HT_ESTATE without a tree / prefill / (for drafting) transfer; HT_ECAPACITY if n + max(T, k) > max_cache. */
+int ht_tree_verify_step(ht_model *m, const int32_t *tree_tokens, int32_t *argmax_out, float *logits_out,
+                        void *stream);
+
+/* Greedy acceptance and cache compaction (Fig. 2; Sec. 3.4, 4.1).  From the root, repeatedly follows the
+ * first child (lowest node index) whose token equals the greedy token after the current node.  The m >= 1
+ * nodes on that path are accepted: their K/V rows move to cache slots n..n+m-1, n += m, the pending root
+ * becomes the greedy token after the last accepted node and its layer-t residual becomes the transfer
+ * source.  All outputs are HOST pointers (may be NULL) filled before return: this call waits for `stream`.
+ * accepted_tokens, path_out: [k+1]. HT_ESTATE unless it follows a verify step. */
+int ht_accept_and_compact(ht_model *m, int32_t *n_accepted, int32_t *accepted_tokens, int32_t *next_root,
+                          int32_t *path_out, void *stream);
+
+int32_t ht_cache_len(const ht_model *m);      /* n */
+const char *ht_last_error(void);
+
+/* Read-only views of the model's device buffers, for tests and tools.  `which` is one of HT_BUF_*;
+ * `layer` is used by the cache views only.  The pointer stays valid until ht_free_model. */
+enum { HT_BUF_DRAFT_LOGITS = 0 /* float [k, vocab] */, HT_BUF_CANDIDATES = 1 /* int32 [k, HT_MAX_TOPK] */,
+       HT_BUF_TREE_TOKENS = 2 /* int32 [T] */, HT_BUF_SAVED_HIDDEN = 3 /* float [T, d] layer-t residuals */,
+       HT_BUF_TRANSFER_SRC = 4 /* float [d] */, HT_BUF_K_CACHE = 5 /* dtype [max_cache, n_kv_heads, head_dim] */,
+       HT_BUF_V_CACHE = 6 /* dtype [n_kv_heads, head_dim, max_cache]: key index contiguous */,
+       HT_BUF_PSEUDO = 7 /* float [k, d] */, HT_BUF_ROOT = 8 /* int32 [1] pending root token */ };
+int ht_get_buffer(const ht_model *m, int32_t which, int32_t layer, void **dev_ptr, size_t *bytes);
+
+/* ---- op-level entry points (same kernels as the model path) -------------------------------------- */
+
+/* Tree-masked attention over a KV cache (Sec. 3.4.1): rotary at original positional indices, append,
+ * ancestor-only softmax attention.
+ *   q      [T, Hq, hd]  queries of the tree rows (pre-rotary if k_new != NULL)
+ *   k_new, v_new [T, Hkv, hd] or both NULL.  If given, q and k_new are rotated at position n + depth[v]
+ *          (pairs (j, j+hd/2), angle pos * rope_base^(-2j/hd)) and row v is stored at cache slot n+v
+ *          before attending; if NULL, slots n..n+T-1 already hold the tree rows and q is used as is.
+ *   k_cache [cap, Hkv, hd], v_cache [Hkv, hd, cap] (key index contiguous); cap multiple of 8, n + T <= cap
+ *   out    [T, Hq*hd]: row v = softmax over {cache 0..n-1} U {n+u : u ancestor-or-self of v} of q.k/sqrt(hd), times V
+ *   scratch: device bytes >= ht_tree_attention_scratch_bytes(...)
+ * parent is a host array.  dtype selects HT_F32 or HT_BF16 for q/k/v/out (softmax and sums in fp32). */
+size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd);
+int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                      int32_t cap, int32_t n, int32_t T, const int32_t *parent /*host*/, int32_t Hq, int32_t Hkv,
+                      int32_t hd, int32_t dtype, float rope_base, void *out, void *scratch, size_t scratch_bytes,
+                      void *stream);
+
+/* Skinny weight-streaming product out[M, N] (float32) = a[M, K] . w[N, K]^T with M <= HT_MAX_TREE rows,
+ * the contraction every projection of the verify step uses (Sec. 1: decoding time goes to loading the
+ * parameters).  a must be readable up to ht_padded_rows(M) rows.  scratch: >= ht_skinny_gemm_scratch_bytes. */
+int32_t ht_padded_rows(int32_t M);
+size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
+                   void *scratch, size_t scratch_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HT_H_ */

@@ -73,6 +73,11 @@ class OracleWeights:
             setattr(self, name, [cv(a) for a in tensors[name]])
 
 
+def linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """y = x W^T for a row-major [out, in] matrix: the textbook matrix product, in fp64."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+
+
 def rms_norm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
     """x / sqrt(mean(x^2) + eps) * gain, row-wise."""
     ms = np.mean(x * x, axis=-1, keepdims=True)
@@ -136,21 +141,21 @@ class OracleModel:
         c, w = self.cfg, self.w
         r = x.shape[0]
         u = rms_norm(x, w.attn_norm[layer], c.rms_eps)
-        q = (u @ w.wq[layer].T).reshape(r, c.n_heads, c.head_dim)
-        k = (u @ w.wk[layer].T).reshape(r, c.n_kv_heads, c.head_dim)
-        v = (u @ w.wv[layer].T).reshape(r, c.n_kv_heads, c.head_dim)
+        q = linear(u, w.wq[layer]).reshape(r, c.n_heads, c.head_dim)
+        k = linear(u, w.wk[layer]).reshape(r, c.n_kv_heads, c.head_dim)
+        v = linear(u, w.wv[layer]).reshape(r, c.n_kv_heads, c.head_dim)
         q, k = rope(q, pos, c.rope_base), rope(k, pos, c.rope_base)
         keys = np.concatenate([k_old, k], axis=0)
         vals = np.concatenate([v_old, v], axis=0)
         vis = np.concatenate([vis_old, vis_new], axis=1)
         a = masked_attention(q, keys, vals, vis).reshape(r, c.n_heads * c.head_dim)
-        x = x + a @ w.wo[layer].T
+        x = x + linear(a, w.wo[layer])
         u2 = rms_norm(x, w.ffn_norm[layer], c.rms_eps)
-        x = x + (silu(u2 @ w.w_gate[layer].T) * (u2 @ w.w_up[layer].T)) @ w.w_down[layer].T
+        x = x + linear(silu(linear(u2, w.w_gate[layer])) * linear(u2, w.w_up[layer]), w.w_down[layer])
         return x, k, v
 
     def logits(self, x: np.ndarray) -> np.ndarray:
-        return rms_norm(x, self.w.final_norm, self.cfg.rms_eps) @ self.w.lm_head.T
+        return linear(rms_norm(x, self.w.final_norm, self.cfg.rms_eps), self.w.lm_head)
 
     # ---- plain causal forward, full recompute: the textbook definition everything is pinned to
     def causal_forward(self, tokens: Sequence[int]):
@@ -262,7 +267,7 @@ class HiddenTransferOracle:
     # -- step 1
     def transfer(self) -> List[np.ndarray]:
         """p_i = W_i h^{t_i} for i = 1..k: a bare matrix product, no bias, norm or residual."""
-        return [self.m.w.w_transfer[i] @ self.h_src[t] for i, t in enumerate(self.cfg.transfer_layers)]
+        return [linear(self.h_src[t], self.m.w.w_transfer[i]) for i, t in enumerate(self.cfg.transfer_layers)]
 
     # -- step 2
     def draft(self, pseudo: List[np.ndarray]) -> np.ndarray:
@@ -361,7 +366,7 @@ class HiddenTransferOracle:
         for layer in range(c.n_layers):
             for i, t in enumerate(c.transfer_layers):
                 if t == layer:
-                    new = np.stack([self.m.w.w_transfer[i] @ x[v] for v in range(t_rows)])
+                    new = linear(x[:t_rows], self.m.w.w_transfer[i])
                     x = np.concatenate([x, new], axis=0)
                     owner += list(range(t_rows))
                     step += [i + 1] * t_rows

@@ -1,0 +1,241 @@
+"""ctypes binding of libht.so: the same entry points as include/ht.h, argument marshalling only.
+
+`HTModel` is a convenience holder that keeps the torch tensors (weights, workspace) alive and turns
+them into pointers; it performs no arithmetic.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libht.so")
+
+HT_OK, HT_EINVAL, HT_ECAPACITY, HT_ETREE, HT_ESTATE, HT_EHIP, HT_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+HT_F32, HT_BF16 = 0, 1
+HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_TOPK = 8, 128, 64
+(HT_BUF_DRAFT_LOGITS, HT_BUF_CANDIDATES, HT_BUF_TREE_TOKENS, HT_BUF_SAVED_HIDDEN, HT_BUF_TRANSFER_SRC,
+ HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT) = range(9)
+
+EXPORTS = [
+    "ht_workspace_bytes", "ht_init_model", "ht_free_model", "ht_set_tree", "ht_prefill", "ht_transfer",
+    "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
+    "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
+    "ht_skinny_gemm",
+]
+
+
+class ht_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
+        ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32), ("k", C.c_int32),
+        ("transfer_layer", C.c_int32 * HT_MAX_TRANSFER), ("max_cache", C.c_int32), ("max_tree", C.c_int32)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class ht_weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP), ("ffn_norm", _PP),
+                ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP), ("w_transfer", _PP)]
+
+
+class HTError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libht error {code}: {message}")
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2404_12022_amd.build); "
+                          "there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    i32p, f32p, vp, sz = C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p, C.c_size_t
+    sig = {
+        "ht_workspace_bytes": (C.c_int, [C.POINTER(ht_config), C.POINTER(sz)]),
+        "ht_init_model": (C.c_int, [C.POINTER(ht_config), C.POINTER(ht_weights), vp, sz, vp, C.POINTER(vp)]),
+        "ht_free_model": (C.c_int, [vp]),
+        "ht_set_tree": (C.c_int, [vp, C.c_int32, i32p, i32p, vp]),
+        "ht_prefill": (C.c_int, [vp, i32p, C.c_int32, vp]),
+        "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
+        "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
+        "ht_accept_and_compact": (C.c_int, [vp, i32p, i32p, i32p, i32p, vp]),
+        "ht_cache_len": (C.c_int32, [vp]),
+        "ht_last_error": (C.c_char_p, []),
+        "ht_get_buffer": (C.c_int, [vp, C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(sz)]),
+        "ht_tree_attention_scratch_bytes": (sz, [C.c_int32, C.c_int32, C.c_int32]),
+        "ht_tree_attention": (C.c_int, [vp, vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int32, C.c_int32,
+                                        C.c_int32, C.c_int32, C.c_float, vp, vp, sz, vp]),
+        "ht_padded_rows": (C.c_int32, [C.c_int32]),
+        "ht_skinny_gemm_scratch_bytes": (sz, [C.c_int32, C.c_int32, C.c_int32]),
+        "ht_skinny_gemm": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int) -> None:
+    if rc != HT_OK:
+        raise HTError(rc, lib.ht_last_error().decode())
+
+
+def _i32(seq: Sequence[int]):
+    return (C.c_int32 * len(seq))(*[int(v) for v in seq])
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+# ------------------------------------------------------------------ thin wrappers, same names as the ABI
+def ht_last_error() -> str:
+    return lib.ht_last_error().decode()
+
+
+def ht_padded_rows(m: int) -> int:
+    return lib.ht_padded_rows(m)
+
+
+def ht_workspace_bytes(cfg: ht_config) -> int:
+    out = C.c_size_t(0)
+    _check(lib.ht_workspace_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def ht_tree_attention_scratch_bytes(T: int, Hq: int, hd: int) -> int:
+    return lib.ht_tree_attention_scratch_bytes(T, Hq, hd)
+
+
+def ht_tree_attention(q, k_new, v_new, k_cache, v_cache, cap, n, T, parent, Hq, Hkv, hd, dtype, rope_base, out, scratch,
+                      stream=None) -> None:
+    _check(lib.ht_tree_attention(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), cap, n, T,
+                                 _i32(parent), Hq, Hkv, hd, dtype, rope_base, _ptr(out), _ptr(scratch),
+                                 scratch.numel() * scratch.element_size(), _stream_ptr(stream)))
+
+
+def ht_skinny_gemm_scratch_bytes(M: int, N: int, K: int) -> int:
+    return lib.ht_skinny_gemm_scratch_bytes(M, N, K)
+
+
+def ht_skinny_gemm(a, w, M, N, K, dtype, out, scratch=None, stream=None) -> None:
+    sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib.ht_skinny_gemm(_ptr(a), _ptr(w), M, N, K, dtype, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
+
+
+def make_config(shape, max_cache: Optional[int] = None, max_tree: Optional[int] = None) -> ht_config:
+    """ht_config from any object with the Workload attributes."""
+    cfg = ht_config()
+    for name in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "k"):
+        setattr(cfg, name, int(getattr(shape, name)))
+    cfg.rms_eps, cfg.rope_base = float(shape.rms_eps), float(shape.rope_base)
+    cfg.dtype = HT_F32 if shape.dtype == "f32" else HT_BF16
+    for i, t in enumerate(shape.transfer_layers):
+        cfg.transfer_layer[i] = int(t)
+    cfg.max_cache = int(max_cache if max_cache is not None else shape.max_cache)
+    cfg.max_tree = int(max_tree if max_tree is not None else shape.tree_size)
+    return cfg
+
+
+class HTModel:
+    """Owns the workspace tensor and the pointer tables for one ht_model handle."""
+
+    def __init__(self, cfg: ht_config, weights: Dict[str, object], device="cuda:0", stream=None):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.weights = weights                      # keep the tensors alive
+        self.device = torch.device(device)
+        L, k = cfg.n_layers, cfg.k
+        w = ht_weights()
+        w.tok_emb, w.final_norm, w.lm_head = (weights[n].data_ptr() for n in ("tok_emb", "final_norm", "lm_head"))
+        self._tables = {}
+        for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+            arr = (C.c_void_p * L)(*[weights[name][l].data_ptr() for l in range(L)])
+            self._tables[name] = arr
+            setattr(w, name, C.cast(arr, _PP))
+        arr = (C.c_void_p * k)(*[weights["w_transfer"][i].data_ptr() for i in range(k)])
+        self._tables["w_transfer"] = arr
+        w.w_transfer = C.cast(arr, _PP)
+        nbytes = ht_workspace_bytes(cfg)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        handle = C.c_void_p()
+        _check(lib.ht_init_model(C.byref(cfg), C.byref(w), self.workspace.data_ptr(), nbytes, _stream_ptr(stream),
+                                 C.byref(handle)))
+        self.handle = handle
+        self.T = 0
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            lib.ht_free_model(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the ABI calls
+    def ht_set_tree(self, parent: Sequence[int], rank: Sequence[int], stream=None) -> None:
+        _check(lib.ht_set_tree(self.handle, len(parent), _i32(parent), _i32(rank), _stream_ptr(stream)))
+        self.T = len(parent)
+
+    def ht_prefill(self, tokens: Sequence[int], stream=None) -> None:
+        _check(lib.ht_prefill(self.handle, _i32(tokens), len(tokens), _stream_ptr(stream)))
+
+    def ht_transfer(self, h_src=None, pseudo_out=None, stream=None) -> None:
+        _check(lib.ht_transfer(self.handle, _ptr(h_src), _ptr(pseudo_out), _stream_ptr(stream)))
+
+    def ht_tree_verify_step(self, tree_tokens=None, argmax_out=None, logits_out=None, stream=None) -> None:
+        _check(lib.ht_tree_verify_step(self.handle, _ptr(tree_tokens), _ptr(argmax_out), _ptr(logits_out),
+                                       _stream_ptr(stream)))
+
+    def ht_accept_and_compact(self, stream=None):
+        k1 = self.cfg.k + 1
+        m, root = C.c_int32(0), C.c_int32(0)
+        toks, path = (C.c_int32 * k1)(), (C.c_int32 * k1)()
+        _check(lib.ht_accept_and_compact(self.handle, C.byref(m), toks, C.byref(root), path, _stream_ptr(stream)))
+        return m.value, list(toks[:m.value]), root.value, list(path[:m.value])
+
+    def ht_cache_len(self) -> int:
+        return lib.ht_cache_len(self.handle)
+
+    def ht_get_buffer(self, which: int, layer: int = 0):
+        """Device buffer as a torch tensor view (read-only by convention)."""
+        torch = self.torch
+        p, nb = C.c_void_p(), C.c_size_t()
+        _check(lib.ht_get_buffer(self.handle, which, layer, C.byref(p), C.byref(nb)))
+        off = p.value - self.workspace.data_ptr()
+        raw = self.workspace[off:off + nb.value]
+        c = self.cfg
+        mdt = torch.float32 if c.dtype == HT_F32 else torch.bfloat16
+        if which == HT_BUF_DRAFT_LOGITS:
+            return raw.view(torch.float32).view(c.k, c.vocab)
+        if which == HT_BUF_CANDIDATES:
+            return raw.view(torch.int32).view(c.k, HT_MAX_TOPK)
+        if which in (HT_BUF_TREE_TOKENS, HT_BUF_ROOT):
+            return raw.view(torch.int32)
+        if which == HT_BUF_SAVED_HIDDEN:
+            return raw.view(torch.float32).view(-1, c.d_model)
+        if which == HT_BUF_TRANSFER_SRC:
+            return raw.view(torch.float32)
+        if which == HT_BUF_PSEUDO:
+            return raw.view(torch.float32).view(c.k, c.d_model)
+        if which == HT_BUF_K_CACHE:
+            return raw.view(mdt).view(c.max_cache, c.n_kv_heads, c.head_dim)
+        if which == HT_BUF_V_CACHE:
+            return raw.view(mdt).view(c.n_kv_heads, c.head_dim, c.max_cache)
+        raise ValueError(which)

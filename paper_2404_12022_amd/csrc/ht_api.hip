@@ -1,0 +1,630 @@
+// C ABI of libht: argument validation, workspace carving and the order in which the kernels of one
+// decode step are enqueued.  All arithmetic lives in the kernels; nothing here touches tensor data
+// on the host.
+#include "../../include/ht.h"
+#include "ht_common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+using namespace ht;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HT_HIP(expr)                                                                              \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess) return fail(HT_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+  } while (0)
+
+size_t elem_size(int dtype) { return dtype == HT_F32 ? 4 : 2; }
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int padded_rows(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128; }
+
+// Bump allocator over the workspace; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <typename T> T* take(size_t count) {
+    off = align_up(off, 256);
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+  void* take_bytes(size_t bytes) { return take<char>(bytes); }
+};
+
+struct TreeTables {
+  int32_t *parent, *depth, *rank;
+  uint64_t* anc;
+  TreeDev dev() const { return TreeDev{parent, depth, rank, anc}; }
+};
+
+struct Buffers {
+  float* x;            // residual stream [Mp, d]
+  void* u;             // normalised rows (dtype) [Mp, d]
+  float* qkv;          // [Mp, (Hq + 2 Hkv) hd]
+  void* q;             // rotated queries (dtype) [Mp, Hq hd]
+  void* attn;          // attention output (dtype) [Mp, Hq hd]
+  float* gu;           // gate | up [Mp, 2 f]
+  void* act;           // silu(gate) * up (dtype) [Mp, f]
+  float* part;         // split-K partial sums [kMaxSplitK][Mp][d]
+  float* logits;       // [Mp, V]
+  float* dlogits;      // draft logits [k, V]
+  float* saved_h;      // layer-t residuals of the last verify pass [Mp, d]
+  float* h_src;        // transfer source [d]
+  float* pseudo;       // [k, d]
+  float* cs;           // rotary table [Mp, hd/2] (cos, sin)
+  int32_t *tok, *g, *cand, *width, *prompt;
+  TreeTables tree, chain;
+  StepState* state;
+  void** kc_ptrs;      // device array [L]
+  void** vc_ptrs;
+  void** wt_ptrs;      // device array [k]
+  void* attn_scratch;
+  std::vector<void*> kc, vc;   // host copies of the per-layer cache pointers
+};
+
+void carve(const ht_config& c, Carver& cv, Buffers& b) {
+  const size_t es = elem_size(c.dtype);
+  const size_t Mp = padded_rows(c.max_tree > c.k ? c.max_tree : c.k);
+  const size_t d = c.d_model, qd = (size_t)c.n_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+  b.x = cv.take<float>(Mp * d);
+  b.u = cv.take_bytes(Mp * d * es);
+  b.qkv = cv.take<float>(Mp * (qd + 2 * kvd));
+  b.q = cv.take_bytes(Mp * qd * es);
+  b.attn = cv.take_bytes(Mp * qd * es);
+  b.gu = cv.take<float>(Mp * 2 * c.d_ffn);
+  b.act = cv.take_bytes(Mp * c.d_ffn * es);
+  b.part = cv.take<float>((size_t)kMaxSplitK * Mp * d);
+  b.logits = cv.take<float>(Mp * c.vocab);
+  b.dlogits = cv.take<float>((size_t)padded_rows(c.k) * c.vocab);
+  b.saved_h = cv.take<float>(Mp * d);
+  b.h_src = cv.take<float>(d);
+  b.pseudo = cv.take<float>((size_t)c.k * d);
+  b.cs = cv.take<float>(Mp * c.head_dim);
+  b.tok = cv.take<int32_t>(Mp);
+  b.g = cv.take<int32_t>(Mp);
+  b.cand = cv.take<int32_t>((size_t)kMaxTransfer * kMaxTopK);
+  b.width = cv.take<int32_t>(kMaxTransfer + 2);
+  b.prompt = cv.take<int32_t>(c.max_cache);
+  for (TreeTables* t : {&b.tree, &b.chain}) {
+    t->parent = cv.take<int32_t>(kMaxTree);
+    t->depth = cv.take<int32_t>(kMaxTree);
+    t->rank = cv.take<int32_t>(kMaxTree);
+    t->anc = cv.take<uint64_t>((size_t)kMaxTree * kMaskWords);
+  }
+  b.state = cv.take<StepState>(1);
+  b.kc_ptrs = cv.take<void*>(c.n_layers);
+  b.vc_ptrs = cv.take<void*>(c.n_layers);
+  b.wt_ptrs = cv.take<void*>(kMaxTransfer);
+  b.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes((int)Mp, c.n_heads, c.head_dim));
+  b.kc.resize(c.n_layers);
+  b.vc.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    b.kc[l] = cv.take_bytes((size_t)c.max_cache * kvd * es);
+    b.vc[l] = cv.take_bytes((size_t)c.max_cache * kvd * es);
+  }
+}
+
+int check_config(const ht_config* c) {
+  if (!c) return fail(HT_EINVAL, "config is NULL");
+  if (c->n_layers < 2 || c->d_model < 8 || c->n_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 || c->d_ffn < 8 ||
+      c->vocab < 2)
+    return fail(HT_EINVAL, "non-positive or too small model dimension");
+  if (c->dtype != HT_F32 && c->dtype != HT_BF16) return fail(HT_EINVAL, "dtype must be HT_F32 or HT_BF16");
+  if (c->n_heads % c->n_kv_heads) return fail(HT_EINVAL, "n_heads must be a multiple of n_kv_heads");
+  if (c->head_dim % 2 || c->head_dim > 256) return fail(HT_EINVAL, "head_dim must be even and <= 256");
+  if (c->d_model % 8 || c->d_ffn % 8 || (c->n_heads * c->head_dim) % 8)
+    return fail(HT_EINVAL, "d_model, d_ffn and n_heads*head_dim must be multiples of 8");
+  if (c->k < 1 || c->k > HT_MAX_TRANSFER) return fail(HT_EINVAL, "k must be in 1..%d", HT_MAX_TRANSFER);
+  for (int i = 0; i < c->k; ++i) {
+    if (c->transfer_layer[i] < 1 || c->transfer_layer[i] >= c->n_layers)
+      return fail(HT_EINVAL, "transfer_layer[%d]=%d outside 1..n_layers-1", i, c->transfer_layer[i]);
+    if (c->transfer_layer[i] != c->transfer_layer[0])
+      return fail(HT_EUNSUPPORTED, "distinct transfer layers per step are not supported by this build");
+  }
+  if (c->max_tree < 1 || c->max_tree > HT_MAX_TREE) return fail(HT_EINVAL, "max_tree must be in 1..%d", HT_MAX_TREE);
+  if (c->max_cache < 8 || c->max_cache % 8) return fail(HT_EINVAL, "max_cache must be a positive multiple of 8");
+  if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(HT_EINVAL, "rms_eps must be > 0 and rope_base > 1");
+  return HT_OK;
+}
+
+}  // namespace
+
+struct ht_model {
+  ht_config cfg;
+  const void *tok_emb, *final_norm, *lm_head;
+  std::vector<const void*> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down, w_transfer;
+  Buffers b;
+  int Mp = 0;
+  int n = 0;
+  int T = 0;
+  bool has_tree = false, has_prefill = false, transfer_ready = false, verify_done = false;
+  bool use_mfma = true;
+  std::vector<int32_t> depth;
+  // pinned host staging
+  int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
+  StepState* h_state = nullptr;
+};
+
+namespace {
+
+int product(ht_model* m, const void* a, WeightSegs w, int M, int N, int K, float* out, int max_split, int* nsplit,
+            hipStream_t s) {
+  if (m->cfg.dtype == HT_BF16 && m->use_mfma && gemm_mfma_supported(M, N, K)) {
+    int sp = gemm_mfma_splits(M, N, K);
+    if (sp > max_split) sp = max_split;
+    *nsplit = sp;
+    HT_HIP(launch_gemm_mfma(a, w, M, N, K, out, sp, s));
+  } else {
+    *nsplit = 1;
+    HT_HIP(launch_gemm_simple(m->cfg.dtype, a, w, M, N, K, out, s));
+  }
+  return HT_OK;
+}
+
+WeightSegs segs1(const void* w0, int r0) { return WeightSegs{{w0, nullptr, nullptr}, {r0, 0, 0}, 1}; }
+
+int attention(ht_model* m, int layer, int n, int M, const TreeDev& tree, hipStream_t s) {
+  const ht_config& c = m->cfg;
+  Buffers& b = m->b;
+  if (c.dtype == HT_BF16 && m->use_mfma && attn_mfma_supported(M, c.n_heads, c.n_kv_heads, c.head_dim)) {
+    HT_HIP(launch_attn_mfma(b.q, b.kc[layer], b.vc[layer], c.max_cache, n, M, tree, c.n_heads, c.n_kv_heads, c.head_dim,
+                            b.attn, b.attn_scratch, s));
+  } else {
+    HT_HIP(launch_attn_simple(c.dtype, b.q, b.kc[layer], b.vc[layer], c.max_cache, n, M, tree, c.n_heads, c.n_kv_heads,
+                              c.head_dim, b.attn, s));
+  }
+  return HT_OK;
+}
+
+// Rows already in b.x go through blocks layer_from+1 .. L (0-based index layer_from .. L-1), then the
+// final norm and, if `logits` is given, the LM head and the row arg-max.
+int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_hidden, float* logits, int32_t* gout,
+             hipStream_t s) {
+  const ht_config& c = m->cfg;
+  Buffers& b = m->b;
+  const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn;
+  const size_t pstride = (size_t)M * d;
+  const int n = m->n;
+  int rc;
+  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M, c.head_dim, c.rope_base, s));
+  int pending = 0;
+  for (int l = layer_from; l < c.n_layers; ++l) {
+    float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
+    HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
+    int one;
+    WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
+    if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, 1, &one, s))) return rc;
+    HT_HIP(launch_rope_append(c.dtype, b.qkv, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads, c.head_dim,
+                              c.max_cache, s));
+    if ((rc = attention(m, l, n, M, tree, s))) return rc;
+    if ((rc = product(m, b.attn, segs1(m->wo[l], d), M, d, qd, b.part, kMaxSplitK, &pending, s))) return rc;
+    HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->ffn_norm[l], b.u, nullptr, M, d, c.rms_eps, s));
+    WeightSegs gu{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2};
+    if ((rc = product(m, b.u, gu, M, 2 * f, d, b.gu, 1, &one, s))) return rc;
+    HT_HIP(launch_silu_mul(c.dtype, b.gu, b.act, M, f, s));
+    if ((rc = product(m, b.act, segs1(m->w_down[l], d), M, d, f, b.part, kMaxSplitK, &pending, s))) return rc;
+  }
+  HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->final_norm, logits ? b.u : nullptr, nullptr, M, d,
+                         c.rms_eps, s));
+  if (logits) {
+    int one;
+    if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, 1, &one, s))) return rc;
+    HT_HIP(launch_argmax(logits, gout, M, c.vocab, s));
+  }
+  return HT_OK;
+}
+
+// host-side tree tables: depth, ancestor-or-self bit masks
+void fill_tables(int T, const int32_t* parent, const int32_t* rank, int32_t* stage) {
+  int32_t* sp = stage;                       // parent
+  int32_t* sd = stage + kMaxTree;            // depth
+  int32_t* sr = stage + 2 * kMaxTree;        // rank
+  uint64_t* sa = (uint64_t*)(stage + 3 * kMaxTree);
+  memset(stage, 0, sizeof(int32_t) * 3 * kMaxTree + sizeof(uint64_t) * kMaxTree * kMaskWords);
+  for (int v = 0; v < T; ++v) {
+    sp[v] = parent[v];
+    sr[v] = rank ? rank[v] : 0;
+    sd[v] = v == 0 ? 0 : sd[parent[v]] + 1;
+    for (int wd = 0; wd < kMaskWords; ++wd) sa[v * kMaskWords + wd] = v == 0 ? 0 : sa[parent[v] * kMaskWords + wd];
+    sa[v * kMaskWords + (v >> 6)] |= 1ull << (v & 63);
+  }
+}
+constexpr size_t kTableInts = 3 * kMaxTree + 2 * kMaxTree * kMaskWords;   // int32 units of one table image
+
+int upload_tables(const TreeTables& t, const int32_t* stage, hipStream_t s) {
+  HT_HIP(hipMemcpyAsync(t.parent, stage, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.depth, stage + kMaxTree, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.rank, stage + 2 * kMaxTree, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.anc, stage + 3 * kMaxTree, sizeof(uint64_t) * kMaxTree * kMaskWords, hipMemcpyHostToDevice, s));
+  return HT_OK;
+}
+
+int validate_tree(int T, const int32_t* parent, const int32_t* rank, int max_depth, int max_T) {
+  if (T < 1 || T > max_T) return fail(HT_ETREE, "tree size %d outside 1..%d", T, max_T);
+  if (!parent) return fail(HT_EINVAL, "parent is NULL");
+  if (parent[0] != -1) return fail(HT_ETREE, "parent[0] must be -1");
+  std::vector<int> depth(T, 0);
+  for (int v = 1; v < T; ++v) {
+    if (parent[v] < 0 || parent[v] >= v) return fail(HT_ETREE, "parent[%d]=%d must be in 0..%d", v, parent[v], v - 1);
+    depth[v] = depth[parent[v]] + 1;
+    if (depth[v] > max_depth) return fail(HT_ETREE, "node %d has depth %d > %d", v, depth[v], max_depth);
+    if (rank) {
+      if (rank[v] < 0 || rank[v] >= HT_MAX_TOPK) return fail(HT_ETREE, "rank[%d]=%d outside 0..%d", v, rank[v], HT_MAX_TOPK - 1);
+      for (int u = 1; u < v; ++u)
+        if (parent[u] == parent[v] && rank[u] == rank[v]) return fail(HT_ETREE, "siblings %d and %d share rank %d", u, v, rank[v]);
+    }
+  }
+  return HT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ht_last_error(void) { return g_err; }
+
+int32_t ht_padded_rows(int32_t M) { return padded_rows(M); }
+
+int ht_workspace_bytes(const ht_config* cfg, size_t* out_bytes) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!out_bytes) return fail(HT_EINVAL, "out_bytes is NULL");
+  Carver cv(nullptr);
+  Buffers b;
+  carve(*cfg, cv, b);
+  *out_bytes = align_up(cv.off, 256);
+  return HT_OK;
+}
+
+int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, size_t workspace_bytes, void* stream,
+                  ht_model** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!w || !workspace || !out) return fail(HT_EINVAL, "NULL argument");
+  if ((uintptr_t)workspace % 256) return fail(HT_EINVAL, "workspace must be 256-byte aligned");
+  size_t need = 0;
+  ht_workspace_bytes(cfg, &need);
+  if (workspace_bytes < need) return fail(HT_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+      !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down || !w->w_transfer)
+    return fail(HT_EINVAL, "a weight pointer is NULL");
+  const int L = cfg->n_layers;
+  for (int l = 0; l < L; ++l)
+    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
+        !w->w_up[l] || !w->w_down[l])
+      return fail(HT_EINVAL, "a weight pointer of layer %d is NULL", l);
+  for (int i = 0; i < cfg->k; ++i)
+    if (!w->w_transfer[i]) return fail(HT_EINVAL, "w_transfer[%d] is NULL", i);
+
+  hipStream_t s = (hipStream_t)stream;
+  ht_model* m = new ht_model();
+  m->cfg = *cfg;
+  m->tok_emb = w->tok_emb;
+  m->final_norm = w->final_norm;
+  m->lm_head = w->lm_head;
+  m->attn_norm.assign(w->attn_norm, w->attn_norm + L);
+  m->wq.assign(w->wq, w->wq + L);
+  m->wk.assign(w->wk, w->wk + L);
+  m->wv.assign(w->wv, w->wv + L);
+  m->wo.assign(w->wo, w->wo + L);
+  m->ffn_norm.assign(w->ffn_norm, w->ffn_norm + L);
+  m->w_gate.assign(w->w_gate, w->w_gate + L);
+  m->w_up.assign(w->w_up, w->w_up + L);
+  m->w_down.assign(w->w_down, w->w_down + L);
+  m->w_transfer.assign(w->w_transfer, w->w_transfer + cfg->k);
+  m->Mp = padded_rows(cfg->max_tree > cfg->k ? cfg->max_tree : cfg->k);
+  const char* env = getenv("HT_FORCE_SIMPLE");
+  m->use_mfma = !(env && env[0] == '1');
+  Carver cv(workspace);
+  carve(*cfg, cv, m->b);
+
+  auto cleanup = [&](int code) {
+    if (m->h_stage) (void)hipHostFree(m->h_stage);
+    if (m->h_state) (void)hipHostFree(m->h_state);
+    delete m;
+    return code;
+  };
+  size_t stage_ints = (size_t)cfg->max_cache > 2 * kTableInts ? (size_t)cfg->max_cache : 2 * kTableInts;
+  stage_ints += 3 * (size_t)L * 2 + 64;     // per-layer pointer tables (as 8-byte entries) follow the ints
+  hipError_t e = hipHostMalloc((void**)&m->h_stage, stage_ints * sizeof(int32_t) + 16, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&m->h_state, sizeof(StepState), hipHostMallocDefault);
+  if (e == hipSuccess) e = hipMemsetAsync(workspace, 0, need, s);
+  if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init allocation/clear failed: %s", hipGetErrorString(e)));
+
+  // chain tables (prefill chunks and pseudo rows): row i has depth i and sees rows 0..i
+  std::vector<int32_t> cp(kMaxTree);
+  for (int i = 0; i < kMaxTree; ++i) cp[i] = i - 1;
+  fill_tables(kMaxTree, cp.data(), nullptr, m->h_stage);
+  if ((rc = upload_tables(m->b.chain, m->h_stage, s))) return cleanup(rc);
+  // pointer tables
+  void** hp = (void**)(m->h_stage + 2 * kTableInts);
+  for (int l = 0; l < L; ++l) { hp[l] = m->b.kc[l]; hp[L + l] = m->b.vc[l]; }
+  for (int i = 0; i < cfg->k; ++i) hp[2 * L + i] = (void*)m->w_transfer[i];
+  e = hipMemcpyAsync(m->b.kc_ptrs, hp, sizeof(void*) * L, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(m->b.vc_ptrs, hp + L, sizeof(void*) * L, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(m->b.wt_ptrs, hp + 2 * L, sizeof(void*) * cfg->k, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init upload failed: %s", hipGetErrorString(e)));
+  *out = m;
+  return HT_OK;
+}
+
+int ht_free_model(ht_model* m) {
+  if (!m) return HT_OK;
+  if (m->h_stage) (void)hipHostFree(m->h_stage);
+  if (m->h_state) (void)hipHostFree(m->h_state);
+  delete m;
+  return HT_OK;
+}
+
+int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* rank, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!rank) return fail(HT_EINVAL, "rank is NULL");
+  int rc = validate_tree(T, parent, rank, m->cfg.k, m->cfg.max_tree);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
+  fill_tables(T, parent, rank, m->h_stage);
+  int32_t* width = m->h_stage + kTableInts;
+  for (int e = 0; e < kMaxTransfer + 2; ++e) width[e] = 0;
+  const int32_t* depth = m->h_stage + kMaxTree;
+  for (int v = 1; v < T; ++v)
+    if (rank[v] + 1 > width[depth[v]]) width[depth[v]] = rank[v] + 1;
+  if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
+  HT_HIP(hipMemcpyAsync(m->b.width, width, sizeof(int32_t) * (kMaxTransfer + 2), hipMemcpyHostToDevice, s));
+  HT_HIP(hipStreamSynchronize(s));
+  m->depth.assign(depth, depth + T);
+  m->T = T;
+  m->has_tree = true;
+  m->verify_done = false;
+  return HT_OK;
+}
+
+int ht_prefill(ht_model* m, const int32_t* tokens, int32_t n, void* stream) {
+  if (!m || !tokens) return fail(HT_EINVAL, "NULL argument");
+  const ht_config& c = m->cfg;
+  if (n < 1) return fail(HT_EINVAL, "prompt must have at least one token");
+  if (n > c.max_cache) return fail(HT_ECAPACITY, "prompt of %d tokens exceeds max_cache %d", n, c.max_cache);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(HT_EINVAL, "token %d at %d outside the vocabulary", tokens[i], i);
+  hipStream_t s = (hipStream_t)stream;
+  HT_HIP(hipStreamSynchronize(s));
+  memcpy(m->h_stage, tokens, sizeof(int32_t) * n);
+  HT_HIP(hipMemcpyAsync(m->b.prompt, m->h_stage, sizeof(int32_t) * n, hipMemcpyHostToDevice, s));
+  m->n = 0;
+  m->has_prefill = m->transfer_ready = m->verify_done = false;
+  const TreeDev chain = m->b.chain.dev();
+  int rc;
+  for (int start = 0; start < n; start += m->Mp) {
+    const int rows = n - start < m->Mp ? n - start : m->Mp;
+    const bool last = start + rows == n;
+    HT_HIP(launch_embed(c.dtype, m->tok_emb, m->b.prompt + start, m->b.x, rows, c.d_model, s));
+    if ((rc = run_pass(m, chain, rows, 0, true, last ? m->b.logits : nullptr, m->b.g, s))) return rc;
+    if (last) HT_HIP(launch_prefill_finish(m->b.state, m->b.g, m->b.saved_h, m->b.h_src, rows - 1, c.d_model, s));
+    m->n += rows;                              // chain rows are already in their final slots
+  }
+  HT_HIP(hipStreamSynchronize(s));
+  m->has_prefill = true;
+  return HT_OK;
+}
+
+int ht_transfer(ht_model* m, const void* h_src, float* pseudo_out, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!h_src && !m->has_prefill) return fail(HT_ESTATE, "no saved hidden state: call ht_prefill first or pass h_src");
+  hipStream_t s = (hipStream_t)stream;
+  const ht_config& c = m->cfg;
+  if (h_src) HT_HIP(launch_convert_to_f32(c.dtype, h_src, m->b.h_src, c.d_model, s));
+  HT_HIP(launch_transfer(c.dtype, m->b.h_src, (const void* const*)m->b.wt_ptrs, m->b.pseudo, c.k, c.d_model, s));
+  if (pseudo_out)
+    HT_HIP(hipMemcpyAsync(pseudo_out, m->b.pseudo, sizeof(float) * c.k * c.d_model, hipMemcpyDeviceToDevice, s));
+  m->transfer_ready = true;
+  return HT_OK;
+}
+
+int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax_out, float* logits_out, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
+  if (!m->has_prefill) return fail(HT_ESTATE, "empty cache: call ht_prefill first");
+  if (!tree_tokens && !m->transfer_ready) return fail(HT_ESTATE, "drafting needs a preceding ht_transfer");
+  const ht_config& c = m->cfg;
+  const int T = m->T;
+  const int rows = T > c.k ? T : c.k;
+  if (m->n + rows > c.max_cache)
+    return fail(HT_ECAPACITY, "cache_len %d + %d rows exceeds max_cache %d", m->n, rows, c.max_cache);
+  hipStream_t s = (hipStream_t)stream;
+  Buffers& b = m->b;
+  int rc;
+  if (!tree_tokens) {
+    // draft: pseudo rows through blocks t+1..L as a chain at positions n, n+1, ..; their K/V land in
+    // slots n.. and are overwritten by the verify pass below
+    HT_HIP(launch_load_rows(b.pseudo, b.x, c.k, c.d_model, s));
+    if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, b.g, s))) return rc;
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, c.k, c.vocab, s));
+    HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
+  } else {
+    HT_HIP(hipMemcpyAsync(b.tok, tree_tokens, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));
+  }
+  HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
+  float* z = logits_out ? logits_out : b.logits;
+  if ((rc = run_pass(m, b.tree.dev(), T, 0, true, z, b.g, s))) return rc;
+  if (argmax_out) HT_HIP(hipMemcpyAsync(argmax_out, b.g, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));
+  m->verify_done = true;
+  m->transfer_ready = false;
+  return HT_OK;
+}
+
+int ht_accept_and_compact(ht_model* m, int32_t* n_accepted, int32_t* accepted_tokens, int32_t* next_root,
+                          int32_t* path_out, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!m->verify_done) return fail(HT_ESTATE, "ht_accept_and_compact must follow ht_tree_verify_step");
+  hipStream_t s = (hipStream_t)stream;
+  const ht_config& c = m->cfg;
+  Buffers& b = m->b;
+  HT_HIP(launch_accept(b.state, b.tree.dev(), b.tok, b.g, m->T, s));
+  HT_HIP(launch_compact(c.dtype, b.state, b.kc_ptrs, b.vc_ptrs, c.n_layers, m->n, c.n_kv_heads, c.head_dim, c.max_cache,
+                        b.saved_h, b.h_src, c.d_model, s));
+  HT_HIP(hipMemcpyAsync(m->h_state, b.state, sizeof(StepState), hipMemcpyDeviceToHost, s));
+  HT_HIP(hipStreamSynchronize(s));
+  const StepState& st = *m->h_state;
+  if (st.m < 1 || st.m > c.k + 1) return fail(HT_EHIP, "accept kernel returned an impossible count %d", st.m);
+  m->n += st.m;
+  m->verify_done = false;
+  if (n_accepted) *n_accepted = st.m;
+  if (next_root) *next_root = st.next_root;
+  for (int j = 0; j < st.m; ++j) {
+    if (accepted_tokens) accepted_tokens[j] = st.emitted[j];
+    if (path_out) path_out[j] = st.path[j];
+  }
+  return HT_OK;
+}
+
+int32_t ht_cache_len(const ht_model* m) { return m ? m->n : -1; }
+
+int ht_get_buffer(const ht_model* m, int32_t which, int32_t layer, void** dev_ptr, size_t* bytes) {
+  if (!m || !dev_ptr) return fail(HT_EINVAL, "NULL argument");
+  const ht_config& c = m->cfg;
+  const size_t es = elem_size(c.dtype);
+  void* p = nullptr;
+  size_t sz = 0;
+  switch (which) {
+    case HT_BUF_DRAFT_LOGITS: p = m->b.dlogits; sz = sizeof(float) * c.k * c.vocab; break;
+    case HT_BUF_CANDIDATES: p = m->b.cand; sz = sizeof(int32_t) * c.k * kMaxTopK; break;
+    case HT_BUF_TREE_TOKENS: p = m->b.tok; sz = sizeof(int32_t) * m->T; break;
+    case HT_BUF_SAVED_HIDDEN: p = m->b.saved_h; sz = sizeof(float) * m->T * c.d_model; break;
+    case HT_BUF_TRANSFER_SRC: p = m->b.h_src; sz = sizeof(float) * c.d_model; break;
+    case HT_BUF_PSEUDO: p = m->b.pseudo; sz = sizeof(float) * c.k * c.d_model; break;
+    case HT_BUF_ROOT: p = &m->b.state->root; sz = sizeof(int32_t); break;
+    case HT_BUF_K_CACHE:
+    case HT_BUF_V_CACHE:
+      if (layer < 0 || layer >= c.n_layers) return fail(HT_EINVAL, "layer %d out of range", layer);
+      p = which == HT_BUF_K_CACHE ? m->b.kc[layer] : m->b.vc[layer];
+      sz = (size_t)c.max_cache * c.n_kv_heads * c.head_dim * es;
+      break;
+    default: return fail(HT_EINVAL, "unknown buffer id %d", which);
+  }
+  *dev_ptr = p;
+  if (bytes) *bytes = sz;
+  return HT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ op level
+namespace {
+struct AttnScratch {
+  int32_t *parent, *depth, *rank;
+  uint64_t* anc;
+  float* cs;
+  void* q_rot;
+  void* mfma;
+  size_t total;
+};
+AttnScratch attn_scratch_layout(char* base, int T, int Hq, int hd, size_t es) {
+  Carver cv(base);
+  AttnScratch a;
+  a.parent = cv.take<int32_t>(kMaxTree);
+  a.depth = cv.take<int32_t>(kMaxTree);
+  a.rank = cv.take<int32_t>(kMaxTree);
+  a.anc = cv.take<uint64_t>((size_t)kMaxTree * kMaskWords);
+  a.cs = cv.take<float>((size_t)padded_rows(T) * hd);
+  a.q_rot = cv.take_bytes((size_t)padded_rows(T) * Hq * hd * es);
+  a.mfma = cv.take_bytes(attn_mfma_scratch_bytes(padded_rows(T), Hq, hd));
+  a.total = align_up(cv.off, 256);
+  return a;
+}
+int32_t* g_op_stage = nullptr;       // pinned staging for the op-level tree tables
+hipEvent_t g_op_event = nullptr;
+}  // namespace
+
+size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd) {
+  if (T < 1 || T > kMaxTree || Hq < 1 || hd < 2) return 0;
+  return attn_scratch_layout(nullptr, T, Hq, hd, 4).total;
+}
+
+int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache, int32_t cap,
+                      int32_t n, int32_t T, const int32_t* parent, int32_t Hq, int32_t Hkv, int32_t hd, int32_t dtype,
+                      float rope_base, void* out, void* scratch, size_t scratch_bytes, void* stream) {
+  if (!q || !k_cache || !v_cache || !parent || !out || !scratch) return fail(HT_EINVAL, "NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return fail(HT_EINVAL, "k_new and v_new must both be given or both be NULL");
+  if (dtype != HT_F32 && dtype != HT_BF16) return fail(HT_EINVAL, "bad dtype");
+  if (Hq < 1 || Hkv < 1 || Hq % Hkv || hd < 2 || hd % 2 || hd > 256) return fail(HT_EINVAL, "bad head shape");
+  if (n < 0 || cap < 8 || cap % 8) return fail(HT_EINVAL, "cap must be a positive multiple of 8 and n >= 0");
+  int rc = validate_tree(T, parent, nullptr, kMaxTree, kMaxTree);
+  if (rc) return rc;
+  if (n + T > cap) return fail(HT_ECAPACITY, "n + T = %d exceeds cap %d", n + T, cap);
+  if (scratch_bytes < ht_tree_attention_scratch_bytes(T, Hq, hd)) return fail(HT_EINVAL, "scratch too small");
+  if ((uintptr_t)scratch % 256) return fail(HT_EINVAL, "scratch must be 256-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  if (!g_op_stage) {
+    HT_HIP(hipHostMalloc((void**)&g_op_stage, sizeof(int32_t) * kTableInts, hipHostMallocDefault));
+    HT_HIP(hipEventCreateWithFlags(&g_op_event, hipEventDisableTiming));
+  } else {
+    HT_HIP(hipEventSynchronize(g_op_event));   // the previous call's upload must have left the staging buffer
+  }
+  fill_tables(T, parent, nullptr, g_op_stage);
+  AttnScratch a = attn_scratch_layout((char*)scratch, T, Hq, hd, elem_size(dtype));
+  TreeTables tt{a.parent, a.depth, a.rank, a.anc};
+  if ((rc = upload_tables(tt, g_op_stage, s))) return rc;
+  HT_HIP(hipEventRecord(g_op_event, s));
+  const void* qq = q;
+  if (k_new) {
+    HT_HIP(launch_rope_table(a.cs, a.depth, n, T, hd, rope_base, s));
+    HT_HIP(launch_rope_append_split(dtype, q, k_new, v_new, a.cs, a.q_rot, k_cache, v_cache, n, T, Hq, Hkv, hd, cap, s));
+    qq = a.q_rot;
+  }
+  const char* env = getenv("HT_FORCE_SIMPLE");
+  const bool simple = env && env[0] == '1';
+  if (dtype == HT_BF16 && !simple && attn_mfma_supported(T, Hq, Hkv, hd)) {
+    HT_HIP(launch_attn_mfma(qq, k_cache, v_cache, cap, n, T, tt.dev(), Hq, Hkv, hd, out, a.mfma, s));
+  } else {
+    HT_HIP(launch_attn_simple(dtype, qq, k_cache, v_cache, cap, n, T, tt.dev(), Hq, Hkv, hd, out, s));
+  }
+  return HT_OK;
+}
+
+size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  return align_up((size_t)kMaxSplitK * M * N * sizeof(float), 256);
+}
+
+int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K, int32_t dtype, float* out,
+                   void* scratch, size_t scratch_bytes, void* stream) {
+  if (!a || !w || !out) return fail(HT_EINVAL, "NULL argument");
+  if (dtype != HT_F32 && dtype != HT_BF16) return fail(HT_EINVAL, "bad dtype");
+  if (M < 1 || M > kMaxTree || N < 1 || K < 1) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  hipStream_t s = (hipStream_t)stream;
+  WeightSegs ws = segs1(w, N);
+  const char* env = getenv("HT_FORCE_SIMPLE");
+  const bool simple = env && env[0] == '1';
+  if (dtype == HT_BF16 && !simple && gemm_mfma_supported(M, N, K)) {
+    int sp = gemm_mfma_splits(M, N, K);
+    if (sp > 1 && (!scratch || scratch_bytes < (size_t)sp * M * N * sizeof(float))) sp = 1;
+    if (sp == 1) {
+      HT_HIP(launch_gemm_mfma(a, ws, M, N, K, out, 1, s));
+    } else {
+      HT_HIP(launch_gemm_mfma(a, ws, M, N, K, (float*)scratch, sp, s));
+      HT_HIP(launch_reduce_splits((const float*)scratch, sp, (size_t)M * N, out, s));
+    }
+  } else {
+    HT_HIP(launch_gemm_simple(dtype, a, ws, M, N, K, out, s));
+  }
+  return HT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Internal declarations shared by the HIP sources of libht (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace ht {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__host__ __device__ inline float bf16_to_float(bf16_t v) {
+  union { uint32_t u; float f; } c;
+  c.u = (uint32_t)v << 16;
+  return c.f;
+}
+// round-to-nearest-even; NaN stays NaN
+__host__ __device__ inline bf16_t float_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40u);
+  c.u += 0x7fffu + ((c.u >> 16) & 1u);
+  return (bf16_t)(c.u >> 16);
+}
+
+template <typename T> struct Conv;
+template <> struct Conv<float> {
+  __device__ static inline float load(const float* p) { return *p; }
+  __device__ static inline void store(float* p, float v) { *p = v; }
+};
+template <> struct Conv<bf16_t> {
+  __device__ static inline float load(const bf16_t* p) { return bf16_to_float(*p); }
+  __device__ static inline void store(bf16_t* p, float v) { *p = float_to_bf16(v); }
+};
+
+constexpr int kMaxTree = 128;            // rows per pass (tree nodes, prefill chunk, pseudo rows)
+constexpr int kMaskWords = kMaxTree / 64;
+constexpr int kMaxTopK = 64;
+constexpr int kMaxTransfer = 8;
+constexpr int kMaxSplitK = 8;
+
+// Tree tables as the kernels see them (device pointers).
+struct TreeDev {
+  const int32_t* parent;     // [T]
+  const int32_t* depth;      // [T]
+  const int32_t* rank;       // [T]
+  const uint64_t* anc;       // [T][kMaskWords] bit u set iff u is ancestor-or-self
+};
+
+// Device-resident decoder state written by the accept kernel and read back by the host.
+struct StepState {
+  int32_t root;                              // pending root token
+  int32_t m;                                 // accepted count of the last step
+  int32_t next_root;
+  int32_t path[kMaxTransfer + 1];
+  int32_t emitted[kMaxTransfer + 1];
+  int32_t pad[4];
+};
+
+// One weight operand made of up to three row segments sharing K (Wq|Wk|Wv, Wgate|Wup).
+struct WeightSegs {
+  const void* w[3];
+  int32_t rows[3];
+  int32_t nseg;
+};
+
+// ------------------------------------------------------------------------------------------------
+// launchers (definitions in the .hip files); all enqueue on `s` and return the launch status
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_embed(int dtype, const void* emb, const int32_t* tok, float* x, int M, int d, hipStream_t s);
+hipError_t launch_load_rows(const float* src, float* x, int M, int d, hipStream_t s);
+// x[m] += sum_s part[s][m]; optional save; u[m] = rmsnorm(x[m]) * gain
+hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
+                           void* u, float* save_h, int M, int d, float eps, hipStream_t s);
+hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s);
+hipError_t launch_rope_append(int dtype, const float* qkv, const float* cs, void* q, void* kc, void* vc, int n, int M,
+                              int Hq, int Hkv, int hd, int cap, hipStream_t s);
+hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
+                                    void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
+                                    hipStream_t s);
+hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int M, int f, hipStream_t s);
+hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s);
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int k, int V, hipStream_t s);
+hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
+hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s);
+hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
+                          int hd, int cap, const float* saved_h, float* h_src, int d, hipStream_t s);
+hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, float* h_src, int last, int d,
+                                 hipStream_t s);
+hipError_t launch_transfer(int dtype, const float* h, const void* const* w_dev, float* pseudo, int k, int d,
+                           hipStream_t s);
+hipError_t launch_convert_to_f32(int dtype, const void* src, float* dst, int n, hipStream_t s);
+// out[i] = sum_s part[s][i] in the fixed order s = 0, 1, ..
+hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, float* out, hipStream_t s);
+
+// generic (any dtype, any shape) product: out[s=0][m][n] = sum_k a[m][k] w[n][k]
+hipError_t launch_gemm_simple(int dtype, const void* a, WeightSegs w, int M, int N, int K, float* out, hipStream_t s);
+// bf16 MFMA product with optional split-K: out[s][m][n]; returns the number of splits used in *nsplit
+bool gemm_mfma_supported(int M, int N, int K);
+int gemm_mfma_splits(int M, int N, int K);
+hipError_t launch_gemm_mfma(const void* a, WeightSegs w, int M, int N, int K, float* out, int nsplit, hipStream_t s);
+
+// attention over cache + tree rows; out[m][h*hd+e] in dtype
+hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,
+                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s);
+bool attn_mfma_supported(int M, int Hq, int Hkv, int hd);
+size_t attn_mfma_scratch_bytes(int M, int Hq, int hd);
+hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
+                            int Hkv, int hd, void* out, void* scratch, hipStream_t s);
+
+}  // namespace ht

@@ -1,0 +1,473 @@
+// Row-wise and integer kernels of the tree-verify step, plus dtype-generic reference-grade
+// products and attention used by the fp32 model path (the bf16 hot path uses the MFMA kernels).
+#include "ht_common.h"
+
+namespace ht {
+
+#define HT_DISPATCH_DTYPE(dtype, ...)                       \
+  if ((dtype) == 0) { typedef float T; __VA_ARGS__ }        \
+  else { typedef bf16_t T; __VA_ARGS__ }
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// block-wide sum for 256-thread blocks; `red` is __shared__ float[4]
+__device__ inline float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__device__ inline float block_max_256(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// ------------------------------------------------------------------------------------------------ embed
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tok, float* __restrict__ x, int d) {
+  const int m = blockIdx.x;
+  const T* row = emb + (size_t)tok[m] * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) x[(size_t)m * d + c] = Conv<T>::load(row + c);
+}
+hipError_t launch_embed(int dtype, const void* emb, const int32_t* tok, float* x, int M, int d, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, s, (const T*)emb, tok, x, d);)
+  return hipGetLastError();
+}
+
+__global__ void copy_rows_kernel(const float* __restrict__ src, float* __restrict__ dst, size_t count) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = src[i];
+}
+hipError_t launch_load_rows(const float* src, float* x, int M, int d, hipStream_t s) {
+  size_t count = (size_t)M * d;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, src, x, count);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void convert_to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = Conv<T>::load(src + i);
+}
+hipError_t launch_convert_to_f32(int dtype, const void* src, float* dst, int n, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(convert_to_f32_kernel<T>, dim3((n + 255) / 256), dim3(256), 0, s,
+                                              (const T*)src, dst, n);)
+  return hipGetLastError();
+}
+
+__global__ void reduce_splits_kernel(const float* __restrict__ part, int nsplit, size_t stride, float* __restrict__ out) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= stride) return;
+  float v = part[i];
+  for (int sp = 1; sp < nsplit; ++sp) v += part[sp * stride + i];
+  out[i] = v;
+}
+hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((stride + 255) / 256)), dim3(256), 0, s, part, nsplit, stride, out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ residual + RMSNorm
+// x[m] += sum over split-K partials of the previous projection (fixed order: deterministic), the
+// updated residual is optionally saved (layer-t hidden states), then u[m] = x[m] * rsqrt(mean(x^2)+eps) * gain.
+template <typename T>
+__global__ void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit, size_t part_stride,
+                                const T* __restrict__ gain, T* __restrict__ u, float* __restrict__ save_h, int d,
+                                float eps) {
+  __shared__ float red[4];
+  const int m = blockIdx.x;
+  float* xr = x + (size_t)m * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float v = xr[c];
+    for (int sp = 0; sp < nsplit; ++sp) v += part[sp * part_stride + (size_t)m * d + c];
+    if (nsplit) xr[c] = v;
+    if (save_h) save_h[(size_t)m * d + c] = v;
+    ss += v * v;
+  }
+  ss = block_sum_256(ss, red);
+  const float scale = 1.0f / sqrtf(ss / (float)d + eps);
+  if (u) {
+    for (int c = threadIdx.x; c < d; c += 256)
+      Conv<T>::store(u + (size_t)m * d + c, xr[c] * scale * Conv<T>::load(gain + c));
+  }
+}
+hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
+                           void* u, float* save_h, int M, int d, float eps, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(add_norm_kernel<T>, dim3(M), dim3(256), 0, s, x, part, nsplit,
+                                              part_stride, (const T*)gain, (T*)u, save_h, d, eps);)
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ rotary
+// cs[m][j] = (cos, sin) of (n + depth[m]) * base^(-2j/hd), evaluated in fp64 and rounded once.
+__global__ void rope_table_kernel(float2* __restrict__ cs, const int32_t* __restrict__ depth, int n, int half,
+                                  float base) {
+  const int m = blockIdx.x;
+  const int j = threadIdx.x;
+  if (j >= half) return;
+  const double pos = (double)(n + depth[m]);
+  const double inv = exp(-(2.0 * (double)j / (double)(2 * half)) * log((double)base));
+  double sn, cn;
+  sincos(pos * inv, &sn, &cn);
+  cs[(size_t)m * half + j] = make_float2((float)cn, (float)sn);
+}
+hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s) {
+  hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(hd / 2), 0, s, (float2*)cs, depth, n, hd / 2, base);
+  return hipGetLastError();
+}
+
+// Rotates q and k of row m at its tree position and appends k, v to cache slot n+m.
+// Layouts: q[M][Hq][hd]; K cache [cap][Hkv][hd]; V cache [Hkv][hd][cap] (key index contiguous).
+template <typename T, typename TIN>
+__global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in,
+                                   int k_stride, const TIN* __restrict__ v_in, int v_stride,
+                                   const float2* __restrict__ cs, T* __restrict__ q, T* __restrict__ kc,
+                                   T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap) {
+  const int m = blockIdx.x, hh = blockIdx.y, j = threadIdx.x, half = hd / 2;
+  if (j >= half) return;
+  const float2 c = cs[(size_t)m * half + j];
+  if (hh < Hq + Hkv) {
+    const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
+                             : k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd;
+    const float a = Conv<TIN>::load(src + j), b = Conv<TIN>::load(src + j + half);
+    const float ra = a * c.x - b * c.y, rb = b * c.x + a * c.y;
+    T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
+    Conv<T>::store(dst + j, ra);
+    Conv<T>::store(dst + j + half, rb);
+  } else {
+    const int h = hh - Hq - Hkv;
+    const TIN* src = v_in + (size_t)m * v_stride + (size_t)h * hd;
+    Conv<T>::store(vc + ((size_t)h * hd + j) * cap + n + m, Conv<TIN>::load(src + j));
+    Conv<T>::store(vc + ((size_t)h * hd + j + half) * cap + n + m, Conv<TIN>::load(src + j + half));
+  }
+}
+hipError_t launch_rope_append(int dtype, const float* qkv, const float* cs, void* q, void* kc, void* vc, int n, int M,
+                              int Hq, int Hkv, int hd, int cap, hipStream_t s) {
+  const int stride = (Hq + 2 * Hkv) * hd;
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
+                                              s, qkv, stride, qkv + (size_t)Hq * hd, stride,
+                                              qkv + (size_t)(Hq + Hkv) * hd, stride, (const float2*)cs, (T*)q, (T*)kc,
+                                              (T*)vc, n, Hq, Hkv, hd, cap);)
+  return hipGetLastError();
+}
+hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
+                                    void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
+                                    hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
+                                              (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
+                                              Hkv * hd, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,
+                                              cap);)
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ SwiGLU gate
+template <typename T>
+__global__ void silu_mul_kernel(const float* __restrict__ gu, T* __restrict__ act, int f) {
+  const int m = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= f) return;
+  const float g = gu[(size_t)m * 2 * f + j], up = gu[(size_t)m * 2 * f + f + j];
+  Conv<T>::store(act + (size_t)m * f + j, g / (1.0f + expf(-g)) * up);
+}
+hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int M, int f, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(silu_mul_kernel<T>, dim3((f + 255) / 256, M), dim3(256), 0, s, gu,
+                                              (T*)act, f);)
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ argmax / top-k
+// (value, id) order: larger value first, lower id first on equal values.  NaN never wins.
+__device__ inline bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+__device__ inline void block_best_256(float& v, int& i, float* sv, int* si) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(v, o, 64);
+    int oi = __shfl_xor(i, o, 64);
+    if (better(ov, oi, v, i)) { v = ov; i = oi; }
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = v; si[threadIdx.x >> 6] = i; }
+  __syncthreads();
+  v = sv[0]; i = si[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w)
+    if (better(sv[w], si[w], v, i)) { v = sv[w]; i = si[w]; }
+}
+
+__global__ void argmax_kernel(const float* __restrict__ z, int32_t* __restrict__ g, int V) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const float* row = z + (size_t)blockIdx.x * V;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int j = threadIdx.x; j < V; j += 256) {
+    float v = row[j];
+    if (better(v, j, bv, bi)) { bv = v; bi = j; }
+  }
+  block_best_256(bv, bi, sv, si);
+  if (threadIdx.x == 0) g[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
+}
+hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s) {
+  hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, z, g, V);
+  return hipGetLastError();
+}
+
+// cand[i][r], r < width[i+1]: the r-th entry of logit row i in (value desc, id asc) order.  Selection
+// by repeated arg-best over the entries that come strictly after the previous pick in that order.
+__global__ void topk_kernel(const float* __restrict__ d, int32_t* __restrict__ cand, const int32_t* __restrict__ width,
+                            int V) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int i = blockIdx.x;
+  const float* row = d + (size_t)i * V;
+  const int b = width[i + 1];
+  float pv = INFINITY;
+  int pi = -1;
+  for (int r = 0; r < b; ++r) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = threadIdx.x; j < V; j += 256) {
+      float v = row[j];
+      bool after = r == 0 || v < pv || (v == pv && j > pi);
+      if (after && better(v, j, bv, bi)) { bv = v; bi = j; }
+    }
+    block_best_256(bv, bi, sv, si);
+    if (bi == 0x7fffffff) bi = 0;
+    if (threadIdx.x == 0) cand[i * kMaxTopK + r] = bi;
+    pv = bv; pi = bi;
+    __syncthreads();
+  }
+}
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int k, int V, hipStream_t s) {
+  hipLaunchKernelGGL(topk_kernel, dim3(k), dim3(256), 0, s, d, cand, width, V);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ tree build / accept / compact
+__global__ void tree_build_kernel(const StepState* __restrict__ st, const int32_t* __restrict__ cand, TreeDev tree,
+                                  int32_t* __restrict__ tok, int T) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= T) return;
+  tok[v] = v == 0 ? st->root : cand[(tree.depth[v] - 1) * kMaxTopK + tree.rank[v]];
+}
+hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(tree_build_kernel, dim3((T + 63) / 64), dim3(64), 0, s, st, cand, tree, tok, T);
+  return hipGetLastError();
+}
+
+// One wavefront: each round, every lane tests a slice of the nodes for "child of cur carrying the
+// greedy token after cur" and the lowest such node index wins.
+__global__ void accept_kernel(StepState* __restrict__ st, TreeDev tree, const int32_t* __restrict__ tok,
+                              const int32_t* __restrict__ g, int T) {
+  const int lane = threadIdx.x;
+  int cur = 0, m = 1;
+  if (lane == 0) { st->path[0] = 0; st->emitted[0] = tok[0]; }
+  while (m < kMaxTransfer + 1) {
+    const int want = g[cur];
+    int best = 0x7fffffff;
+    for (int c = cur + 1 + lane; c < T; c += 64)
+      if (tree.parent[c] == cur && tok[c] == want) { best = c; break; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o, 64));
+    if (best == 0x7fffffff) break;
+    if (lane == 0) { st->path[m] = best; st->emitted[m] = tok[best]; }
+    cur = best;
+    ++m;
+  }
+  if (lane == 0) { st->m = m; st->next_root = g[cur]; st->root = g[cur]; }
+}
+hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s) {
+  hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, st, tree, tok, g, T);
+  return hipGetLastError();
+}
+
+// Moves the accepted rows to slots n..n+m-1 (ascending j; path[j] >= j so in place is safe) and makes
+// the last accepted node's saved residual the next transfer source.  blockIdx.y = layer.
+template <typename T>
+__global__ void compact_kernel(const StepState* __restrict__ st, void* const* __restrict__ kcs,
+                               void* const* __restrict__ vcs, int n, int row_elems, int cap,
+                               const float* __restrict__ saved_h, float* __restrict__ h_src, int d) {
+  const int layer = blockIdx.y;
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  const int m = st->m;
+  if (e < row_elems) {
+    T* kc = (T*)kcs[layer];
+    T* vc = (T*)vcs[layer];
+    for (int j = 0; j < m; ++j) {
+      const int src = st->path[j];
+      if (src == j) continue;
+      kc[(size_t)(n + j) * row_elems + e] = kc[(size_t)(n + src) * row_elems + e];
+      vc[(size_t)e * cap + n + j] = vc[(size_t)e * cap + n + src];
+    }
+  }
+  if (layer == 0 && e < d) h_src[e] = saved_h[(size_t)st->path[m - 1] * d + e];
+}
+hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
+                          int hd, int cap, const float* saved_h, float* h_src, int d, hipStream_t s) {
+  const int row = Hkv * hd;
+  const int cols = row > d ? row : d;
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(compact_kernel<T>, dim3((cols + 255) / 256, L), dim3(256), 0, s, st, kc,
+                                              vc, n, row, cap, saved_h, h_src, d);)
+  return hipGetLastError();
+}
+
+__global__ void prefill_finish_kernel(StepState* __restrict__ st, const int32_t* __restrict__ g,
+                                      const float* __restrict__ saved_h, float* __restrict__ h_src, int last, int d) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < d) h_src[e] = saved_h[(size_t)last * d + e];
+  if (e == 0) { st->root = g[last]; st->next_root = g[last]; st->m = 0; }
+}
+hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, float* h_src, int last, int d,
+                                 hipStream_t s) {
+  hipLaunchKernelGGL(prefill_finish_kernel, dim3((d + 255) / 256), dim3(256), 0, s, st, g, saved_h, h_src, last, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ hidden transfer
+// pseudo[i][o] = sum_c W_i[o][c] h[c].  One wavefront per output feature; the weight row is read
+// once, fully coalesced (16 bytes per lane), h stays in L2.  grid = (d / 4, k), block = 256.
+template <typename T>
+__global__ void transfer_kernel(const float* __restrict__ h, const void* const* __restrict__ ws,
+                                float* __restrict__ pseudo, int d) {
+  const int i = blockIdx.y;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (o >= d) return;
+  const T* row = (const T*)ws[i] + (size_t)o * d;
+  float acc = 0.f;
+  constexpr int VEC = 16 / sizeof(T);
+  for (int c = lane * VEC; c < d; c += 64 * VEC) {
+    if (c + VEC <= d) {
+      const uint4 raw = *(const uint4*)(row + c);
+      const T* v = (const T*)&raw;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc += Conv<T>::load(v + e) * h[c + e];
+    } else {
+      for (int e = 0; c + e < d; ++e) acc += Conv<T>::load(row + c + e) * h[c + e];
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) pseudo[(size_t)i * d + o] = acc;
+}
+hipError_t launch_transfer(int dtype, const float* h, const void* const* w_dev, float* pseudo, int k, int d,
+                           hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(transfer_kernel<T>, dim3((d + 3) / 4, k), dim3(256), 0, s, h, w_dev,
+                                              pseudo, d);)
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ generic product
+// out[m][n] = sum_k a[m][k] w[n][k], fp32 accumulation.  One wavefront per output feature n, rows in
+// groups of 4.  Used by the fp32 model path and as the fallback for shapes the MFMA kernel rejects.
+template <typename T>
+__global__ void gemm_simple_kernel(const T* __restrict__ a, WeightSegs w, int M, int N, int K, float* __restrict__ out) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (n >= N) return;
+  int seg = 0, local = n;
+  while (seg + 1 < w.nseg && local >= w.rows[seg]) { local -= w.rows[seg]; ++seg; }
+  const T* row = (const T*)w.w[seg] + (size_t)local * K;
+  for (int m0 = 0; m0 < M; m0 += 4) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = lane; c < K; c += 64) {
+      const float wv = Conv<T>::load(row + c);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (m0 + r < M) acc[r] += wv * Conv<T>::load(a + (size_t)(m0 + r) * K + c);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float v = wave_sum(acc[r]);
+      if (lane == 0 && m0 + r < M) out[(size_t)(m0 + r) * N + n] = v;
+    }
+  }
+}
+hipError_t launch_gemm_simple(int dtype, const void* a, WeightSegs w, int M, int N, int K, float* out, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(gemm_simple_kernel<T>, dim3((N + 3) / 4), dim3(256), 0, s, (const T*)a,
+                                              w, M, N, K, out);)
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ generic attention
+// One block per (query head, tree row).  Scores of all visible keys go to LDS, softmax in fp32, then
+// every thread owns one (output element, key residue class).  Dynamic LDS: (n + M) floats + hd + 256.
+template <typename T>
+__global__ void attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc, int cap,
+                                   int n, int M, TreeDev tree, int Hq, int Hkv, int hd, T* __restrict__ out) {
+  extern __shared__ float smem[];
+  __shared__ float red[4];
+  const int h = blockIdx.x, m = blockIdx.y, hk = h / (Hq / Hkv), tid = threadIdx.x;
+  const int S = n + M;
+  float* sc = smem;            // [S]
+  float* qs = smem + S;        // [hd]
+  float* acc = qs + hd;        // [256]
+  for (int e = tid; e < hd; e += 256) qs[e] = Conv<T>::load(q + ((size_t)m * Hq + h) * hd + e);
+  __syncthreads();
+  const float scale = 1.0f / sqrtf((float)hd);
+  float mx = -INFINITY;
+  for (int j = tid; j < S; j += 256) {
+    bool vis = j < n;
+    if (!vis) {
+      const int u = j - n;
+      vis = (tree.anc[(size_t)m * kMaskWords + (u >> 6)] >> (u & 63)) & 1ull;
+    }
+    float s = -INFINITY;
+    if (vis) {
+      const T* kr = kc + ((size_t)j * Hkv + hk) * hd;
+      float dot = 0.f;
+      for (int e = 0; e < hd; ++e) dot += qs[e] * Conv<T>::load(kr + e);
+      s = dot * scale;
+    }
+    sc[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = block_max_256(mx, red);
+  float sum = 0.f;
+  for (int j = tid; j < S; j += 256) {
+    const float p = sc[j] == -INFINITY ? 0.f : expf(sc[j] - mx);
+    sc[j] = p;
+    sum += p;
+  }
+  sum = block_sum_256(sum, red);
+  const int groups = 256 / hd > 0 ? 256 / hd : 1;      // hd <= 256
+  const int e = tid % hd, part = tid / hd;
+  float o = 0.f;
+  if (part < groups) {
+    const T* vr = vc + ((size_t)hk * hd + e) * cap;
+    for (int j = part; j < S; j += groups)
+      if (sc[j] != 0.f) o += sc[j] * Conv<T>::load(vr + j);
+  }
+  acc[tid] = o;
+  __syncthreads();
+  if (tid < hd) {
+    float t = 0.f;
+    for (int p = 0; p < groups; ++p) t += acc[p * hd + tid];
+    Conv<T>::store(out + (size_t)m * Hq * hd + (size_t)h * hd + tid, t / sum);
+  }
+}
+hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,
+                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s) {
+  const size_t smem = (size_t)(n + M + hd + 256) * sizeof(float);
+  if (smem > 64 * 1024 || hd > 256) return hipErrorInvalidValue;
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(attn_simple_kernel<T>, dim3(Hq, M), dim3(256), smem, s, (const T*)q,
+                                              (const T*)kc, (const T*)vc, cap, n, M, tree, Hq, Hkv, hd, (T*)out);)
+  return hipGetLastError();
+}
+
+}  // namespace ht

@@ -1,0 +1,138 @@
+"""GPU-side glue for the parity tests: builds an HTModel for a workload and runs the step-by-step
+comparison of the HIP path against the oracle.  Imported only by tests marked `gpu`."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from ht_inputs import make_weights, prune_tree
+from oracle import ht_oracle as O
+from helpers import torch_dtype, oracle_model, oracle_decoder, prompt_of, tree_of
+
+import paper_2404_12022_amd.binding as B
+
+DEV = "cuda:0"
+
+FP32_LOGIT_TOL = 1e-4          # max-abs, fp32 model
+BF16_REL_TOL = 3e-2            # bf16 model: per row, max|a-b| <= tol * max|b| and ||a-b|| <= tol * ||b||
+
+
+def within_bf16(got: np.ndarray, want: np.ndarray, tol=BF16_REL_TOL):
+    """bf16 criterion, per row (last axis): max-abs error <= tol * max-abs reference, and relative L2 error <= tol.
+    Returns (ok, worst error / bound)."""
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - want)
+    peak = np.max(np.abs(want), axis=-1)
+    l2 = np.sqrt(np.sum(want * want, axis=-1))
+    r1 = np.max(err, axis=-1) / (tol * peak)
+    r2 = np.sqrt(np.sum(err * err, axis=-1)) / (tol * l2)
+    worst = float(max(np.max(r1), np.max(r2)))
+    return worst <= 1.0, worst
+
+
+def assert_close(got, want, dtype: str, what: str, tol=None):
+    """Returns the max-abs error (fp32) or the worst error/bound ratio (bf16)."""
+    got = np.asarray(got, dtype=np.float64)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values from the GPU"
+    if dtype == "f32":
+        err = float(np.max(np.abs(got - want)))
+        assert err <= (tol or FP32_LOGIT_TOL), f"{what}: max-abs error {err:.3e}"
+        return err
+    else:
+        ok, worst = within_bf16(got, want, tol or BF16_REL_TOL)
+        assert ok, f"{what}: worst error is {worst:.2f}x the bf16 bound"
+        return worst
+
+
+def gpu_model(wl, tensors=None, max_tree=None):
+    tensors = tensors or make_weights(wl, wl.seed, DEV, torch_dtype(wl))
+    cfg = B.make_config(wl, max_tree=max_tree)
+    return B.HTModel(cfg, tensors, DEV)
+
+
+def cpu(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class StepCompare:
+    """Runs oracle and HIP path side by side, one decode step at a time."""
+
+    def __init__(self, wl, tensors_gpu=None, tensors_cpu=None, tree=None, prompt=None):
+        self.wl = wl
+        self.model = oracle_model(wl, tensors_cpu)
+        self.parent, self.rank = tree or tree_of(wl)
+        self.ora = O.HiddenTransferOracle(self.model, self.parent, self.rank, wl.max_cache)
+        self.gpu = gpu_model(wl, tensors_gpu, max_tree=max(len(self.parent), 1))
+        self.gpu.ht_set_tree(self.parent, self.rank)
+        self.prompt = prompt or prompt_of(wl)
+        self.ora.prefill(self.prompt)
+        self.gpu.ht_prefill(self.prompt)
+        self.T = len(self.parent)
+        self.z_gpu = torch.empty(self.T, wl.vocab, dtype=torch.float32, device=DEV)
+        self.g_gpu = torch.empty(self.T, dtype=torch.int32, device=DEV)
+        self.min_margin = float("inf")
+        self.max_err = 0.0          # largest logit error seen (fp32: absolute; bf16: fraction of the bound)
+
+    def check_prefill(self):
+        wl = self.wl
+        assert self.gpu.ht_cache_len() == len(self.prompt) == self.ora.n
+        root = int(self.gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item())
+        assert root == self.ora.root
+        h = cpu(self.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC))
+        assert_close(h, self.ora.h_src[wl.transfer_layers[0]], wl.dtype, "prefill transfer source", tol=None if wl.dtype != "f32" else 1e-4)
+        self.check_cache("prefill")
+
+    def check_cache(self, what):
+        wl, n = self.wl, self.ora.n
+        for layer in (0, wl.n_layers - 1):
+            kc = cpu(self.gpu.ht_get_buffer(B.HT_BUF_K_CACHE, layer))[:n]
+            vc = cpu(self.gpu.ht_get_buffer(B.HT_BUF_V_CACHE, layer))[:, :, :n]
+            assert_close(kc, self.ora.K[layer][:n], wl.dtype, f"{what}: K cache layer {layer}")
+            assert_close(np.transpose(vc, (2, 0, 1)), self.ora.V[layer][:n], wl.dtype, f"{what}: V cache layer {layer}")
+
+    def step(self, forced=None, require_same_tokens=True):
+        wl, ora, gpu = self.wl, self.ora, self.gpu
+        res = ora.step(forced_tokens=forced)
+        if forced is None:
+            pseudo = torch.empty(wl.k, wl.d_model, dtype=torch.float32, device=DEV)
+            gpu.ht_transfer(None, pseudo)
+            gpu.ht_tree_verify_step(None, self.g_gpu, self.z_gpu)
+        else:
+            gpu.ht_tree_verify_step(torch.tensor(forced, dtype=torch.int32, device=DEV), self.g_gpu, self.z_gpu)
+        torch.cuda.synchronize()
+        tok_gpu = [int(t) for t in gpu.ht_get_buffer(B.HT_BUF_TREE_TOKENS).cpu()]
+        z = cpu(self.z_gpu)
+        g = [int(t) for t in self.g_gpu.cpu()]
+        if forced is None:
+            assert_close(cpu(pseudo), np.stack(res["pseudo"]), wl.dtype, "pseudo hidden states")
+            d = cpu(gpu.ht_get_buffer(B.HT_BUF_DRAFT_LOGITS))
+            self.max_err = max(self.max_err, assert_close(d, res["D"], wl.dtype, "draft logits"))
+            cand = gpu.ht_get_buffer(B.HT_BUF_CANDIDATES).cpu().numpy()
+            # integer stages: the oracle's rules applied to the GPU's own logits must give the GPU's integers
+            want_cand = [[]] + [O.top_candidates(d[e - 1], ora.width[e]) for e in range(1, len(ora.width))]
+            for e in range(1, len(ora.width)):
+                assert list(cand[e - 1][:ora.width[e]]) == want_cand[e], f"top-k at depth {e}"
+            root = res["tok"][0]
+            want_tok = [root] + [want_cand[ora.depth[v]][ora.rank[v]] for v in range(1, self.T)]
+            assert tok_gpu == want_tok, "tree build"
+            for e in range(1, len(ora.width)):           # margin of the oracle's own candidate order
+                srt = np.sort(res["D"][e - 1])[::-1][:ora.width[e] + 1]
+                self.min_margin = min(self.min_margin, float(np.min(srt[:-1] - srt[1:])))
+        else:
+            assert tok_gpu == list(forced)
+        if require_same_tokens:
+            assert tok_gpu == res["tok"], "tree tokens differ from the fp64 oracle"
+        if tok_gpu == res["tok"]:
+            self.max_err = max(self.max_err, assert_close(z, res["Z"], wl.dtype, "verify logits"))
+        assert g == [int(j) for j in np.argmax(z, axis=1)], "row arg-max of the GPU's own logits"
+        top2 = np.sort(res["Z"], axis=1)[:, -2:]
+        self.min_margin = min(self.min_margin, float(np.min(top2[:, 1] - top2[:, 0])))
+        m, emitted, root, path = gpu.ht_accept_and_compact()
+        want_path, want_root = O.accept_walk(self.parent, tok_gpu, g)
+        assert (path, root, m) == (want_path, want_root, len(want_path)), "acceptance walk on the GPU's own integers"
+        assert emitted == [tok_gpu[v] for v in path]
+        if require_same_tokens:
+            assert (path, emitted, root) == (res["path"], res["emitted"], res["root"])
+            assert gpu.ht_cache_len() == ora.n
+        return dict(oracle=res, emitted=emitted, path=path, root=root, m=m)

@@ -1,0 +1,295 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI.  Needs a real MI355X.
+
+Tolerances: fp32 model logits max-abs <= 1e-4; bf16, per row: max-abs error <= 3e-2 * max|reference| and
+relative L2 error <= 3e-2.
+Integer stages (top-k, tree tokens, arg-max, acceptance path, accepted count) are compared bit-exactly
+against the oracle's rules applied to the GPU's own logits, and on the fp32 model also against the
+fp64 oracle's integers, with the smallest logit margin of the run asserted to be far above tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from ht_inputs import WORKLOADS, make_weights, counter_normal, random_tree, chain_tree, star_tree, prune_tree
+from ht_inputs.workloads import ATTENTION_OP
+from oracle import ht_oracle as O
+from helpers import torch_dtype, oracle_model, prompt_of, tree_of, small_workload
+
+
+def _B():
+    import paper_2404_12022_amd.binding as B
+    return B
+
+
+def _H():
+    import gpu_harness as H
+    return H
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ inputs
+def test_generators_give_the_same_bits_on_the_gpu():
+    for dt in (torch.float32, torch.bfloat16):
+        a = counter_normal(7, 1001, (300, 129), 0.02, device="cpu", dtype=dt)
+        b = counter_normal(7, 1001, (300, 129), 0.02, device="cuda:0", dtype=dt)
+        assert torch.equal(a, b.cpu())
+    g = counter_normal(7, 2, (4096,), 0.02, mean=1.0, device="cuda:0")
+    assert torch.equal(g.cpu(), counter_normal(7, 2, (4096,), 0.02, mean=1.0))
+
+
+# ------------------------------------------------------------------ skinny product, op level
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (3, 208, 200), (8, 1024, 256), (16, 768, 688), (17, 4096, 1024),
+                                   (64, 8192, 512), (64, 1024, 4096), (100, 256, 11008), (128, 12288, 128)])
+def test_skinny_product_matches_textbook_product(dtype, M, N, K):
+    B, H = _B(), _H()
+    say(f"gemm {dtype} M={M} N={N} K={K}")
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    Mp = B.ht_padded_rows(M)
+    a = torch.zeros(Mp, K, dtype=tdt, device=H.DEV)
+    a[:M] = counter_normal(1, 11, (M, K), 1.0, device=H.DEV, dtype=tdt)
+    w = counter_normal(1, 12, (N, K), 0.05, device=H.DEV, dtype=tdt)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device=H.DEV)
+    scratch = torch.empty(B.ht_skinny_gemm_scratch_bytes(M, N, K), dtype=torch.uint8, device=H.DEV)
+    B.ht_skinny_gemm(a, w, M, N, K, B.HT_F32 if dtype == "f32" else B.HT_BF16, out, scratch)
+    torch.cuda.synchronize()
+    want = O.linear(H.cpu(a[:M]), H.cpu(w))
+    got = H.cpu(out)
+    assert np.all(np.isfinite(got))
+    # inputs are exact in both paths; only fp32 accumulation order differs
+    bound = 2e-5 * np.sqrt(K) * np.abs(H.cpu(a[:M])).max() * 0.05 * 8 + 1e-6
+    assert np.max(np.abs(got - want)) <= bound, (np.max(np.abs(got - want)), bound)
+
+
+# ------------------------------------------------------------------ tree attention, op level
+def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=True, base=10000.0):
+    B, H = _B(), _H()
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    cap = cap or ((n + T + 7) // 8 * 8)
+    q = counter_normal(seed, 21, (T, Hq, hd), 1.0, device=H.DEV, dtype=tdt)
+    kc = counter_normal(seed, 22, (cap, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
+    vc = counter_normal(seed, 23, (Hkv, hd, cap), 1.0, device=H.DEV, dtype=tdt)
+    kn = counter_normal(seed, 24, (T, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
+    vn = counter_normal(seed, 25, (T, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
+    out = torch.full((T, Hq * hd), float("nan"), dtype=tdt, device=H.DEV)
+    scratch = torch.empty(B.ht_tree_attention_scratch_bytes(T, Hq, hd), dtype=torch.uint8, device=H.DEV)
+    depth = O.tree_depth(parent)
+    pos = np.array([n + e for e in depth])
+    k_old = H.cpu(kc)[:n]
+    v_old = np.transpose(H.cpu(vc), (2, 0, 1))[:n]
+    if rotate:
+        B.ht_tree_attention(q, kn, vn, kc, vc, cap, n, T, parent, Hq, Hkv, hd, B.HT_F32 if dtype == "f32" else B.HT_BF16,
+                            base, out, scratch)
+        qq, kk, vv = O.rope(H.cpu(q), pos, base), O.rope(H.cpu(kn), pos, base), H.cpu(vn)
+    else:
+        kc[n:n + T] = kn
+        vc[:, :, n:n + T] = vn.permute(1, 2, 0)
+        B.ht_tree_attention(q, None, None, kc, vc, cap, n, T, parent, Hq, Hkv, hd,
+                            B.HT_F32 if dtype == "f32" else B.HT_BF16, base, out, scratch)
+        qq, kk, vv = H.cpu(q), H.cpu(kn), H.cpu(vn)
+    torch.cuda.synchronize()
+    vis = np.concatenate([np.ones((T, n), dtype=bool), O.ancestor_matrix(parent)], axis=1)
+    want = O.masked_attention(qq, np.concatenate([k_old, kk]), np.concatenate([v_old, vv]), vis).reshape(T, Hq * hd)
+    got = H.cpu(out)
+    assert np.all(np.isfinite(got))
+    if dtype == "f32":
+        assert np.max(np.abs(got - want)) <= 2e-5, np.max(np.abs(got - want))
+    else:
+        # bf16: rotated q/k and the output are rounded to bf16 (2^-9 relative each); scores of size ~sqrt(hd)
+        # move the softmax weights by up to ~2e-2, values are O(1)
+        ok, worst = H.within_bf16(got, want, 3e-2)
+        assert ok, worst
+    if rotate:                                      # appended rows landed in slots n..n+T-1
+        assert_k = H.cpu(kc)[n:n + T]
+        if dtype == "f32":
+            assert np.max(np.abs(assert_k - kk)) <= 1e-5
+        else:
+            assert H.within_bf16(assert_k, kk, 1e-2)[0]
+        assert torch.equal(vc[:, :, n:n + T], vn.permute(1, 2, 0))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ["random", "chain", "star", "single", "gqa", "empty_cache", "no_rotate", "ragged"])
+def test_tree_attention_small(dtype, case):
+    say(f"attention {dtype} {case}")
+    if case == "random":
+        _attention_case(dtype, 24, 37, 4, 4, 64, random_tree(5, 24, 4)[0], 3)
+    elif case == "chain":
+        _attention_case(dtype, 9, 64, 2, 2, 128, chain_tree(9)[0], 4)
+    elif case == "star":
+        _attention_case(dtype, 17, 100, 2, 2, 128, star_tree(17)[0], 5)
+    elif case == "single":
+        _attention_case(dtype, 1, 33, 4, 4, 64, [-1], 6)
+    elif case == "gqa":
+        _attention_case(dtype, 20, 70, 8, 2, 128, random_tree(8, 20, 5)[0], 7)
+    elif case == "empty_cache":
+        _attention_case(dtype, 12, 0, 2, 2, 64, random_tree(9, 12, 3)[0], 8)
+    elif case == "no_rotate":
+        _attention_case(dtype, 24, 37, 4, 4, 64, random_tree(5, 24, 4)[0], 9, rotate=False)
+    else:
+        _attention_case(dtype, 70, 203, 3, 3, 128, random_tree(11, 70, 6)[0], 10, cap=280)
+
+
+def test_tree_attention_at_the_op_workload_size():
+    a = ATTENTION_OP
+    say("attention bf16 op workload")
+    parent, _ = random_tree(a["seed"], a["tree_size"], a["max_depth"])
+    _attention_case("bf16", a["tree_size"], a["cache_len"], a["n_heads"], a["n_kv_heads"], a["head_dim"], parent,
+                    a["seed"], cap=a["cache_len"] + a["tree_size"], base=a["rope_base"])
+
+
+# ------------------------------------------------------------------ end to end, tiny model
+@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_full7"])
+def test_tiny_fp32_sixteen_steps_match_oracle_and_greedy(name):
+    H = _H()
+    wl = WORKLOADS[name]
+    say(f"end-to-end {name}")
+    sc = H.StepCompare(wl)
+    sc.check_prefill()
+    out = []
+    for step in range(16):
+        out += sc.step()["emitted"]
+    want = sc.model.ar_greedy(sc.prompt, len(out))
+    assert out == want                                               # losslessness on the GPU
+    sc.check_cache("after 16 steps")
+    # no near-tie could hide or fake a mismatch: every decision of the run (top-1/top-2 of each verify row,
+    # neighbouring draft candidates) has a margin above the tolerance and 10x above the error actually seen
+    say(f"{name}: smallest decision margin {sc.min_margin:.3e}, largest logit error {sc.max_err:.3e}")
+    assert sc.min_margin > H.FP32_LOGIT_TOL and sc.min_margin > 10 * sc.max_err, (sc.min_margin, sc.max_err)
+
+
+def test_tiny_bf16_sixteen_steps():
+    H = _H()
+    wl = WORKLOADS["tiny_bf16"]
+    say("end-to-end tiny_bf16")
+    sc = H.StepCompare(wl)
+    sc.check_prefill()
+    same = 0
+    for step in range(16):
+        r = sc.step(require_same_tokens=False)
+        same += r["emitted"] == r["oracle"]["emitted"]
+        if r["emitted"] != r["oracle"]["emitted"]:
+            break                                                   # sequences diverged at a near-tie: stop comparing
+    assert same >= 4
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_bf16"])
+def test_forced_acceptance_every_root_path(name):
+    H = _H()
+    wl = WORKLOADS[name]
+    say(f"forced acceptance {name}")
+    model = oracle_model(wl)
+    prompt = prompt_of(wl, 10)
+    truth = model.ar_greedy(prompt, wl.k + 3)
+    parent, rank = tree_of(wl)
+    tensors = make_weights(wl, wl.seed, H.DEV, torch_dtype(wl))
+    seen = set()
+    for leaf in range(len(parent)):
+        full = []
+        v = leaf
+        while v >= 0:
+            full.append(v)
+            v = parent[v]
+        full = full[::-1]
+        for m_star in range(1, len(full) + 1):
+            target = tuple(full[:m_star])
+            if target in seen:
+                continue
+            seen.add(target)
+            sc = H.StepCompare(wl, tensors_gpu=tensors, prompt=prompt)
+            wrong = [t for t in range(wl.vocab) if t not in set(truth)]
+            tok = [wrong[v] for v in range(len(parent))]
+            for j, node in enumerate(target):
+                tok[node] = truth[j]
+            strict = wl.dtype == "f32"
+            r = sc.step(forced=tok, require_same_tokens=strict)
+            if strict:
+                assert r["path"] == list(target) and r["emitted"] == truth[:m_star] and r["root"] == truth[m_star]
+                nxt = sc.step()
+                assert nxt["emitted"][0] == truth[m_star]
+                sc.check_cache(f"after forced path {target}")
+            sc.gpu.close()
+
+
+def test_one_token_tree_is_a_plain_decode_step():
+    H = _H()
+    wl = WORKLOADS["tiny"]
+    say("T=1 decode")
+    sc = H.StepCompare(wl, tree=([-1], [0]))
+    out = []
+    for _ in range(8):
+        out += sc.step()["emitted"]
+    assert out == sc.model.ar_greedy(sc.prompt, 8)
+
+
+def test_long_prompt_prefills_in_chunks():
+    H = _H()
+    wl = WORKLOADS["tiny"].with_(prompt_len=100)
+    say("chunked prefill")
+    sc = H.StepCompare(wl)
+    sc.check_prefill()
+    sc.step()
+
+
+# ------------------------------------------------------------------ error paths (host-side validation)
+def test_error_codes():
+    B, H = _B(), _H()
+    wl = WORKLOADS["tiny"]
+    gpu = H.gpu_model(wl)
+    parent, rank = tree_of(wl)
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_tree_verify_step()
+    assert e.value.code == B.HT_ESTATE
+    for bad_parent in ([0] + parent[1:], parent[:3] + [5] + parent[4:]):
+        with pytest.raises(B.HTError) as e:
+            gpu.ht_set_tree(bad_parent, rank)
+        assert e.value.code == B.HT_ETREE
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_set_tree([-1, 0, 1, 2], [0, 0, 0, 0])                # depth 3 > k = 2
+    assert e.value.code == B.HT_ETREE
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_set_tree([-1, 0, 0], [0, 1, 1])                      # siblings share a rank
+    assert e.value.code == B.HT_ETREE
+    gpu.ht_set_tree(parent, rank)
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_tree_verify_step()
+    assert e.value.code == B.HT_ESTATE                              # no prefill yet
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_prefill([1, 2, wl.vocab])
+    assert e.value.code == B.HT_EINVAL
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_prefill(list(range(wl.max_cache + 1)))
+    assert e.value.code == B.HT_ECAPACITY
+    gpu.ht_prefill(prompt_of(wl, wl.max_cache - 4))
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_tree_verify_step()                                   # drafting without ht_transfer
+    assert e.value.code == B.HT_ESTATE
+    gpu.ht_transfer()
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_tree_verify_step()                                   # 124 + 8 > 128
+    assert e.value.code == B.HT_ECAPACITY
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_accept_and_compact()
+    assert e.value.code == B.HT_ESTATE
+    gpu.close()
+
+
+# ------------------------------------------------------------------ large shapes
+def test_llama7b_width_two_layers_against_oracle():
+    """Full 7B widths (d 4096, 32x128 heads, FFN 11008, vocab 32000), 64-node tree, cache 512, the launch
+    configuration the benchmark times; depth cut to 2 layers so the fp64 oracle finishes in seconds."""
+    H = _H()
+    wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), prompt_len=512, max_cache=640)
+    say("7B-width 2 layers: generating weights")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    say("7B-width 2 layers: oracle + gpu")
+    sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors)
+    sc.check_prefill()
+    r = sc.step(require_same_tokens=False)
+    say(f"7B-width 2 layers: emitted {r['emitted']} oracle {r['oracle']['emitted']}")
