@@ -14,7 +14,8 @@
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked "host".  The library
- *     allocates no device memory: all of its device state lives in the caller's `workspace`.
+ *     allocates no device memory: all of its device state lives in the caller's `workspace`, including,
+ *     for bf16 models, a repacked copy of every projection matrix (streaming layout).
  *   - Matrices are row-major [out_features, in_features]; y = x W^T.  No biases.
  *   - `stream` is a hipStream_t passed as void*.  Calls enqueue on it and return without waiting unless
  *     stated otherwise.  One model is used from one stream at a time; calls are not re-entrant.
@@ -150,9 +151,20 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
 
 /* Skinny weight-streaming product out[M, N] (float32) = a[M, K] . w[N, K]^T with M <= HT_MAX_TREE rows,
  * the contraction every projection of the verify step uses (Sec. 1: decoding time goes to loading the
- * parameters).  a must be readable up to ht_padded_rows(M) rows.  scratch: >= ht_skinny_gemm_scratch_bytes. */
+ * parameters).  a must be readable up to ht_padded_rows(M) rows.
+ *   ht_weight_pack        : bf16 w[N, K] (N % 16 == 0, K % 8 == 0) -> the library's streaming layout
+ *                           (16-row x 32-column tiles in matrix-core operand order, contiguous along K);
+ *                           `packed` needs ht_weight_pack_bytes(N, K) bytes (0 = shape not packable).
+ *                           ht_init_model does the same for every projection of a bf16 model.
+ *   ht_skinny_gemm_packed : the product on packed bf16 weights; scratch (may be NULL) holds split-K partials.
+ *   ht_skinny_gemm        : convenience for either dtype: packs into scratch when it can, then multiplies.
+ *                           scratch >= ht_skinny_gemm_scratch_bytes(M, N, K), 256-byte aligned. */
 int32_t ht_padded_rows(int32_t M);
+size_t ht_weight_pack_bytes(int32_t N, int32_t K);
+int ht_weight_pack(const void *w, int32_t N, int32_t K, void *packed, void *stream);
 size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+int ht_skinny_gemm_packed(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
+                          void *scratch, size_t scratch_bytes, void *stream);
 int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
                    void *scratch, size_t scratch_bytes, void *stream);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "ht_workspace_bytes", "ht_init_model", "ht_free_model", "ht_set_tree", "ht_prefill", "ht_transfer",
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
-    "ht_skinny_gemm",
+    "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed",
 ]
 
 
@@ -71,6 +71,9 @@ def _load() -> C.CDLL:
         "ht_padded_rows": (C.c_int32, [C.c_int32]),
         "ht_skinny_gemm_scratch_bytes": (sz, [C.c_int32, C.c_int32, C.c_int32]),
         "ht_skinny_gemm": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
+        "ht_weight_pack_bytes": (sz, [C.c_int32, C.c_int32]),
+        "ht_weight_pack": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp]),
+        "ht_skinny_gemm_packed": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -133,6 +136,19 @@ def ht_skinny_gemm_scratch_bytes(M: int, N: int, K: int) -> int:
 def ht_skinny_gemm(a, w, M, N, K, dtype, out, scratch=None, stream=None) -> None:
     sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.ht_skinny_gemm(_ptr(a), _ptr(w), M, N, K, dtype, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
+
+
+def ht_weight_pack_bytes(N: int, K: int) -> int:
+    return lib.ht_weight_pack_bytes(N, K)
+
+
+def ht_weight_pack(w, N, K, packed, stream=None) -> None:
+    _check(lib.ht_weight_pack(_ptr(w), N, K, _ptr(packed), _stream_ptr(stream)))
+
+
+def ht_skinny_gemm_packed(a, packed, M, N, K, out, scratch=None, stream=None) -> None:
+    sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib.ht_skinny_gemm_packed(_ptr(a), _ptr(packed), M, N, K, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
 
 
 def make_config(shape, max_cache: Optional[int] = None, max_tree: Optional[int] = None) -> ht_config:

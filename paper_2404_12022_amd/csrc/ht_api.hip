@@ -78,7 +78,16 @@ struct Buffers {
   void** wt_ptrs;      // device array [k]
   void* attn_scratch;
   std::vector<void*> kc, vc;   // host copies of the per-layer cache pointers
+  // bf16 only: projection weights repacked into MFMA-fragment order
+  std::vector<PackedW> p_qkv, p_o, p_gu, p_down;
+  PackedW p_head;
 };
+
+bool shapes_packable(const ht_config& c) {
+  const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+  return c.dtype == HT_BF16 && qd % 16 == 0 && kvd % 16 == 0 && c.d_model % 16 == 0 && c.d_ffn % 16 == 0 &&
+         c.vocab % 16 == 0;
+}
 
 void carve(const ht_config& c, Carver& cv, Buffers& b) {
   const size_t es = elem_size(c.dtype);
@@ -120,6 +129,22 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
     b.kc[l] = cv.take_bytes((size_t)c.max_cache * kvd * es);
     b.vc[l] = cv.take_bytes((size_t)c.max_cache * kvd * es);
   }
+  if (shapes_packable(c)) {
+    auto pk = [&](int N, int K) {
+      return PackedW{(const bf16_t*)cv.take_bytes(packed_weight_bytes(N, K)), N, K, packed_cols(K)};
+    };
+    b.p_qkv.resize(c.n_layers);
+    b.p_o.resize(c.n_layers);
+    b.p_gu.resize(c.n_layers);
+    b.p_down.resize(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+      b.p_qkv[l] = pk((int)(qd + 2 * kvd), (int)d);
+      b.p_o[l] = pk((int)d, (int)qd);
+      b.p_gu[l] = pk(2 * c.d_ffn, (int)d);
+      b.p_down[l] = pk((int)d, c.d_ffn);
+    }
+    b.p_head = pk(c.vocab, (int)d);
+  }
 }
 
 int check_config(const ht_config* c) {
@@ -157,6 +182,7 @@ struct ht_model {
   int T = 0;
   bool has_tree = false, has_prefill = false, transfer_ready = false, verify_done = false;
   bool use_mfma = true;
+  bool packed = false;          // bf16 projections run on the repacked weights
   std::vector<int32_t> depth;
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
@@ -165,17 +191,8 @@ struct ht_model {
 
 namespace {
 
-int product(ht_model* m, const void* a, WeightSegs w, int M, int N, int K, float* out, int max_split, int* nsplit,
-            hipStream_t s) {
-  if (m->cfg.dtype == HT_BF16 && m->use_mfma && gemm_mfma_supported(M, N, K)) {
-    int sp = gemm_mfma_splits(M, N, K);
-    if (sp > max_split) sp = max_split;
-    *nsplit = sp;
-    HT_HIP(launch_gemm_mfma(a, w, M, N, K, out, sp, s));
-  } else {
-    *nsplit = 1;
-    HT_HIP(launch_gemm_simple(m->cfg.dtype, a, w, M, N, K, out, s));
-  }
+int product(ht_model* m, const void* a, WeightSegs w, int M, int N, int K, float* out, hipStream_t s) {
+  HT_HIP(launch_gemm_simple(m->cfg.dtype, a, w, M, N, K, out, s));
   return HT_OK;
 }
 
@@ -209,24 +226,43 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   for (int l = layer_from; l < c.n_layers; ++l) {
     float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
     HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
-    int one;
-    WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
-    if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, 1, &one, s))) return rc;
+    if (m->packed) {
+      HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, 1, s));
+    } else {
+      WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
+      if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
+    }
     HT_HIP(launch_rope_append(c.dtype, b.qkv, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads, c.head_dim,
                               c.max_cache, s));
     if ((rc = attention(m, l, n, M, tree, s))) return rc;
-    if ((rc = product(m, b.attn, segs1(m->wo[l], d), M, d, qd, b.part, kMaxSplitK, &pending, s))) return rc;
+    if (m->packed) {
+      pending = gemm_mfma_splits(M, d, qd);
+      HT_HIP(launch_gemm_packed(b.attn, b.p_o[l], M, b.part, pending, s));
+    } else {
+      pending = 1;
+      if ((rc = product(m, b.attn, segs1(m->wo[l], d), M, d, qd, b.part, s))) return rc;
+    }
     HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->ffn_norm[l], b.u, nullptr, M, d, c.rms_eps, s));
-    WeightSegs gu{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2};
-    if ((rc = product(m, b.u, gu, M, 2 * f, d, b.gu, 1, &one, s))) return rc;
-    HT_HIP(launch_silu_mul(c.dtype, b.gu, b.act, M, f, s));
-    if ((rc = product(m, b.act, segs1(m->w_down[l], d), M, d, f, b.part, kMaxSplitK, &pending, s))) return rc;
+    if (m->packed) {
+      HT_HIP(launch_gemm_packed_silu(b.u, b.p_gu[l], M, b.act, s));
+      pending = gemm_mfma_splits(M, d, f);
+      HT_HIP(launch_gemm_packed(b.act, b.p_down[l], M, b.part, pending, s));
+    } else {
+      WeightSegs gu{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2};
+      if ((rc = product(m, b.u, gu, M, 2 * f, d, b.gu, s))) return rc;
+      HT_HIP(launch_silu_mul(c.dtype, b.gu, b.act, M, f, s));
+      pending = 1;
+      if ((rc = product(m, b.act, segs1(m->w_down[l], d), M, d, f, b.part, s))) return rc;
+    }
   }
   HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->final_norm, logits ? b.u : nullptr, nullptr, M, d,
                          c.rms_eps, s));
   if (logits) {
-    int one;
-    if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, 1, &one, s))) return rc;
+    if (m->packed) {
+      HT_HIP(launch_gemm_packed(b.u, b.p_head, M, logits, 1, s));
+    } else if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, s))) {
+      return rc;
+    }
     HT_HIP(launch_argmax(logits, gout, M, c.vocab, s));
   }
   return HT_OK;
@@ -348,6 +384,19 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   if (e == hipSuccess) e = hipHostMalloc((void**)&m->h_state, sizeof(StepState), hipHostMallocDefault);
   if (e == hipSuccess) e = hipMemsetAsync(workspace, 0, need, s);
   if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init allocation/clear failed: %s", hipGetErrorString(e)));
+
+  m->packed = m->use_mfma && shapes_packable(*cfg);
+  if (m->packed) {
+    const int qd = cfg->n_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim, d = cfg->d_model, f = cfg->d_ffn;
+    for (int l = 0; l < L && e == hipSuccess; ++l) {
+      e = launch_repack(WeightSegs{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3}, d, 0, (void*)m->b.p_qkv[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->wo[l], nullptr, nullptr}, {d, 0, 0}, 1}, qd, 0, (void*)m->b.p_o[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2}, d, 1, (void*)m->b.p_gu[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_down[l], nullptr, nullptr}, {d, 0, 0}, 1}, f, 0, (void*)m->b.p_down[l].p, s);
+    }
+    if (e == hipSuccess) e = launch_repack(WeightSegs{{m->lm_head, nullptr, nullptr}, {cfg->vocab, 0, 0}, 1}, d, 0, (void*)m->b.p_head.p, s);
+    if (e != hipSuccess) return cleanup(fail(HT_EHIP, "weight repack failed: %s", hipGetErrorString(e)));
+  }
 
   // chain tables (prefill chunks and pseudo rows): row i has depth i and sees rows 0..i
   std::vector<int32_t> cp(kMaxTree);
@@ -598,9 +647,38 @@ int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void*
   return HT_OK;
 }
 
+size_t ht_weight_pack_bytes(int32_t N, int32_t K) {
+  if (N < 16 || N % 16 || K < 8 || K % 8) return 0;
+  return align_up(packed_weight_bytes(N, K), 256);
+}
+
+int ht_weight_pack(const void* w, int32_t N, int32_t K, void* packed, void* stream) {
+  if (!w || !packed) return fail(HT_EINVAL, "NULL argument");
+  if (!ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "packing needs N %% 16 == 0 and K %% 8 == 0 (N=%d K=%d)", N, K);
+  HT_HIP(launch_repack(segs1(w, N), K, 0, packed, (hipStream_t)stream));
+  return HT_OK;
+}
+
 size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) return 0;
-  return align_up((size_t)kMaxSplitK * M * N * sizeof(float), 256);
+  return align_up((size_t)kMaxSplitK * M * N * sizeof(float), 256) + ht_weight_pack_bytes(N, K);
+}
+
+int ht_skinny_gemm_packed(const void* a, const void* packed, int32_t M, int32_t N, int32_t K, float* out, void* scratch,
+                          size_t scratch_bytes, void* stream) {
+  if (!a || !packed || !out) return fail(HT_EINVAL, "NULL argument");
+  if (M < 1 || M > kMaxTree || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  hipStream_t s = (hipStream_t)stream;
+  PackedW pw{(const bf16_t*)packed, N, K, packed_cols(K)};
+  int sp = gemm_mfma_splits(M, N, K);
+  if (sp > 1 && (!scratch || scratch_bytes < (size_t)sp * M * N * sizeof(float))) sp = 1;
+  if (sp == 1) {
+    HT_HIP(launch_gemm_packed(a, pw, M, out, 1, s));
+  } else {
+    HT_HIP(launch_gemm_packed(a, pw, M, (float*)scratch, sp, s));
+    HT_HIP(launch_reduce_splits((const float*)scratch, sp, (size_t)M * N, out, s));
+  }
+  return HT_OK;
 }
 
 int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K, int32_t dtype, float* out,
@@ -609,21 +687,15 @@ int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K
   if (dtype != HT_F32 && dtype != HT_BF16) return fail(HT_EINVAL, "bad dtype");
   if (M < 1 || M > kMaxTree || N < 1 || K < 1) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
   hipStream_t s = (hipStream_t)stream;
-  WeightSegs ws = segs1(w, N);
   const char* env = getenv("HT_FORCE_SIMPLE");
   const bool simple = env && env[0] == '1';
-  if (dtype == HT_BF16 && !simple && gemm_mfma_supported(M, N, K)) {
-    int sp = gemm_mfma_splits(M, N, K);
-    if (sp > 1 && (!scratch || scratch_bytes < (size_t)sp * M * N * sizeof(float))) sp = 1;
-    if (sp == 1) {
-      HT_HIP(launch_gemm_mfma(a, ws, M, N, K, out, 1, s));
-    } else {
-      HT_HIP(launch_gemm_mfma(a, ws, M, N, K, (float*)scratch, sp, s));
-      HT_HIP(launch_reduce_splits((const float*)scratch, sp, (size_t)M * N, out, s));
-    }
-  } else {
-    HT_HIP(launch_gemm_simple(dtype, a, ws, M, N, K, out, s));
+  const size_t pb = ht_weight_pack_bytes(N, K);
+  if (dtype == HT_BF16 && !simple && pb && scratch && scratch_bytes >= pb && (uintptr_t)scratch % 256 == 0) {
+    int rc = ht_weight_pack(w, N, K, scratch, stream);
+    if (rc) return rc;
+    return ht_skinny_gemm_packed(a, scratch, M, N, K, out, (char*)scratch + pb, scratch_bytes - pb, stream);
   }
+  HT_HIP(launch_gemm_simple(dtype, a, segs1(w, N), M, N, K, out, s));
   return HT_OK;
 }
 

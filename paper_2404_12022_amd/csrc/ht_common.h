@@ -94,10 +94,22 @@ hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, fl
 
 // generic (any dtype, any shape) product: out[s=0][m][n] = sum_k a[m][k] w[n][k]
 hipError_t launch_gemm_simple(int dtype, const void* a, WeightSegs w, int M, int N, int K, float* out, hipStream_t s);
-// bf16 MFMA product with optional split-K: out[s][m][n]; returns the number of splits used in *nsplit
+// bf16 MFMA product over weights repacked into MFMA-fragment order (see ht_gemm_mfma.hip)
+struct PackedW {
+  const bf16_t* p;   // fragment-ordered copy
+  int32_t N, K, Kp;  // rows (multiple of 16), columns, columns rounded up to packed_cols(K)
+};
 bool gemm_mfma_supported(int M, int N, int K);
+int packed_cols(int K);
+size_t packed_weight_bytes(int N, int K);
 int gemm_mfma_splits(int M, int N, int K);
-hipError_t launch_gemm_mfma(const void* a, WeightSegs w, int M, int N, int K, float* out, int nsplit, hipStream_t s);
+// mode 0: row blocks in natural order over the concatenated segments; mode 1: two equal segments
+// interleaved block by block (gate block i, up block i, gate block i+1, ..)
+hipError_t launch_repack(WeightSegs w, int K, int mode, void* dst, hipStream_t s);
+// out[s][m][n], s < nsplit (split-K partial sums, fp32)
+hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s);
+// w packed with mode 1 from (gate, up): act[m][j] = silu(a.gate_j) * (a.up_j), bf16 [M][N/2]
+hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s);
 
 // attention over cache + tree rows; out[m][h*hd+e] in dtype
 hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,

@@ -1,94 +1,137 @@
 // Skinny weight-streaming product for bf16 on CDNA4 matrix cores.
 //
-//   out[s][m][n] = sum_{k in split s} a[m][k] * w[n][k]        m < M <= 128, fp32 accumulate
+//   out[m][n] = sum_k a[m][k] * w[n][k]        m < M <= 128 tokens, fp32 accumulate
 //
-// The weights are the big operand (N x K, streamed from HBM exactly once); the activations are a
-// small panel (M x K) that every workgroup re-reads from L2.  Mapping on v_mfma_f32_16x16x32_bf16:
-// weight rows are the MFMA "A" rows (16 output features per instruction), tokens are the "B"
-// columns, so each lane ends with four consecutive output features of one token.
+// The weights are the big operand (N x K, read from HBM exactly once per pass); the activations are
+// a small panel (M x K) that every workgroup re-reads from L2.  On v_mfma_f32_16x16x32_bf16 the weight
+// rows are the MFMA "A" rows (16 output features per instruction) and the tokens are the "B" columns,
+// so each lane ends with four consecutive output features of one token.
 //
-//   * A wavefront owns R blocks of 16 weight rows and streams them straight from global memory
-//     into MFMA operand registers: per 64-wide K chunk a lane reads 32 contiguous bytes of its row,
-//     four lanes cover a full 128-byte line, and a ring of PD chunks stays in flight per wavefront.
-//     The contraction index inside a chunk is permuted the same way for both operands (lane group
-//     g, step s  <->  k = 16 g + 8 s .. + 7), which is what makes those reads contiguous.
-//   * The activation panel for the chunk is staged once per workgroup in LDS (rows padded to 144
-//     bytes so 128-bit reads are bank-conflict free) and shared by the four wavefronts.
-//   * Optional split-K over blockIdx.y writes partial sums that the consumer adds in a fixed order.
+// Weight layout.  At model init every projection matrix is repacked once into MFMA-fragment order:
+// fragment (rb, j) holds rows 16 rb .. 16 rb + 15 and columns 32 j .. 32 j + 31 as 64 lanes x 16 bytes
+// (lane l: row l % 16, columns 8 (l / 16) .. + 7), and the fragments of one row block follow each other
+// along K.  A wavefront therefore streams one contiguous run of 16 x K x 2 bytes per row block with
+// fully coalesced 1 KiB loads that drop straight into MFMA operand registers: no LDS transpose, no
+// partially used cache lines, sequential DRAM pages.  Row blocks can be ordered freely at pack time,
+// which is how gate and up rows meet in one wavefront for the fused SiLU epilogue.
+//
+// The activation chunk (M x 128 columns) is staged once per workgroup in LDS (rows padded by 16 bytes:
+// conflict-free 128-bit reads) and shared by the four wavefronts; a ring of PD weight chunks per
+// wavefront stays in flight.  Split-K over blockIdx.y writes fp32 partial sums that the consumer adds
+// in a fixed order (deterministic).
 #include "ht_common.h"
 
 namespace ht {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int KC = 64;                 // K elements per chunk
+constexpr int KC = 128;                // K elements per activation chunk
+constexpr int STEPS = KC / 32;         // MFMA steps per chunk
 constexpr int ROWB = KC * 2 + 16;      // LDS row stride in bytes
-constexpr int PD = 4;                  // weight chunks in flight per wavefront
+constexpr int PD = 3;                  // weight chunks in flight per wavefront
 
 union Frag {
   uint4 raw;
+  u32x4_t nat;
   bf16x8_t v;
 };
 
-template <int MT, int R>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ a, WeightSegs w, int M, int N, int K,
-                                                        float* __restrict__ out, int nsplit) {
+enum { EPI_F32 = 0, EPI_SILU = 1 };
+
+// --------------------------------------------------------------------------------------------- repack
+// dst fragment order from row-major segments.  One thread per 16-byte piece.
+__global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, bf16_t* __restrict__ dst) {
+  const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)n_rb * KS * 64;
+  if (piece >= total) return;
+  const int lane = (int)(piece & 63);
+  const size_t frag = piece >> 6;
+  const int j = (int)(frag % KS);
+  const int rb = (int)(frag / KS);
+  int seg, src_rb;
+  if (mode == 1) {               // two equal segments interleaved block by block (gate, up)
+    seg = rb & 1;
+    src_rb = rb >> 1;
+  } else {                       // natural order over the concatenated segments
+    seg = 0;
+    src_rb = rb;
+    while (seg + 1 < w.nseg && src_rb * 16 >= w.rows[seg]) { src_rb -= w.rows[seg] / 16; ++seg; }
+  }
+  const int row = src_rb * 16 + (lane & 15);
+  const int k = j * 32 + (lane >> 4) * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (k < K) v = *(const uint4*)((const bf16_t*)w.w[seg] + (size_t)row * K + k);
+  *(uint4*)(dst + piece * 8) = v;
+}
+
+// --------------------------------------------------------------------------------------------- product
+// The hot loop is straight-line code (no predicated loads, no data-dependent branches) so that the
+// compiler can keep exact outstanding-load counts and the weight ring really stays in flight: chunk
+// indices past the end of this block's K range are clamped to its last chunk (a redundant, in-bounds
+// reload that is never used), rows past N are clamped to the last row block (never stored), and
+// activation columns past K are clamped into the row (they meet zero-padded weights).
+template <int MT, int R, int WAVES, int EPI>
+__global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
+                                                                 const bf16_t* __restrict__ wp, int M, int N, int K,
+                                                                 int KS, void* __restrict__ outp, int nsplit) {
+  constexpr int THREADS = 64 * WAVES;
   constexpr int ROWS = MT * 16;
-  constexpr int PIECES = ROWS * 8;                       // 16-byte pieces of the activation chunk
-  constexpr int APASS = (PIECES + 255) / 256;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][ROWS * ROWB];
+  constexpr int PIECES = ROWS * (KC / 8);                // 16-byte pieces of the activation chunk
+  static_assert(PIECES % THREADS == 0, "activation chunk must divide evenly over the threads");
+  constexpr int APASS = PIECES / THREADS;
+  constexpr int STAGE = ROWS * ROWB;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
-  const int chunks = (K + KC - 1) / KC;
+  const int chunks = KS / STEPS;                         // KS is a multiple of STEPS (weights zero-padded)
   const int c0 = (int)((long long)chunks * blockIdx.y / nsplit);
   const int c1 = (int)((long long)chunks * (blockIdx.y + 1) / nsplit);
+  const int n_rb = N / 16;
+  const int rb0 = (blockIdx.x * WAVES + wave) * R;
+  if (c0 >= c1) return;                                  // uniform over the block
 
-  // weight rows of this wavefront
-  const bf16_t* wrow[R];
-  bool wvalid[R];
+  const u32x4_t* wbase[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int rb = (blockIdx.x * 4 + wave) * R + r;
-    int row = rb * 16 + r16;
-    wvalid[r] = rb * 16 < N;
-    int seg = 0;
-    if (wvalid[r]) {
-      while (seg + 1 < w.nseg && row >= w.rows[seg]) { row -= w.rows[seg]; ++seg; }
-    } else {
-      row = 0;
-    }
-    wrow[r] = (const bf16_t*)w.w[seg] + (size_t)row * K + g * 16;
+    const int rb = rb0 + r < n_rb ? rb0 + r : n_rb - 1;
+    wbase[r] = (const u32x4_t*)wp + ((size_t)rb * KS) * 64 + lane;
   }
+  const int last = c1 - 1;
 
-  auto load_w = [&](Frag (&dst)[R][2], int c) {
+  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const int k = c * KC + g * 16 + s * 8;
-        if (wvalid[r] && k < K) dst[r][s].raw = *(const uint4*)(wrow[r] + c * KC + s * 8);
-        else dst[r][s].raw = make_uint4(0, 0, 0, 0);
-      }
+      for (int s = 0; s < STEPS; ++s)
+        dst[r][s].nat = __builtin_nontemporal_load(wbase[r] + (size_t)(c * STEPS + s) * 64);
   };
-  auto load_a = [&](uint4 (&dst)[APASS], int c) {
+  // activation pieces of this thread: row p / 16, 16-byte column p % 16 of the chunk
+  const bf16_t* arow[APASS];
+  int acol[APASS], alds[APASS];
+#pragma unroll
+  for (int i = 0; i < APASS; ++i) {
+    const int p = tid + i * THREADS;
+    arow[i] = a + (size_t)(p / (KC / 8)) * K;
+    acol[i] = (p % (KC / 8)) * 8;
+    alds[i] = (p / (KC / 8)) * ROWB + (p % (KC / 8)) * 16;
+  }
+  auto load_a = [&](u32x4_t (&dst)[APASS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
 #pragma unroll
     for (int i = 0; i < APASS; ++i) {
-      const int p = tid + i * 256;
-      const int row = p >> 3, col = p & 7;
-      const int k = c * KC + col * 8;
-      if (p < PIECES && k < K) dst[i] = *(const uint4*)(a + (size_t)row * K + k);
-      else dst[i] = make_uint4(0, 0, 0, 0);
+      int k = c * KC + acol[i];
+      k = k < K - 8 ? k : K - 8;
+      dst[i] = *(const u32x4_t*)(arow[i] + k);
     }
   };
-  auto store_a = [&](const uint4 (&src)[APASS], int stage) {
+  auto store_a = [&](const u32x4_t (&src)[APASS], int stage) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < APASS; ++i) {
-      const int p = tid + i * 256;
-      if (p < PIECES) *(uint4*)(&lds[stage][(p >> 3) * ROWB + (p & 7) * 16]) = src[i];
-    }
+    for (int i = 0; i < APASS; ++i) *(u32x4_t*)(&lds[stage * STAGE + alds[i]]) = src[i];
   };
 
   floatx4_t acc[R][MT];
@@ -97,72 +140,120 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  Frag wreg[PD][R][2];
-  uint4 areg[APASS];
-#pragma unroll
-  for (int p = 0; p < PD; ++p)
-    if (c0 + p < c1) load_w(wreg[p], c0 + p);
-  if (c0 < c1) {
-    load_a(areg, c0);
-    store_a(areg, 0);
-  }
-  if (c0 + 1 < c1) load_a(areg, c0 + 1);
-  __syncthreads();
-
-  for (int cb = c0; cb < c1; cb += PD) {
+  // Loads retire in issue order, so everything is issued oldest-needed-first: at chunk c the ring holds
+  // weights of chunks c .. c+PD-1 and activations of chunks c+1 .. c+PD; each iteration consumes the
+  // oldest of both and issues activation chunk c+PD+1, then weight chunk c+PD.
+  Frag wreg[PD][R][STEPS];
+  u32x4_t areg[PD][APASS];
+  {
+    u32x4_t first[APASS];
+    load_a(first, c0);
 #pragma unroll
     for (int p = 0; p < PD; ++p) {
-      const int c = cb + p;
-      if (c < c1) {
-        const int stage = p & 1;
-        if (c + 1 < c1) store_a(areg, stage ^ 1);
-        if (c + 2 < c1) load_a(areg, c + 2);
+      load_a(areg[p], c0 + 1 + p);
+      load_w(wreg[p], c0 + p);
+    }
+    store_a(first, 0);
+  }
+  __syncthreads();
+
+  auto body = [&](Frag (&wslot)[R][STEPS], u32x4_t (&aslot)[APASS], int c) __attribute__((always_inline)) {
+    const int stage = (c - c0) & 1;
+    store_a(aslot, stage ^ 1);                 // activation chunk c+1 becomes visible after the barrier below
+    load_a(aslot, c + PD + 1);
+    const unsigned char* ab = &lds[stage * STAGE + r16 * ROWB + g * 16];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          Frag b[MT];
+    for (int s = 0; s < STEPS; ++s) {
+      Frag b[MT];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            b[mt].raw = *(const uint4*)(&lds[stage][(mt * 16 + r16) * ROWB + g * 32 + s * 16]);
+      for (int mt = 0; mt < MT; ++mt) b[mt].nat = *(const u32x4_t*)(ab + mt * 16 * ROWB + s * 64);
 #pragma unroll
-          for (int r = 0; r < R; ++r)
+      for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[p][r][s].v, b[mt].v, acc[r][mt], 0, 0, 0);
-        }
-        if (c + PD < c1) load_w(wreg[p], c + PD);
-        __syncthreads();
+        for (int mt = 0; mt < MT; ++mt)
+          acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[mt].v, acc[r][mt], 0, 0, 0);
+    }
+    load_w(wslot, c + PD);
+    __syncthreads();
+  };
+
+  int c = c0;
+  for (; c + PD <= c1; c += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) body(wreg[p], areg[p], c + p);
+  }
+#pragma unroll
+  for (int p = 0; p < PD - 1; ++p)
+    if (c + p < c1) body(wreg[p], areg[p], c + p);                // uniform tail
+
+  if (EPI == EPI_F32) {
+    float* dst = (float*)outp + (size_t)blockIdx.y * M * N;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (rb0 + r >= n_rb) continue;
+      const int n0 = (rb0 + r) * 16 + g * 4;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + r16;
+        if (m < M)
+          *(float4*)(dst + (size_t)m * N + n0) = make_float4(acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]);
       }
     }
-  }
-
-  float* dst = out + (size_t)blockIdx.y * M * N;
+  } else {
+    // row block rb0 holds gate rows, rb0 + 1 the matching up rows: act = silu(gate) * up, bf16
+    if (rb0 + 1 < n_rb) {
+      bf16_t* dst = (bf16_t*)outp;
+      const int f = N / 2;
+      const int j0 = (rb0 / 2) * 16 + g * 4;
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int rb = (blockIdx.x * 4 + wave) * R + r;
-    if (rb * 16 >= N) continue;
-    const int n0 = rb * 16 + g * 4;
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 16 + r16;
+        if (m < M) {
+          bf16_t o[4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + r16;
-      if (m < M) *(float4*)(dst + (size_t)m * N + n0) = make_float4(acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]);
+          for (int i = 0; i < 4; ++i) {
+            const float gt = acc[0][mt][i], up = acc[R - 1][mt][i];
+            o[i] = float_to_bf16(gt / (1.0f + __expf(-gt)) * up);
+          }
+          *(uint2*)(dst + (size_t)m * f + j0) = *(const uint2*)o;
+        }
+      }
     }
   }
 }
 
 template <int MT>
-hipError_t launch_mt(const bf16_t* a, const WeightSegs& w, int M, int N, int K, float* out, int nsplit, hipStream_t s) {
-  const int rbs = N / 16;
-  if (N >= 8192) {
-    hipLaunchKernelGGL((gemm_mfma_kernel<MT, 2>), dim3((rbs + 7) / 8, nsplit), dim3(256), 0, s, a, w, M, N, K, out, nsplit);
+hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, hipStream_t s) {
+  const int n_rb = w.N / 16;
+  const int KS = w.Kp / 32;
+  if (epi == EPI_SILU) {
+    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU>), dim3((n_rb + 7) / 8, 1), dim3(256), 0, s, a, w.p, M,
+                       w.N, w.K, KS, out, 1);
+  } else if (w.N >= 8192) {
+    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a, w.p,
+                       M, w.N, w.K, KS, out, nsplit);
   } else {
-    hipLaunchKernelGGL((gemm_mfma_kernel<MT, 1>), dim3((rbs + 3) / 4, nsplit), dim3(256), 0, s, a, w, M, N, K, out, nsplit);
+    hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a, w.p,
+                       M, w.N, w.K, KS, out, nsplit);
   }
   return hipGetLastError();
+}
+
+hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsplit, int epi, hipStream_t s) {
+  const bf16_t* ap = (const bf16_t*)a;
+  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, s);
+  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, s);
+  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, s);
+  return launch_mt<8>(ap, w, M, out, nsplit, epi, s);
 }
 
 }  // namespace
 
 bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && M <= 128 && N % 16 == 0 && K % 8 == 0 && N >= 16; }
+
+int packed_cols(int K) { return (K + KC - 1) / KC * KC; }
+
+size_t packed_weight_bytes(int N, int K) { return (size_t)N * packed_cols(K) * sizeof(bf16_t); }
 
 int gemm_mfma_splits(int M, int N, int K) {
   (void)M;
@@ -176,12 +267,22 @@ int gemm_mfma_splits(int M, int N, int K) {
   return s;
 }
 
-hipError_t launch_gemm_mfma(const void* a, WeightSegs w, int M, int N, int K, float* out, int nsplit, hipStream_t s) {
-  const bf16_t* ap = (const bf16_t*)a;
-  if (M <= 16) return launch_mt<1>(ap, w, M, N, K, out, nsplit, s);
-  if (M <= 32) return launch_mt<2>(ap, w, M, N, K, out, nsplit, s);
-  if (M <= 64) return launch_mt<4>(ap, w, M, N, K, out, nsplit, s);
-  return launch_mt<8>(ap, w, M, N, K, out, nsplit, s);
+hipError_t launch_repack(WeightSegs w, int K, int mode, void* dst, hipStream_t s) {
+  int rows = 0;
+  for (int i = 0; i < w.nseg; ++i) rows += w.rows[i];
+  const int n_rb = rows / 16, KS = packed_cols(K) / 32;
+  const size_t pieces = (size_t)n_rb * KS * 64;
+  hipLaunchKernelGGL(repack_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, w, K, KS, n_rb, mode,
+                     (bf16_t*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s) {
+  return launch_any(a, w, M, out, nsplit, EPI_F32, s);
+}
+
+hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s) {
+  return launch_any(a, w, M, act, 1, EPI_SILU, s);
 }
 
 }  // namespace ht
