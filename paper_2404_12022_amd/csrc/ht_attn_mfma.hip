@@ -1,19 +1,306 @@
-// Tree-masked attention on CDNA4 matrix cores (bf16).  Placeholder: not yet enabled.
+// Tree-masked attention over the KV cache on CDNA4 matrix cores (bf16 in, fp32 softmax and sums).
+//
+//   out[m][h] = softmax_{j visible to m}( q[m][h] . K[j] / sqrt(hd) ) V[j]
+//   visible(m) = cache slots 0 .. n-1  U  { n + u : u is m or an ancestor of m }          (ancestor bit masks)
+//
+// Everything is computed transposed so that no operand ever needs an LDS transpose:
+//   S^T[key][query] = K[key][:] . Q[query][:]      MFMA "A" rows = keys   (K cache rows are contiguous in e)
+//   O^T[e][query]  += V^T[e][key] . P[key][query]  MFMA "A" rows = e      (V cache is stored [head][e][slot],
+//                                                                          so 8 consecutive keys are 16 bytes)
+// K and V fragments are loaded from global memory straight into MFMA operand registers.  The 32 keys of
+// a chunk are assigned to the two 16-row score blocks in the interleaved order key = 8 (r / 4) + 4 b + r % 4,
+// which makes the eight scores a lane holds after the S MFMAs exactly the eight consecutive keys the P
+// operand of the O MFMA wants: probabilities go from accumulator to operand registers without leaving the
+// lane.  Online softmax runs per lane (a query column lives in 4 lanes: two xor-shuffles for the row max).
+//
+// A workgroup is 4 wavefronts working on one query head, QB blocks of 16 tree rows and one slice of the
+// keys; the wavefronts take 32-key chunks round-robin and merge (max, sum, O) through LDS.  With more than
+// one key slice the merged partials go to scratch and a small kernel combines them.
 #include "ht_common.h"
 
 namespace ht {
 
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+union Frag {
+  u32x4_t nat;
+  bf16x8_t v;
+  uint32_t u[4];
+};
+
+constexpr int kMaxSplits = 16;
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+}
+
+template <int HD, int QB>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                        const bf16_t* __restrict__ vc, int cap, int n, int M,
+                                                        const uint64_t* __restrict__ anc, int Hq, int Hkv,
+                                                        bf16_t* __restrict__ out, float* __restrict__ part_o,
+                                                        float* __restrict__ part_ml, int nsplit, float scale_log2) {
+  constexpr int ES = HD / 32;      // contraction steps of the score MFMAs
+  constexpr int EB = HD / 16;      // 16-row blocks of O^T
+  // LDS merge area: per wave, O accumulators [QB][EB][4][64], running max [QB][64], partial sums [QB][64]
+  constexpr int O_FLOATS = QB * EB * 4 * 64;
+  __shared__ float lds_o[4 * O_FLOATS];
+  __shared__ float lds_m[4 * QB * 64];
+  __shared__ float lds_l[4 * QB * 64];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  const int h = blockIdx.x, hk = h / (Hq / Hkv);
+  const int m0 = blockIdx.y * QB * 16;
+  const int split = blockIdx.z;
+  const int S = n + M;
+  const int chunks = (S + 31) / 32;
+  const int cs = (int)((long long)chunks * split / nsplit), ce = (int)((long long)chunks * (split + 1) / nsplit);
+
+  // queries of this lane: token m0 + qb*16 + r16 (clamped for loads), e columns es*32 + g*8 ..
+  Frag qf[QB][ES];
+  uint64_t amask[QB][kMaskWords];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int m = m0 + qb * 16 + r16;
+    const int mc = m < M ? m : M - 1;
+    const bf16_t* qrow = q + ((size_t)mc * Hq + h) * HD + g * 8;
+#pragma unroll
+    for (int es = 0; es < ES; ++es) qf[qb][es].nat = *(const u32x4_t*)(qrow + es * 32);
+#pragma unroll
+    for (int wd = 0; wd < kMaskWords; ++wd) amask[qb][wd] = m < M ? anc[(size_t)m * kMaskWords + wd] : 0ull;
+  }
+
+  floatx4_t oacc[QB][EB];
+  float mrun[QB], lrun[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    mrun[qb] = -INFINITY;
+    lrun[qb] = 0.f;
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const bf16_t* kbase = kc + (size_t)hk * HD + g * 8;
+  const bf16_t* vbase = vc + ((size_t)hk * HD + r16) * cap;
+
+  for (int c = cs + wave; c < ce; c += 4) {
+    const int j0 = c * 32;
+    // ---- K fragments: row r of block b is key j0 + 8 (r / 4) + 4 b + r % 4 (clamped into the cache)
+    Frag kf[2][ES];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      int key = j0 + (r16 >> 2) * 8 + b * 4 + (r16 & 3);
+      key = key < cap ? key : cap - 1;
+      const bf16_t* krow = kbase + (size_t)key * Hkv * HD;
+#pragma unroll
+      for (int es = 0; es < ES; ++es) kf[b][es].nat = *(const u32x4_t*)(krow + es * 32);
+    }
+    // ---- V^T fragments: rows e = eb*16 + r16, keys j0 + g*8 .. + 7 (clamped start keeps the load in bounds)
+    Frag vf[EB];
+    {
+      int kv = j0 + g * 8;
+      kv = kv + 8 <= cap ? kv : cap - 8;
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb) vf[eb].nat = *(const u32x4_t*)(vbase + (size_t)eb * 16 * cap + kv);
+    }
+    if (j0 + 32 > S) {            // keys past the last tree row carry no defined values: zero them
+      const int first_bad = S - (j0 + g * 8);       // elements >= first_bad are invalid
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+          uint32_t keep = 0;
+          if (2 * w2 < first_bad) keep |= 0x0000ffffu;
+          if (2 * w2 + 1 < first_bad) keep |= 0xffff0000u;
+          vf[eb].u[w2] &= keep;
+        }
+    }
+    const bool need_mask = j0 + 32 > n;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      floatx4_t s[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        s[b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int es = 0; es < ES; ++es)
+          s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][es].v, qf[qb][es].v, s[b], 0, 0, 0);
+      }
+      // lane holds keys j0 + g*8 + t, t = 4 b + i
+      float p[8];
+      float cmax = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        float v = s[t >> 2][t & 3] * scale_log2;
+        if (need_mask) {
+          const int j = j0 + g * 8 + t;
+          bool vis = j < n;
+          if (!vis && j < S) {
+            const int u = j - n;
+            vis = (amask[qb][u >> 6] >> (u & 63)) & 1ull;
+          }
+          v = vis ? v : -INFINITY;
+        }
+        p[t] = v;
+        cmax = fmaxf(cmax, v);
+      }
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
+      const float mnew = fmaxf(mrun[qb], cmax);
+      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      const float alpha = exp2f(mrun[qb] - msafe);           // mrun = -inf -> 0
+      float psum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        p[t] = exp2f(p[t] - msafe);
+        psum += p[t];
+      }
+      mrun[qb] = mnew;
+      lrun[qb] = lrun[qb] * alpha + psum;
+      Frag pf;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) pf.u[w2] = pack_bf16(p[2 * w2], p[2 * w2 + 1]);
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb) {
+        oacc[qb][eb] *= alpha;
+        oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- merge the four wavefronts
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    lds_m[(wave * QB + qb) * 64 + lane] = mrun[qb];
+    lds_l[(wave * QB + qb) * 64 + lane] = lrun[qb];
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) lds_o[wave * O_FLOATS + ((qb * EB + eb) * 4 + i) * 64 + lane] = oacc[qb][eb][i];
+  }
+  __syncthreads();
+  // wavefront w finalises e blocks w, w + 4, ..
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    float mw[4], mall = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mw[w] = lds_m[(w * QB + qb) * 64 + lane];
+      mall = fmaxf(mall, mw[w]);
+    }
+    const float msafe = mall == -INFINITY ? 0.f : mall;
+    float fw[4], lsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      fw[w] = exp2f(mw[w] - msafe);
+      lsum += fw[w] * lds_l[(w * QB + qb) * 64 + lane];
+    }
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    const int m = m0 + qb * 16 + r16;
+    for (int eb = wave; eb < EB; eb += 4) {
+      float o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t += fw[w] * lds_o[w * O_FLOATS + ((qb * EB + eb) * 4 + i) * 64 + lane];
+        o[i] = t;
+      }
+      if (m < M) {
+        const int e0 = eb * 16 + g * 4;
+        if (nsplit == 1) {
+          const float inv = 1.0f / lsum;
+          bf16_t ob[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(o[i] * inv);
+          *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
+        } else {
+          float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
+          *(float4*)dst = make_float4(o[0], o[1], o[2], o[3]);
+        }
+      }
+    }
+    if (nsplit > 1 && wave == 0 && g == 0 && m < M) {
+      float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
+      ml[0] = mall;
+      ml[1] = lsum;
+    }
+  }
+}
+
+// out[m][h] = sum_s exp2(m_s - m*) O_s / sum_s exp2(m_s - m*) l_s, splits added in index order
+template <int HD>
+__global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplit, int M,
+                                  int Hq, bf16_t* __restrict__ out) {
+  const int m = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
+  float mall = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) mall = fmaxf(mall, part_ml[(((size_t)h * nsplit + s) * M + m) * 2]);
+  const float msafe = mall == -INFINITY ? 0.f : mall;
+  float l = 0.f, o = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t idx = ((size_t)h * nsplit + s) * M + m;
+    const float f = exp2f(part_ml[idx * 2] - msafe);
+    l += f * part_ml[idx * 2 + 1];
+    o += f * part_o[idx * HD + e];
+  }
+  out[(size_t)m * Hq * HD + (size_t)h * HD + e] = float_to_bf16(o / l);
+}
+
+int pick_qb(int M) { return M <= 16 ? 1 : 2; }
+
+int pick_splits(int M, int Hq, int S) {
+  const int qb = pick_qb(M);
+  const int groups = (M + qb * 16 - 1) / (qb * 16);
+  const int chunks = (S + 31) / 32;
+  int s = (256 + Hq * groups - 1) / (Hq * groups);
+  if (s > chunks / 4) s = chunks / 4;
+  if (s > kMaxSplits) s = kMaxSplits;
+  if (s < 1) s = 1;
+  return s;
+}
+
+template <int HD, int QB>
+void launch_t(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
+              int Hkv, bf16_t* out, void* scratch, int nsplit, hipStream_t s) {
+  const int groups = (M + QB * 16 - 1) / (QB * 16);
+  float* part_o = (float*)scratch;
+  float* part_ml = part_o + (size_t)Hq * kMaxSplits * M * HD;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+  hipLaunchKernelGGL((attn_mfma_kernel<HD, QB>), dim3(Hq, groups, nsplit), dim3(256), 0, s, q, kc, vc, cap, n, M, anc, Hq,
+                     Hkv, out, part_o, part_ml, nsplit, scale_log2);
+  if (nsplit > 1)
+    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, nsplit, M, Hq, out);
+}
+
+}  // namespace
+
 bool attn_mfma_supported(int M, int Hq, int Hkv, int hd) {
-  (void)M; (void)Hq; (void)Hkv; (void)hd;
-  return false;
+  return (hd == 64 || hd == 128) && M >= 1 && M <= kMaxTree && Hq % Hkv == 0;
 }
+
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
-  (void)M; (void)Hq; (void)hd;
-  return 256;
+  return ((size_t)Hq * kMaxSplits * M * hd + (size_t)Hq * kMaxSplits * M * 2) * sizeof(float) + 256;
 }
-hipError_t launch_attn_mfma(const void*, const void*, const void*, int, int, int, TreeDev, int, int, int, void*, void*,
-                            hipStream_t) {
-  return hipErrorNotSupported;
+
+hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
+                            int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
+  const int nsplit = pick_splits(M, Hq, n + M);
+  const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
+  bf16_t* op = (bf16_t*)out;
+  const int qb = pick_qb(M);
+  if (hd == 128) {
+    if (qb == 1) launch_t<128, 1>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
+    else launch_t<128, 2>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
+  } else {
+    if (qb == 1) launch_t<64, 1>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
+    else launch_t<64, 2>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace ht
