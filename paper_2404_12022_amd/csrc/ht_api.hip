@@ -95,7 +95,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   const size_t d = c.d_model, qd = (size_t)c.n_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
   b.x = cv.take<float>(Mp * d);
   b.u = cv.take_bytes(Mp * d * es);
-  b.qkv = cv.take<float>(Mp * (qd + 2 * kvd));
+  b.qkv = cv.take<float>((size_t)kMaxSplitK * Mp * (qd + 2 * kvd));
   b.q = cv.take_bytes(Mp * qd * es);
   b.attn = cv.take_bytes(Mp * qd * es);
   b.gu = cv.take<float>(Mp * 2 * c.d_ffn);
@@ -226,13 +226,15 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   for (int l = layer_from; l < c.n_layers; ++l) {
     float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
     HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
+    int qsplit = 1;
     if (m->packed) {
-      HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, 1, s));
+      qsplit = gemm_mfma_splits(M, qd + 2 * kvd, d);
+      HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, qsplit, s));
     } else {
       WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
       if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
     }
-    HT_HIP(launch_rope_append(c.dtype, b.qkv, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads, c.head_dim,
+    HT_HIP(launch_rope_append(c.dtype, b.qkv, qsplit, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads, c.head_dim,
                               c.max_cache, s));
     if ((rc = attention(m, l, n, M, tree, s))) return rc;
     if (m->packed) {
@@ -259,7 +261,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
                          c.rms_eps, s));
   if (logits) {
     if (m->packed) {
-      HT_HIP(launch_gemm_packed(b.u, b.p_head, M, logits, 1, s));
+      HT_HIP(launch_gemm_packed(b.u, b.p_head, M, logits, 1, s));      // vocab-sized N: never split
     } else if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, s))) {
       return rc;
     }

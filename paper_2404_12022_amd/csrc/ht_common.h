@@ -72,8 +72,9 @@ hipError_t launch_load_rows(const float* src, float* x, int M, int d, hipStream_
 hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
                            void* u, float* save_h, int M, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s);
-hipError_t launch_rope_append(int dtype, const float* qkv, const float* cs, void* q, void* kc, void* vc, int n, int M,
-                              int Hq, int Hkv, int hd, int cap, hipStream_t s);
+// qkv may be `nsplit` split-K partial sums of [M][(Hq + 2 Hkv) hd] each
+hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
+                              int n, int M, int Hq, int Hkv, int hd, int cap, hipStream_t s);
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
                                     void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
                                     hipStream_t s);

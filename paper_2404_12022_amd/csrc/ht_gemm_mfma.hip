@@ -222,6 +222,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   }
 }
 
+// Workgroup shape: 4 wavefronts; R = 2 row blocks per wavefront when that still leaves >= 90 workgroups,
+// else R = 1.  Measured on MI355X, every projection shape streams fastest with 170 .. 260 workgroups in
+// total, so split-K (gemm_mfma_splits) tops the grid up to about 256.
+int rows_per_wave(int N) { return N / 16 / 8 >= 90 ? 2 : 1; }
+
 template <int MT>
 hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, hipStream_t s) {
   const int n_rb = w.N / 16;
@@ -229,7 +234,7 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
   if (epi == EPI_SILU) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU>), dim3((n_rb + 7) / 8, 1), dim3(256), 0, s, a, w.p, M,
                        w.N, w.K, KS, out, 1);
-  } else if (w.N >= 8192) {
+  } else if (rows_per_wave(w.N) == 2) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a, w.p,
                        M, w.N, w.K, KS, out, nsplit);
   } else {
@@ -257,9 +262,9 @@ size_t packed_weight_bytes(int N, int K) { return (size_t)N * packed_cols(K) * s
 
 int gemm_mfma_splits(int M, int N, int K) {
   (void)M;
-  const int per_wg = N >= 8192 ? 128 : 64;
+  const int per_wg = 64 * rows_per_wave(N);
   const int tiles = (N + per_wg - 1) / per_wg;
-  int s = 512 / tiles;
+  int s = (256 + tiles / 2) / tiles;         // nearest grid to 256 workgroups
   const int chunks = (K + KC - 1) / KC;
   if (s > chunks / 4) s = chunks / 4;        // at least four chunks per split
   if (s > kMaxSplitK) s = kMaxSplitK;

@@ -83,32 +83,78 @@ hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, fl
 // ------------------------------------------------------------------------------------------------ residual + RMSNorm
 // x[m] += sum over split-K partials of the previous projection (fixed order: deterministic), the
 // updated residual is optionally saved (layer-t hidden states), then u[m] = x[m] * rsqrt(mean(x^2)+eps) * gain.
-template <typename T>
-__global__ void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int nsplit, size_t part_stride,
+// One block of NT threads per row, four consecutive columns per thread and pass, every load of a pass
+// issued before the first add so a row costs one memory round trip.
+__device__ inline float block_sum_any(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += red[w];
+  return t;
+}
+
+template <typename T, int NS>
+__global__ void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, size_t part_stride,
                                 const T* __restrict__ gain, T* __restrict__ u, float* __restrict__ save_h, int d,
                                 float eps) {
-  __shared__ float red[4];
+  __shared__ float red[16];
   const int m = blockIdx.x;
   float* xr = x + (size_t)m * d;
+  const float* pr = part + (size_t)m * d;
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += 256) {
-    float v = xr[c];
-    for (int sp = 0; sp < nsplit; ++sp) v += part[sp * part_stride + (size_t)m * d + c];
-    if (nsplit) xr[c] = v;
-    if (save_h) save_h[(size_t)m * d + c] = v;
-    ss += v * v;
+  constexpr int MAXP = 4;                       // d <= MAXP * 4 * blockDim.x (checked by the launcher)
+  float4 keep[MAXP];
+#pragma unroll
+  for (int p = 0; p < MAXP; ++p) {
+    const int c = (p * blockDim.x + threadIdx.x) * 4;
+    if (c < d) {
+      float4 v = *(const float4*)(xr + c);
+      float4 pv[NS > 0 ? NS : 1];
+#pragma unroll
+      for (int sp = 0; sp < NS; ++sp) pv[sp] = *(const float4*)(pr + sp * part_stride + c);
+#pragma unroll
+      for (int sp = 0; sp < NS; ++sp) { v.x += pv[sp].x; v.y += pv[sp].y; v.z += pv[sp].z; v.w += pv[sp].w; }
+      if (NS) *(float4*)(xr + c) = v;
+      if (save_h) *(float4*)(save_h + (size_t)m * d + c) = v;
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      keep[p] = v;
+    }
   }
-  ss = block_sum_256(ss, red);
+  ss = block_sum_any(ss, red);
   const float scale = 1.0f / sqrtf(ss / (float)d + eps);
   if (u) {
-    for (int c = threadIdx.x; c < d; c += 256)
-      Conv<T>::store(u + (size_t)m * d + c, xr[c] * scale * Conv<T>::load(gain + c));
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+      const int c = (p * blockDim.x + threadIdx.x) * 4;
+      if (c < d) {
+        const float4 v = keep[p];
+        T* dst = u + (size_t)m * d + c;
+        Conv<T>::store(dst + 0, v.x * scale * Conv<T>::load(gain + c + 0));
+        Conv<T>::store(dst + 1, v.y * scale * Conv<T>::load(gain + c + 1));
+        Conv<T>::store(dst + 2, v.z * scale * Conv<T>::load(gain + c + 2));
+        Conv<T>::store(dst + 3, v.w * scale * Conv<T>::load(gain + c + 3));
+      }
+    }
   }
 }
 hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
                            void* u, float* save_h, int M, int d, float eps, hipStream_t s) {
-  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(add_norm_kernel<T>, dim3(M), dim3(256), 0, s, x, part, nsplit,
-                                              part_stride, (const T*)gain, (T*)u, save_h, d, eps);)
+  if (d % 4 || nsplit < 0 || nsplit > kMaxSplitK) return hipErrorInvalidValue;
+  int nt = 64;
+  while (nt < 1024 && nt * 4 < d) nt *= 2;
+  if (d > 16 * nt) return hipErrorInvalidValue;
+#define HT_ADD_NORM(NS)                                                                                         \
+  case NS:                                                                                                      \
+    hipLaunchKernelGGL((add_norm_kernel<T, NS>), dim3(M), dim3(nt), 0, s, x, part, part_stride, (const T*)gain, \
+                       (T*)u, save_h, d, eps);                                                                  \
+    break;
+  HT_DISPATCH_DTYPE(dtype, switch (nsplit) {
+    HT_ADD_NORM(0) HT_ADD_NORM(1) HT_ADD_NORM(2) HT_ADD_NORM(3) HT_ADD_NORM(4) HT_ADD_NORM(5) HT_ADD_NORM(6)
+    HT_ADD_NORM(7) HT_ADD_NORM(8)
+  })
+#undef HT_ADD_NORM
   return hipGetLastError();
 }
 
@@ -132,18 +178,23 @@ hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int 
 
 // Rotates q and k of row m at its tree position and appends k, v to cache slot n+m.
 // Layouts: q[M][Hq][hd]; K cache [cap][Hkv][hd]; V cache [Hkv][hd][cap] (key index contiguous).
+// The inputs may come as `nsplit` split-K partial sums `split_stride` elements apart (added in index order).
 template <typename T, typename TIN>
 __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in,
-                                   int k_stride, const TIN* __restrict__ v_in, int v_stride,
-                                   const float2* __restrict__ cs, T* __restrict__ q, T* __restrict__ kc,
-                                   T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap) {
+                                   int k_stride, const TIN* __restrict__ v_in, int v_stride, int nsplit,
+                                   size_t split_stride, const float2* __restrict__ cs, T* __restrict__ q,
+                                   T* __restrict__ kc, T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap) {
   const int m = blockIdx.x, hh = blockIdx.y, j = threadIdx.x, half = hd / 2;
   if (j >= half) return;
   const float2 c = cs[(size_t)m * half + j];
   if (hh < Hq + Hkv) {
     const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
                              : k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd;
-    const float a = Conv<TIN>::load(src + j), b = Conv<TIN>::load(src + j + half);
+    float a = Conv<TIN>::load(src + j), b = Conv<TIN>::load(src + j + half);
+    for (int sp = 1; sp < nsplit; ++sp) {
+      a += Conv<TIN>::load(src + sp * split_stride + j);
+      b += Conv<TIN>::load(src + sp * split_stride + j + half);
+    }
     const float ra = a * c.x - b * c.y, rb = b * c.x + a * c.y;
     T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
     Conv<T>::store(dst + j, ra);
@@ -151,17 +202,22 @@ __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, c
   } else {
     const int h = hh - Hq - Hkv;
     const TIN* src = v_in + (size_t)m * v_stride + (size_t)h * hd;
-    Conv<T>::store(vc + ((size_t)h * hd + j) * cap + n + m, Conv<TIN>::load(src + j));
-    Conv<T>::store(vc + ((size_t)h * hd + j + half) * cap + n + m, Conv<TIN>::load(src + j + half));
+    float a = Conv<TIN>::load(src + j), b = Conv<TIN>::load(src + j + half);
+    for (int sp = 1; sp < nsplit; ++sp) {
+      a += Conv<TIN>::load(src + sp * split_stride + j);
+      b += Conv<TIN>::load(src + sp * split_stride + j + half);
+    }
+    Conv<T>::store(vc + ((size_t)h * hd + j) * cap + n + m, a);
+    Conv<T>::store(vc + ((size_t)h * hd + j + half) * cap + n + m, b);
   }
 }
-hipError_t launch_rope_append(int dtype, const float* qkv, const float* cs, void* q, void* kc, void* vc, int n, int M,
-                              int Hq, int Hkv, int hd, int cap, hipStream_t s) {
+hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
+                              int n, int M, int Hq, int Hkv, int hd, int cap, hipStream_t s) {
   const int stride = (Hq + 2 * Hkv) * hd;
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
                                               s, qkv, stride, qkv + (size_t)Hq * hd, stride,
-                                              qkv + (size_t)(Hq + Hkv) * hd, stride, (const float2*)cs, (T*)q, (T*)kc,
-                                              (T*)vc, n, Hq, Hkv, hd, cap);)
+                                              qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride,
+                                              (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap);)
   return hipGetLastError();
 }
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
@@ -169,7 +225,7 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
                                     hipStream_t s) {
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
                                               (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
-                                              Hkv * hd, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,
+                                              Hkv * hd, 1, (size_t)0, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,
                                               cap);)
   return hipGetLastError();
 }
