@@ -280,6 +280,35 @@ def test_error_codes():
 
 
 # ------------------------------------------------------------------ large shapes
+def _shallow_case(name, prompt_len, tree_size=None, cache=None):
+    """Full widths of a named workload (the launch configurations the benchmark uses), depth cut to 2 layers and
+    the prompt shortened so that the fp64 oracle finishes in seconds."""
+    H = _H()
+    base = WORKLOADS[name]
+    T = tree_size or base.tree_size
+    wl = base.with_(n_layers=2, transfer_layers=tuple(1 for _ in range(base.k)), prompt_len=prompt_len,
+                    max_cache=cache or (prompt_len + 2 * T + 8) // 8 * 8, tree_size=T)
+    say(f"{name} width, 2 layers, T={T}, n={prompt_len}: generating weights")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    say(f"{name}: oracle + gpu")
+    sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors)
+    sc.check_prefill()
+    r = sc.step(require_same_tokens=False)
+    say(f"{name}: emitted {r['emitted']} oracle {r['oracle']['emitted']} worst logit error / bound {sc.max_err:.3f}")
+    sc.check_cache("after one step")
+    sc.gpu.close()
+
+
+@pytest.mark.parametrize("tree_size", [1, 16, 32, 64, 128])
+def test_llama13b_width_tree_size_sweep(tree_size):
+    _shallow_case("llama13b", 96, tree_size=tree_size)
+
+
+def test_llama70b_width_grouped_query_attention():
+    _shallow_case("llama70b", 80)
+
+
 def test_llama7b_width_two_layers_against_oracle():
     """Full 7B widths (d 4096, 32x128 heads, FFN 11008, vocab 32000), 64-node tree, cache 512, the launch
     configuration the benchmark times; depth cut to 2 layers so the fp64 oracle finishes in seconds."""
