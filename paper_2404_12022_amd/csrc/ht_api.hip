@@ -184,6 +184,7 @@ struct ht_model {
   bool use_mfma = true;
   bool packed = false;          // bf16 projections run on the repacked weights
   std::vector<int32_t> depth;
+  int max_width = 1;           // most candidates any pseudo position must supply
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
   StepState* h_state = nullptr;
@@ -265,7 +266,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
     } else if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, s))) {
       return rc;
     }
-    HT_HIP(launch_argmax(logits, gout, M, c.vocab, s));
+    if (gout) HT_HIP(launch_argmax(logits, gout, M, c.vocab, s));
   }
   return HT_OK;
 }
@@ -443,6 +444,9 @@ int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* ra
   HT_HIP(hipMemcpyAsync(m->b.width, width, sizeof(int32_t) * (kMaxTransfer + 2), hipMemcpyHostToDevice, s));
   HT_HIP(hipStreamSynchronize(s));
   m->depth.assign(depth, depth + T);
+  m->max_width = 1;
+  for (int e = 0; e < kMaxTransfer + 2; ++e)
+    if (width[e] > m->max_width) m->max_width = width[e];
   m->T = T;
   m->has_tree = true;
   m->verify_done = false;
@@ -507,8 +511,8 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
     // draft: pseudo rows through blocks t+1..L as a chain at positions n, n+1, ..; their K/V land in
     // slots n.. and are overwritten by the verify pass below
     HT_HIP(launch_load_rows(b.pseudo, b.x, c.k, c.d_model, s));
-    if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, b.g, s))) return rc;
-    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, c.k, c.vocab, s));
+    if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, nullptr, s))) return rc;
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, m->max_width, c.k, c.vocab, s));
     HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
   } else {
     HT_HIP(hipMemcpyAsync(b.tok, tree_tokens, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));

@@ -249,7 +249,8 @@ hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int M, int f, 
 // (value, id) order: larger value first, lower id first on equal values.  NaN never wins.
 __device__ inline bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-__device__ inline void block_best_256(float& v, int& i, float* sv, int* si) {
+// block-wide best for any block size that is a multiple of 64 (<= 1024); sv/si hold 16 entries
+__device__ inline void block_best_any(float& v, int& i, float* sv, int* si) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     float ov = __shfl_xor(v, o, 64);
@@ -260,57 +261,86 @@ __device__ inline void block_best_256(float& v, int& i, float* sv, int* si) {
   if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = v; si[threadIdx.x >> 6] = i; }
   __syncthreads();
   v = sv[0]; i = si[0];
-#pragma unroll
-  for (int w = 1; w < 4; ++w)
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
     if (better(sv[w], si[w], v, i)) { v = sv[w]; i = si[w]; }
 }
 
-__global__ void argmax_kernel(const float* __restrict__ z, int32_t* __restrict__ g, int V) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+// g[row] = arg-max of a logit row, lowest id on ties.  1024 threads per row, 16-byte loads.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ z, int32_t* __restrict__ g, int V,
+                                                      int vec) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const float* row = z + (size_t)blockIdx.x * V;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int j = threadIdx.x; j < V; j += 256) {
-    float v = row[j];
-    if (better(v, j, bv, bi)) { bv = v; bi = j; }
+  const int v4 = vec ? (V & ~3) : 0;            // vec: rows are 16-byte aligned
+  for (int j = threadIdx.x * 4; j < v4; j += blockDim.x * 4) {
+    const float4 q = *(const float4*)(row + j);
+    if (better(q.x, j, bv, bi)) { bv = q.x; bi = j; }
+    if (better(q.y, j + 1, bv, bi)) { bv = q.y; bi = j + 1; }
+    if (better(q.z, j + 2, bv, bi)) { bv = q.z; bi = j + 2; }
+    if (better(q.w, j + 3, bv, bi)) { bv = q.w; bi = j + 3; }
   }
-  block_best_256(bv, bi, sv, si);
+  for (int j = v4 + threadIdx.x; j < V; j += blockDim.x)
+    if (better(row[j], j, bv, bi)) { bv = row[j]; bi = j; }
+  block_best_any(bv, bi, sv, si);
   if (threadIdx.x == 0) g[blockIdx.x] = bi == 0x7fffffff ? 0 : bi;
 }
 hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s) {
-  hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, z, g, V);
+  const int vec = !((uintptr_t)z & 15) && !(V & 3);
+  hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(1024), 0, s, z, g, V, vec);
   return hipGetLastError();
 }
 
-// cand[i][r], r < width[i+1]: the r-th entry of logit row i in (value desc, id asc) order.  Selection
-// by repeated arg-best over the entries that come strictly after the previous pick in that order.
-__global__ void topk_kernel(const float* __restrict__ d, int32_t* __restrict__ cand, const int32_t* __restrict__ width,
-                            int V) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+// cand[i][r], r < width[i+1]: the r-th entry of logit row i in (value desc, id asc) order.
+// One pass over the row: every thread keeps the best LOCAL entries of its strided slice sorted in
+// registers (LOCAL >= b makes this exact: no slice can contribute more than b of the top b), then b
+// rounds of block-wide arg-best over the heads of the per-thread lists pop the winners in order.
+template <int LOCAL>
+__global__ __launch_bounds__(1024) void topk_kernel(const float* __restrict__ d, int32_t* __restrict__ cand,
+                                                    const int32_t* __restrict__ width, int V) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const int i = blockIdx.x;
   const float* row = d + (size_t)i * V;
   const int b = width[i + 1];
-  float pv = INFINITY;
-  int pi = -1;
-  for (int r = 0; r < b; ++r) {
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int j = threadIdx.x; j < V; j += 256) {
-      float v = row[j];
-      bool after = r == 0 || v < pv || (v == pv && j > pi);
-      if (after && better(v, j, bv, bi)) { bv = v; bi = j; }
+  float lv[LOCAL];
+  int li[LOCAL];
+#pragma unroll
+  for (int t = 0; t < LOCAL; ++t) { lv[t] = -INFINITY; li[t] = 0x7fffffff; }
+  for (int j = threadIdx.x; j < V; j += blockDim.x) {
+    float v = row[j];
+    int id = j;
+    if (better(v, id, lv[LOCAL - 1], li[LOCAL - 1])) {
+#pragma unroll
+      for (int t = 0; t < LOCAL; ++t) {          // insertion by a chain of compare-exchanges
+        if (better(v, id, lv[t], li[t])) {
+          const float tv = lv[t]; const int ti = li[t];
+          lv[t] = v; li[t] = id;
+          v = tv; id = ti;
+        }
+      }
     }
-    block_best_256(bv, bi, sv, si);
-    if (bi == 0x7fffffff) bi = 0;
-    if (threadIdx.x == 0) cand[i * kMaxTopK + r] = bi;
-    pv = bv; pi = bi;
+  }
+  for (int r = 0; r < b; ++r) {
+    float bv = lv[0];
+    int bi = li[0];
+    block_best_any(bv, bi, sv, si);
+    if (li[0] == bi && bi != 0x7fffffff) {       // the winner pops its head
+#pragma unroll
+      for (int t = 0; t + 1 < LOCAL; ++t) { lv[t] = lv[t + 1]; li[t] = li[t + 1]; }
+      lv[LOCAL - 1] = -INFINITY;
+      li[LOCAL - 1] = 0x7fffffff;
+    }
+    if (threadIdx.x == 0) cand[i * kMaxTopK + r] = bi == 0x7fffffff ? 0 : bi;
     __syncthreads();
   }
 }
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int k, int V, hipStream_t s) {
-  hipLaunchKernelGGL(topk_kernel, dim3(k), dim3(256), 0, s, d, cand, width, V);
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int max_width, int k, int V,
+                       hipStream_t s) {
+  if (max_width <= 4) hipLaunchKernelGGL(topk_kernel<4>, dim3(k), dim3(1024), 0, s, d, cand, width, V);
+  else if (max_width <= 16) hipLaunchKernelGGL(topk_kernel<16>, dim3(k), dim3(1024), 0, s, d, cand, width, V);
+  else hipLaunchKernelGGL(topk_kernel<kMaxTopK>, dim3(k), dim3(256), 0, s, d, cand, width, V);
   return hipGetLastError();
 }
 

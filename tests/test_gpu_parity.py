@@ -216,6 +216,24 @@ def test_forced_acceptance_every_root_path(name):
             sc.gpu.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "tiny_bf16"])
+def test_exactly_tied_logits_resolve_to_lowest_ids(name):
+    """LM head with only 64 distinct rows tiled over the vocabulary: every logit value occurs 16 times, so every
+    arg-max and every top-k decision is a tie that must resolve by token id."""
+    H = _H()
+    wl = WORKLOADS[name]
+    say(f"tied logits {name}")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch_dtype(wl))
+    tensors["lm_head"] = tensors["lm_head"][:64].repeat(wl.vocab // 64, 1).contiguous()
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors)
+    for _ in range(4):
+        r = sc.step(require_same_tokens=(wl.dtype == "f32"))
+        assert all(t < 64 for t in r["emitted"]) and r["root"] < 64          # lowest id of each tie class
+        cand = sc.gpu.ht_get_buffer(_B().HT_BUF_CANDIDATES).cpu().numpy()
+        assert cand[0][1] == cand[0][0] + 64                                  # second best = same value, next id
+
+
 def test_one_token_tree_is_a_plain_decode_step():
     H = _H()
     wl = WORKLOADS["tiny"]
