@@ -183,6 +183,7 @@ struct ht_model {
   bool has_tree = false, has_prefill = false, transfer_ready = false, verify_done = false;
   bool use_mfma = true;
   bool packed = false;          // bf16 projections run on the repacked weights
+  bool qkv_fused = false;       // rotary + KV append run in the QKV projection's epilogue
   std::vector<int32_t> depth;
   int max_width = 1;           // most candidates any pseudo position must supply
   // pinned host staging
@@ -227,16 +228,22 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   for (int l = layer_from; l < c.n_layers; ++l) {
     float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
     HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
-    int qsplit = 1;
-    if (m->packed) {
-      qsplit = gemm_mfma_splits(M, qd + 2 * kvd, d);
-      HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, qsplit, s));
+    if (m->qkv_fused) {
+      QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
+                     c.max_cache};
+      HT_HIP(launch_gemm_packed_qkv(b.u, b.p_qkv[l], M, qe, s));
     } else {
-      WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
-      if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
+      int qsplit = 1;
+      if (m->packed) {
+        qsplit = gemm_mfma_splits(M, qd + 2 * kvd, d);
+        HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, qsplit, s));
+      } else {
+        WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
+        if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
+      }
+      HT_HIP(launch_rope_append(c.dtype, b.qkv, qsplit, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads,
+                                c.head_dim, c.max_cache, s));
     }
-    HT_HIP(launch_rope_append(c.dtype, b.qkv, qsplit, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads, c.head_dim,
-                              c.max_cache, s));
     if ((rc = attention(m, l, n, M, tree, s))) return rc;
     if (m->packed) {
       pending = gemm_mfma_splits(M, d, qd);
@@ -389,15 +396,17 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init allocation/clear failed: %s", hipGetErrorString(e)));
 
   m->packed = m->use_mfma && shapes_packable(*cfg);
+  m->qkv_fused = m->packed && qkv_fusable(cfg->head_dim);
   if (m->packed) {
     const int qd = cfg->n_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim, d = cfg->d_model, f = cfg->d_ffn;
     for (int l = 0; l < L && e == hipSuccess; ++l) {
-      e = launch_repack(WeightSegs{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3}, d, 0, (void*)m->b.p_qkv[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->wo[l], nullptr, nullptr}, {d, 0, 0}, 1}, qd, 0, (void*)m->b.p_o[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2}, d, 1, (void*)m->b.p_gu[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_down[l], nullptr, nullptr}, {d, 0, 0}, 1}, f, 0, (void*)m->b.p_down[l].p, s);
+      e = launch_repack(WeightSegs{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3}, d, m->qkv_fused ? 2 : 0, cfg->head_dim,
+                        (void*)m->b.p_qkv[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->wo[l], nullptr, nullptr}, {d, 0, 0}, 1}, qd, 0, 0, (void*)m->b.p_o[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2}, d, 1, 0, (void*)m->b.p_gu[l].p, s);
+      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_down[l], nullptr, nullptr}, {d, 0, 0}, 1}, f, 0, 0, (void*)m->b.p_down[l].p, s);
     }
-    if (e == hipSuccess) e = launch_repack(WeightSegs{{m->lm_head, nullptr, nullptr}, {cfg->vocab, 0, 0}, 1}, d, 0, (void*)m->b.p_head.p, s);
+    if (e == hipSuccess) e = launch_repack(WeightSegs{{m->lm_head, nullptr, nullptr}, {cfg->vocab, 0, 0}, 1}, d, 0, 0, (void*)m->b.p_head.p, s);
     if (e != hipSuccess) return cleanup(fail(HT_EHIP, "weight repack failed: %s", hipGetErrorString(e)));
   }
 
@@ -661,7 +670,7 @@ size_t ht_weight_pack_bytes(int32_t N, int32_t K) {
 int ht_weight_pack(const void* w, int32_t N, int32_t K, void* packed, void* stream) {
   if (!w || !packed) return fail(HT_EINVAL, "NULL argument");
   if (!ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "packing needs N %% 16 == 0 and K %% 8 == 0 (N=%d K=%d)", N, K);
-  HT_HIP(launch_repack(segs1(w, N), K, 0, packed, (hipStream_t)stream));
+  HT_HIP(launch_repack(segs1(w, N), K, 0, 0, packed, (hipStream_t)stream));
   return HT_OK;
 }
 

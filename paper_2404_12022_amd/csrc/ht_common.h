@@ -107,12 +107,22 @@ int packed_cols(int K);
 size_t packed_weight_bytes(int N, int K);
 int gemm_mfma_splits(int M, int N, int K);
 // mode 0: row blocks in natural order over the concatenated segments; mode 1: two equal segments
-// interleaved block by block (gate block i, up block i, gate block i+1, ..)
-hipError_t launch_repack(WeightSegs w, int K, int mode, void* dst, hipStream_t s);
+// interleaved block by block (gate block i, up block i, gate block i+1, ..); mode 2: segments (q, k, v), in
+// every q and k head the 16-row block p is followed by its rotary partner block p + head_dim/32
+hipError_t launch_repack(WeightSegs w, int K, int mode, int head_dim, void* dst, hipStream_t s);
 // out[s][m][n], s < nsplit (split-K partial sums, fp32)
 hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s);
 // w packed with mode 1 from (gate, up): act[m][j] = silu(a.gate_j) * (a.up_j), bf16 [M][N/2]
 hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s);
+// w packed with mode 2 from (q, k, v): rotary at the row's position, q rows to `q`, k/v rows appended to the
+// caches at slot n + m (all bf16); cs is the (cos, sin) table [M][hd/2]
+struct QkvEpilogue {
+  const float* cs;
+  bf16_t *q, *kc, *vc;
+  int32_t n, Hq, Hkv, hd, cap;
+};
+bool qkv_fusable(int head_dim);
+hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s);
 
 // attention over cache + tree rows; out[m][h*hd+e] in dtype
 hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,

@@ -42,11 +42,12 @@ union Frag {
   bf16x8_t v;
 };
 
-enum { EPI_F32 = 0, EPI_SILU = 1 };
+enum { EPI_F32 = 0, EPI_SILU = 1, EPI_QKV = 2 };
 
 // --------------------------------------------------------------------------------------------- repack
 // dst fragment order from row-major segments.  One thread per 16-byte piece.
-__global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, bf16_t* __restrict__ dst) {
+__global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, int head_blocks,
+                              bf16_t* __restrict__ dst) {
   const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int n_tiles = (n_rb + kTileBlocks - 1) / kTileBlocks;
   const size_t total = (size_t)n_tiles * KS * kTileBlocks * 64;
@@ -63,6 +64,17 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, b
     if (mode == 1) {               // two equal segments interleaved block by block (gate, up)
       seg = rb & 1;
       src_rb = rb >> 1;
+    } else if (mode == 2) {        // q | k | v: inside every q and k head, block p is followed by block p + hb/2
+      const int hb = head_blocks;  // (the rotary partner rows), v heads keep their order
+      const int qk_rbs = (w.rows[0] + w.rows[1]) / 16;
+      int r2 = rb;
+      if (rb < qk_rbs) {
+        const int in_head = rb % hb, head0 = rb - in_head;
+        r2 = head0 + (in_head >> 1) + (in_head & 1) * (hb / 2);
+      }
+      seg = 0;
+      src_rb = r2;
+      while (seg + 1 < w.nseg && src_rb * 16 >= w.rows[seg]) { src_rb -= w.rows[seg] / 16; ++seg; }
     } else {                       // natural order over the concatenated segments
       seg = 0;
       src_rb = rb;
@@ -84,7 +96,8 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, b
 template <int MT, int R, int WAVES, int EPI, int KC = kChunkCols, int PD = kRingDepth>
 __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
                                                                  const bf16_t* __restrict__ wp, int M, int N, int K,
-                                                                 int KS, void* __restrict__ outp, int nsplit) {
+                                                                 int KS, void* __restrict__ outp, int nsplit,
+                                                                 QkvEpilogue qe) {
   constexpr int STEPS = KC / 32;                         // MFMA steps per chunk
   constexpr int ROWB = KC * 2 + 16;                      // LDS row stride in bytes (padded: conflict-free b128 reads)
   constexpr int THREADS = 64 * WAVES;
@@ -215,7 +228,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
           *(float4*)(dst + (size_t)m * N + n0) = make_float4(acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]);
       }
     }
-  } else {
+  } else if (EPI == EPI_SILU) {
     // row block rb0 holds gate rows, rb0 + 1 the matching up rows: act = silu(gate) * up, bf16
     if (rb0 + 1 < n_rb) {
       bf16_t* dst = (bf16_t*)outp;
@@ -235,6 +248,56 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
         }
       }
     }
+  } else {
+    // q | k | v rows packed so that a wavefront holds features j (block rb0) and j + hd/2 (block rb0 + 1) of one
+    // q or k head: rotate the pair by the row's position and store q, or append k to the cache; v rows are
+    // appended to the slot-contiguous value cache.
+    if (rb0 + 1 < n_rb) {
+      const int hd = qe.hd, half = hd / 2, pp = hd / 32;       // pp: block pairs per head
+      int P = rb0 / 2;
+      const int q_pairs = qe.Hq * pp, k_pairs = qe.Hkv * pp;
+      if (P < q_pairs + k_pairs) {
+        const bool is_q = P < q_pairs;
+        if (!is_q) P -= q_pairs;
+        const int h = P / pp, j = (P % pp) * 16 + g * 4;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = mt * 16 + r16;
+          if (m < M) {
+            const float4 c01 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2);
+            const float4 c23 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2 + 4);
+            const float cs_[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+            bf16_t lo[4], hi[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float x = acc[0][mt][i], y = acc[1][mt][i], co = cs_[2 * i], si = cs_[2 * i + 1];
+              lo[i] = float_to_bf16(x * co - y * si);
+              hi[i] = float_to_bf16(y * co + x * si);
+            }
+            bf16_t* dst = is_q ? qe.q + ((size_t)m * qe.Hq + h) * hd + j
+                               : qe.kc + ((size_t)(qe.n + m) * qe.Hkv + h) * hd + j;
+            *(uint2*)dst = *(const uint2*)lo;
+            *(uint2*)(dst + half) = *(const uint2*)hi;
+          }
+        }
+      } else {
+        P -= q_pairs + k_pairs;
+        const int hb = hd / 16;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const int vb = 2 * P + r, h = vb / hb, e0 = (vb % hb) * 16 + g * 4;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + r16;
+            if (m < M) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                qe.vc[((size_t)h * hd + e0 + i) * qe.cap + qe.n + m] = float_to_bf16(acc[r][mt][i]);
+            }
+          }
+        }
+      }
+    }
   }
 }
 
@@ -244,29 +307,34 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 int rows_per_wave(int N) { return N / 16 / 8 >= 90 ? 2 : 1; }
 
 template <int MT>
-hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, hipStream_t s) {
+hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
+                     hipStream_t s) {
   const int n_rb = w.N / 16;
   const int KS = w.Kp / 32;
   constexpr int KC = MT == 1 ? 128 : kChunkCols;     // the chunk must give every thread at least one 16-byte piece
   if (epi == EPI_SILU) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU, KC>), dim3((n_rb + 7) / 8, 1), dim3(256), 0, s, a, w.p,
-                       M, w.N, w.K, KS, out, 1);
+                       M, w.N, w.K, KS, out, 1, qe);
+  } else if (epi == EPI_QKV) {
+    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 2, EPI_QKV, KC>), dim3((n_rb + 3) / 4, 1), dim3(128), 0, s, a, w.p,
+                       M, w.N, w.K, KS, out, 1, qe);
   } else if (rows_per_wave(w.N) == 2) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
   } else {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32, KC>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsplit, int epi, hipStream_t s) {
+hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
+                      hipStream_t s) {
   const bf16_t* ap = (const bf16_t*)a;
-  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, s);
-  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, s);
-  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, s);
-  return launch_mt<8>(ap, w, M, out, nsplit, epi, s);
+  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, s);
+  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, s);
+  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, s);
+  return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, s);
 }
 
 }  // namespace
@@ -292,22 +360,28 @@ int gemm_mfma_splits(int M, int N, int K) {
   return s;
 }
 
-hipError_t launch_repack(WeightSegs w, int K, int mode, void* dst, hipStream_t s) {
+hipError_t launch_repack(WeightSegs w, int K, int mode, int head_dim, void* dst, hipStream_t s) {
   int rows = 0;
   for (int i = 0; i < w.nseg; ++i) rows += w.rows[i];
   const int n_rb = rows / 16, KS = packed_cols(K) / 32;
   const size_t pieces = (size_t)((n_rb + kTileBlocks - 1) / kTileBlocks) * kTileBlocks * KS * 64;
   hipLaunchKernelGGL(repack_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, w, K, KS, n_rb, mode,
-                     (bf16_t*)dst);
+                     head_dim / 16, (bf16_t*)dst);
   return hipGetLastError();
 }
 
 hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s) {
-  return launch_any(a, w, M, out, nsplit, EPI_F32, s);
+  return launch_any(a, w, M, out, nsplit, EPI_F32, QkvEpilogue{}, s);
 }
 
 hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s) {
-  return launch_any(a, w, M, act, 1, EPI_SILU, s);
+  return launch_any(a, w, M, act, 1, EPI_SILU, QkvEpilogue{}, s);
+}
+
+bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
+
+hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s) {
+  return launch_any(a, w, M, nullptr, 1, EPI_QKV, qe, s);
 }
 
 }  // namespace ht
