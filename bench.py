@@ -230,7 +230,7 @@ def main():
         "one_token_hbm_GBps": round(one_bytes / (ms_one * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(),
-                     "kernel": (f"gemm_packed_kernel<MT=4,R=2,WAVES=4,EPI_F32> at the gate/up projection shape "
+                     "kernel": (f"gemm_packed_kernel<MT=4,R=2,WAVES=3,EPI_F32,KC=128> at the gate/up projection shape "
                                 f"M={kern['M']} N={kern['N']} K={kern['K']}"),
                      "bytes_per_launch": kern["bytes"], "ms_per_launch": round(kern["ms"], 5)},
     }

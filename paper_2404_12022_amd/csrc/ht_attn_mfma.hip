@@ -17,6 +17,7 @@
 // keys; the wavefronts take 32-key chunks round-robin and merge (max, sum, O) through LDS.  With more than
 // one key slice the merged partials go to scratch and a small kernel combines them.
 #include "ht_common.h"
+#include <cstdlib>
 
 namespace ht {
 
@@ -289,7 +290,8 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
-  const int nsplit = pick_splits(M, Hq, n + M);
+  int nsplit = pick_splits(M, Hq, n + M);
+  if (const char* e = getenv("HT_ATTN_SPLITS")) nsplit = atoi(e);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
   bf16_t* op = (bf16_t*)out;
   const int qb = pick_qb(M);

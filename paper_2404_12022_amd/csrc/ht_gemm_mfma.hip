@@ -103,8 +103,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   constexpr int THREADS = 64 * WAVES;
   constexpr int ROWS = MT * 16;
   constexpr int PIECES = ROWS * (KC / 8);                // 16-byte pieces of the activation chunk
-  static_assert(PIECES % THREADS == 0, "activation chunk must divide evenly over the threads");
-  constexpr int APASS = PIECES / THREADS;
+  static_assert(PIECES >= THREADS, "every thread stages at least one piece of the activation chunk");
+  constexpr int APASS = (PIECES + THREADS - 1) / THREADS;   // surplus threads of the last pass repeat the last piece
   constexpr int STAGE = ROWS * ROWB;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
 
@@ -139,7 +139,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   int acol[APASS], alds[APASS];
 #pragma unroll
   for (int i = 0; i < APASS; ++i) {
-    const int p = tid + i * THREADS;
+    int p = tid + i * THREADS;
+    p = p < PIECES ? p : PIECES - 1;
     arow[i] = a + (size_t)(p / (KC / 8)) * K;
     acol[i] = (p % (KC / 8)) * 8;
     alds[i] = (p / (KC / 8)) * ROWB + (p % (KC / 8)) * 16;
@@ -301,10 +302,13 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   }
 }
 
-// Workgroup shape: 4 wavefronts; R = 2 row blocks per wavefront when that still leaves >= 90 workgroups,
-// else R = 1.  Measured on MI355X, every projection shape streams fastest with 170 .. 260 workgroups in
-// total, so split-K (gemm_mfma_splits) tops the grid up to about 256.
+// Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 90 workgroups, else R = 1.
+// Every workgroup re-reads the whole activation panel, and a compute unit ingests only ~45 GB/s (measured,
+// weights + panel), so the fastest grid is the one closest to one workgroup on each of the 256 compute
+// units: 3 wavefronts (6 row blocks) per workgroup when that gives <= 260 workgroups, else 4 (8 row
+// blocks); split-K (gemm_mfma_splits) tops small-N grids up to about 256.
 int rows_per_wave(int N) { return N / 16 / 8 >= 90 ? 2 : 1; }
+int waves_per_group(int n_rb) { return (n_rb + 5) / 6 <= 260 ? 3 : 4; }
 
 template <int MT>
 hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
@@ -312,15 +316,27 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
   const int n_rb = w.N / 16;
   const int KS = w.Kp / 32;
   constexpr int KC = MT == 1 ? 128 : kChunkCols;     // the chunk must give every thread at least one 16-byte piece
-  if (epi == EPI_SILU) {
-    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU, KC>), dim3((n_rb + 7) / 8, 1), dim3(256), 0, s, a, w.p,
-                       M, w.N, w.K, KS, out, 1, qe);
+  if (epi == EPI_SILU || (epi == EPI_F32 && rows_per_wave(w.N) == 2)) {
+    const bool three = waves_per_group(n_rb) == 3;
+    const dim3 grid(three ? (n_rb + 5) / 6 : (n_rb + 7) / 8, epi == EPI_SILU ? 1 : nsplit);
+    if (epi == EPI_SILU) {
+      if (three)
+        hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_SILU, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
+                           out, 1, qe);
+      else
+        hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
+                           out, 1, qe);
+    } else {
+      if (three)
+        hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_F32, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
+                           out, nsplit, qe);
+      else
+        hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
+                           out, nsplit, qe);
+    }
   } else if (epi == EPI_QKV) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 2, EPI_QKV, KC>), dim3((n_rb + 3) / 4, 1), dim3(128), 0, s, a, w.p,
                        M, w.N, w.K, KS, out, 1, qe);
-  } else if (rows_per_wave(w.N) == 2) {
-    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
   } else {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32, KC>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a,
                        w.p, M, w.N, w.K, KS, out, nsplit, qe);
@@ -350,8 +366,9 @@ size_t packed_weight_bytes(int N, int K) {
 
 int gemm_mfma_splits(int M, int N, int K) {
   (void)M;
-  const int per_wg = 64 * rows_per_wave(N);
-  const int tiles = (N + per_wg - 1) / per_wg;
+  const int n_rb = N / 16;
+  const int per_wg = rows_per_wave(N) == 2 ? 2 * waves_per_group(n_rb) : 4;      // row blocks per workgroup
+  const int tiles = (n_rb + per_wg - 1) / per_wg;
   int s = (256 + tiles / 2) / tiles;         // nearest grid to 256 workgroups
   const int chunks = (K + 127) / 128;
   if (s > chunks / 4) s = chunks / 4;        // at least 512 columns per split
