@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tree-sizes", default="",
+                    help="comma-separated tree sizes: adds a `sweep` list of verify-pass latencies at the same cache")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop plus a device copy of known size (for rocprofv3 runs)")
     args = ap.parse_args()
@@ -161,14 +163,33 @@ def main():
         k = time_dominant_kernel(wl, wl.tree_size, dev, tdt0, torch.cuda.current_stream(), calibrate=True)
         print(json.dumps({"kernel_ms": k["ms"], "bytes": k["bytes"], "GBps": k["bytes"] / (k["ms"] * 1e-3) / 1e9}))
         return
-    headroom = (args.steps + args.warmup + 4) * (wl.k + 1) + wl.tree_size
+    sweep_sizes = [int(t) for t in args.tree_sizes.split(",") if t]
+    headroom = (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size] + sweep_sizes)
     wl = wl.with_(max_cache=(wl.prompt_len + headroom + 7) // 8 * 8)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     T, n0 = wl.tree_size, wl.prompt_len
     parent, rank = prune_tree(wl.branching, T)
     prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n0, wl.vocab)]
-    weights = make_weights(wl, wl.seed, dev, tdt)
-    model = B.HTModel(B.make_config(wl), weights, dev)
+    param_bytes = 2 * wl.n_layers * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim +
+                                     wl.n_heads * wl.head_dim * wl.d_model + 3 * wl.d_model * wl.d_ffn)
+    if param_bytes > 100e9:
+        # too large to hold the original and the packed copy together: supply one layer at a time
+        from ht_inputs import layer_weights
+        weights = make_weights(wl, wl.seed, dev, tdt, layers=[])
+        head = weights["lm_head"]
+        weights["lm_head"] = None
+        model = B.HTModel(B.make_config(wl, max_tree=max([T] + sweep_sizes)), weights, dev)
+        for layer in range(wl.n_layers):
+            lw = layer_weights(wl, wl.seed, layer, dev, tdt)
+            model.ht_load_layer(layer, lw)
+            torch.cuda.synchronize()
+            del lw
+        model.ht_load_lm_head(head)
+        torch.cuda.synchronize()
+        del head
+    else:
+        weights = make_weights(wl, wl.seed, dev, tdt)
+        model = B.HTModel(B.make_config(wl, max_tree=max([T] + sweep_sizes)), weights, dev)
     model.ht_set_tree(parent, rank)
     model.ht_prefill(prompt)
     stream = torch.cuda.current_stream()
@@ -207,6 +228,13 @@ def main():
     reps = max(5, args.steps)
     ms_verify = time_verify(parent, rank, reps)
     ms_one = time_verify([-1], [0], reps)
+    sweep = []
+    for ts in sweep_sizes:
+        tp, tr = prune_tree(wl.branching, ts)
+        ms_t = time_verify(tp, tr, reps)
+        by = model_bytes(wl, ts, n_now)
+        sweep.append({"T": ts, "verify_pass_ms": round(ms_t, 4), "hbm_GBps": round(by / (ms_t * 1e-3) / 1e9, 1),
+                      "hbm_frac_of_peak": round(by / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
     model.ht_set_tree(parent, rank)
 
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)
@@ -229,12 +257,15 @@ def main():
         "verify_hbm_frac_of_peak": round(verify_bytes / (ms_verify * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "one_token_hbm_GBps": round(one_bytes / (ms_one * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic() if wl.name == "llama7b" else None,
                      "kernel": (f"gemm_packed_kernel<MT=4,R=2,WAVES=3,EPI_F32,KC=128> at the gate/up projection shape "
                                 f"M={kern['M']} N={kern['N']} K={kern['K']}"),
                      "bytes_per_launch": kern["bytes"], "ms_per_launch": round(kern["ms"], 5)},
     }
-    if not args.no_cpu_baseline:
+    if sweep:
+        res["sweep"] = sweep
+    if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     print(json.dumps(res))
 

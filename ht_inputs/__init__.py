@@ -9,6 +9,7 @@ from .generators import (  # noqa: F401
     counter_tokens,
     counter_u64_reference,
     make_weights,
+    layer_weights,
     TENSOR_IDS,
 )
 from .trees import prune_tree, random_tree, chain_tree, star_tree, tree_depths  # noqa: F401

@@ -129,6 +129,26 @@ PROMPT_STREAM = 7
 _LAYER_SLOTS = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 
+def _dims(shape):
+    d, hq, hkv, hd, f = shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn
+    return {
+        "attn_norm": (d,), "wq": (hq * hd, d), "wk": (hkv * hd, d), "wv": (hkv * hd, d), "wo": (d, hq * hd),
+        "ffn_norm": (d,), "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f),
+    }
+
+
+def layer_weights(shape, seed: int, layer: int, device="cpu", dtype: torch.dtype = torch.float32,
+                  sigma: float = 0.02) -> Dict[str, torch.Tensor]:
+    """The nine tensors of one decoder layer (same values `make_weights` gives for that layer)."""
+    dims = _dims(shape)
+    out = {}
+    for name in _LAYER_SLOTS:
+        tid = TENSOR_IDS["layer_base"] + 16 * layer + TENSOR_IDS[name]
+        out[name] = counter_normal(seed, tid, dims[name], sigma, 1.0 if name.endswith("norm") else 0.0,
+                                   device=device, dtype=dtype)
+    return out
+
+
 def make_weights(shape, seed: int, device: str | torch.device = "cpu", dtype: torch.dtype = torch.float32,
                  layers: Optional[Iterable[int]] = None, sigma: float = 0.02,
                  with_head: bool = True) -> Dict[str, object]:
@@ -137,13 +157,10 @@ def make_weights(shape, seed: int, device: str | torch.device = "cpu", dtype: to
     `shape` needs attributes n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, k.
     All matrices are N(0, sigma^2), row-major [out, in]; norm gains are 1 + N(0, sigma^2) so a
     dropped gain multiply is visible.  `layers` restricts generation to a subset of layer indices
-    (others are None) so a single layer of a large shape can be rebuilt on the host.
+    (their matrices are None, their norm gains are still generated) so a single layer of a large
+    shape can be rebuilt on the host, or a large model can be supplied to the GPU layer by layer.
     """
-    d, hq, hkv, hd, f, v = shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab
-    dims = {
-        "attn_norm": (d,), "wq": (hq * hd, d), "wk": (hkv * hd, d), "wv": (hkv * hd, d), "wo": (d, hq * hd),
-        "ffn_norm": (d,), "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f),
-    }
+    d, v = shape.d_model, shape.vocab
 
     def gen(tid, shp, is_gain=False):
         return counter_normal(seed, tid, shp, sigma, 1.0 if is_gain else 0.0, device=device, dtype=dtype)
@@ -156,11 +173,15 @@ def make_weights(shape, seed: int, device: str | torch.device = "cpu", dtype: to
     want = set(range(shape.n_layers)) if layers is None else set(layers)
     for name in _LAYER_SLOTS:
         w[name] = []
+    dims = _dims(shape)
     for layer in range(shape.n_layers):
+        lw = layer_weights(shape, seed, layer, device, dtype, sigma) if layer in want else None
         for name in _LAYER_SLOTS:
-            if layer in want:
+            if lw is not None:
+                w[name].append(lw[name])
+            elif name.endswith("norm"):                  # the small gain vectors are always generated
                 tid = TENSOR_IDS["layer_base"] + 16 * layer + TENSOR_IDS[name]
-                w[name].append(gen(tid, dims[name], name.endswith("norm")))
+                w[name].append(gen(tid, dims[name], True))
             else:
                 w[name].append(None)
     return w

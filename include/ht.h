@@ -69,6 +69,17 @@ typedef struct {
   const void *const *w_transfer;             /* k x [d, d] */
 } ht_weights;
 
+/* Loading a model that is larger than half of the GPU memory (bf16 only).  Every bf16 projection is copied
+ * into the workspace in the library's streaming layout, so the original wq/wk/wv/wo/w_gate/w_up/w_down
+ * matrices and lm_head are only read while they are packed.  A caller that cannot hold both copies leaves those
+ * ht_weights entries NULL in ht_init_model (per layer, all seven together) and supplies them afterwards, one
+ * layer at a time; the source tensors may be released as soon as `stream` has passed the call.  Every layer and
+ * the head must have been supplied before ht_prefill (HT_ESTATE otherwise).  Norm gains, the embedding table
+ * and the transfer maps are always borrowed. */
+int ht_load_layer(ht_model *m, int32_t layer, const void *wq, const void *wk, const void *wv, const void *wo,
+                  const void *w_gate, const void *w_up, const void *w_down, void *stream);
+int ht_load_lm_head(ht_model *m, const void *lm_head, void *stream);
+
 /* Bytes of device workspace `ht_init_model` needs for this configuration (KV cache, activations,
  * tree tables, decoder state). */
 int ht_workspace_bytes(const ht_config *cfg, size_t *out_bytes);

@@ -22,7 +22,8 @@ EXPORTS = [
     "ht_workspace_bytes", "ht_init_model", "ht_free_model", "ht_set_tree", "ht_prefill", "ht_transfer",
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
-    "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed",
+    "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
+    "ht_load_lm_head",
 ]
 
 
@@ -71,6 +72,8 @@ def _load() -> C.CDLL:
         "ht_padded_rows": (C.c_int32, [C.c_int32]),
         "ht_skinny_gemm_scratch_bytes": (sz, [C.c_int32, C.c_int32, C.c_int32]),
         "ht_skinny_gemm": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
+        "ht_load_layer": (C.c_int, [vp, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "ht_load_lm_head": (C.c_int, [vp, vp, vp]),
         "ht_weight_pack_bytes": (sz, [C.c_int32, C.c_int32]),
         "ht_weight_pack": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp]),
         "ht_skinny_gemm_packed": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
@@ -176,10 +179,11 @@ class HTModel:
         self.device = torch.device(device)
         L, k = cfg.n_layers, cfg.k
         w = ht_weights()
-        w.tok_emb, w.final_norm, w.lm_head = (weights[n].data_ptr() for n in ("tok_emb", "final_norm", "lm_head"))
+        w.tok_emb, w.final_norm = (weights[n].data_ptr() for n in ("tok_emb", "final_norm"))
+        w.lm_head = _ptr(weights.get("lm_head"))           # None: supplied later through ht_load_lm_head
         self._tables = {}
         for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
-            arr = (C.c_void_p * L)(*[weights[name][l].data_ptr() for l in range(L)])
+            arr = (C.c_void_p * L)(*[_ptr(weights[name][l]) for l in range(L)])   # None: ht_load_layer later
             self._tables[name] = arr
             setattr(w, name, C.cast(arr, _PP))
         arr = (C.c_void_p * k)(*[weights["w_transfer"][i].data_ptr() for i in range(k)])
@@ -205,6 +209,14 @@ class HTModel:
             pass
 
     # -- the ABI calls
+    def ht_load_layer(self, layer: int, tensors: Dict[str, object], stream=None) -> None:
+        _check(lib.ht_load_layer(self.handle, layer, *[tensors[n].data_ptr() for n in
+                                                       ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")],
+                                 _stream_ptr(stream)))
+
+    def ht_load_lm_head(self, lm_head, stream=None) -> None:
+        _check(lib.ht_load_lm_head(self.handle, lm_head.data_ptr(), _stream_ptr(stream)))
+
     def ht_set_tree(self, parent: Sequence[int], rank: Sequence[int], stream=None) -> None:
         _check(lib.ht_set_tree(self.handle, len(parent), _i32(parent), _i32(rank), _stream_ptr(stream)))
         self.T = len(parent)

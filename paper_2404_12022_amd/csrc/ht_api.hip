@@ -184,6 +184,8 @@ struct ht_model {
   bool use_mfma = true;
   bool packed = false;          // bf16 projections run on the repacked weights
   bool qkv_fused = false;       // rotary + KV append run in the QKV projection's epilogue
+  std::vector<char> layer_loaded;   // packed copy of each layer present
+  bool head_loaded = false;
   std::vector<int32_t> depth;
   int max_width = 1;           // most candidates any pseudo position must supply
   // pinned host staging
@@ -278,6 +280,24 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   return HT_OK;
 }
 
+hipError_t pack_layer(ht_model* m, int l, const void* wq, const void* wk, const void* wv, const void* wo,
+                      const void* wg, const void* wu, const void* wd, hipStream_t s) {
+  const ht_config& c = m->cfg;
+  const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, d = c.d_model, f = c.d_ffn;
+  hipError_t e = launch_repack(WeightSegs{{wq, wk, wv}, {qd, kvd, kvd}, 3}, d, m->qkv_fused ? 2 : 0, c.head_dim,
+                               (void*)m->b.p_qkv[l].p, s);
+  if (e == hipSuccess) e = launch_repack(WeightSegs{{wo, nullptr, nullptr}, {d, 0, 0}, 1}, qd, 0, 0, (void*)m->b.p_o[l].p, s);
+  if (e == hipSuccess) e = launch_repack(WeightSegs{{wg, wu, nullptr}, {f, f, 0}, 2}, d, 1, 0, (void*)m->b.p_gu[l].p, s);
+  if (e == hipSuccess) e = launch_repack(WeightSegs{{wd, nullptr, nullptr}, {d, 0, 0}, 1}, f, 0, 0, (void*)m->b.p_down[l].p, s);
+  return e;
+}
+
+bool all_loaded(const ht_model* m) {
+  for (char c : m->layer_loaded)
+    if (!c) return false;
+  return m->head_loaded;
+}
+
 // host-side tree tables: depth, ancestor-or-self bit masks
 void fill_tables(int T, const int32_t* parent, const int32_t* rank, int32_t* stage) {
   int32_t* sp = stage;                       // parent
@@ -349,14 +369,20 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   size_t need = 0;
   ht_workspace_bytes(cfg, &need);
   if (workspace_bytes < need) return fail(HT_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
-      !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down || !w->w_transfer)
+  if (!w->tok_emb || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm ||
+      !w->w_gate || !w->w_up || !w->w_down || !w->w_transfer)
     return fail(HT_EINVAL, "a weight pointer is NULL");
   const int L = cfg->n_layers;
-  for (int l = 0; l < L; ++l)
-    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
-        !w->w_up[l] || !w->w_down[l])
-      return fail(HT_EINVAL, "a weight pointer of layer %d is NULL", l);
+  const char* env0 = getenv("HT_FORCE_SIMPLE");
+  const bool can_defer = shapes_packable(*cfg) && !(env0 && env0[0] == '1');
+  if (!w->lm_head && !can_defer) return fail(HT_EINVAL, "lm_head is NULL (deferred loading needs a packable bf16 model)");
+  for (int l = 0; l < L; ++l) {
+    if (!w->attn_norm[l] || !w->ffn_norm[l]) return fail(HT_EINVAL, "a norm gain of layer %d is NULL", l);
+    const int given = !!w->wq[l] + !!w->wk[l] + !!w->wv[l] + !!w->wo[l] + !!w->w_gate[l] + !!w->w_up[l] + !!w->w_down[l];
+    if (given != 7 && !(given == 0 && can_defer))
+      return fail(HT_EINVAL, "layer %d: projection pointers must all be given (or all NULL for deferred loading of a "
+                             "packable bf16 model)", l);
+  }
   for (int i = 0; i < cfg->k; ++i)
     if (!w->w_transfer[i]) return fail(HT_EINVAL, "w_transfer[%d] is NULL", i);
 
@@ -397,17 +423,22 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
 
   m->packed = m->use_mfma && shapes_packable(*cfg);
   m->qkv_fused = m->packed && qkv_fusable(cfg->head_dim);
+  m->layer_loaded.assign(L, 0);
   if (m->packed) {
-    const int qd = cfg->n_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim, d = cfg->d_model, f = cfg->d_ffn;
-    for (int l = 0; l < L && e == hipSuccess; ++l) {
-      e = launch_repack(WeightSegs{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3}, d, m->qkv_fused ? 2 : 0, cfg->head_dim,
-                        (void*)m->b.p_qkv[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->wo[l], nullptr, nullptr}, {d, 0, 0}, 1}, qd, 0, 0, (void*)m->b.p_o[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_gate[l], m->w_up[l], nullptr}, {f, f, 0}, 2}, d, 1, 0, (void*)m->b.p_gu[l].p, s);
-      if (e == hipSuccess) e = launch_repack(WeightSegs{{m->w_down[l], nullptr, nullptr}, {d, 0, 0}, 1}, f, 0, 0, (void*)m->b.p_down[l].p, s);
+    for (int l = 0; l < L && e == hipSuccess; ++l)
+      if (m->wq[l]) {
+        e = pack_layer(m, l, m->wq[l], m->wk[l], m->wv[l], m->wo[l], m->w_gate[l], m->w_up[l], m->w_down[l], s);
+        m->layer_loaded[l] = 1;
+      }
+    if (e == hipSuccess && m->lm_head) {
+      e = launch_repack(WeightSegs{{m->lm_head, nullptr, nullptr}, {cfg->vocab, 0, 0}, 1}, cfg->d_model, 0, 0,
+                        (void*)m->b.p_head.p, s);
+      m->head_loaded = true;
     }
-    if (e == hipSuccess) e = launch_repack(WeightSegs{{m->lm_head, nullptr, nullptr}, {cfg->vocab, 0, 0}, 1}, d, 0, 0, (void*)m->b.p_head.p, s);
     if (e != hipSuccess) return cleanup(fail(HT_EHIP, "weight repack failed: %s", hipGetErrorString(e)));
+  } else {
+    m->layer_loaded.assign(L, 1);
+    m->head_loaded = true;
   }
 
   // chain tables (prefill chunks and pseudo rows): row i has depth i and sees rows 0..i
@@ -425,6 +456,26 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init upload failed: %s", hipGetErrorString(e)));
   *out = m;
+  return HT_OK;
+}
+
+int ht_load_layer(ht_model* m, int32_t layer, const void* wq, const void* wk, const void* wv, const void* wo,
+                  const void* w_gate, const void* w_up, const void* w_down, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!m->packed) return fail(HT_EUNSUPPORTED, "deferred loading needs a bf16 model whose projections are packed");
+  if (layer < 0 || layer >= m->cfg.n_layers) return fail(HT_EINVAL, "layer %d out of range", layer);
+  if (!wq || !wk || !wv || !wo || !w_gate || !w_up || !w_down) return fail(HT_EINVAL, "NULL weight pointer");
+  HT_HIP(pack_layer(m, layer, wq, wk, wv, wo, w_gate, w_up, w_down, (hipStream_t)stream));
+  m->layer_loaded[layer] = 1;
+  return HT_OK;
+}
+
+int ht_load_lm_head(ht_model* m, const void* lm_head, void* stream) {
+  if (!m || !lm_head) return fail(HT_EINVAL, "NULL argument");
+  if (!m->packed) return fail(HT_EUNSUPPORTED, "deferred loading needs a bf16 model whose projections are packed");
+  HT_HIP(launch_repack(WeightSegs{{lm_head, nullptr, nullptr}, {m->cfg.vocab, 0, 0}, 1}, m->cfg.d_model, 0, 0,
+                       (void*)m->b.p_head.p, (hipStream_t)stream));
+  m->head_loaded = true;
   return HT_OK;
 }
 
@@ -465,6 +516,7 @@ int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* ra
 int ht_prefill(ht_model* m, const int32_t* tokens, int32_t n, void* stream) {
   if (!m || !tokens) return fail(HT_EINVAL, "NULL argument");
   const ht_config& c = m->cfg;
+  if (!all_loaded(m)) return fail(HT_ESTATE, "deferred weights: ht_load_layer / ht_load_lm_head have not supplied every layer");
   if (n < 1) return fail(HT_EINVAL, "prompt must have at least one token");
   if (n > c.max_cache) return fail(HT_ECAPACITY, "prompt of %d tokens exceeds max_cache %d", n, c.max_cache);
   for (int i = 0; i < n; ++i)

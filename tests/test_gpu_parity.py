@@ -254,6 +254,46 @@ def test_long_prompt_prefills_in_chunks():
     sc.step()
 
 
+def test_deferred_layer_loading_gives_identical_results():
+    """Projections supplied one layer at a time after ht_init_model (models larger than half the GPU memory)."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["tiny_bf16"]
+    say("deferred loading")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    parent, rank = tree_of(wl)
+    prompt = prompt_of(wl)
+    ref = B.HTModel(B.make_config(wl), tensors, H.DEV)
+    lazy_tensors = dict(tensors)
+    for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+        lazy_tensors[name] = [None] * wl.n_layers
+    lazy_tensors["lm_head"] = None
+    lazy = B.HTModel(B.make_config(wl), lazy_tensors, H.DEV)
+    lazy.ht_set_tree(parent, rank)
+    with pytest.raises(B.HTError) as e:
+        lazy.ht_prefill(prompt)
+    assert e.value.code == B.HT_ESTATE
+    for layer in reversed(range(wl.n_layers)):
+        lazy.ht_load_layer(layer, {k: v[layer] for k, v in tensors.items() if isinstance(v, list) and k != "w_transfer"})
+    lazy.ht_load_lm_head(tensors["lm_head"])
+    outs = []
+    for model in (ref, lazy):
+        model.ht_set_tree(parent, rank)
+        model.ht_prefill(prompt)
+        z = torch.empty(len(parent), wl.vocab, dtype=torch.float32, device=H.DEV)
+        model.ht_transfer()
+        model.ht_tree_verify_step(None, None, z)
+        outs.append((z.clone(), model.ht_accept_and_compact()))
+    assert torch.equal(outs[0][0], outs[1][0]) and outs[0][1] == outs[1][1]
+    f32 = WORKLOADS["tiny"]
+    t32 = make_weights(f32, f32.seed, H.DEV, torch.float32)
+    t32["lm_head"] = None
+    with pytest.raises(B.HTError) as e:
+        B.HTModel(B.make_config(f32), t32, H.DEV)                   # fp32 models cannot defer
+    assert e.value.code == B.HT_EINVAL
+    ref.close()
+    lazy.close()
+
+
 # ------------------------------------------------------------------ error paths (host-side validation)
 def test_error_codes():
     B, H = _B(), _H()
