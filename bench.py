@@ -125,6 +125,47 @@ def time_dominant_kernel(wl, T, dev, tdt, stream, calibrate=False):
     return {"M": M, "N": N, "K": K, "ms": ms_kernel, "bytes": kernel_bytes}
 
 
+def time_attention_op(dev):
+    """ht_tree_attention at the op workload: bf16, 32 query heads x 128, KV cache 4096 + 128 tree rows, random tree of
+    depth <= 6, rotary + append + attention per call, eight rotating cache copies (8 x 69 MB > last-level cache)."""
+    import torch
+    from ht_inputs import counter_normal, random_tree
+    from ht_inputs.workloads import ATTENTION_OP as A
+    import paper_2404_12022_amd.binding as B
+    T, n, Hq, Hkv, hd = A["tree_size"], A["cache_len"], A["n_heads"], A["n_kv_heads"], A["head_dim"]
+    cap = n + T
+    parent, _ = random_tree(A["seed"], T, A["max_depth"])
+    bf = torch.bfloat16
+    q = counter_normal(A["seed"], 21, (T, Hq, hd), 1.0, device=dev, dtype=bf)
+    kn = counter_normal(A["seed"], 24, (T, Hkv, hd), 1.0, device=dev, dtype=bf)
+    vn = counter_normal(A["seed"], 25, (T, Hkv, hd), 1.0, device=dev, dtype=bf)
+    copies = 8
+    kcs = [counter_normal(A["seed"], 100 + i, (cap, Hkv, hd), 1.0, device=dev, dtype=bf) for i in range(copies)]
+    vcs = [counter_normal(A["seed"], 200 + i, (Hkv, hd, cap), 1.0, device=dev, dtype=bf) for i in range(copies)]
+    out = torch.empty(T, Hq * hd, dtype=bf, device=dev)
+    scratch = torch.empty(B.ht_tree_attention_scratch_bytes(T, Hq, hd), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def call(i):
+        B.ht_tree_attention(q, kn, vn, kcs[i % copies], vcs[i % copies], cap, n, T, parent, Hq, Hkv, hd, B.HT_BF16,
+                            A["rope_base"], out, scratch)
+    for i in range(copies):
+        call(i)
+    reps = 40
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(reps):
+        call(i)
+    e1.record(stream)
+    e1.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    by = 2 * cap * Hkv * hd * 2 + 2 * T * Hq * hd * 2 + 2 * T * Hkv * hd * 2 * 2
+    return {"op": "ht_tree_attention", "T": T, "cache_len": n, "heads": Hq, "head_dim": hd, "us_per_call": round(us, 2),
+            "algorithmic_bytes": by, "GBps": round(by / (us * 1e-6) / 1e9, 1),
+            "frac_of_hbm_peak": round(by / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+            "note": "per call: tree-table upload + rotary/append kernel + attention kernel + slice merge kernel"}
+
+
 def measured_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None."""
     path = os.path.join(ROOT, "profiles", "gemm_gateup_hbm_traffic.json")
@@ -144,6 +185,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tree-sizes", default="",
                     help="comma-separated tree sizes: adds a `sweep` list of verify-pass latencies at the same cache")
+    ap.add_argument("--attention-op", action="store_true",
+                    help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop plus a device copy of known size (for rocprofv3 runs)")
     args = ap.parse_args()
@@ -158,6 +201,9 @@ def main():
 
     dev = "cuda:0"
     wl = WORKLOADS[args.workload]
+    if args.attention_op:
+        print(json.dumps(time_attention_op(dev)))
+        return
     if args.roofline_only:
         tdt0 = torch.bfloat16
         k = time_dominant_kernel(wl, wl.tree_size, dev, tdt0, torch.cuda.current_stream(), calibrate=True)

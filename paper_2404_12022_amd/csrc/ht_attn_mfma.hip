@@ -13,9 +13,11 @@
 // operand of the O MFMA wants: probabilities go from accumulator to operand registers without leaving the
 // lane.  Online softmax runs per lane (a query column lives in 4 lanes: two xor-shuffles for the row max).
 //
-// A workgroup is 4 wavefronts working on one query head, QB blocks of 16 tree rows and one slice of the
-// keys; the wavefronts take 32-key chunks round-robin and merge (max, sum, O) through LDS.  With more than
-// one key slice the merged partials go to scratch and a small kernel combines them.
+// A workgroup works on one query head and one slice of the keys.  For up to 16 rows its four wavefronts
+// take 32-key chunks round-robin and merge (max, sum, O) through LDS; for more rows each wavefront owns
+// 16 or 32 rows and all of them walk the same chunks (the K/V lines then come from L2 once per compute
+// unit and nothing is exchanged).  The next chunk's fragments are loaded while the current one is
+// multiplied.  With more than one key slice the partials go to scratch and a small kernel combines them.
 #include "ht_common.h"
 #include <cstdlib>
 
@@ -24,6 +26,8 @@ namespace ht {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -35,11 +39,7 @@ union Frag {
 
 constexpr int kMaxSplits = 16;
 
-__device__ inline uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
-}
-
-template <int HD, int QB>
+template <int HD, int QB, bool QSPLIT>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                         const bf16_t* __restrict__ vc, int cap, int n, int M,
                                                         const uint64_t* __restrict__ anc, int Hq, int Hkv,
@@ -49,13 +49,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   constexpr int EB = HD / 16;      // 16-row blocks of O^T
   // LDS merge area: per wave, O accumulators [QB][EB][4][64], running max [QB][64], partial sums [QB][64]
   constexpr int O_FLOATS = QB * EB * 4 * 64;
-  __shared__ float lds_o[4 * O_FLOATS];
-  __shared__ float lds_m[4 * QB * 64];
-  __shared__ float lds_l[4 * QB * 64];
+  constexpr int NLDS = QSPLIT ? 1 : 4;             // the query-split variant needs no merge area
+  __shared__ float lds_o[NLDS * O_FLOATS];
+  __shared__ float lds_m[NLDS * QB * 64];
+  __shared__ float lds_l[NLDS * QB * 64];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
   const int h = blockIdx.x, hk = h / (Hq / Hkv);
-  const int m0 = blockIdx.y * QB * 16;
+  // key-split: the workgroup's wavefronts share QB row blocks and take every 4th chunk;
+  // query-split: every wavefront owns its own QB row blocks and walks all chunks (same K/V lines: L1 hits)
+  const int m0 = QSPLIT ? (blockIdx.y * 4 + wave) * QB * 16 : blockIdx.y * QB * 16;
   const int split = blockIdx.z;
   const int S = n + M;
   const int chunks = (S + 31) / 32;
@@ -88,10 +91,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   const bf16_t* kbase = kc + (size_t)hk * HD + g * 8;
   const bf16_t* vbase = vc + ((size_t)hk * HD + r16) * cap;
 
-  for (int c = cs + wave; c < ce; c += 4) {
+  // K fragments: row r of block b is key j0 + 8 (r / 4) + 4 b + r % 4 (clamped into the cache).
+  // V^T fragments: rows e = eb*16 + r16, keys j0 + g*8 .. + 7 (clamped start keeps the load in bounds).
+  auto load_kv = [&](Frag (&kf)[2][ES], Frag (&vf)[EB], int c) __attribute__((always_inline)) {
     const int j0 = c * 32;
-    // ---- K fragments: row r of block b is key j0 + 8 (r / 4) + 4 b + r % 4 (clamped into the cache)
-    Frag kf[2][ES];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       int key = j0 + (r16 >> 2) * 8 + b * 4 + (r16 & 3);
@@ -100,14 +103,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int es = 0; es < ES; ++es) kf[b][es].nat = *(const u32x4_t*)(krow + es * 32);
     }
-    // ---- V^T fragments: rows e = eb*16 + r16, keys j0 + g*8 .. + 7 (clamped start keeps the load in bounds)
-    Frag vf[EB];
-    {
-      int kv = j0 + g * 8;
-      kv = kv + 8 <= cap ? kv : cap - 8;
+    int kv = j0 + g * 8;
+    kv = kv + 8 <= cap ? kv : cap - 8;
 #pragma unroll
-      for (int eb = 0; eb < EB; ++eb) vf[eb].nat = *(const u32x4_t*)(vbase + (size_t)eb * 16 * cap + kv);
-    }
+    for (int eb = 0; eb < EB; ++eb) vf[eb].nat = *(const u32x4_t*)(vbase + (size_t)eb * 16 * cap + kv);
+  };
+
+  auto process = [&](Frag (&kf)[2][ES], Frag (&vf)[EB], int c) __attribute__((always_inline)) {
+    const int j0 = c * 32;
     if (j0 + 32 > S) {            // keys past the last tree row carry no defined values: zero them
       const int first_bad = S - (j0 + g * 8);       // elements >= first_bad are invalid
 #pragma unroll
@@ -131,12 +134,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
         for (int es = 0; es < ES; ++es)
           s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][es].v, qf[qb][es].v, s[b], 0, 0, 0);
       }
-      // lane holds keys j0 + g*8 + t, t = 4 b + i
+      // lane holds keys j0 + g*8 + t, t = 4 b + i  (raw scores; the softmax scale is folded into the exponent)
       float p[8];
       float cmax = -INFINITY;
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        float v = s[t >> 2][t & 3] * scale_log2;
+        float v = s[t >> 2][t & 3];
         if (need_mask) {
           const int j = j0 + g * 8 + t;
           bool vis = j < n;
@@ -151,26 +154,82 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
       }
       cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
       cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
-      const float mnew = fmaxf(mrun[qb], cmax);
+      const float mnew = fmaxf(mrun[qb], cmax * scale_log2);       // running max in scaled (log2) units
       const float msafe = mnew == -INFINITY ? 0.f : mnew;
-      const float alpha = exp2f(mrun[qb] - msafe);           // mrun = -inf -> 0
       float psum = 0.f;
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        p[t] = exp2f(p[t] - msafe);
+        p[t] = __builtin_amdgcn_exp2f(fmaf(p[t], scale_log2, -msafe));   // masked: exp2(-inf) = 0
         psum += p[t];
       }
-      mrun[qb] = mnew;
-      lrun[qb] = lrun[qb] * alpha + psum;
+      // the accumulators are rescaled only when some row of the wavefront saw a new maximum
+      if (__any(mnew != mrun[qb])) {
+        const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - msafe);    // mrun = -inf -> 0
+        lrun[qb] *= alpha;
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] *= alpha;
+        mrun[qb] = mnew;
+      }
+      lrun[qb] += psum;
       Frag pf;
 #pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) pf.u[w2] = pack_bf16(p[2 * w2], p[2 * w2 + 1]);
+      for (int w2 = 0; w2 < 4; ++w2) {
+        floatx2_t f2 = {p[2 * w2], p[2 * w2 + 1]};
+        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);             // v_cvt_pk_bf16_f32 (RNE)
+        pf.u[w2] = *(const uint32_t*)&b2;
+      }
 #pragma unroll
-      for (int eb = 0; eb < EB; ++eb) {
-        oacc[qb][eb] *= alpha;
+      for (int eb = 0; eb < EB; ++eb)
         oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
+    }
+  };
+
+  // two register sets: the next chunk of this wavefront is in flight while the current one is multiplied
+  {
+    constexpr int STEP = QSPLIT ? 1 : 4;
+    Frag kf0[2][ES], vf0[EB], kf1[2][ES], vf1[EB];
+    int c = QSPLIT ? cs : cs + wave;
+    if (c < ce) load_kv(kf0, vf0, c);
+    for (; c < ce; c += 2 * STEP) {
+      if (c + STEP < ce) load_kv(kf1, vf1, c + STEP);
+      process(kf0, vf0, c);
+      if (c + STEP < ce) {
+        if (c + 2 * STEP < ce) load_kv(kf0, vf0, c + 2 * STEP);
+        process(kf1, vf1, c + STEP);
       }
     }
+  }
+
+  if (QSPLIT) {
+    // every wavefront finishes its own rows: no exchange
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float lsum = lrun[qb];
+      lsum += __shfl_xor(lsum, 16, 64);
+      lsum += __shfl_xor(lsum, 32, 64);
+      const int m = m0 + qb * 16 + r16;
+      if (m >= M) continue;
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb) {
+        const int e0 = eb * 16 + g * 4;
+        if (nsplit == 1) {
+          const float inv = 1.0f / lsum;
+          bf16_t ob[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(oacc[qb][eb][i] * inv);
+          *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
+        } else {
+          float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
+          *(float4*)dst = make_float4(oacc[qb][eb][0], oacc[qb][eb][1], oacc[qb][eb][2], oacc[qb][eb][3]);
+        }
+      }
+      if (nsplit > 1 && g == 0) {
+        float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
+        ml[0] = mrun[qb];
+        ml[1] = lsum;
+      }
+    }
+    return;
   }
 
   // ---- merge the four wavefronts
@@ -252,30 +311,38 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
   out[(size_t)m * Hq * HD + (size_t)h * HD + e] = float_to_bf16(o / l);
 }
 
-int pick_qb(int M) { return M <= 16 ? 1 : 2; }
+// Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts split the keys.
+// More rows: every wavefront owns 16 (M <= 64) or 32 rows and all wavefronts of a workgroup walk the same
+// keys, so a K/V line is pulled from L2 once per compute unit.
+struct AttnPlan { int qb, waves, groups, nsplit; bool qsplit; };
 
-int pick_splits(int M, int Hq, int S) {
-  const int qb = pick_qb(M);
-  const int groups = (M + qb * 16 - 1) / (qb * 16);
+AttnPlan plan_attention(int M, int Hq, int S) {
+  AttnPlan p;
+  p.qsplit = M > 16;
+  p.qb = M > 64 ? 2 : 1;
+  const int blocks = (M + p.qb * 16 - 1) / (p.qb * 16);
+  p.waves = p.qsplit ? (blocks < 4 ? blocks : 4) : 4;
+  p.groups = p.qsplit ? (blocks + 3) / 4 : blocks;
   const int chunks = (S + 31) / 32;
-  int s = (256 + Hq * groups - 1) / (Hq * groups);
-  if (s > chunks / 4) s = chunks / 4;
+  int s = (256 + Hq * p.groups - 1) / (Hq * p.groups);
+  const int min_chunks = p.qsplit ? 2 : 4;       // chunks per slice that keep every wavefront busy
+  if (s > chunks / min_chunks) s = chunks / min_chunks;
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
-  return s;
+  p.nsplit = s;
+  return p;
 }
 
-template <int HD, int QB>
+template <int HD, int QB, bool QSPLIT>
 void launch_t(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
-              int Hkv, bf16_t* out, void* scratch, int nsplit, hipStream_t s) {
-  const int groups = (M + QB * 16 - 1) / (QB * 16);
+              int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s) {
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (size_t)Hq * kMaxSplits * M * HD;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-  hipLaunchKernelGGL((attn_mfma_kernel<HD, QB>), dim3(Hq, groups, nsplit), dim3(256), 0, s, q, kc, vc, cap, n, M, anc, Hq,
-                     Hkv, out, part_o, part_ml, nsplit, scale_log2);
-  if (nsplit > 1)
-    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, nsplit, M, Hq, out);
+  hipLaunchKernelGGL((attn_mfma_kernel<HD, QB, QSPLIT>), dim3(Hq, p.groups, p.nsplit), dim3(64 * p.waves), 0, s, q, kc,
+                     vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2);
+  if (p.nsplit > 1)
+    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, p.nsplit, M, Hq, out);
 }
 
 }  // namespace
@@ -290,18 +357,16 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
-  int nsplit = pick_splits(M, Hq, n + M);
-  if (const char* e = getenv("HT_ATTN_SPLITS")) nsplit = atoi(e);
+  AttnPlan p = plan_attention(M, Hq, n + M);
+  if (const char* e = getenv("HT_ATTN_SPLITS")) p.nsplit = atoi(e);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
   bf16_t* op = (bf16_t*)out;
-  const int qb = pick_qb(M);
-  if (hd == 128) {
-    if (qb == 1) launch_t<128, 1>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
-    else launch_t<128, 2>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
-  } else {
-    if (qb == 1) launch_t<64, 1>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
-    else launch_t<64, 2>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, nsplit, s);
-  }
+#define HT_ATTN(HD_)                                                                                              \
+  if (!p.qsplit) launch_t<HD_, 1, false>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);            \
+  else if (p.qb == 1) launch_t<HD_, 1, true>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);        \
+  else launch_t<HD_, 2, true>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);
+  if (hd == 128) { HT_ATTN(128) } else { HT_ATTN(64) }
+#undef HT_ATTN
   return hipGetLastError();
 }
 
