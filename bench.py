@@ -66,7 +66,7 @@ def cpu_baseline(wl, T, n, weights):
         return t1 - t0, t2 - t1, t3 - t2, t4 - t3
 
     first = sample()
-    reps = max(3, min(200, int(12.0 / max(sum(first), 1e-3))))                 # about 12 s of CPU work in total
+    reps = max(3, min(600, int(18.0 / max(sum(first), 1e-3))))                 # 10-20 s of CPU work in total
     acc = [0.0, 0.0, 0.0, 0.0]
     for _ in range(reps):
         for i, t in enumerate(sample()):

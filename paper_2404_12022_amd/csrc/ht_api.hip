@@ -77,6 +77,7 @@ struct Buffers {
   void** vc_ptrs;
   void** wt_ptrs;      // device array [k]
   void* attn_scratch;
+  void* topk_scratch;
   std::vector<void*> kc, vc;   // host copies of the per-layer cache pointers
   // bf16 only: projection weights repacked into MFMA-fragment order
   std::vector<PackedW> p_qkv, p_o, p_gu, p_down;
@@ -122,6 +123,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.kc_ptrs = cv.take<void*>(c.n_layers);
   b.vc_ptrs = cv.take<void*>(c.n_layers);
   b.wt_ptrs = cv.take<void*>(kMaxTransfer);
+  b.topk_scratch = cv.take_bytes(topk_scratch_bytes(c.k));
   b.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes((int)Mp, c.n_heads, c.head_dim));
   b.kc.resize(c.n_layers);
   b.vc.resize(c.n_layers);
@@ -573,7 +575,7 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
     // slots n.. and are overwritten by the verify pass below
     HT_HIP(launch_load_rows(b.pseudo, b.x, c.k, c.d_model, s));
     if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, nullptr, s))) return rc;
-    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, m->max_width, c.k, c.vocab, s));
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.vocab, s));
     HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
   } else {
     HT_HIP(hipMemcpyAsync(b.tok, tree_tokens, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));

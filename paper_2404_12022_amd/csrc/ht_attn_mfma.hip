@@ -13,13 +13,15 @@
 // operand of the O MFMA wants: probabilities go from accumulator to operand registers without leaving the
 // lane.  Online softmax runs per lane (a query column lives in 4 lanes: two xor-shuffles for the row max).
 //
-// A workgroup works on one query head and one slice of the keys.  For up to 16 rows its four wavefronts
-// take 32-key chunks round-robin and merge (max, sum, O) through LDS; for more rows each wavefront owns
-// 16 or 32 rows and all of them walk the same chunks (the K/V lines then come from L2 once per compute
-// unit and nothing is exchanged).  The next chunk's fragments are loaded while the current one is
-// multiplied.  With more than one key slice the partials go to scratch and a small kernel combines them.
+// A workgroup works on one query head and one slice of the keys.  Two kernels share this scheme:
+//   attn_mfma_kernel (<= 16 rows): K and V fragments are loaded from global memory straight into MFMA
+//     operand registers, the four wavefronts take 32-key chunks round-robin and merge (max, sum, O)
+//     through LDS;
+//   attn_tile_kernel (more rows): every wavefront owns 16 or 32 rows, 64-key tiles of K and V^T are staged
+//     in LDS with fully coalesced loads and shared by the wavefronts (per-lane operand loads from global
+//     memory cost one L1 tag lookup per lane and made the first version L1-bound).
+// With more than one key slice the partials go to scratch and a small kernel combines them.
 #include "ht_common.h"
-#include <cstdlib>
 
 namespace ht {
 
@@ -39,7 +41,7 @@ union Frag {
 
 constexpr int kMaxSplits = 16;
 
-template <int HD, int QB, bool QSPLIT>
+template <int HD, int QB>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                         const bf16_t* __restrict__ vc, int cap, int n, int M,
                                                         const uint64_t* __restrict__ anc, int Hq, int Hkv,
@@ -49,16 +51,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   constexpr int EB = HD / 16;      // 16-row blocks of O^T
   // LDS merge area: per wave, O accumulators [QB][EB][4][64], running max [QB][64], partial sums [QB][64]
   constexpr int O_FLOATS = QB * EB * 4 * 64;
-  constexpr int NLDS = QSPLIT ? 1 : 4;             // the query-split variant needs no merge area
-  __shared__ float lds_o[NLDS * O_FLOATS];
-  __shared__ float lds_m[NLDS * QB * 64];
-  __shared__ float lds_l[NLDS * QB * 64];
+  __shared__ float lds_o[4 * O_FLOATS];
+  __shared__ float lds_m[4 * QB * 64];
+  __shared__ float lds_l[4 * QB * 64];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
   const int h = blockIdx.x, hk = h / (Hq / Hkv);
-  // key-split: the workgroup's wavefronts share QB row blocks and take every 4th chunk;
-  // query-split: every wavefront owns its own QB row blocks and walks all chunks (same K/V lines: L1 hits)
-  const int m0 = QSPLIT ? (blockIdx.y * 4 + wave) * QB * 16 : blockIdx.y * QB * 16;
+  // the workgroup's wavefronts share QB row blocks and take every 4th chunk of the key slice
+  const int m0 = blockIdx.y * QB * 16;
   const int split = blockIdx.z;
   const int S = n + M;
   const int chunks = (S + 31) / 32;
@@ -186,9 +186,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
 
   // two register sets: the next chunk of this wavefront is in flight while the current one is multiplied
   {
-    constexpr int STEP = QSPLIT ? 1 : 4;
+    constexpr int STEP = 4;
     Frag kf0[2][ES], vf0[EB], kf1[2][ES], vf1[EB];
-    int c = QSPLIT ? cs : cs + wave;
+    int c = cs + wave;
     if (c < ce) load_kv(kf0, vf0, c);
     for (; c < ce; c += 2 * STEP) {
       if (c + STEP < ce) load_kv(kf1, vf1, c + STEP);
@@ -198,38 +198,6 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
         process(kf1, vf1, c + STEP);
       }
     }
-  }
-
-  if (QSPLIT) {
-    // every wavefront finishes its own rows: no exchange
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float lsum = lrun[qb];
-      lsum += __shfl_xor(lsum, 16, 64);
-      lsum += __shfl_xor(lsum, 32, 64);
-      const int m = m0 + qb * 16 + r16;
-      if (m >= M) continue;
-#pragma unroll
-      for (int eb = 0; eb < EB; ++eb) {
-        const int e0 = eb * 16 + g * 4;
-        if (nsplit == 1) {
-          const float inv = 1.0f / lsum;
-          bf16_t ob[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(oacc[qb][eb][i] * inv);
-          *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
-        } else {
-          float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
-          *(float4*)dst = make_float4(oacc[qb][eb][0], oacc[qb][eb][1], oacc[qb][eb][2], oacc[qb][eb][3]);
-        }
-      }
-      if (nsplit > 1 && g == 0) {
-        float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
-        ml[0] = mrun[qb];
-        ml[1] = lsum;
-      }
-    }
-    return;
   }
 
   // ---- merge the four wavefronts
@@ -293,6 +261,225 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// More than 16 rows: every wavefront owns QB blocks of 16 rows and all wavefronts of the workgroup need the
+// same keys, so the workgroup stages 64-key tiles of K ([key][e]) and V^T ([e][key]) in LDS with fully
+// coalesced loads (whole 128/256-byte runs per row) and each wavefront reads its MFMA operands from there.
+// The 16-byte pieces of a row are XOR-swizzled so that the 16 rows a fragment read touches fall into
+// different banks.  The tile after next is in flight in registers while the current one is multiplied.
+template <int HD, int QB, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                            const bf16_t* __restrict__ vc, int cap, int n, int M,
+                                                            const uint64_t* __restrict__ anc, int Hq, int Hkv,
+                                                            bf16_t* __restrict__ out, float* __restrict__ part_o,
+                                                            float* __restrict__ part_ml, int nsplit, float scale_log2) {
+  constexpr int TK = 64;                 // keys per tile
+  constexpr int ES = HD / 32, EB = HD / 16;
+  constexpr int THREADS = 64 * NW;
+  constexpr int PK = HD / 8;             // 16-byte pieces per K row
+  constexpr int KPIECES = TK * PK, VPIECES = HD * (TK / 8);
+  constexpr int KP = KPIECES / THREADS, VP = VPIECES / THREADS;
+  static_assert(KPIECES % THREADS == 0 && VPIECES % THREADS == 0, "tile must divide over the threads");
+  constexpr int KBYTES = TK * HD * 2, VBYTES = HD * TK * 2;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][KBYTES + VBYTES];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  const int h = blockIdx.x, hk = h / (Hq / Hkv);
+  const int m0 = (blockIdx.y * NW + wave) * QB * 16;
+  const int split = blockIdx.z;
+  const int S = n + M;
+  const int tiles = (S + TK - 1) / TK;
+  const int ts = (int)((long long)tiles * split / nsplit), te = (int)((long long)tiles * (split + 1) / nsplit);
+
+  Frag qf[QB][ES];
+  uint64_t amask[QB][kMaskWords];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int m = m0 + qb * 16 + r16;
+    const int mc = m < M ? m : M - 1;
+    const bf16_t* qrow = q + ((size_t)mc * Hq + h) * HD + g * 8;
+#pragma unroll
+    for (int es = 0; es < ES; ++es) qf[qb][es].nat = *(const u32x4_t*)(qrow + es * 32);
+#pragma unroll
+    for (int wd = 0; wd < kMaskWords; ++wd) amask[qb][wd] = m < M ? anc[(size_t)m * kMaskWords + wd] : 0ull;
+  }
+  floatx4_t oacc[QB][EB];
+  float mrun[QB], lrun[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    mrun[qb] = -INFINITY;
+    lrun[qb] = 0.f;
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // staging: thread t moves K pieces t, t + THREADS, .. (row = piece / PK) and V pieces (row e = piece / 8)
+  u32x4_t kreg[KP], vreg[VP];
+  auto load_tile = [&](int t) __attribute__((always_inline)) {
+    const int j0 = t * TK;
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+      const int p = tid + i * THREADS, kl = p / PK, pc = p % PK;
+      int key = j0 + kl;
+      key = key < cap ? key : cap - 1;
+      kreg[i] = *(const u32x4_t*)(kc + ((size_t)key * Hkv + hk) * HD + pc * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < VP; ++i) {
+      const int p = tid + i * THREADS, e = p / (TK / 8), pc = p % (TK / 8);
+      int kv = j0 + pc * 8;
+      const int valid = S - kv;                       // keys of this piece below S carry data
+      kv = kv + 8 <= cap ? kv : cap - 8;
+      u32x4_t v = *(const u32x4_t*)(vc + ((size_t)hk * HD + e) * cap + kv);
+      if (valid < 8) {                                // zero what lies past the last tree row
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+          uint32_t keep = 0;
+          if (2 * w2 < valid) keep |= 0x0000ffffu;
+          if (2 * w2 + 1 < valid) keep |= 0xffff0000u;
+          v[w2] &= keep;
+        }
+      }
+      vreg[i] = v;
+    }
+  };
+  auto store_tile = [&](int stage) __attribute__((always_inline)) {
+    unsigned char* kb = lds[stage];
+    unsigned char* vb = lds[stage] + KBYTES;
+#pragma unroll
+    for (int i = 0; i < KP; ++i) {
+      const int p = tid + i * THREADS, kl = p / PK, pc = p % PK;
+      const int sw = ((((kl >> 3) & 3) << 2) | (kl & 3)) & (PK - 1);
+      *(u32x4_t*)(kb + kl * (HD * 2) + ((pc ^ sw) << 4)) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VP; ++i) {
+      const int p = tid + i * THREADS, e = p / (TK / 8), pc = p % (TK / 8);
+      *(u32x4_t*)(vb + e * (TK * 2) + ((pc ^ ((e >> 1) & 7)) << 4)) = vreg[i];
+    }
+  };
+
+  auto process = [&](int stage, int t, int sub) __attribute__((always_inline)) {
+    const unsigned char* kb = lds[stage];
+    const unsigned char* vb = lds[stage] + KBYTES;
+    const int j0 = t * TK + sub * 32;
+    Frag kf[2][ES];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int kl = sub * 32 + (r16 >> 2) * 8 + b * 4 + (r16 & 3);      // interleaved key order (see top)
+      const int sw = r16 & (PK - 1);
+#pragma unroll
+      for (int es = 0; es < ES; ++es) kf[b][es].nat = *(const u32x4_t*)(kb + kl * (HD * 2) + (((es * 4 + g) ^ sw) << 4));
+    }
+    Frag vf[EB];
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) {
+      const int e = eb * 16 + r16;
+      vf[eb].nat = *(const u32x4_t*)(vb + e * (TK * 2) + (((sub * 4 + g) ^ ((e >> 1) & 7)) << 4));
+    }
+    const bool need_mask = j0 + 32 > n;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      floatx4_t s[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        s[b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int es = 0; es < ES; ++es)
+          s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][es].v, qf[qb][es].v, s[b], 0, 0, 0);
+      }
+      float p[8];
+      float cmax = -INFINITY;
+#pragma unroll
+      for (int tt = 0; tt < 8; ++tt) {
+        float v = s[tt >> 2][tt & 3];
+        if (need_mask) {
+          const int j = j0 + g * 8 + tt;
+          bool vis = j < n;
+          if (!vis && j < S) {
+            const int u = j - n;
+            vis = (amask[qb][u >> 6] >> (u & 63)) & 1ull;
+          }
+          v = vis ? v : -INFINITY;
+        }
+        p[tt] = v;
+        cmax = fmaxf(cmax, v);
+      }
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
+      const float mnew = fmaxf(mrun[qb], cmax * scale_log2);
+      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      float psum = 0.f;
+#pragma unroll
+      for (int tt = 0; tt < 8; ++tt) {
+        p[tt] = __builtin_amdgcn_exp2f(fmaf(p[tt], scale_log2, -msafe));
+        psum += p[tt];
+      }
+      if (__any(mnew != mrun[qb])) {
+        const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - msafe);
+        lrun[qb] *= alpha;
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] *= alpha;
+        mrun[qb] = mnew;
+      }
+      lrun[qb] += psum;
+      Frag pf;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) {
+        floatx2_t f2 = {p[2 * w2], p[2 * w2 + 1]};
+        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);
+        pf.u[w2] = *(const uint32_t*)&b2;
+      }
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb)
+        oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
+    }
+  };
+
+  if (ts < te) {
+    load_tile(ts);
+    store_tile(0);
+    if (ts + 1 < te) load_tile(ts + 1);
+    __syncthreads();
+    for (int t = ts; t < te; ++t) {
+      const int stage = (t - ts) & 1;
+      if (t + 1 < te) store_tile(stage ^ 1);
+      if (t + 2 < te) load_tile(t + 2);
+      process(stage, t, 0);
+      if (t * TK + 32 < S) process(stage, t, 1);
+      __syncthreads();
+    }
+  }
+
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    float lsum = lrun[qb];
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    const int m = m0 + qb * 16 + r16;
+    if (m >= M) continue;
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) {
+      const int e0 = eb * 16 + g * 4;
+      if (nsplit == 1) {
+        const float inv = 1.0f / lsum;
+        bf16_t ob[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(oacc[qb][eb][i] * inv);
+        *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
+      } else {
+        float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
+        *(float4*)dst = make_float4(oacc[qb][eb][0], oacc[qb][eb][1], oacc[qb][eb][2], oacc[qb][eb][3]);
+      }
+    }
+    if (nsplit > 1 && g == 0) {
+      float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
+      ml[0] = mrun[qb];
+      ml[1] = lsum;
+    }
+  }
+}
+
 // out[m][h] = sum_s exp2(m_s - m*) O_s / sum_s exp2(m_s - m*) l_s, splits added in index order
 template <int HD>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplit, int M,
@@ -311,36 +498,40 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
   out[(size_t)m * Hq * HD + (size_t)h * HD + e] = float_to_bf16(o / l);
 }
 
-// Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts split the keys.
-// More rows: every wavefront owns 16 (M <= 64) or 32 rows and all wavefronts of a workgroup walk the same
-// keys, so a K/V line is pulled from L2 once per compute unit.
-struct AttnPlan { int qb, waves, groups, nsplit; bool qsplit; };
+// Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts of a workgroup
+// split the keys of the slice and fragments come straight from global memory.  More rows: the tile kernel,
+// each wavefront owning 16 rows (two row groups of workgroups above 64 rows).
+struct AttnPlan { int qb, waves, groups, nsplit; bool tiled; };
 
 AttnPlan plan_attention(int M, int Hq, int S) {
   AttnPlan p;
-  p.qsplit = M > 16;
-  p.qb = M > 64 ? 2 : 1;
-  const int blocks = (M + p.qb * 16 - 1) / (p.qb * 16);
-  p.waves = p.qsplit ? (blocks < 4 ? blocks : 4) : 4;
-  p.groups = p.qsplit ? (blocks + 3) / 4 : blocks;
-  const int chunks = (S + 31) / 32;
-  int s = (256 + Hq * p.groups - 1) / (Hq * p.groups);
-  const int min_chunks = p.qsplit ? 2 : 4;       // chunks per slice that keep every wavefront busy
-  if (s > chunks / min_chunks) s = chunks / min_chunks;
+  p.tiled = M > 16;
+  p.qb = 1;                                       // 32 rows per wavefront measured slower (one wave per SIMD)
+  p.waves = !p.tiled ? 4 : (M <= 32 ? 2 : 4);
+  p.groups = p.tiled ? (M + p.waves * p.qb * 16 - 1) / (p.waves * p.qb * 16) : 1;
+  const int units = p.tiled ? (S + 63) / 64 : (S + 31) / 32;     // tiles or chunks
+  int s = (512 + Hq * p.groups - 1) / (Hq * p.groups);           // about two workgroups per compute unit
+  const int min_units = p.tiled ? 2 : 4;                          // per slice, so that every wavefront has work
+  if (s > units / min_units) s = units / min_units;
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
   p.nsplit = s;
   return p;
 }
 
-template <int HD, int QB, bool QSPLIT>
-void launch_t(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
-              int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s) {
+template <int HD>
+void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
+               int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s) {
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (size_t)Hq * kMaxSplits * M * HD;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-  hipLaunchKernelGGL((attn_mfma_kernel<HD, QB, QSPLIT>), dim3(Hq, p.groups, p.nsplit), dim3(64 * p.waves), 0, s, q, kc,
-                     vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2);
+  const dim3 grid(Hq, p.groups, p.nsplit);
+#define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2
+  if (!p.tiled) hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  else if (p.waves == 2) hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 2>), grid, dim3(128), 0, s, HT_ATTN_ARGS);
+  else if (p.qb == 1) hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  else hipLaunchKernelGGL((attn_tile_kernel<HD, 2, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+#undef HT_ATTN_ARGS
   if (p.nsplit > 1)
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, p.nsplit, M, Hq, out);
 }
@@ -357,16 +548,10 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
-  AttnPlan p = plan_attention(M, Hq, n + M);
-  if (const char* e = getenv("HT_ATTN_SPLITS")) p.nsplit = atoi(e);
+  const AttnPlan p = plan_attention(M, Hq, n + M);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
-  bf16_t* op = (bf16_t*)out;
-#define HT_ATTN(HD_)                                                                                              \
-  if (!p.qsplit) launch_t<HD_, 1, false>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);            \
-  else if (p.qb == 1) launch_t<HD_, 1, true>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);        \
-  else launch_t<HD_, 2, true>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, op, scratch, p, s);
-  if (hd == 128) { HT_ATTN(128) } else { HT_ATTN(64) }
-#undef HT_ATTN
+  if (hd == 128) launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s);
+  else launch_hd<64>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s);
   return hipGetLastError();
 }
 

@@ -80,8 +80,9 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
                                     hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int M, int f, hipStream_t s);
 hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s);
-// max_width = largest entry of width[1..k] (host copy): selects the per-thread list length
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int max_width, int k, int V,
+// scratch: topk_scratch_bytes(k) bytes for the per-slice survivors
+size_t topk_scratch_bytes(int k);
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int k, int V,
                        hipStream_t s);
 hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
 hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s);

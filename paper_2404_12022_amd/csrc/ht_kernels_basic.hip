@@ -293,54 +293,63 @@ hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s
 }
 
 // cand[i][r], r < width[i+1]: the r-th entry of logit row i in (value desc, id asc) order.
-// One pass over the row: every thread keeps the best LOCAL entries of its strided slice sorted in
-// registers (LOCAL >= b makes this exact: no slice can contribute more than b of the top b), then b
-// rounds of block-wide arg-best over the heads of the per-thread lists pop the winners in order.
-template <int LOCAL>
-__global__ __launch_bounds__(1024) void topk_kernel(const float* __restrict__ d, int32_t* __restrict__ cand,
-                                                    const int32_t* __restrict__ width, int V) {
+// Two stages of the same selection: repeated block-wide arg-best over the entries that come strictly after
+// the previous pick in that order.  Stage 1 runs it on kTopkSlices slices of the row in parallel and leaves
+// each slice's best b entries in scratch (any of the row's top b is among its slice's top b); stage 2 runs
+// it once more over those kTopkSlices * b survivors.
+constexpr int kTopkSlices = 32;
+
+template <bool FINAL>
+__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, const float* __restrict__ sv_in,
+                                                   const int32_t* __restrict__ si_in, float* __restrict__ sv_out,
+                                                   int32_t* __restrict__ si_out, int32_t* __restrict__ cand,
+                                                   const int32_t* __restrict__ width, int V) {
   __shared__ float sv[16];
   __shared__ int si[16];
-  const int i = blockIdx.x;
-  const float* row = d + (size_t)i * V;
+  const int i = blockIdx.x, slice = blockIdx.y;
   const int b = width[i + 1];
-  float lv[LOCAL];
-  int li[LOCAL];
-#pragma unroll
-  for (int t = 0; t < LOCAL; ++t) { lv[t] = -INFINITY; li[t] = 0x7fffffff; }
-  for (int j = threadIdx.x; j < V; j += blockDim.x) {
-    float v = row[j];
-    int id = j;
-    if (better(v, id, lv[LOCAL - 1], li[LOCAL - 1])) {
-#pragma unroll
-      for (int t = 0; t < LOCAL; ++t) {          // insertion by a chain of compare-exchanges
-        if (better(v, id, lv[t], li[t])) {
-          const float tv = lv[t]; const int ti = li[t];
-          lv[t] = v; li[t] = id;
-          v = tv; id = ti;
-        }
+  // element range of this block: a slice of the logit row, or the survivors of all slices
+  int lo, hi;
+  if (FINAL) { lo = 0; hi = kTopkSlices * b; }
+  else {
+    const int per = (V + kTopkSlices - 1) / kTopkSlices;
+    lo = slice * per;
+    hi = lo + per < V ? lo + per : V;
+  }
+  float pv = INFINITY;
+  int pi = -1;
+  for (int r = 0; r < b; ++r) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = lo + threadIdx.x; j < hi; j += 256) {
+      float v;
+      int id;
+      if (FINAL) { v = sv_in[(size_t)i * kTopkSlices * kMaxTopK + j]; id = si_in[(size_t)i * kTopkSlices * kMaxTopK + j]; }
+      else { v = d[(size_t)i * V + j]; id = j; }
+      const bool after = r == 0 || v < pv || (v == pv && id > pi);
+      if (after && better(v, id, bv, bi)) { bv = v; bi = id; }
+    }
+    block_best_any(bv, bi, sv, si);
+    if (threadIdx.x == 0) {
+      if (FINAL) cand[i * kMaxTopK + r] = bi == 0x7fffffff ? 0 : bi;
+      else {
+        sv_out[(size_t)i * kTopkSlices * kMaxTopK + slice * b + r] = bi == 0x7fffffff ? -INFINITY : bv;
+        si_out[(size_t)i * kTopkSlices * kMaxTopK + slice * b + r] = bi;
       }
     }
-  }
-  for (int r = 0; r < b; ++r) {
-    float bv = lv[0];
-    int bi = li[0];
-    block_best_any(bv, bi, sv, si);
-    if (li[0] == bi && bi != 0x7fffffff) {       // the winner pops its head
-#pragma unroll
-      for (int t = 0; t + 1 < LOCAL; ++t) { lv[t] = lv[t + 1]; li[t] = li[t + 1]; }
-      lv[LOCAL - 1] = -INFINITY;
-      li[LOCAL - 1] = 0x7fffffff;
-    }
-    if (threadIdx.x == 0) cand[i * kMaxTopK + r] = bi == 0x7fffffff ? 0 : bi;
+    pv = bv; pi = bi;
     __syncthreads();
   }
 }
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, int max_width, int k, int V,
+// scratch: float[k][kTopkSlices][kMaxTopK] followed by int32 of the same shape
+size_t topk_scratch_bytes(int k) { return (size_t)k * kTopkSlices * kMaxTopK * 8; }
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int k, int V,
                        hipStream_t s) {
-  if (max_width <= 4) hipLaunchKernelGGL(topk_kernel<4>, dim3(k), dim3(1024), 0, s, d, cand, width, V);
-  else if (max_width <= 16) hipLaunchKernelGGL(topk_kernel<16>, dim3(k), dim3(1024), 0, s, d, cand, width, V);
-  else hipLaunchKernelGGL(topk_kernel<kMaxTopK>, dim3(k), dim3(256), 0, s, d, cand, width, V);
+  float* sv = (float*)scratch;
+  int32_t* si = (int32_t*)(sv + (size_t)k * kTopkSlices * kMaxTopK);
+  hipLaunchKernelGGL(topk_kernel<false>, dim3(k, kTopkSlices), dim3(256), 0, s, d, nullptr, nullptr, sv, si, cand,
+                     width, V);
+  hipLaunchKernelGGL(topk_kernel<true>, dim3(k, 1), dim3(256), 0, s, d, sv, si, nullptr, nullptr, cand, width, V);
   return hipGetLastError();
 }
 
