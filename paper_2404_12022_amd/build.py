@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are kept off for the device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators stay in ordinary vector registers: the attention kernels rescale them with vector
+    # ALU instructions, and copies to and from accumulation registers doubled their instruction count
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

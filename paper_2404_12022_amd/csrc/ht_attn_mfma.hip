@@ -22,6 +22,7 @@
 //     memory cost one L1 tag lookup per lane and made the first version L1-bound).
 // With more than one key slice the partials go to scratch and a small kernel combines them.
 #include "ht_common.h"
+#include <type_traits>
 
 namespace ht {
 
@@ -262,11 +263,32 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
 }
 
 // ------------------------------------------------------------------------------------------------
-// More than 16 rows: every wavefront owns QB blocks of 16 rows and all wavefronts of the workgroup need the
+// More than 16 rows: every wavefront owns one block of 16 rows and all wavefronts of the workgroup need the
 // same keys, so the workgroup stages 64-key tiles of K ([key][e]) and V^T ([e][key]) in LDS with fully
 // coalesced loads (whole 128/256-byte runs per row) and each wavefront reads its MFMA operands from there.
 // The 16-byte pieces of a row are XOR-swizzled so that the 16 rows a fragment read touches fall into
 // different banks.  The tile after next is in flight in registers while the current one is multiplied.
+// Tiles that lie entirely inside the cache (keys < n) run a loop body without any mask or tail code; only
+// the last one to three tiles evaluate the ancestor masks and zero the V columns past the last tree row.
+
+// max over lanes l, l ^ 16, l ^ 32, l ^ 48 with the two gfx950 half/row swaps (no LDS round trip)
+__device__ __forceinline__ float max_over_groups(float x) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);      // rows (0,0,2,2) and (1,1,3,3)
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  u = __float_as_uint(x);
+  auto r2 = __builtin_amdgcn_permlane32_swap(u, u, false, false);     // halves (lo,lo) and (hi,hi)
+  return fmaxf(__uint_as_float(r2[0]), __uint_as_float(r2[1]));
+}
+__device__ __forceinline__ float sum_over_groups(float x) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  u = __float_as_uint(x);
+  auto r2 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+}
+
 template <int HD, int QB, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                             const bf16_t* __restrict__ vc, int cap, int n, int M,
@@ -280,6 +302,9 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   constexpr int KPIECES = TK * PK, VPIECES = HD * (TK / 8);
   constexpr int KP = KPIECES / THREADS, VP = VPIECES / THREADS;
   static_assert(KPIECES % THREADS == 0 && VPIECES % THREADS == 0, "tile must divide over the threads");
+  static_assert(THREADS % PK == 0 && THREADS % (TK / 8) == 0, "a thread keeps its column in every pass");
+  constexpr int KROWS = THREADS / PK;    // key rows covered by one pass of K pieces
+  constexpr int VROWS = THREADS / (TK / 8);
   constexpr int KBYTES = TK * HD * 2, VBYTES = HD * TK * 2;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][KBYTES + VBYTES];
 
@@ -290,6 +315,8 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   const int S = n + M;
   const int tiles = (S + TK - 1) / TK;
   const int ts = (int)((long long)tiles * split / nsplit), te = (int)((long long)tiles * (split + 1) / nsplit);
+  int tmid = n / TK;                     // tiles below tmid hold cache keys only
+  tmid = tmid < ts ? ts : (tmid > te ? te : tmid);
 
   Frag qf[QB][ES];
   uint64_t amask[QB][kMaskWords];
@@ -313,71 +340,79 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
     for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   }
 
-  // staging: thread t moves K pieces t, t + THREADS, .. (row = piece / PK) and V pieces (row e = piece / 8)
+  // staging: in pass i a thread moves the K piece (row tid / PK + i * KROWS, column tid % PK) and the V piece
+  // (row e = tid / 8 + i * VROWS, keys (tid % 8) * 8 ..); everything but the tile offset is loop invariant
+  const int kl0 = tid / PK, kpc = tid % PK;
+  const int ve0 = tid / (TK / 8), vpc = tid % (TK / 8);
+  const bf16_t* kcol = kc + (size_t)hk * HD + kpc * 8;
+  const bf16_t* vrow = vc + ((size_t)hk * HD + ve0) * cap;
+  const size_t krow_stride = (size_t)Hkv * HD;
+  int klds[KP], vlds[VP];
+#pragma unroll
+  for (int i = 0; i < KP; ++i) {
+    const int kl = kl0 + i * KROWS;
+    const int sw = ((((kl >> 3) & 3) << 2) | (kl & 3)) & (PK - 1);
+    klds[i] = kl * (HD * 2) + ((kpc ^ sw) << 4);
+  }
+#pragma unroll
+  for (int i = 0; i < VP; ++i) {
+    const int e = ve0 + i * VROWS;
+    vlds[i] = KBYTES + e * (TK * 2) + ((vpc ^ ((e >> 1) & 7)) << 4);
+  }
   u32x4_t kreg[KP], vreg[VP];
   auto load_tile = [&](int t) __attribute__((always_inline)) {
     const int j0 = t * TK;
 #pragma unroll
     for (int i = 0; i < KP; ++i) {
-      const int p = tid + i * THREADS, kl = p / PK, pc = p % PK;
-      int key = j0 + kl;
+      int key = j0 + kl0 + i * KROWS;
       key = key < cap ? key : cap - 1;
-      kreg[i] = *(const u32x4_t*)(kc + ((size_t)key * Hkv + hk) * HD + pc * 8);
+      kreg[i] = *(const u32x4_t*)(kcol + (size_t)key * krow_stride);
     }
+    int kv = j0 + vpc * 8;
+    const int valid = S - kv;                         // keys of this piece below S carry data
+    kv = kv + 8 <= cap ? kv : cap - 8;
 #pragma unroll
-    for (int i = 0; i < VP; ++i) {
-      const int p = tid + i * THREADS, e = p / (TK / 8), pc = p % (TK / 8);
-      int kv = j0 + pc * 8;
-      const int valid = S - kv;                       // keys of this piece below S carry data
-      kv = kv + 8 <= cap ? kv : cap - 8;
-      u32x4_t v = *(const u32x4_t*)(vc + ((size_t)hk * HD + e) * cap + kv);
-      if (valid < 8) {                                // zero what lies past the last tree row
+    for (int i = 0; i < VP; ++i) vreg[i] = *(const u32x4_t*)(vrow + (size_t)i * VROWS * cap + kv);
+    if (t >= tmid && valid < 8) {                     // zero what lies past the last tree row
+      uint32_t keep[4];
 #pragma unroll
-        for (int w2 = 0; w2 < 4; ++w2) {
-          uint32_t keep = 0;
-          if (2 * w2 < valid) keep |= 0x0000ffffu;
-          if (2 * w2 + 1 < valid) keep |= 0xffff0000u;
-          v[w2] &= keep;
-        }
-      }
-      vreg[i] = v;
+      for (int w2 = 0; w2 < 4; ++w2) keep[w2] = (2 * w2 < valid ? 0x0000ffffu : 0u) | (2 * w2 + 1 < valid ? 0xffff0000u : 0u);
+#pragma unroll
+      for (int i = 0; i < VP; ++i)
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) vreg[i][w2] &= keep[w2];
     }
   };
   auto store_tile = [&](int stage) __attribute__((always_inline)) {
-    unsigned char* kb = lds[stage];
-    unsigned char* vb = lds[stage] + KBYTES;
+    unsigned char* base = lds[stage];
 #pragma unroll
-    for (int i = 0; i < KP; ++i) {
-      const int p = tid + i * THREADS, kl = p / PK, pc = p % PK;
-      const int sw = ((((kl >> 3) & 3) << 2) | (kl & 3)) & (PK - 1);
-      *(u32x4_t*)(kb + kl * (HD * 2) + ((pc ^ sw) << 4)) = kreg[i];
-    }
+    for (int i = 0; i < KP; ++i) *(u32x4_t*)(base + klds[i]) = kreg[i];
 #pragma unroll
-    for (int i = 0; i < VP; ++i) {
-      const int p = tid + i * THREADS, e = p / (TK / 8), pc = p % (TK / 8);
-      *(u32x4_t*)(vb + e * (TK * 2) + ((pc ^ ((e >> 1) & 7)) << 4)) = vreg[i];
-    }
+    for (int i = 0; i < VP; ++i) *(u32x4_t*)(base + vlds[i]) = vreg[i];
   };
 
-  auto process = [&](int stage, int t, int sub) __attribute__((always_inline)) {
-    const unsigned char* kb = lds[stage];
-    const unsigned char* vb = lds[stage] + KBYTES;
+  // fragment addresses inside a stage (sub = 32-key half of the tile adds a constant)
+  int kfo[2], vfo[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) kfo[b] = ((r16 >> 2) * 8 + b * 4 + (r16 & 3)) * (HD * 2);   // interleaved key order
+  const int ksw = r16 & (PK - 1);
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) vfo[sub] = KBYTES + r16 * (TK * 2) + (((sub * 4 + g) ^ ((r16 >> 1) & 7)) << 4);
+
+  auto process = [&](auto masked, int stage, int t, int sub) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked)::value;
+    const unsigned char* base = lds[stage];
     const int j0 = t * TK + sub * 32;
     Frag kf[2][ES];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int kl = sub * 32 + (r16 >> 2) * 8 + b * 4 + (r16 & 3);      // interleaved key order (see top)
-      const int sw = r16 & (PK - 1);
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int es = 0; es < ES; ++es) kf[b][es].nat = *(const u32x4_t*)(kb + kl * (HD * 2) + (((es * 4 + g) ^ sw) << 4));
-    }
+      for (int es = 0; es < ES; ++es)
+        kf[b][es].nat = *(const u32x4_t*)(base + kfo[b] + sub * 32 * (HD * 2) + (((es * 4 + g) ^ ksw) << 4));
     Frag vf[EB];
 #pragma unroll
-    for (int eb = 0; eb < EB; ++eb) {
-      const int e = eb * 16 + r16;
-      vf[eb].nat = *(const u32x4_t*)(vb + e * (TK * 2) + (((sub * 4 + g) ^ ((e >> 1) & 7)) << 4));
-    }
-    const bool need_mask = j0 + 32 > n;
+    for (int eb = 0; eb < EB; ++eb)       // rows e = eb * 16 + r16: (e >> 1) & 7 does not depend on eb
+      vf[eb].nat = *(const u32x4_t*)(base + vfo[sub] + eb * 16 * (TK * 2));
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       floatx4_t s[2];
@@ -388,35 +423,35 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
         for (int es = 0; es < ES; ++es)
           s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][es].v, qf[qb][es].v, s[b], 0, 0, 0);
       }
+      // lane holds keys j0 + g*8 + tt, tt = 4 b + i (raw scores; the softmax scale is folded into the exponent)
       float p[8];
-      float cmax = -INFINITY;
 #pragma unroll
-      for (int tt = 0; tt < 8; ++tt) {
-        float v = s[tt >> 2][tt & 3];
-        if (need_mask) {
+      for (int tt = 0; tt < 8; ++tt) p[tt] = s[tt >> 2][tt & 3];
+      if (MASKED) {
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt) {
           const int j = j0 + g * 8 + tt;
           bool vis = j < n;
           if (!vis && j < S) {
             const int u = j - n;
             vis = (amask[qb][u >> 6] >> (u & 63)) & 1ull;
           }
-          v = vis ? v : -INFINITY;
+          p[tt] = vis ? p[tt] : -INFINITY;
         }
-        p[tt] = v;
-        cmax = fmaxf(cmax, v);
       }
-      cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
-      cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
-      const float mnew = fmaxf(mrun[qb], cmax * scale_log2);
-      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      float cmax = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
+      cmax = max_over_groups(cmax);
+      const float mnew = fmaxf(mrun[qb], cmax * scale_log2);       // running max in scaled (log2) units
+      const float msafe = MASKED ? (mnew == -INFINITY ? 0.f : mnew) : mnew;   // unmasked scores are finite
       float psum = 0.f;
 #pragma unroll
       for (int tt = 0; tt < 8; ++tt) {
-        p[tt] = __builtin_amdgcn_exp2f(fmaf(p[tt], scale_log2, -msafe));
+        p[tt] = __builtin_amdgcn_exp2f(fmaf(p[tt], scale_log2, -msafe));      // masked: exp2(-inf) = 0
         psum += p[tt];
       }
+      // the accumulators are rescaled only when some row of the wavefront saw a new maximum
       if (__any(mnew != mrun[qb])) {
-        const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - msafe);
+        const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - msafe);         // mrun = -inf -> 0
         lrun[qb] *= alpha;
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] *= alpha;
@@ -427,7 +462,7 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
 #pragma unroll
       for (int w2 = 0; w2 < 4; ++w2) {
         floatx2_t f2 = {p[2 * w2], p[2 * w2 + 1]};
-        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);
+        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);                   // v_cvt_pk_bf16_f32 (RNE)
         pf.u[w2] = *(const uint32_t*)&b2;
       }
 #pragma unroll
@@ -435,27 +470,28 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
         oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
     }
   };
+  auto step = [&](auto masked, int t) __attribute__((always_inline)) {
+    const int stage = (t - ts) & 1;
+    if (t + 1 < te) store_tile(stage ^ 1);
+    if (t + 2 < te) load_tile(t + 2);
+    process(masked, stage, t, 0);
+    if (!decltype(masked)::value || t * TK + 32 < S) process(masked, stage, t, 1);
+    __syncthreads();
+  };
 
   if (ts < te) {
     load_tile(ts);
     store_tile(0);
     if (ts + 1 < te) load_tile(ts + 1);
     __syncthreads();
-    for (int t = ts; t < te; ++t) {
-      const int stage = (t - ts) & 1;
-      if (t + 1 < te) store_tile(stage ^ 1);
-      if (t + 2 < te) load_tile(t + 2);
-      process(stage, t, 0);
-      if (t * TK + 32 < S) process(stage, t, 1);
-      __syncthreads();
-    }
+    int t = ts;
+    for (; t < tmid; ++t) step(std::false_type{}, t);
+    for (; t < te; ++t) step(std::true_type{}, t);
   }
 
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    float lsum = lrun[qb];
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
+    const float lsum = sum_over_groups(lrun[qb]);
     const int m = m0 + qb * 16 + r16;
     if (m >= M) continue;
 #pragma unroll
