@@ -41,6 +41,7 @@ union Frag {
 };
 
 constexpr int kMaxSplits = 16;
+constexpr float kRescaleStep = 8.0f;    // log2 units the running maximum may lag behind before accumulators are rescaled
 
 template <int HD, int QB>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
@@ -346,19 +347,19 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   const int ve0 = tid / (TK / 8), vpc = tid % (TK / 8);
   const bf16_t* kcol = kc + (size_t)hk * HD + kpc * 8;
   const bf16_t* vrow = vc + ((size_t)hk * HD + ve0) * cap;
-  const size_t krow_stride = (size_t)Hkv * HD;
-  int klds[KP], vlds[VP];
+  const unsigned krow_stride = (unsigned)(Hkv * HD);
+  int klds[KP];
 #pragma unroll
   for (int i = 0; i < KP; ++i) {
     const int kl = kl0 + i * KROWS;
     const int sw = ((((kl >> 3) & 3) << 2) | (kl & 3)) & (PK - 1);
     klds[i] = kl * (HD * 2) + ((kpc ^ sw) << 4);
   }
-#pragma unroll
-  for (int i = 0; i < VP; ++i) {
-    const int e = ve0 + i * VROWS;
-    vlds[i] = KBYTES + e * (TK * 2) + ((vpc ^ ((e >> 1) & 7)) << 4);
-  }
+  static_assert(VROWS % 16 == 0, "the V swizzle of a thread's piece is the same in every pass");
+  const int vlds0 = KBYTES + ve0 * (TK * 2) + ((vpc ^ ((ve0 >> 1) & 7)) << 4);     // pass i adds i * VROWS rows
+  // The tile after next is in flight in registers while the current one is multiplied out of LDS and the next
+  // one sits in the other LDS stage (a second register set, two tiles in flight, measured slower: the
+  // staging side already runs near the streaming rate of the memory system).
   u32x4_t kreg[KP], vreg[VP];
   auto load_tile = [&](int t) __attribute__((always_inline)) {
     const int j0 = t * TK;
@@ -366,14 +367,19 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
     for (int i = 0; i < KP; ++i) {
       int key = j0 + kl0 + i * KROWS;
       key = key < cap ? key : cap - 1;
-      kreg[i] = *(const u32x4_t*)(kcol + (size_t)key * krow_stride);
+      kreg[i] = *(const u32x4_t*)(kcol + (unsigned)key * krow_stride);   // the launcher checks cap*Hkv*HD < 2^31
     }
     int kv = j0 + vpc * 8;
-    const int valid = S - kv;                         // keys of this piece below S carry data
     kv = kv + 8 <= cap ? kv : cap - 8;
 #pragma unroll
     for (int i = 0; i < VP; ++i) vreg[i] = *(const u32x4_t*)(vrow + (size_t)i * VROWS * cap + kv);
-    if (t >= tmid && valid < 8) {                     // zero what lies past the last tree row
+  };
+  auto store_tile = [&](int stage, int t) __attribute__((always_inline)) {
+    unsigned char* base = lds[stage];
+#pragma unroll
+    for (int i = 0; i < KP; ++i) *(u32x4_t*)(base + klds[i]) = kreg[i];
+    const int valid = S - (t * TK + vpc * 8);           // keys of this thread's V pieces below S carry data
+    if (t >= tmid && valid < 8) {                       // zero what lies past the last tree row
       uint32_t keep[4];
 #pragma unroll
       for (int w2 = 0; w2 < 4; ++w2) keep[w2] = (2 * w2 < valid ? 0x0000ffffu : 0u) | (2 * w2 + 1 < valid ? 0xffff0000u : 0u);
@@ -382,16 +388,11 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
 #pragma unroll
         for (int w2 = 0; w2 < 4; ++w2) vreg[i][w2] &= keep[w2];
     }
-  };
-  auto store_tile = [&](int stage) __attribute__((always_inline)) {
-    unsigned char* base = lds[stage];
 #pragma unroll
-    for (int i = 0; i < KP; ++i) *(u32x4_t*)(base + klds[i]) = kreg[i];
-#pragma unroll
-    for (int i = 0; i < VP; ++i) *(u32x4_t*)(base + vlds[i]) = vreg[i];
+    for (int i = 0; i < VP; ++i) *(u32x4_t*)(base + vlds0 + i * VROWS * (TK * 2)) = vreg[i];
   };
 
-  // fragment addresses inside a stage (sub = 32-key half of the tile adds a constant)
+  // fragment addresses inside a stage: K rows of score block b of the 32-key half `sub`, V^T pieces of `sub`
   int kfo[2], vfo[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) kfo[b] = ((r16 >> 2) * 8 + b * 4 + (r16 & 3)) * (HD * 2);   // interleaved key order
@@ -399,94 +400,108 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) vfo[sub] = KBYTES + r16 * (TK * 2) + (((sub * 4 + g) ^ ((r16 >> 1) & 7)) << 4);
 
-  auto process = [&](auto masked, int stage, int t, int sub) __attribute__((always_inline)) {
+  // One 64-key tile: 4 score blocks (two per 32-key half), one softmax update over the 16 scores a lane
+  // holds, then the two halves' probabilities multiply V.
+  auto process = [&](auto masked, int stage, int t) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked)::value;
     const unsigned char* base = lds[stage];
-    const int j0 = t * TK + sub * 32;
-    Frag kf[2][ES];
+    const int j0 = t * TK;
+    Frag kf[2][2][ES];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int es = 0; es < ES; ++es)
-        kf[b][es].nat = *(const u32x4_t*)(base + kfo[b] + sub * 32 * (HD * 2) + (((es * 4 + g) ^ ksw) << 4));
-    Frag vf[EB];
-#pragma unroll
-    for (int eb = 0; eb < EB; ++eb)       // rows e = eb * 16 + r16: (e >> 1) & 7 does not depend on eb
-      vf[eb].nat = *(const u32x4_t*)(base + vfo[sub] + eb * 16 * (TK * 2));
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      floatx4_t s[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        s[b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int es = 0; es < ES; ++es)
-          s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][es].v, qf[qb][es].v, s[b], 0, 0, 0);
-      }
-      // lane holds keys j0 + g*8 + tt, tt = 4 b + i (raw scores; the softmax scale is folded into the exponent)
-      float p[8];
+          kf[sub][b][es].nat = *(const u32x4_t*)(base + kfo[b] + sub * 32 * (HD * 2) + (((es * 4 + g) ^ ksw) << 4));
 #pragma unroll
-      for (int tt = 0; tt < 8; ++tt) p[tt] = s[tt >> 2][tt & 3];
+    for (int qb = 0; qb < QB; ++qb) {
+      floatx4_t s[2][2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          s[sub][b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int es = 0; es < ES; ++es)
+            s[sub][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sub][b][es].v, qf[qb][es].v, s[sub][b], 0, 0, 0);
+        }
+      // lane holds keys j0 + 32 sub + g*8 + tt, tt = 4 b + i (raw scores; the softmax scale is folded into
+      // the exponent)
+      float p[16];
+#pragma unroll
+      for (int x = 0; x < 16; ++x) p[x] = s[x >> 3][(x >> 2) & 1][x & 3];
       if (MASKED) {
 #pragma unroll
-        for (int tt = 0; tt < 8; ++tt) {
-          const int j = j0 + g * 8 + tt;
+        for (int x = 0; x < 16; ++x) {
+          const int j = j0 + (x >> 3) * 32 + g * 8 + (x & 7);
           bool vis = j < n;
           if (!vis && j < S) {
             const int u = j - n;
             vis = (amask[qb][u >> 6] >> (u & 63)) & 1ull;
           }
-          p[tt] = vis ? p[tt] : -INFINITY;
+          p[x] = vis ? p[x] : -INFINITY;
         }
       }
-      float cmax = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
-      cmax = max_over_groups(cmax);
-      const float mnew = fmaxf(mrun[qb], cmax * scale_log2);       // running max in scaled (log2) units
-      const float msafe = MASKED ? (mnew == -INFINITY ? 0.f : mnew) : mnew;   // unmasked scores are finite
-      float psum = 0.f;
+      float cmax = p[0];
 #pragma unroll
-      for (int tt = 0; tt < 8; ++tt) {
-        p[tt] = __builtin_amdgcn_exp2f(fmaf(p[tt], scale_log2, -msafe));      // masked: exp2(-inf) = 0
-        psum += p[tt];
-      }
-      // the accumulators are rescaled only when some row of the wavefront saw a new maximum
-      if (__any(mnew != mrun[qb])) {
-        const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - msafe);         // mrun = -inf -> 0
+      for (int x = 1; x < 16; ++x) cmax = fmaxf(cmax, p[x]);
+      cmax = max_over_groups(cmax) * scale_log2;                   // in scaled (log2) units
+      // The reference point of the exponentials only follows the running maximum when that grew by more
+      // than kRescaleStep (probabilities stay below 2^kRescaleStep: exact in fp32 sums, same relative
+      // precision in bf16), so the accumulators are rescaled once or twice per key slice, not per tile.
+      const bool grow = cmax > mrun[qb] + kRescaleStep;            // mrun = -inf: true for any finite score
+      if (__any(grow)) {
+        const float mnew = grow ? cmax : mrun[qb];
+        const float alpha = grow ? __builtin_amdgcn_exp2f(mrun[qb] - cmax) : 1.0f;   // mrun = -inf -> 0
         lrun[qb] *= alpha;
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb) oacc[qb][eb] *= alpha;
         mrun[qb] = mnew;
       }
-      lrun[qb] += psum;
-      Frag pf;
+      const float msafe = MASKED ? (mrun[qb] == -INFINITY ? 0.f : mrun[qb]) : mrun[qb];   // unmasked scores are finite
+      float psum = 0.f;
 #pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) {
-        floatx2_t f2 = {p[2 * w2], p[2 * w2 + 1]};
-        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);                   // v_cvt_pk_bf16_f32 (RNE)
-        pf.u[w2] = *(const uint32_t*)&b2;
+      for (int x = 0; x < 16; ++x) {
+        p[x] = __builtin_amdgcn_exp2f(fmaf(p[x], scale_log2, -msafe));        // masked: exp2(-inf) = 0
+        psum += p[x];
       }
+      lrun[qb] += psum;
 #pragma unroll
-      for (int eb = 0; eb < EB; ++eb)
-        oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
+      for (int sub = 0; sub < 2; ++sub) {
+        Frag vf[EB];                        // read after the softmax: the K fragments are dead by now
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)     // rows e = eb * 16 + r16: (e >> 1) & 7 does not depend on eb
+          vf[eb].nat = *(const u32x4_t*)(base + vfo[sub] + eb * 16 * (TK * 2));
+        Frag pf;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+          floatx2_t f2 = {p[sub * 8 + 2 * w2], p[sub * 8 + 2 * w2 + 1]};
+          bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);                 // v_cvt_pk_bf16_f32 (RNE)
+          pf.u[w2] = *(const uint32_t*)&b2;
+        }
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)
+          oacc[qb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[qb][eb], 0, 0, 0);
+      }
     }
   };
   auto step = [&](auto masked, int t) __attribute__((always_inline)) {
     const int stage = (t - ts) & 1;
-    if (t + 1 < te) store_tile(stage ^ 1);
+    if (t + 1 < te) store_tile(stage ^ 1, t + 1);
     if (t + 2 < te) load_tile(t + 2);
-    process(masked, stage, t, 0);
-    if (!decltype(masked)::value || t * TK + 32 < S) process(masked, stage, t, 1);
+    if (m0 < M) process(masked, stage, t);      // wavefronts past the last row only help staging
     __syncthreads();
   };
 
   if (ts < te) {
     load_tile(ts);
-    store_tile(0);
+    store_tile(0, ts);
     if (ts + 1 < te) load_tile(ts + 1);
     __syncthreads();
     int t = ts;
     for (; t < tmid; ++t) step(std::false_type{}, t);
-    for (; t < te; ++t) step(std::true_type{}, t);
+    for (; t < te; ++t) step(std::true_type{}, t);      // the few tiles that reach past the cache
   }
 
 #pragma unroll
@@ -543,7 +558,7 @@ AttnPlan plan_attention(int M, int Hq, int S) {
   AttnPlan p;
   p.tiled = M > 16;
   p.qb = 1;                                       // 32 rows per wavefront measured slower (one wave per SIMD)
-  p.waves = !p.tiled ? 4 : (M <= 32 ? 2 : 4);
+  p.waves = 4;
   p.groups = p.tiled ? (M + p.waves * p.qb * 16 - 1) / (p.waves * p.qb * 16) : 1;
   const int units = p.tiled ? (S + 63) / 64 : (S + 31) / 32;     // tiles or chunks
   int s = (512 + Hq * p.groups - 1) / (Hq * p.groups);           // about two workgroups per compute unit
@@ -564,9 +579,7 @@ void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int
   const dim3 grid(Hq, p.groups, p.nsplit);
 #define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2
   if (!p.tiled) hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
-  else if (p.waves == 2) hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 2>), grid, dim3(128), 0, s, HT_ATTN_ARGS);
-  else if (p.qb == 1) hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
-  else hipLaunchKernelGGL((attn_tile_kernel<HD, 2, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  else hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
 #undef HT_ATTN_ARGS
   if (p.nsplit > 1)
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, p.nsplit, M, Hq, out);
@@ -584,6 +597,7 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
+  if ((size_t)cap * Hkv * hd >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside a cache
   const AttnPlan p = plan_attention(M, Hq, n + M);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
   if (hd == 128) launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s);
