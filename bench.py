@@ -270,10 +270,33 @@ def main():
         e1.synchronize()
         return e0.elapsed_time(e1) / reps
 
+    # ---- the same pass captured once in a HIP graph: median of 100 single launches after 20 warm-up launches
+    def time_verify_graph(tree_parent, tree_rank, launches=100, warm=20):
+        model.ht_set_tree(tree_parent, tree_rank)
+        toks = torch.tensor(prompt[:len(tree_parent)], dtype=torch.int32, device=dev)
+        model.ht_tree_verify_step(toks)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            model.ht_tree_verify_step(toks)
+        for _ in range(warm):
+            graph.replay()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for a, b in ev:
+            a.record(stream)
+            graph.replay()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts_ = sorted(a.elapsed_time(b) for a, b in ev)
+        del graph
+        return ts_[len(ts_) // 2]
+
     n_now = model.ht_cache_len()
     reps = max(5, args.steps)
     ms_verify = time_verify(parent, rank, reps)
     ms_one = time_verify([-1], [0], reps)
+    ms_verify_graph = time_verify_graph(parent, rank)
+    ms_one_graph = time_verify_graph([-1], [0])
     sweep = []
     for ts in sweep_sizes:
         tp, tr = prune_tree(wl.branching, ts)
@@ -297,6 +320,9 @@ def main():
                                f"top-k + tree build + verify + accept + compact"},
         "verify_pass_ms": round(ms_verify, 4), "one_token_step_ms": round(ms_one, 4),
         "verify_over_one_token": round(ms_verify / ms_one, 4),
+        "graph_launch_median": {"verify_pass_ms": round(ms_verify_graph, 4), "one_token_step_ms": round(ms_one_graph, 4),
+                                "verify_over_one_token": round(ms_verify_graph / ms_one_graph, 4),
+                                "launches": 100, "warmup_launches": 20},
         "candidate_tokens_per_s": round(T / (ms_verify * 1e-3), 1),
         "accepted_tokens_per_step": round(accepted / args.steps, 3),
         "verify_hbm_GBps": round(verify_bytes / (ms_verify * 1e-3) / 1e9, 1),

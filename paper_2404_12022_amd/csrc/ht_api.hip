@@ -189,7 +189,6 @@ struct ht_model {
   std::vector<char> layer_loaded;   // packed copy of each layer present
   bool head_loaded = false;
   std::vector<int32_t> depth;
-  int max_width = 1;           // most candidates any pseudo position must supply
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
   StepState* h_state = nullptr;
@@ -506,9 +505,6 @@ int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* ra
   HT_HIP(hipMemcpyAsync(m->b.width, width, sizeof(int32_t) * (kMaxTransfer + 2), hipMemcpyHostToDevice, s));
   HT_HIP(hipStreamSynchronize(s));
   m->depth.assign(depth, depth + T);
-  m->max_width = 1;
-  for (int e = 0; e < kMaxTransfer + 2; ++e)
-    if (width[e] > m->max_width) m->max_width = width[e];
   m->T = T;
   m->has_tree = true;
   m->verify_done = false;

@@ -1,0 +1,153 @@
+"""Full-size checks of the HIP path in the launch configuration the benchmark times (llama7b workload:
+32 layers, cache 512, 64-node tree), through the C ABI.  Needs a real MI355X.
+
+A 32-layer fp64 oracle pass at this size takes far too long on the host, so these tests use properties that
+hold at any size and need no oracle values:
+
+* Sec. 3.4.1 (tree attention): the logits of a tree node equal those of a plain causal pass over the tokens
+  on its root-to-node path.  The plain pass here is the library's own one-token decode step (a different
+  kernel configuration: M = 1 instances, key-split attention), run on a second model with the same weights.
+* Sec. 3.4 / 4.1 (greedy verification is lossless): a tree that holds the greedy continuation on one of its
+  paths is accepted along exactly that path.
+* A verify pass captured in a HIP graph gives the same bits on every replay as the eager call.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from ht_inputs import WORKLOADS, make_weights, prune_tree
+from helpers import prompt_of
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _mods():
+    import paper_2404_12022_amd.binding as B
+    import gpu_harness as H
+    return B, H
+
+
+def _rank0_chain(parent, rank):
+    """Node ids of the path root -> rank-0 child -> its rank-0 child ..."""
+    chain, cur = [0], 0
+    while True:
+        kids = [v for v in range(len(parent)) if parent[v] == cur and rank[v] == 0]
+        if not kids:
+            return chain
+        cur = kids[0]
+        chain.append(cur)
+
+
+def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_accepted():
+    B, H = _mods()
+    wl = WORKLOADS["llama7b"].with_(max_cache=640)
+    T = wl.tree_size
+    parent, rank = prune_tree(wl.branching, T)
+    chain = _rank0_chain(parent, rank)
+    assert len(chain) == wl.k + 1
+    say("7B full depth: generating weights")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    prompt = prompt_of(wl)
+
+    say("7B full depth: plain decode, one token per pass")
+    plain = H.gpu_model(wl, tensors, max_tree=T)
+    plain.ht_set_tree([-1], [0])
+    plain.ht_prefill(prompt)
+    z1 = torch.empty(1, wl.vocab, dtype=torch.float32, device=H.DEV)
+    g1 = torch.empty(1, dtype=torch.int32, device=H.DEV)
+    greedy = [int(plain.ht_get_buffer(B.HT_BUF_ROOT)[0])]
+    rows = []
+    for _ in range(len(chain)):
+        tok = torch.tensor([greedy[-1]], dtype=torch.int32, device=H.DEV)
+        plain.ht_tree_verify_step(tok, g1, z1)
+        m, toks, root, _ = plain.ht_accept_and_compact()
+        assert m == 1 and toks == [greedy[-1]]
+        rows.append(z1[0].cpu().numpy().astype(np.float64))
+        assert root == int(np.argmax(rows[-1]))
+        greedy.append(root)
+    plain.close()
+    del plain
+
+    say("7B full depth: one 64-node verify pass holding the greedy continuation on the rank-0 chain")
+    tree = H.gpu_model(wl, tensors, max_tree=T)
+    tree.ht_set_tree(parent, rank)
+    tree.ht_prefill(prompt)
+    assert int(tree.ht_get_buffer(B.HT_BUF_ROOT)[0]) == greedy[0]
+    toks = [(greedy[0] + 7 + 13 * v) % wl.vocab for v in range(T)]
+    depth_tok = {d: greedy[d] for d in range(len(chain))}
+    for v in range(T):                                   # no other node may carry a greedy token by accident
+        while toks[v] in depth_tok.values():
+            toks[v] = (toks[v] + 1) % wl.vocab
+    for d, v in enumerate(chain):
+        toks[v] = greedy[d]
+    z = torch.empty(T, wl.vocab, dtype=torch.float32, device=H.DEV)
+    g = torch.empty(T, dtype=torch.int32, device=H.DEV)
+    tree.ht_tree_verify_step(torch.tensor(toks, dtype=torch.int32, device=H.DEV), g, z)
+    torch.cuda.synchronize()
+    zc = z.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(zc))
+    assert np.array_equal(g.cpu().numpy(), np.argmax(zc, axis=1))
+    worst_diff = 0.0
+    for d, v in enumerate(chain):
+        # each bf16 pass may be 3e-2 away from the exact logits, so two passes may differ by twice that
+        ok, ratio = H.within_bf16(zc[v], rows[d], tol=2 * H.BF16_REL_TOL)
+        diff = float(np.max(np.abs(zc[v] - rows[d])))
+        worst_diff = max(worst_diff, diff)
+        say(f"  depth {d}: tree row {v} vs plain decode: error / bound {ratio:.3f}, max-abs {diff:.2e}")
+        assert ok, f"tree node {v} (depth {d}) differs from the causal pass over its path: {ratio:.3f} x bound"
+    m, emitted, root, path = tree.ht_accept_and_compact()
+    # the walk must follow the chain for as long as the plain pass decided its token by more than the two
+    # passes differ; past a narrower decision either token is a legitimate bf16 outcome
+    sure = 0
+    for d in range(len(chain) - 1):
+        srt = np.sort(rows[d])
+        if srt[-1] - srt[-2] <= 2 * worst_diff:
+            break
+        sure += 1
+    say(f"  accepted {m} nodes {path}, decisions well above the pass-to-pass difference: {sure}")
+    assert m >= sure + 1 and path[:sure + 1] == chain[:sure + 1] and emitted[:sure + 1] == greedy[:sure + 1]
+    assert tree.ht_cache_len() == wl.prompt_len + m
+    tree.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama7b_2layers"])
+def test_verify_pass_replayed_from_a_graph_matches_the_eager_pass(name):
+    B, H = _mods()
+    if name == "tiny":
+        wl = WORKLOADS["tiny"]
+        dt = torch.float32
+    else:
+        wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), max_cache=640)
+        dt = torch.bfloat16
+    T = wl.tree_size
+    parent, rank = prune_tree(wl.branching, T)
+    say(f"graph replay, {name}")
+    model = H.gpu_model(wl, make_weights(wl, wl.seed, H.DEV, dt), max_tree=T)
+    model.ht_set_tree(parent, rank)
+    model.ht_prefill(prompt_of(wl))
+    toks = torch.tensor([(3 + 5 * v) % wl.vocab for v in range(T)], dtype=torch.int32, device=H.DEV)
+    z_e = torch.empty(T, wl.vocab, dtype=torch.float32, device=H.DEV)
+    g_e = torch.empty(T, dtype=torch.int32, device=H.DEV)
+    z_g, g_g = torch.empty_like(z_e), torch.empty_like(g_e)
+    model.ht_tree_verify_step(toks, g_e, z_e)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.ht_tree_verify_step(toks, g_g, z_g)
+    for replay in range(4):
+        z_g.zero_()
+        g_g.zero_()
+        other = torch.roll(toks, replay + 1)
+        model.ht_tree_verify_step(other, g_e, z_e)        # eager work of the program between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        model.ht_tree_verify_step(toks, g_e, z_e)
+        torch.cuda.synchronize()
+        assert torch.equal(g_g, g_e), f"replay {replay}: arg-max differs from the eager pass"
+        assert torch.equal(z_g, z_e), f"replay {replay}: logits differ from the eager pass"
+    del graph
+    model.close()
