@@ -96,6 +96,21 @@ int ht_free_model(ht_model *m);
  * before return.  HT_ETREE if malformed. */
 int ht_set_tree(ht_model *m, int32_t T, const int32_t *parent /*host*/, const int32_t *rank /*host*/, void *stream);
 
+/* Draft inside the verify pass (Fig. 2 caption and the end of Sec. 3.4: one forward verifies the current
+ * candidates and produces the next ones; Sec. 5 names the price, a longer input sequence).  Every listed
+ * tree node v gets k pseudo rows: when the pass reaches the transfer layer, row (v, i) = W_i applied to v's
+ * layer-t residual joins at position n + depth[v] + i and sees the cache, v's ancestors-or-self, the pseudo
+ * rows (v, j < i) and itself; the LM head turns it into the distribution of the token i places after v.  If
+ * the next acceptance ends on a listed node, the following `ht_tree_verify_step(tree_tokens = NULL)` builds its
+ * tree from those rows and needs no `ht_transfer` and no draft pass (an `ht_transfer(m, NULL, NULL, ..)` in
+ * between returns at once); if it ends elsewhere the step drafts after acceptance as without this call.
+ * Either way the tokens are the same (the two schedules compute the same distributions).
+ * nodes: host array of `count` distinct node ids of the current tree, count = 0 switches the feature off;
+ * `ht_set_tree` also switches it off.  The pass then has T + count * k rows, which must fit max_tree (and
+ * n + T + count * k must fit max_cache at every step): HT_ECAPACITY otherwise; HT_ETREE for bad ids;
+ * HT_ESTATE without a tree. */
+int ht_set_fused_nodes(ht_model *m, int32_t count, const int32_t *nodes /*host*/, void *stream);
+
 /* Runs the prompt (host array of n token ids, n >= 1) through the model in chunks with plain causal
  * attention, fills the KV cache, sets the pending root token to the greedy next token and keeps the
  * layer-t residual of the last prompt token as the transfer source.  Resets any previous cache. */
@@ -117,7 +132,8 @@ int ht_transfer(ht_model *m, const void *h_src, float *pseudo_out, void *stream)
  * and its ancestors-or-self; K/V go to cache slot n+v; the layer-t residuals are saved.
  * argmax_out: device [T] int32 or NULL, greedy token after each node (ties -> lowest id).
  * logits_out: device [T, vocab] float32 or NULL.
- * HT_ESTATE without a tree / prefill / (for drafting) transfer; HT_ECAPACITY if n + max(T, k) > max_cache. */
+ * HT_ESTATE without a tree / prefill / (for drafting) transfer or in-pass drafts of the accepted node;
+ * HT_ECAPACITY if n + max(T + fused rows, k) > max_cache. */
 int ht_tree_verify_step(ht_model *m, const int32_t *tree_tokens, int32_t *argmax_out, float *logits_out,
                         void *stream);
 
@@ -139,7 +155,9 @@ enum { HT_BUF_DRAFT_LOGITS = 0 /* float [k, vocab] */, HT_BUF_CANDIDATES = 1 /* 
        HT_BUF_TREE_TOKENS = 2 /* int32 [T] */, HT_BUF_SAVED_HIDDEN = 3 /* float [T, d] layer-t residuals */,
        HT_BUF_TRANSFER_SRC = 4 /* float [d] */, HT_BUF_K_CACHE = 5 /* dtype [max_cache, n_kv_heads, head_dim] */,
        HT_BUF_V_CACHE = 6 /* dtype [n_kv_heads, head_dim, max_cache]: key index contiguous */,
-       HT_BUF_PSEUDO = 7 /* float [k, d] */, HT_BUF_ROOT = 8 /* int32 [1] pending root token */ };
+       HT_BUF_PSEUDO = 7 /* float [k, d] */, HT_BUF_ROOT = 8 /* int32 [1] pending root token */,
+       HT_BUF_FUSED_DRAFT_LOGITS = 9 /* float [fused nodes, k, vocab] of the last verify pass */,
+       HT_BUF_FUSED_CANDIDATES = 10 /* int32 [fused nodes, k, HT_MAX_TOPK] */ };
 int ht_get_buffer(const ht_model *m, int32_t which, int32_t layer, void **dev_ptr, size_t *bytes);
 
 /* ---- op-level entry points (same kernels as the model path) -------------------------------------- */

@@ -16,14 +16,15 @@ HT_OK, HT_EINVAL, HT_ECAPACITY, HT_ETREE, HT_ESTATE, HT_EHIP, HT_EUNSUPPORTED = 
 HT_F32, HT_BF16 = 0, 1
 HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_TOPK = 8, 128, 64
 (HT_BUF_DRAFT_LOGITS, HT_BUF_CANDIDATES, HT_BUF_TREE_TOKENS, HT_BUF_SAVED_HIDDEN, HT_BUF_TRANSFER_SRC,
- HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT) = range(9)
+ HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT, HT_BUF_FUSED_DRAFT_LOGITS,
+ HT_BUF_FUSED_CANDIDATES) = range(11)
 
 EXPORTS = [
     "ht_workspace_bytes", "ht_init_model", "ht_free_model", "ht_set_tree", "ht_prefill", "ht_transfer",
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
-    "ht_load_lm_head",
+    "ht_load_lm_head", "ht_set_fused_nodes",
 ]
 
 
@@ -59,6 +60,7 @@ def _load() -> C.CDLL:
         "ht_init_model": (C.c_int, [C.POINTER(ht_config), C.POINTER(ht_weights), vp, sz, vp, C.POINTER(vp)]),
         "ht_free_model": (C.c_int, [vp]),
         "ht_set_tree": (C.c_int, [vp, C.c_int32, i32p, i32p, vp]),
+        "ht_set_fused_nodes": (C.c_int, [vp, C.c_int32, i32p, vp]),
         "ht_prefill": (C.c_int, [vp, i32p, C.c_int32, vp]),
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
         "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
@@ -220,6 +222,11 @@ class HTModel:
     def ht_set_tree(self, parent: Sequence[int], rank: Sequence[int], stream=None) -> None:
         _check(lib.ht_set_tree(self.handle, len(parent), _i32(parent), _i32(rank), _stream_ptr(stream)))
         self.T = len(parent)
+        self.fused = []
+
+    def ht_set_fused_nodes(self, nodes: Sequence[int], stream=None) -> None:
+        _check(lib.ht_set_fused_nodes(self.handle, len(nodes), _i32(nodes) if len(nodes) else None, _stream_ptr(stream)))
+        self.fused = list(nodes)
 
     def ht_prefill(self, tokens: Sequence[int], stream=None) -> None:
         _check(lib.ht_prefill(self.handle, _i32(tokens), len(tokens), _stream_ptr(stream)))
@@ -254,6 +261,10 @@ class HTModel:
             return raw.view(torch.float32).view(c.k, c.vocab)
         if which == HT_BUF_CANDIDATES:
             return raw.view(torch.int32).view(c.k, HT_MAX_TOPK)
+        if which == HT_BUF_FUSED_DRAFT_LOGITS:
+            return raw.view(torch.float32).view(-1, c.k, c.vocab)
+        if which == HT_BUF_FUSED_CANDIDATES:
+            return raw.view(torch.int32).view(-1, c.k, HT_MAX_TOPK)
         if which in (HT_BUF_TREE_TOKENS, HT_BUF_ROOT):
             return raw.view(torch.int32)
         if which == HT_BUF_SAVED_HIDDEN:

@@ -71,6 +71,8 @@ struct Buffers {
   float* pseudo;       // [k, d]
   float* cs;           // rotary table [Mp, hd/2] (cos, sin)
   int32_t *tok, *g, *cand, *width, *prompt;
+  int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
+  int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
   TreeTables tree, chain;
   StepState* state;
   void** kc_ptrs;      // device array [L]
@@ -113,6 +115,8 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.cand = cv.take<int32_t>((size_t)kMaxTransfer * kMaxTopK);
   b.width = cv.take<int32_t>(kMaxTransfer + 2);
   b.prompt = cv.take<int32_t>(c.max_cache);
+  b.fused_rows = cv.take<int32_t>(kMaxTree);
+  b.cand_fused = cv.take<int32_t>((size_t)kMaxTree * kMaxTopK);
   for (TreeTables* t : {&b.tree, &b.chain}) {
     t->parent = cv.take<int32_t>(kMaxTree);
     t->depth = cv.take<int32_t>(kMaxTree);
@@ -123,7 +127,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.kc_ptrs = cv.take<void*>(c.n_layers);
   b.vc_ptrs = cv.take<void*>(c.n_layers);
   b.wt_ptrs = cv.take<void*>(kMaxTransfer);
-  b.topk_scratch = cv.take_bytes(topk_scratch_bytes(c.k));
+  b.topk_scratch = cv.take_bytes(topk_scratch_bytes(kMaxTree));
   b.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes((int)Mp, c.n_heads, c.head_dim));
   b.kc.resize(c.n_layers);
   b.vc.resize(c.n_layers);
@@ -188,7 +192,9 @@ struct ht_model {
   bool qkv_fused = false;       // rotary + KV append run in the QKV projection's epilogue
   std::vector<char> layer_loaded;   // packed copy of each layer present
   bool head_loaded = false;
-  std::vector<int32_t> depth;
+  std::vector<int32_t> depth, parent, rank;
+  std::vector<int32_t> fused;   // tree nodes with pseudo rows in the verify pass (empty: draft after accept only)
+  int drafts_of = -1;           // index into `fused` of the node the last acceptance ended on, -1 if none
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
   StepState* h_state = nullptr;
@@ -218,19 +224,33 @@ int attention(ht_model* m, int layer, int n, int M, const TreeDev& tree, hipStre
 
 // Rows already in b.x go through blocks layer_from+1 .. L (0-based index layer_from .. L-1), then the
 // final norm and, if `logits` is given, the LM head and the row arg-max.
+// With `fused` > 0 the pass starts on M rows and grows by fused * k pseudo rows when it reaches the transfer
+// layer: row M + f k + i is W_(i+1) applied to the layer-t residual of tree node fused_rows[f] (Sec. 3.2), and
+// from there on runs as one more row of the same pass (Fig. 2 caption, Sec. 3.4: verification and the next
+// candidates come out of one forward).  `tree` must then describe all M + fused * k rows.
 int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_hidden, float* logits, int32_t* gout,
-             hipStream_t s) {
+             hipStream_t s, int fused = 0) {
   const ht_config& c = m->cfg;
   Buffers& b = m->b;
   const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn;
-  const size_t pstride = (size_t)M * d;
+  size_t pstride = (size_t)M * d;
   const int n = m->n;
   int rc;
-  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M, c.head_dim, c.rope_base, s));
+  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + fused * c.k, c.head_dim, c.rope_base, s));
   int pending = 0;
   for (int l = layer_from; l < c.n_layers; ++l) {
     float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
     HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
+    if (fused && l == c.transfer_layer[0]) {
+      // the residual after t blocks is complete now: transfer the chosen rows, normalise the new rows, go on wider
+      const int extra = fused * c.k;
+      HT_HIP(launch_transfer(c.dtype, b.x, b.fused_rows, fused, (const void* const*)b.wt_ptrs, b.x + (size_t)M * d, c.k,
+                             d, s));
+      HT_HIP(launch_add_norm(c.dtype, b.x + (size_t)M * d, b.part, 0, 0, m->attn_norm[l],
+                             (char*)b.u + (size_t)M * d * elem_size(c.dtype), nullptr, extra, d, c.rms_eps, s));
+      M += extra;
+      pstride = (size_t)M * d;
+    }
     if (m->qkv_fused) {
       QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
                      c.max_cache};
@@ -505,9 +525,48 @@ int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* ra
   HT_HIP(hipMemcpyAsync(m->b.width, width, sizeof(int32_t) * (kMaxTransfer + 2), hipMemcpyHostToDevice, s));
   HT_HIP(hipStreamSynchronize(s));
   m->depth.assign(depth, depth + T);
+  m->parent.assign(parent, parent + T);
+  m->rank.assign(rank, rank + T);
+  m->fused.clear();
+  m->drafts_of = -1;
   m->T = T;
   m->has_tree = true;
   m->verify_done = false;
+  return HT_OK;
+}
+
+int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
+  if (count < 0 || (count > 0 && !nodes)) return fail(HT_EINVAL, "bad node list");
+  const ht_config& c = m->cfg;
+  const int T = m->T, rows = T + count * c.k;
+  if (rows > c.max_tree || rows > kMaxTree)
+    return fail(HT_ECAPACITY, "%d tree rows + %d x %d pseudo rows exceed max_tree %d", T, count, c.k, c.max_tree);
+  for (int f = 0; f < count; ++f) {
+    if (nodes[f] < 0 || nodes[f] >= T) return fail(HT_ETREE, "fused node %d outside the tree", nodes[f]);
+    for (int e = 0; e < f; ++e)
+      if (nodes[e] == nodes[f]) return fail(HT_ETREE, "fused node %d listed twice", nodes[f]);
+  }
+  // the pass's row tables: the tree, then under every chosen node a chain of k pseudo rows; pseudo row i of
+  // node v sits at v's position + i and sees what v sees, the pseudo rows of v before it and itself
+  std::vector<int32_t> parent(m->parent), rank(m->rank);
+  for (int f = 0; f < count; ++f)
+    for (int i = 0; i < c.k; ++i) {
+      parent.push_back(i == 0 ? nodes[f] : (int32_t)parent.size() - 1);
+      rank.push_back(0);
+    }
+  hipStream_t s = (hipStream_t)stream;
+  HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
+  fill_tables(rows, parent.data(), rank.data(), m->h_stage);
+  int rc;
+  if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
+  int32_t* rows_stage = m->h_stage + kTableInts;
+  for (int f = 0; f < count; ++f) rows_stage[f] = nodes[f];
+  if (count) HT_HIP(hipMemcpyAsync(m->b.fused_rows, rows_stage, sizeof(int32_t) * count, hipMemcpyHostToDevice, s));
+  HT_HIP(hipStreamSynchronize(s));
+  m->fused.assign(nodes, nodes + count);
+  m->drafts_of = -1;
   return HT_OK;
 }
 
@@ -545,8 +604,11 @@ int ht_transfer(ht_model* m, const void* h_src, float* pseudo_out, void* stream)
   if (!h_src && !m->has_prefill) return fail(HT_ESTATE, "no saved hidden state: call ht_prefill first or pass h_src");
   hipStream_t s = (hipStream_t)stream;
   const ht_config& c = m->cfg;
+  if (!h_src && !pseudo_out && m->drafts_of >= 0) return HT_OK;   // the verify pass already drafted from this node
+  m->drafts_of = -1;
   if (h_src) HT_HIP(launch_convert_to_f32(c.dtype, h_src, m->b.h_src, c.d_model, s));
-  HT_HIP(launch_transfer(c.dtype, m->b.h_src, (const void* const*)m->b.wt_ptrs, m->b.pseudo, c.k, c.d_model, s));
+  HT_HIP(launch_transfer(c.dtype, m->b.h_src, nullptr, 1, (const void* const*)m->b.wt_ptrs, m->b.pseudo, c.k, c.d_model,
+                         s));
   if (pseudo_out)
     HT_HIP(hipMemcpyAsync(pseudo_out, m->b.pseudo, sizeof(float) * c.k * c.d_model, hipMemcpyDeviceToDevice, s));
   m->transfer_ready = true;
@@ -557,31 +619,45 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
   if (!m->has_prefill) return fail(HT_ESTATE, "empty cache: call ht_prefill first");
-  if (!tree_tokens && !m->transfer_ready) return fail(HT_ESTATE, "drafting needs a preceding ht_transfer");
+  if (!tree_tokens && !m->transfer_ready && m->drafts_of < 0)
+    return fail(HT_ESTATE, "drafting needs a preceding ht_transfer");
   const ht_config& c = m->cfg;
-  const int T = m->T;
-  const int rows = T > c.k ? T : c.k;
+  const int T = m->T, fused = (int)m->fused.size(), Mall = T + fused * c.k;
+  const int rows = Mall > c.k ? Mall : c.k;
   if (m->n + rows > c.max_cache)
     return fail(HT_ECAPACITY, "cache_len %d + %d rows exceeds max_cache %d", m->n, rows, c.max_cache);
   hipStream_t s = (hipStream_t)stream;
   Buffers& b = m->b;
   int rc;
-  if (!tree_tokens) {
+  if (tree_tokens) {
+    HT_HIP(hipMemcpyAsync(b.tok, tree_tokens, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));
+  } else if (m->drafts_of >= 0 && !m->transfer_ready) {
+    // the last verify pass carried pseudo rows for the node the acceptance ended on: its candidates are the tree
+    HT_HIP(launch_tree_build(b.state, b.cand_fused + (size_t)m->drafts_of * c.k * kMaxTopK, b.tree.dev(), b.tok, T, s));
+  } else {
     // draft: pseudo rows through blocks t+1..L as a chain at positions n, n+1, ..; their K/V land in
     // slots n.. and are overwritten by the verify pass below
     HT_HIP(launch_load_rows(b.pseudo, b.x, c.k, c.d_model, s));
     if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, nullptr, s))) return rc;
-    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.vocab, s));
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, c.vocab, s));
     HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
-  } else {
-    HT_HIP(hipMemcpyAsync(b.tok, tree_tokens, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));
   }
   HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
-  float* z = logits_out ? logits_out : b.logits;
-  if ((rc = run_pass(m, b.tree.dev(), T, 0, true, z, b.g, s))) return rc;
+  if (!fused) {
+    float* z = logits_out ? logits_out : b.logits;
+    if ((rc = run_pass(m, b.tree.dev(), T, 0, true, z, b.g, s))) return rc;
+  } else {
+    // rows T.. of the logits are the draft distributions of the fused nodes (k rows per node)
+    if ((rc = run_pass(m, b.tree.dev(), T, 0, true, b.logits, b.g, s, fused))) return rc;
+    HT_HIP(launch_topk(b.logits + (size_t)T * c.vocab, b.cand_fused, b.width, b.topk_scratch, fused * c.k, c.k, c.vocab,
+                       s));
+    if (logits_out)
+      HT_HIP(hipMemcpyAsync(logits_out, b.logits, sizeof(float) * T * c.vocab, hipMemcpyDeviceToDevice, s));
+  }
   if (argmax_out) HT_HIP(hipMemcpyAsync(argmax_out, b.g, sizeof(int32_t) * T, hipMemcpyDeviceToDevice, s));
   m->verify_done = true;
   m->transfer_ready = false;
+  m->drafts_of = -1;
   return HT_OK;
 }
 
@@ -601,6 +677,9 @@ int ht_accept_and_compact(ht_model* m, int32_t* n_accepted, int32_t* accepted_to
   if (st.m < 1 || st.m > c.k + 1) return fail(HT_EHIP, "accept kernel returned an impossible count %d", st.m);
   m->n += st.m;
   m->verify_done = false;
+  m->drafts_of = -1;
+  for (size_t f = 0; f < m->fused.size(); ++f)
+    if (m->fused[f] == st.path[st.m - 1]) m->drafts_of = (int)f;
   if (n_accepted) *n_accepted = st.m;
   if (next_root) *next_root = st.next_root;
   for (int j = 0; j < st.m; ++j) {
@@ -626,6 +705,11 @@ int ht_get_buffer(const ht_model* m, int32_t which, int32_t layer, void** dev_pt
     case HT_BUF_TRANSFER_SRC: p = m->b.h_src; sz = sizeof(float) * c.d_model; break;
     case HT_BUF_PSEUDO: p = m->b.pseudo; sz = sizeof(float) * c.k * c.d_model; break;
     case HT_BUF_ROOT: p = &m->b.state->root; sz = sizeof(int32_t); break;
+    case HT_BUF_FUSED_DRAFT_LOGITS:
+      p = m->b.logits + (size_t)m->T * c.vocab;
+      sz = sizeof(float) * m->fused.size() * c.k * c.vocab;
+      break;
+    case HT_BUF_FUSED_CANDIDATES: p = m->b.cand_fused; sz = sizeof(int32_t) * m->fused.size() * c.k * kMaxTopK; break;
     case HT_BUF_K_CACHE:
     case HT_BUF_V_CACHE:
       if (layer < 0 || layer >= c.n_layers) return fail(HT_EINVAL, "layer %d out of range", layer);

@@ -350,6 +350,8 @@ hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsp
   if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, s);
   if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, s);
   if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, s);
+  if (M <= 80) return launch_mt<5>(ap, w, M, out, nsplit, epi, qe, s);      // a 64-node tree plus a few pseudo rows
+  if (M <= 96) return launch_mt<6>(ap, w, M, out, nsplit, epi, qe, s);
   return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, s);
 }
 

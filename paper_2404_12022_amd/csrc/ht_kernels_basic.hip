@@ -303,11 +303,11 @@ template <bool FINAL>
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, const float* __restrict__ sv_in,
                                                    const int32_t* __restrict__ si_in, float* __restrict__ sv_out,
                                                    int32_t* __restrict__ si_out, int32_t* __restrict__ cand,
-                                                   const int32_t* __restrict__ width, int V) {
+                                                   const int32_t* __restrict__ width, int period, int V) {
   __shared__ float sv[16];
   __shared__ int si[16];
   const int i = blockIdx.x, slice = blockIdx.y;
-  const int b = width[i + 1];
+  const int b = width[i % period + 1];      // row i drafts the tree level i % period + 1
   // element range of this block: a slice of the logit row, or the survivors of all slices
   int lo, hi;
   if (FINAL) { lo = 0; hi = kTopkSlices * b; }
@@ -341,15 +341,16 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, 
     __syncthreads();
   }
 }
-// scratch: float[k][kTopkSlices][kMaxTopK] followed by int32 of the same shape
-size_t topk_scratch_bytes(int k) { return (size_t)k * kTopkSlices * kMaxTopK * 8; }
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int k, int V,
+// scratch: float[rows][kTopkSlices][kMaxTopK] followed by int32 of the same shape
+size_t topk_scratch_bytes(int rows) { return (size_t)rows * kTopkSlices * kMaxTopK * 8; }
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period, int V,
                        hipStream_t s) {
   float* sv = (float*)scratch;
-  int32_t* si = (int32_t*)(sv + (size_t)k * kTopkSlices * kMaxTopK);
-  hipLaunchKernelGGL(topk_kernel<false>, dim3(k, kTopkSlices), dim3(256), 0, s, d, nullptr, nullptr, sv, si, cand,
-                     width, V);
-  hipLaunchKernelGGL(topk_kernel<true>, dim3(k, 1), dim3(256), 0, s, d, sv, si, nullptr, nullptr, cand, width, V);
+  int32_t* si = (int32_t*)(sv + (size_t)rows * kTopkSlices * kMaxTopK);
+  hipLaunchKernelGGL(topk_kernel<false>, dim3(rows, kTopkSlices), dim3(256), 0, s, d, nullptr, nullptr, sv, si, cand,
+                     width, period, V);
+  hipLaunchKernelGGL(topk_kernel<true>, dim3(rows, 1), dim3(256), 0, s, d, sv, si, nullptr, nullptr, cand, width,
+                     period, V);
   return hipGetLastError();
 }
 
@@ -435,35 +436,54 @@ hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* s
 }
 
 // ------------------------------------------------------------------------------------------------ hidden transfer
-// pseudo[i][o] = sum_c W_i[o][c] h[c].  One wavefront per output feature; the weight row is read
-// once, fully coalesced (16 bytes per lane), h stays in L2.  grid = (d / 4, k), block = 256.
+// pseudo[f][i][o] = sum_c W_i[o][c] h_f[c] for F source vectors h_f = h + row(f) * d, row(f) = src_rows[f] (or f
+// when src_rows is NULL).  One wavefront per output feature; the weight row is read fully coalesced (16 bytes
+// per lane) once per group of four sources, the sources stay in L2.  Every (source, output) sum runs in the
+// same order whatever F is, so one source alone and the same source among several give the same bits.
+// grid = (d / 4, k), block = 256.
 template <typename T>
-__global__ void transfer_kernel(const float* __restrict__ h, const void* const* __restrict__ ws,
-                                float* __restrict__ pseudo, int d) {
+__global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __restrict__ src_rows, int F,
+                                const void* const* __restrict__ ws, float* __restrict__ pseudo, int k, int d) {
+  constexpr int NF = 4;
   const int i = blockIdx.y;
   const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (o >= d) return;
   const T* row = (const T*)ws[i] + (size_t)o * d;
-  float acc = 0.f;
   constexpr int VEC = 16 / sizeof(T);
-  for (int c = lane * VEC; c < d; c += 64 * VEC) {
-    if (c + VEC <= d) {
-      const uint4 raw = *(const uint4*)(row + c);
-      const T* v = (const T*)&raw;
+  for (int f0 = 0; f0 < F; f0 += NF) {
+    const float* hp[NF];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc += Conv<T>::load(v + e) * h[c + e];
-    } else {
-      for (int e = 0; c + e < d; ++e) acc += Conv<T>::load(row + c + e) * h[c + e];
+    for (int j = 0; j < NF; ++j) {
+      const int f = f0 + j < F ? f0 + j : F - 1;
+      hp[j] = h + (size_t)(src_rows ? src_rows[f] : f) * d;
+    }
+    float acc[NF] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = lane * VEC; c < d; c += 64 * VEC) {
+      if (c + VEC <= d) {
+        const uint4 raw = *(const uint4*)(row + c);
+        const T* v = (const T*)&raw;
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[j] += Conv<T>::load(v + e) * hp[j][c + e];
+      } else {
+#pragma unroll
+        for (int j = 0; j < NF; ++j)
+          for (int e = 0; c + e < d; ++e) acc[j] += Conv<T>::load(row + c + e) * hp[j][c + e];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+      const float v = wave_sum(acc[j]);
+      if (lane == 0 && f0 + j < F) pseudo[((size_t)(f0 + j) * k + i) * d + o] = v;
     }
   }
-  acc = wave_sum(acc);
-  if (lane == 0) pseudo[(size_t)i * d + o] = acc;
 }
-hipError_t launch_transfer(int dtype, const float* h, const void* const* w_dev, float* pseudo, int k, int d,
-                           hipStream_t s) {
-  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(transfer_kernel<T>, dim3((d + 3) / 4, k), dim3(256), 0, s, h, w_dev,
-                                              pseudo, d);)
+hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
+                           float* pseudo, int k, int d, hipStream_t s) {
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(transfer_kernel<T>, dim3((d + 3) / 4, k), dim3(256), 0, s, h, src_rows,
+                                              F, w_dev, pseudo, k, d);)
   return hipGetLastError();
 }
 

@@ -58,13 +58,20 @@ def cpu(t):
 class StepCompare:
     """Runs oracle and HIP path side by side, one decode step at a time."""
 
-    def __init__(self, wl, tensors_gpu=None, tensors_cpu=None, tree=None, prompt=None):
+    def __init__(self, wl, tensors_gpu=None, tensors_cpu=None, tree=None, prompt=None, fused=None):
+        """fused: tree nodes that get pseudo rows inside the verify pass (`ht_set_fused_nodes`).  The oracle keeps
+        drafting after acceptance; the two schedules give the same distributions (a CPU test pins that)."""
         self.wl = wl
         self.model = oracle_model(wl, tensors_cpu)
         self.parent, self.rank = tree or tree_of(wl)
         self.ora = O.HiddenTransferOracle(self.model, self.parent, self.rank, wl.max_cache)
-        self.gpu = gpu_model(wl, tensors_gpu, max_tree=max(len(self.parent), 1))
+        self.fused = list(fused or [])
+        self.gpu = gpu_model(wl, tensors_gpu, max_tree=max(len(self.parent) + len(self.fused) * wl.k, 1))
         self.gpu.ht_set_tree(self.parent, self.rank)
+        if self.fused:
+            self.gpu.ht_set_fused_nodes(self.fused)
+        self.in_pass_drafts = None      # (logits [k, V], candidates) of the node the last acceptance ended on
+        self.steps_without_draft_pass = 0
         self.prompt = prompt or prompt_of(wl)
         self.ora.prefill(self.prompt)
         self.gpu.ht_prefill(self.prompt)
@@ -94,7 +101,12 @@ class StepCompare:
     def step(self, forced=None, require_same_tokens=True):
         wl, ora, gpu = self.wl, self.ora, self.gpu
         res = ora.step(forced_tokens=forced)
-        if forced is None:
+        drafts = self.in_pass_drafts
+        if forced is None and drafts is not None:
+            gpu.ht_transfer(None, None)                  # nothing left to do: the last verify pass drafted already
+            gpu.ht_tree_verify_step(None, self.g_gpu, self.z_gpu)
+            self.steps_without_draft_pass += 1
+        elif forced is None:
             pseudo = torch.empty(wl.k, wl.d_model, dtype=torch.float32, device=DEV)
             gpu.ht_transfer(None, pseudo)
             gpu.ht_tree_verify_step(None, self.g_gpu, self.z_gpu)
@@ -105,10 +117,13 @@ class StepCompare:
         z = cpu(self.z_gpu)
         g = [int(t) for t in self.g_gpu.cpu()]
         if forced is None:
-            assert_close(cpu(pseudo), np.stack(res["pseudo"]), wl.dtype, "pseudo hidden states")
-            d = cpu(gpu.ht_get_buffer(B.HT_BUF_DRAFT_LOGITS))
+            if drafts is None:
+                assert_close(cpu(pseudo), np.stack(res["pseudo"]), wl.dtype, "pseudo hidden states")
+                d = cpu(gpu.ht_get_buffer(B.HT_BUF_DRAFT_LOGITS))
+                cand = gpu.ht_get_buffer(B.HT_BUF_CANDIDATES).cpu().numpy()
+            else:
+                d, cand = drafts
             self.max_err = max(self.max_err, assert_close(d, res["D"], wl.dtype, "draft logits"))
-            cand = gpu.ht_get_buffer(B.HT_BUF_CANDIDATES).cpu().numpy()
             # integer stages: the oracle's rules applied to the GPU's own logits must give the GPU's integers
             want_cand = [[]] + [O.top_candidates(d[e - 1], ora.width[e]) for e in range(1, len(ora.width))]
             for e in range(1, len(ora.width)):
@@ -132,6 +147,11 @@ class StepCompare:
         want_path, want_root = O.accept_walk(self.parent, tok_gpu, g)
         assert (path, root, m) == (want_path, want_root, len(want_path)), "acceptance walk on the GPU's own integers"
         assert emitted == [tok_gpu[v] for v in path]
+        self.in_pass_drafts = None
+        if path[-1] in self.fused:                       # keep what the pass drafted for the node it ended on
+            f = self.fused.index(path[-1])
+            self.in_pass_drafts = (cpu(gpu.ht_get_buffer(B.HT_BUF_FUSED_DRAFT_LOGITS)[f]),
+                                   gpu.ht_get_buffer(B.HT_BUF_FUSED_CANDIDATES)[f].cpu().numpy())
         if require_same_tokens:
             assert (path, emitted, root) == (res["path"], res["emitted"], res["root"])
             assert gpu.ht_cache_len() == ora.n

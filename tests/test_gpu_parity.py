@@ -163,6 +163,40 @@ def test_tiny_fp32_sixteen_steps_match_oracle_and_greedy(name):
     assert sc.min_margin > H.FP32_LOGIT_TOL and sc.min_margin > 10 * sc.max_err, (sc.min_margin, sc.max_err)
 
 
+def _rank0_chain(parent, rank):
+    chain, cur = [0], 0
+    while True:
+        kids = [v for v in range(len(parent)) if parent[v] == cur and rank[v] == 0]
+        if not kids:
+            return chain
+        cur = kids[0]
+        chain.append(cur)
+
+
+@pytest.mark.parametrize("name,which", [("tiny", "all"), ("tiny_k3", "all"), ("tiny_full7", "all"), ("tiny", "root"),
+                                        ("tiny_k3", "chain")])
+def test_tiny_fp32_drafting_inside_the_verify_pass(name, which):
+    """Pseudo rows of chosen tree nodes ride along in the verify pass (Fig. 2 caption, end of Sec. 3.4).  The draft
+    distributions they give must equal the oracle's, which drafts after acceptance, and the decoded text must
+    still be the greedy one; nodes outside the chosen set fall back to drafting after acceptance."""
+    H = _H()
+    wl = WORKLOADS[name]
+    parent, rank = tree_of(wl)
+    fused = {"all": list(range(len(parent))), "root": [0], "chain": _rank0_chain(parent, rank)}[which]
+    say(f"in-pass drafting {name}, nodes {fused}")
+    sc = H.StepCompare(wl, fused=fused)
+    out = []
+    for step in range(16):
+        out += sc.step()["emitted"]
+    assert out == sc.model.ar_greedy(sc.prompt, len(out))
+    sc.check_cache("after 16 steps")
+    say(f"{name}/{which}: {sc.steps_without_draft_pass} of 16 steps needed no draft pass, smallest margin "
+        f"{sc.min_margin:.3e}, largest logit error {sc.max_err:.3e}")
+    assert sc.steps_without_draft_pass >= (15 if which == "all" else 1)
+    assert sc.min_margin > H.FP32_LOGIT_TOL and sc.min_margin > 10 * sc.max_err, (sc.min_margin, sc.max_err)
+    sc.gpu.close()
+
+
 def test_tiny_bf16_sixteen_steps():
     H = _H()
     wl = WORKLOADS["tiny_bf16"]
@@ -201,7 +235,9 @@ def test_forced_acceptance_every_root_path(name):
             if target in seen:
                 continue
             seen.add(target)
-            sc = H.StepCompare(wl, tensors_gpu=tensors, prompt=prompt)
+            # odd cases also carry pseudo rows for the rank-0 chain: some forced paths end on it, some beside it
+            fused = _rank0_chain(parent, rank) if len(seen) % 2 else None
+            sc = H.StepCompare(wl, tensors_gpu=tensors, prompt=prompt, fused=fused)
             wrong = [t for t in range(wl.vocab) if t not in set(truth)]
             tok = [wrong[v] for v in range(len(parent))]
             for j, node in enumerate(target):
@@ -313,7 +349,13 @@ def test_error_codes():
     with pytest.raises(B.HTError) as e:
         gpu.ht_set_tree([-1, 0, 0], [0, 1, 1])                      # siblings share a rank
     assert e.value.code == B.HT_ETREE
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_set_fused_nodes([0])                                 # no valid tree yet
+    assert e.value.code == B.HT_ESTATE
     gpu.ht_set_tree(parent, rank)
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_set_fused_nodes([0])                                 # 8 + 2 rows > max_tree = 8
+    assert e.value.code == B.HT_ECAPACITY
     with pytest.raises(B.HTError) as e:
         gpu.ht_tree_verify_step()
     assert e.value.code == B.HT_ESTATE                              # no prefill yet
@@ -338,23 +380,30 @@ def test_error_codes():
 
 
 # ------------------------------------------------------------------ large shapes
-def _shallow_case(name, prompt_len, tree_size=None, cache=None):
+def _shallow_case(name, prompt_len, tree_size=None, cache=None, fused_chain=False, steps=1):
     """Full widths of a named workload (the launch configurations the benchmark uses), depth cut to 2 layers and
     the prompt shortened so that the fp64 oracle finishes in seconds."""
     H = _H()
     base = WORKLOADS[name]
     T = tree_size or base.tree_size
     wl = base.with_(n_layers=2, transfer_layers=tuple(1 for _ in range(base.k)), prompt_len=prompt_len,
-                    max_cache=cache or (prompt_len + 2 * T + 8) // 8 * 8, tree_size=T)
+                    max_cache=cache or (prompt_len + 2 * T + 8 + 8 * steps) // 8 * 8, tree_size=T)
     say(f"{name} width, 2 layers, T={T}, n={prompt_len}: generating weights")
     tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
     cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
     say(f"{name}: oracle + gpu")
-    sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors)
+    fused = _rank0_chain(*tree_of(wl)) if fused_chain else None
+    sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors, fused=fused)
     sc.check_prefill()
-    r = sc.step(require_same_tokens=False)
-    say(f"{name}: emitted {r['emitted']} oracle {r['oracle']['emitted']} worst logit error / bound {sc.max_err:.3f}")
-    sc.check_cache("after one step")
+    for step in range(steps):
+        r = sc.step(require_same_tokens=False)
+        say(f"{name}: emitted {r['emitted']} oracle {r['oracle']['emitted']} worst logit error / bound {sc.max_err:.3f}")
+        if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
+            break                                       # a bf16 near-tie sent the two sequences apart: stop comparing
+    sc.check_cache("after the steps")
+    if fused_chain:
+        say(f"{name}: {sc.steps_without_draft_pass} step(s) built their tree from in-pass drafts")
+        assert sc.steps_without_draft_pass >= 1
     sc.gpu.close()
 
 
@@ -365,6 +414,13 @@ def test_llama13b_width_tree_size_sweep(tree_size):
 
 def test_llama70b_width_grouped_query_attention():
     _shallow_case("llama70b", 80)
+
+
+@pytest.mark.parametrize("name,prompt_len", [("llama7b", 96), ("llama70b", 80)])
+def test_wide_bf16_drafting_inside_the_verify_pass(name, prompt_len):
+    """64-node tree plus k pseudo rows under each node of the rank-0 chain (76 or 84 rows: the 80- and 96-row
+    product instances, two row groups in the tiled attention), three steps."""
+    _shallow_case(name, prompt_len, fused_chain=True, steps=3)
 
 
 def test_llama7b_width_two_layers_against_oracle():
