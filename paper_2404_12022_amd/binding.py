@@ -53,6 +53,10 @@ def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2404_12022_amd.build); "
                           "there is no fallback path")
+    # torch first: the library and torch must share one HIP runtime, and the one torch loads has to be in the
+    # process before libht.so resolves its own dependency (loaded the other way round, the library's runtime
+    # finds no device)
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     i32p, f32p, vp, sz = C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p, C.c_size_t
     sig = {
