@@ -438,13 +438,12 @@ hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* s
 // ------------------------------------------------------------------------------------------------ hidden transfer
 // pseudo[f][i][o] = sum_c W_i[o][c] h_f[c] for F source vectors h_f = h + row(f) * d, row(f) = src_rows[f] (or f
 // when src_rows is NULL).  One wavefront per output feature; the weight row is read fully coalesced (16 bytes
-// per lane) once per group of four sources, the sources stay in L2.  Every (source, output) sum runs in the
+// per lane) once per group of four sources (one source alone has its own instance), the sources stay in L2.  Every (source, output) sum runs in the
 // same order whatever F is, so one source alone and the same source among several give the same bits.
 // grid = (d / 4, k), block = 256.
-template <typename T>
+template <typename T, int NF>
 __global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __restrict__ src_rows, int F,
                                 const void* const* __restrict__ ws, float* __restrict__ pseudo, int k, int d) {
-  constexpr int NF = 4;
   const int i = blockIdx.y;
   const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -458,7 +457,9 @@ __global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __re
       const int f = f0 + j < F ? f0 + j : F - 1;
       hp[j] = h + (size_t)(src_rows ? src_rows[f] : f) * d;
     }
-    float acc[NF] = {0.f, 0.f, 0.f, 0.f};
+    float acc[NF];
+#pragma unroll
+    for (int j = 0; j < NF; ++j) acc[j] = 0.f;
     for (int c = lane * VEC; c < d; c += 64 * VEC) {
       if (c + VEC <= d) {
         const uint4 raw = *(const uint4*)(row + c);
@@ -482,8 +483,13 @@ __global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __re
 }
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
                            float* pseudo, int k, int d, hipStream_t s) {
-  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(transfer_kernel<T>, dim3((d + 3) / 4, k), dim3(256), 0, s, h, src_rows,
-                                              F, w_dev, pseudo, k, d);)
+  if (F == 1) {
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 1>), dim3((d + 3) / 4, k), dim3(256), 0, s, h,
+                                                src_rows, F, w_dev, pseudo, k, d);)
+  } else {
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 4>), dim3((d + 3) / 4, k), dim3(256), 0, s, h,
+                                                src_rows, F, w_dev, pseudo, k, d);)
+  }
   return hipGetLastError();
 }
 
