@@ -531,22 +531,34 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   }
 }
 
-// out[m][h] = sum_s exp2(m_s - m*) O_s / sum_s exp2(m_s - m*) l_s, splits added in index order
+// out[m][h] = sum_s exp2(m_s - m*) O_s / sum_s exp2(m_s - m*) l_s, splits added in index order.
+// HD / 4 lanes per (row, head) pair, four output elements per lane; 256-thread blocks.
 template <int HD>
-__global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int nsplit, int M,
-                                  int Hq, bf16_t* __restrict__ out) {
-  const int m = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
-  float mall = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) mall = fmaxf(mall, part_ml[(((size_t)h * nsplit + s) * M + m) * 2]);
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                                         int nsplit, int M, int Hq, bf16_t* __restrict__ out) {
+  constexpr int LANES = HD / 4, PAIRS = 256 / LANES;
+  const int pair = blockIdx.x * PAIRS + threadIdx.x / LANES;      // pair = h * M + m, the order of the partials
+  const int e = (threadIdx.x % LANES) * 4;
+  if (pair >= M * Hq) return;
+  const int h = pair / M, m = pair % M;
+  float ms[kMaxSplits], mall = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) {
+    ms[s] = part_ml[(((size_t)h * nsplit + s) * M + m) * 2];
+    mall = fmaxf(mall, ms[s]);
+  }
   const float msafe = mall == -INFINITY ? 0.f : mall;
-  float l = 0.f, o = 0.f;
+  float l = 0.f;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < nsplit; ++s) {
     const size_t idx = ((size_t)h * nsplit + s) * M + m;
-    const float f = exp2f(part_ml[idx * 2] - msafe);
+    const float f = exp2f(ms[s] - msafe);
     l += f * part_ml[idx * 2 + 1];
-    o += f * part_o[idx * HD + e];
+    const float4 v = *(const float4*)(part_o + idx * HD + e);
+    o.x += f * v.x; o.y += f * v.y; o.z += f * v.z; o.w += f * v.w;
   }
-  out[(size_t)m * Hq * HD + (size_t)h * HD + e] = float_to_bf16(o / l);
+  const float inv = 1.0f / l;
+  bf16_t ob[4] = {float_to_bf16(o.x * inv), float_to_bf16(o.y * inv), float_to_bf16(o.z * inv), float_to_bf16(o.w * inv)};
+  *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e) = *(const uint2*)ob;
 }
 
 // Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts of a workgroup
@@ -582,7 +594,8 @@ void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int
   else hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
 #undef HT_ATTN_ARGS
   if (p.nsplit > 1)
-    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(M, Hq), dim3(HD), 0, s, part_o, part_ml, p.nsplit, M, Hq, out);
+    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((M * Hq + 256 / (HD / 4) - 1) / (256 / (HD / 4))), dim3(256), 0, s,
+                       part_o, part_ml, p.nsplit, M, Hq, out);
 }
 
 }  // namespace
