@@ -194,6 +194,14 @@ int ht_weight_pack(const void *w, int32_t N, int32_t K, void *packed, void *stre
 size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int ht_skinny_gemm_packed(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
                           void *scratch, size_t scratch_bytes, void *stream);
+
+/* Measurement aid for the roofline (Sec. 1: decoding time is the time to load the parameters): reads `buf`
+ * (device, 16-byte aligned) once with the access pattern of the packed weight stream (256 workgroups, each
+ * walking its own contiguous region in nontemporal 1 KiB wavefront loads) and does nothing else, so its time is
+ * the floor for streaming that many bytes on this machine.  The largest multiple of 8 MiB not above `bytes` is
+ * read and stored in *bytes_read (host, may be NULL); `sink` is a device word the kernel may write.
+ * HT_EINVAL for NULL / misaligned / too small buffers. */
+int ht_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t *bytes_read, void *stream);
 int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
                    void *scratch, size_t scratch_bytes, void *stream);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
-    "ht_load_lm_head", "ht_set_fused_nodes",
+    "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe",
 ]
 
 
@@ -65,6 +65,7 @@ def _load() -> C.CDLL:
         "ht_free_model": (C.c_int, [vp]),
         "ht_set_tree": (C.c_int, [vp, C.c_int32, i32p, i32p, vp]),
         "ht_set_fused_nodes": (C.c_int, [vp, C.c_int32, i32p, vp]),
+        "ht_stream_read_probe": (C.c_int, [vp, sz, vp, C.POINTER(sz), vp]),
         "ht_prefill": (C.c_int, [vp, i32p, C.c_int32, vp]),
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
         "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
@@ -158,6 +159,14 @@ def ht_weight_pack(w, N, K, packed, stream=None) -> None:
 def ht_skinny_gemm_packed(a, packed, M, N, K, out, scratch=None, stream=None) -> None:
     sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.ht_skinny_gemm_packed(_ptr(a), _ptr(packed), M, N, K, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
+
+
+def ht_stream_read_probe(buf, sink, stream=None) -> int:
+    """One streaming pass over the tensor `buf`; returns the bytes read."""
+    got = C.c_size_t(0)
+    _check(lib.ht_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), C.byref(got),
+                                    _stream_ptr(stream)))
+    return got.value
 
 
 def make_config(shape, max_cache: Optional[int] = None, max_tree: Optional[int] = None) -> ht_config:

@@ -796,6 +796,16 @@ int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void*
   return HT_OK;
 }
 
+int ht_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t* bytes_read, void* stream) {
+  if (!buf || !sink) return fail(HT_EINVAL, "NULL argument");
+  if ((uintptr_t)buf % 16) return fail(HT_EINVAL, "buffer must be 16-byte aligned");
+  const size_t got = launch_stream_read(buf, bytes, 256, (uint32_t*)sink, (hipStream_t)stream);
+  if (!got) return fail(HT_EINVAL, "buffer of %zu bytes is smaller than one pass (8 MiB)", bytes);
+  HT_HIP(hipGetLastError());
+  if (bytes_read) *bytes_read = got;
+  return HT_OK;
+}
+
 size_t ht_weight_pack_bytes(int32_t N, int32_t K) {
   if (N < 16 || N % 16 || K < 8 || K % 8) return 0;
   return align_up(packed_weight_bytes(N, K), 256);

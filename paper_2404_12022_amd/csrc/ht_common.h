@@ -91,6 +91,8 @@ hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void*
                           int hd, int cap, const float* saved_h, float* h_src, int d, hipStream_t s);
 hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, float* h_src, int last, int d,
                                  hipStream_t s);
+// measurement aid: one pass over `buf` with the weight stream's access pattern; returns the bytes actually read
+size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* sink, hipStream_t s);
 // pseudo[f][i] = W_i h_f for F sources h_f = h + (src_rows ? src_rows[f] : f) * d
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
                            float* pseudo, int k, int d, hipStream_t s);

@@ -493,6 +493,37 @@ hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, i
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------ streaming probe
+// Reads a buffer once the way the packed projections read their weights (every workgroup walks its own
+// contiguous region, 8 KiB per step as eight nontemporal 1 KiB wavefront loads, eight steps in flight) and does
+// nothing with the data: the time of this kernel is the floor for any weight stream of that size.
+typedef unsigned int probe_u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const probe_u32x4_t* __restrict__ p, size_t vecs_per_group,
+                                                          uint32_t* __restrict__ sink) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const probe_u32x4_t* base = p + (size_t)blockIdx.x * vecs_per_group + wave * 128 + lane;
+  const size_t steps = vecs_per_group / 512;              // 512 vectors = 8 KiB per step
+  probe_u32x4_t acc = {0, 0, 0, 0};
+  for (size_t i = 0; i + 4 <= steps; i += 4) {
+    probe_u32x4_t v[8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      v[2 * u] = __builtin_nontemporal_load(base + (i + u) * 512);
+      v[2 * u + 1] = __builtin_nontemporal_load(base + (i + u) * 512 + 64);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1;     // keeps the loads alive
+}
+// Reads floor(bytes / (groups * 32 KiB)) * groups * 32 KiB bytes; returns that count.
+size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* sink, hipStream_t s) {
+  const size_t per_group = bytes / groups / 32768 * 32768;
+  if (!per_group) return 0;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(groups), dim3(256), 0, s, (const probe_u32x4_t*)buf, per_group / 16, sink);
+  return per_group * groups;
+}
+
 // ------------------------------------------------------------------------------------------------ generic product
 // out[m][n] = sum_k a[m][k] w[n][k], fp32 accumulation.  One wavefront per output feature n, rows in
 // groups of 4.  Used by the fp32 model path and as the fallback for shapes the MFMA kernel rejects.
