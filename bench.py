@@ -74,7 +74,8 @@ def cpu_baseline(wl, T, n, weights):
         reps += 1
     t_block, t_head, t_dblock, t_dhead = (a / reps for a in acc)
     cpu_work = sum(acc)
-    est = wl.n_layers * t_block + t_head + (wl.n_layers - wl.transfer_layers[0]) * t_dblock + t_dhead
+    draft_blocks = sum(wl.n_layers - t for t in wl.transfer_layers) / wl.k      # a k-row block, averaged over the joins
+    est = wl.n_layers * t_block + t_head + draft_blocks * t_dblock + t_dhead
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
@@ -84,7 +85,7 @@ def cpu_baseline(wl, T, n, weights):
             "sample": (f"fp64 numpy oracle, one of {wl.n_layers} decoder blocks at T={T} rows and n={n} cached keys plus "
                        f"the LM head, and one draft block at {wl.k} rows, mean of {reps} repetitions "
                        f"({cpu_work:.1f} s of CPU work) extrapolated to a full step "
-                       f"({wl.n_layers} verify blocks + head + {wl.n_layers - wl.transfer_layers[0]} draft blocks + head)")}
+                       f"({wl.n_layers} verify blocks + head + {draft_blocks:g} draft blocks + head)")}
 
 
 def time_dominant_kernel(wl, T, dev, tdt, stream, calibrate=False):
@@ -346,7 +347,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers d={wl.d_model} {wl.n_heads}x{wl.head_dim} heads "
                                f"ffn={wl.d_ffn} vocab={wl.vocab}, batch 1, cache {n0}, tree T={T} {list(wl.branching)}, "
-                               f"k={wl.k} transfer after layer {wl.transfer_layers[0]}; step = hidden transfer + pseudo "
+                               f"k={wl.k} transfer after layer {sorted(set(wl.transfer_layers))}; step = hidden transfer + pseudo "
                                f"rows through the upper blocks + top-k + tree build + verify + accept + compact, the "
                                f"pseudo rows of the rank-0 chain riding in the verify pass"},
         "step_ms_draft_after_accept": round(ms_step_s1, 4),

@@ -41,10 +41,18 @@ WORKLOADS: Dict[str, Workload] = {
     "tiny_full7": Workload("tiny_full7", 2, 256, 4, 4, 64, 688, 1024, 2, (1, 1), "f32", 32, 128, 7, (2, 2), _SEED + 0),
     # tiny bf16 twin of "tiny" (GPU bf16 kernels at a size the oracle finishes instantly)
     "tiny_bf16": Workload("tiny_bf16", 2, 256, 4, 4, 64, 688, 1024, 2, (1, 1), "bf16", 32, 128, 8, (2, 2), _SEED + 0),
+    # a different transfer layer for every step (Sec. 4.1), and two steps sharing one
+    "tiny_t123": Workload("tiny_t123", 4, 256, 4, 4, 64, 688, 1024, 3, (1, 2, 3), "f32", 32, 128, 8, (2, 2, 1), _SEED + 0),
+    "tiny_t112": Workload("tiny_t112", 3, 256, 4, 4, 64, 688, 1024, 3, (1, 1, 2), "f32", 32, 128, 8, (2, 2, 1), _SEED + 0),
+    "tiny_t123_bf16": Workload("tiny_t123_bf16", 4, 256, 4, 4, 64, 688, 1024, 3, (1, 2, 3), "bf16", 32, 128, 8, (2, 2, 1),
+                               _SEED + 0),
     "llama7b": Workload("llama7b", 32, 4096, 32, 32, 128, 11008, 32000, 3, (24, 24, 24), "bf16", 512, 1024, 64,
                         (10, 3, 2), _SEED + 2),
     "llama13b": Workload("llama13b", 40, 5120, 40, 40, 128, 13824, 32000, 3, (30, 30, 30), "bf16", 2048, 2560, 64,
                          (10, 3, 2), _SEED + 3),
+    # the layers the paper's main experiments name (25 / 30 / 35 of 40, Sec. 4.1)
+    "llama13b_t253035": Workload("llama13b_t253035", 40, 5120, 40, 40, 128, 13824, 32000, 3, (25, 30, 35), "bf16", 2048,
+                                 2560, 64, (10, 3, 2), _SEED + 3),
     "llama70b": Workload("llama70b", 80, 8192, 64, 8, 128, 28672, 32000, 4, (60, 60, 60, 60), "bf16", 4096, 4608, 64,
                          (10, 3, 2, 2), _SEED + 4),
 }

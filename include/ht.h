@@ -42,15 +42,18 @@ enum { HT_F32 = 0, HT_BF16 = 1 };
 enum { HT_MAX_TRANSFER = 8, HT_MAX_TREE = 128, HT_MAX_TOPK = 64 };
 
 /* Llama-style decoder shape plus the hidden-transfer hyper-parameters (Sec. 3.3: the number of
- * transfer steps k and the transfer layers t_i).  This build requires t_1 = ... = t_k. */
+ * transfer steps k and the transfer layers t_i; Sec. 4.1 uses a different layer for every step).  The layers must
+ * not decrease, t_1 <= t_2 <= .. <= t_k; steps that share a layer share one saved hidden state ("slot": slot 0
+ * is the lowest distinct layer). */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_base;
   int32_t dtype;                             /* HT_F32 or HT_BF16: storage type of weights, activations, KV */
   int32_t k;                                 /* 1..HT_MAX_TRANSFER */
-  int32_t transfer_layer[HT_MAX_TRANSFER];   /* 1 <= t_i < n_layers */
+  int32_t transfer_layer[HT_MAX_TRANSFER];   /* 1 <= t_1 <= .. <= t_k < n_layers: residual after t_i blocks */
   int32_t max_cache;                         /* KV slots per layer (multiple of 8) */
-  int32_t max_tree;                          /* largest tree, root included; <= HT_MAX_TREE */
+  int32_t max_tree;                          /* most rows of a pass: tree nodes (root included) plus pseudo
+                                                rows riding in the verify pass; <= HT_MAX_TREE */
 } ht_config;
 
 /* Borrowed weight pointers (device).  They must outlive the model.  Per-layer arrays are host arrays
@@ -117,7 +120,8 @@ int ht_set_fused_nodes(ht_model *m, int32_t count, const int32_t *nodes /*host*/
 int ht_prefill(ht_model *m, const int32_t *tokens /*host*/, int32_t n, void *stream);
 
 /* Hidden transfer (Sec. 3.2; equation of Sec. 3.3): pseudo[i] = W_i h, i = 0..k-1, a bare matrix
- * product.  h_src: [d] in the model dtype, or NULL to use the saved layer-t residual of the last
+ * product of the layer-t_i hidden state.  h_src: [slots, d] in the model dtype (one vector per distinct transfer
+ * layer, lowest first), or NULL to use the saved residuals of the last
  * accepted token.  pseudo_out: [k, d] float32, or NULL; the result is also kept inside the model for
  * the next `ht_tree_verify_step`. */
 int ht_transfer(ht_model *m, const void *h_src, float *pseudo_out, void *stream);
@@ -150,13 +154,17 @@ int32_t ht_cache_len(const ht_model *m);      /* n */
 const char *ht_last_error(void);
 
 /* Read-only views of the model's device buffers, for tests and tools.  `which` is one of HT_BUF_*;
- * `layer` is used by the cache views only.  The pointer stays valid until ht_free_model. */
+ * `layer` selects the decoder layer of the cache views and the transfer-layer slot of the saved residuals and
+ * transfer sources.  The pointer stays valid until ht_free_model. */
 enum { HT_BUF_DRAFT_LOGITS = 0 /* float [k, vocab] */, HT_BUF_CANDIDATES = 1 /* int32 [k, HT_MAX_TOPK] */,
-       HT_BUF_TREE_TOKENS = 2 /* int32 [T] */, HT_BUF_SAVED_HIDDEN = 3 /* float [T, d] layer-t residuals */,
-       HT_BUF_TRANSFER_SRC = 4 /* float [d] */, HT_BUF_K_CACHE = 5 /* dtype [max_cache, n_kv_heads, head_dim] */,
+       HT_BUF_TREE_TOKENS = 2 /* int32 [T] */,
+       HT_BUF_SAVED_HIDDEN = 3 /* float [T, d] residuals at the transfer layer of slot `layer` */,
+       HT_BUF_TRANSFER_SRC = 4 /* float [d] transfer source of slot `layer` */,
+       HT_BUF_K_CACHE = 5 /* dtype [max_cache, n_kv_heads, head_dim] */,
        HT_BUF_V_CACHE = 6 /* dtype [n_kv_heads, head_dim, max_cache]: key index contiguous */,
        HT_BUF_PSEUDO = 7 /* float [k, d] */, HT_BUF_ROOT = 8 /* int32 [1] pending root token */,
-       HT_BUF_FUSED_DRAFT_LOGITS = 9 /* float [fused nodes, k, vocab] of the last verify pass */,
+       HT_BUF_FUSED_DRAFT_LOGITS = 9 /* float [fused nodes * k, vocab] of the last verify pass, rows in the order
+                                        they joined it: slot by slot, node by node, step by step */,
        HT_BUF_FUSED_CANDIDATES = 10 /* int32 [fused nodes, k, HT_MAX_TOPK] */ };
 int ht_get_buffer(const ht_model *m, int32_t which, int32_t layer, void **dev_ptr, size_t *bytes);
 

@@ -258,6 +258,21 @@ class HTModel:
         _check(lib.ht_accept_and_compact(self.handle, C.byref(m), toks, C.byref(root), path, _stream_ptr(stream)))
         return m.value, list(toks[:m.value]), root.value, list(path[:m.value])
 
+    def fused_drafts(self, f: int):
+        """(draft logits [k, vocab], candidates [k, HT_MAX_TOPK]) that the last verify pass produced for fused node
+        number f.  The pass holds pseudo rows in the order they joined: transfer-layer slot by slot, node by node,
+        step by step."""
+        c = self.cfg
+        layers = list(c.transfer_layer[:c.k])
+        firsts = [i for i in range(c.k) if i == 0 or layers[i] != layers[i - 1]]
+        rows = []
+        for i in range(c.k):
+            first = max(j for j in firsts if j <= i)
+            count = sum(1 for t in layers if t == layers[first])
+            rows.append(len(self.fused) * first + f * count + (i - first))
+        z = self.ht_get_buffer(HT_BUF_FUSED_DRAFT_LOGITS)
+        return z[rows], self.ht_get_buffer(HT_BUF_FUSED_CANDIDATES)[f]
+
     def ht_cache_len(self) -> int:
         return lib.ht_cache_len(self.handle)
 
@@ -275,7 +290,7 @@ class HTModel:
         if which == HT_BUF_CANDIDATES:
             return raw.view(torch.int32).view(c.k, HT_MAX_TOPK)
         if which == HT_BUF_FUSED_DRAFT_LOGITS:
-            return raw.view(torch.float32).view(-1, c.k, c.vocab)
+            return raw.view(torch.float32).view(-1, c.vocab)
         if which == HT_BUF_FUSED_CANDIDATES:
             return raw.view(torch.int32).view(-1, c.k, HT_MAX_TOPK)
         if which in (HT_BUF_TREE_TOKENS, HT_BUF_ROOT):

@@ -66,13 +66,14 @@ struct Buffers {
   float* part;         // split-K partial sums [kMaxSplitK][Mp][d]
   float* logits;       // [Mp, V]
   float* dlogits;      // draft logits [k, V]
-  float* saved_h;      // layer-t residuals of the last verify pass [Mp, d]
-  float* h_src;        // transfer source [d]
+  float* saved_h;      // residuals of the last verify pass at every distinct transfer layer [slots <= k][Mp, d]
+  float* h_src;        // transfer sources [slots][d]
   float* pseudo;       // [k, d]
   float* cs;           // rotary table [Mp, hd/2] (cos, sin)
   int32_t *tok, *g, *cand, *width, *prompt;
   int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
   int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
+  int32_t* fused_src;    // logits row (past the tree rows) that holds the draft of (fused node, step) [kMaxTree]
   TreeTables tree, chain;
   StepState* state;
   void** kc_ptrs;      // device array [L]
@@ -106,8 +107,8 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.part = cv.take<float>((size_t)kMaxSplitK * Mp * d);
   b.logits = cv.take<float>(Mp * c.vocab);
   b.dlogits = cv.take<float>((size_t)padded_rows(c.k) * c.vocab);
-  b.saved_h = cv.take<float>(Mp * d);
-  b.h_src = cv.take<float>(d);
+  b.saved_h = cv.take<float>((size_t)c.k * Mp * d);
+  b.h_src = cv.take<float>((size_t)c.k * d);
   b.pseudo = cv.take<float>((size_t)c.k * d);
   b.cs = cv.take<float>(Mp * c.head_dim);
   b.tok = cv.take<int32_t>(Mp);
@@ -117,6 +118,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.prompt = cv.take<int32_t>(c.max_cache);
   b.fused_rows = cv.take<int32_t>(kMaxTree);
   b.cand_fused = cv.take<int32_t>((size_t)kMaxTree * kMaxTopK);
+  b.fused_src = cv.take<int32_t>(kMaxTree);
   for (TreeTables* t : {&b.tree, &b.chain}) {
     t->parent = cv.take<int32_t>(kMaxTree);
     t->depth = cv.take<int32_t>(kMaxTree);
@@ -167,8 +169,8 @@ int check_config(const ht_config* c) {
   for (int i = 0; i < c->k; ++i) {
     if (c->transfer_layer[i] < 1 || c->transfer_layer[i] >= c->n_layers)
       return fail(HT_EINVAL, "transfer_layer[%d]=%d outside 1..n_layers-1", i, c->transfer_layer[i]);
-    if (c->transfer_layer[i] != c->transfer_layer[0])
-      return fail(HT_EUNSUPPORTED, "distinct transfer layers per step are not supported by this build");
+    if (i && c->transfer_layer[i] < c->transfer_layer[i - 1])
+      return fail(HT_EINVAL, "transfer layers must not decrease (t_1 <= t_2 <= ..)");
   }
   if (c->max_tree < 1 || c->max_tree > HT_MAX_TREE) return fail(HT_EINVAL, "max_tree must be in 1..%d", HT_MAX_TREE);
   if (c->max_cache < 8 || c->max_cache % 8) return fail(HT_EINVAL, "max_cache must be a positive multiple of 8");
@@ -193,6 +195,9 @@ struct ht_model {
   std::vector<char> layer_loaded;   // packed copy of each layer present
   bool head_loaded = false;
   std::vector<int32_t> depth, parent, rank;
+  // transfer steps grouped by layer (Sec. 3.2: step i reads the hidden state of layer t_i): slot g covers steps
+  // slot_first[g] .. slot_first[g] + slot_count[g] - 1, all at layer slot_layer[g]; slot_of_layer[l] = g or -1
+  std::vector<int> slot_layer, slot_first, slot_count, slot_of_layer;
   std::vector<int32_t> fused;   // tree nodes with pseudo rows in the verify pass (empty: draft after accept only)
   int drafts_of = -1;           // index into `fused` of the node the last acceptance ended on, -1 if none
   // pinned host staging
@@ -222,35 +227,52 @@ int attention(ht_model* m, int layer, int n, int M, const TreeDev& tree, hipStre
   return HT_OK;
 }
 
-// Rows already in b.x go through blocks layer_from+1 .. L (0-based index layer_from .. L-1), then the
-// final norm and, if `logits` is given, the LM head and the row arg-max.
-// With `fused` > 0 the pass starts on M rows and grows by fused * k pseudo rows when it reaches the transfer
-// layer: row M + f k + i is W_(i+1) applied to the layer-t residual of tree node fused_rows[f] (Sec. 3.2), and
-// from there on runs as one more row of the same pass (Fig. 2 caption, Sec. 3.4: verification and the next
-// candidates come out of one forward).  `tree` must then describe all M + fused * k rows.
+// Rows that join a pass on its way up.  kFromTree: under each of F tree nodes (b.fused_rows) the pseudo rows of
+// every transfer step, W_i applied to the node's residual at layer t_i (Sec. 3.2), created when the pass reaches
+// t_i: verification and the next candidates then come out of one forward (Fig. 2 caption, Sec. 3.4).
+// kFromBuffer: the k rows of b.pseudo (draft pass after acceptance), row i joining at layer t_i.
+enum JoinMode { kNoJoin = 0, kFromTree = 1, kFromBuffer = 2 };
+
+// Rows already in b.x (M of them, possibly none) go through blocks layer_from+1 .. L (0-based index
+// layer_from .. L-1) together with the rows that join on the way, then the final norm and, if `logits` is given,
+// the LM head and the row arg-max.  `tree` must describe all rows the pass ends with.
 int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_hidden, float* logits, int32_t* gout,
-             hipStream_t s, int fused = 0) {
+             hipStream_t s, JoinMode join = kNoJoin, int F = 0) {
   const ht_config& c = m->cfg;
   Buffers& b = m->b;
   const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn;
+  const size_t es = elem_size(c.dtype), slot_stride = (size_t)m->Mp * d;
   size_t pstride = (size_t)M * d;
   const int n = m->n;
   int rc;
-  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + fused * c.k, c.head_dim, c.rope_base, s));
+  const int joining = join == kFromTree ? F * c.k : join == kFromBuffer ? c.k : 0;
+  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + joining, c.head_dim, c.rope_base, s));
   int pending = 0;
   for (int l = layer_from; l < c.n_layers; ++l) {
-    float* save = (save_hidden && l == c.transfer_layer[0]) ? b.saved_h : nullptr;
-    HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
-    if (fused && l == c.transfer_layer[0]) {
-      // the residual after t blocks is complete now: transfer the chosen rows, normalise the new rows, go on wider
-      const int extra = fused * c.k;
-      HT_HIP(launch_transfer(c.dtype, b.x, b.fused_rows, fused, (const void* const*)b.wt_ptrs, b.x + (size_t)M * d, c.k,
-                             d, s));
-      HT_HIP(launch_add_norm(c.dtype, b.x + (size_t)M * d, b.part, 0, 0, m->attn_norm[l],
-                             (char*)b.u + (size_t)M * d * elem_size(c.dtype), nullptr, extra, d, c.rms_eps, s));
+    const int slot = m->slot_of_layer[l];
+    if (M > 0) {
+      float* save = (save_hidden && slot >= 0) ? b.saved_h + slot * slot_stride : nullptr;
+      HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
+    }
+    if (join != kNoJoin && slot >= 0) {
+      // the residual after l blocks is complete now: make the rows of this layer's transfer steps, normalise
+      // them, go on wider
+      const int i0 = m->slot_first[slot], cnt = m->slot_count[slot];
+      int extra;
+      if (join == kFromTree) {
+        extra = F * cnt;                  // row of (node f, step i) = M + f * cnt + (i - i0)
+        HT_HIP(launch_transfer(c.dtype, b.x, b.fused_rows, F, (const void* const*)b.wt_ptrs, b.x + (size_t)M * d, i0, cnt,
+                               cnt, d, s));
+      } else {
+        extra = cnt;
+        HT_HIP(launch_load_rows(b.pseudo + (size_t)i0 * d, b.x + (size_t)M * d, cnt, d, s));
+      }
+      HT_HIP(launch_add_norm(c.dtype, b.x + (size_t)M * d, b.part, 0, 0, m->attn_norm[l], (char*)b.u + (size_t)M * d * es,
+                             nullptr, extra, d, c.rms_eps, s));
       M += extra;
       pstride = (size_t)M * d;
     }
+    if (M == 0) continue;
     if (m->qkv_fused) {
       QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
                      c.max_cache};
@@ -424,6 +446,16 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   m->w_down.assign(w->w_down, w->w_down + L);
   m->w_transfer.assign(w->w_transfer, w->w_transfer + cfg->k);
   m->Mp = padded_rows(cfg->max_tree > cfg->k ? cfg->max_tree : cfg->k);
+  m->slot_of_layer.assign(L, -1);
+  for (int i = 0; i < cfg->k; ++i) {
+    if (i == 0 || cfg->transfer_layer[i] != cfg->transfer_layer[i - 1]) {
+      m->slot_of_layer[cfg->transfer_layer[i]] = (int)m->slot_layer.size();
+      m->slot_layer.push_back(cfg->transfer_layer[i]);
+      m->slot_first.push_back(i);
+      m->slot_count.push_back(0);
+    }
+    ++m->slot_count.back();
+  }
   const char* env = getenv("HT_FORCE_SIMPLE");
   m->use_mfma = !(env && env[0] == '1');
   Carver cv(workspace);
@@ -548,22 +580,36 @@ int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* s
     for (int e = 0; e < f; ++e)
       if (nodes[e] == nodes[f]) return fail(HT_ETREE, "fused node %d listed twice", nodes[f]);
   }
-  // the pass's row tables: the tree, then under every chosen node a chain of k pseudo rows; pseudo row i of
-  // node v sits at v's position + i and sees what v sees, the pseudo rows of v before it and itself
+  // the pass's row tables: the tree, then the pseudo rows in the order they join the pass: transfer layer by
+  // transfer layer, node by node, step by step.  Pseudo row i of node v hangs under row i - 1 of v (the first
+  // under v itself): it sits at v's position + i and sees what v sees, v's earlier pseudo rows and itself.
   std::vector<int32_t> parent(m->parent), rank(m->rank);
-  for (int f = 0; f < count; ++f)
-    for (int i = 0; i < c.k; ++i) {
-      parent.push_back(i == 0 ? nodes[f] : (int32_t)parent.size() - 1);
-      rank.push_back(0);
-    }
+  auto row_of = [&](int f, int i) {            // i: 0-based transfer step
+    int g = 0;
+    while (i >= m->slot_first[g] + m->slot_count[g]) ++g;
+    return T + count * m->slot_first[g] + f * m->slot_count[g] + (i - m->slot_first[g]);
+  };
+  for (size_t g = 0; g < m->slot_layer.size(); ++g)
+    for (int f = 0; f < count; ++f)
+      for (int i = m->slot_first[g]; i < m->slot_first[g] + m->slot_count[g]; ++i) {
+        parent.push_back(i == 0 ? nodes[f] : row_of(f, i - 1));
+        rank.push_back(0);
+      }
   hipStream_t s = (hipStream_t)stream;
   HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
   fill_tables(rows, parent.data(), rank.data(), m->h_stage);
   int rc;
   if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
   int32_t* rows_stage = m->h_stage + kTableInts;
-  for (int f = 0; f < count; ++f) rows_stage[f] = nodes[f];
-  if (count) HT_HIP(hipMemcpyAsync(m->b.fused_rows, rows_stage, sizeof(int32_t) * count, hipMemcpyHostToDevice, s));
+  int32_t* src_stage = rows_stage + kMaxTree;      // logits row, counted from the first pseudo row, of (node, step)
+  for (int f = 0; f < count; ++f) {
+    rows_stage[f] = nodes[f];
+    for (int i = 0; i < c.k; ++i) src_stage[f * c.k + i] = row_of(f, i) - T;
+  }
+  if (count) {
+    HT_HIP(hipMemcpyAsync(m->b.fused_rows, rows_stage, sizeof(int32_t) * count, hipMemcpyHostToDevice, s));
+    HT_HIP(hipMemcpyAsync(m->b.fused_src, src_stage, sizeof(int32_t) * count * c.k, hipMemcpyHostToDevice, s));
+  }
   HT_HIP(hipStreamSynchronize(s));
   m->fused.assign(nodes, nodes + count);
   m->drafts_of = -1;
@@ -591,7 +637,9 @@ int ht_prefill(ht_model* m, const int32_t* tokens, int32_t n, void* stream) {
     const bool last = start + rows == n;
     HT_HIP(launch_embed(c.dtype, m->tok_emb, m->b.prompt + start, m->b.x, rows, c.d_model, s));
     if ((rc = run_pass(m, chain, rows, 0, true, last ? m->b.logits : nullptr, m->b.g, s))) return rc;
-    if (last) HT_HIP(launch_prefill_finish(m->b.state, m->b.g, m->b.saved_h, m->b.h_src, rows - 1, c.d_model, s));
+    if (last)
+      HT_HIP(launch_prefill_finish(m->b.state, m->b.g, m->b.saved_h, (size_t)m->Mp * c.d_model, (int)m->slot_layer.size(),
+                                   m->b.h_src, rows - 1, c.d_model, s));
     m->n += rows;                              // chain rows are already in their final slots
   }
   HT_HIP(hipStreamSynchronize(s));
@@ -606,9 +654,12 @@ int ht_transfer(ht_model* m, const void* h_src, float* pseudo_out, void* stream)
   const ht_config& c = m->cfg;
   if (!h_src && !pseudo_out && m->drafts_of >= 0) return HT_OK;   // the verify pass already drafted from this node
   m->drafts_of = -1;
-  if (h_src) HT_HIP(launch_convert_to_f32(c.dtype, h_src, m->b.h_src, c.d_model, s));
-  HT_HIP(launch_transfer(c.dtype, m->b.h_src, nullptr, 1, (const void* const*)m->b.wt_ptrs, m->b.pseudo, c.k, c.d_model,
-                         s));
+  const int slots = (int)m->slot_layer.size();
+  if (h_src) HT_HIP(launch_convert_to_f32(c.dtype, h_src, m->b.h_src, slots * c.d_model, s));
+  for (int g = 0; g < slots; ++g)       // step i reads the source of its own layer
+    HT_HIP(launch_transfer(c.dtype, m->b.h_src + (size_t)g * c.d_model, nullptr, 1, (const void* const*)m->b.wt_ptrs,
+                           m->b.pseudo + (size_t)m->slot_first[g] * c.d_model, m->slot_first[g], m->slot_count[g], 0,
+                           c.d_model, s));
   if (pseudo_out)
     HT_HIP(hipMemcpyAsync(pseudo_out, m->b.pseudo, sizeof(float) * c.k * c.d_model, hipMemcpyDeviceToDevice, s));
   m->transfer_ready = true;
@@ -637,9 +688,8 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
   } else {
     // draft: pseudo rows through blocks t+1..L as a chain at positions n, n+1, ..; their K/V land in
     // slots n.. and are overwritten by the verify pass below
-    HT_HIP(launch_load_rows(b.pseudo, b.x, c.k, c.d_model, s));
-    if ((rc = run_pass(m, b.chain.dev(), c.k, c.transfer_layer[0], false, b.dlogits, nullptr, s))) return rc;
-    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, c.vocab, s));
+    if ((rc = run_pass(m, b.chain.dev(), 0, c.transfer_layer[0], false, b.dlogits, nullptr, s, kFromBuffer))) return rc;
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, nullptr, c.vocab, s));
     HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
   }
   HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
@@ -648,9 +698,9 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
     if ((rc = run_pass(m, b.tree.dev(), T, 0, true, z, b.g, s))) return rc;
   } else {
     // rows T.. of the logits are the draft distributions of the fused nodes (k rows per node)
-    if ((rc = run_pass(m, b.tree.dev(), T, 0, true, b.logits, b.g, s, fused))) return rc;
-    HT_HIP(launch_topk(b.logits + (size_t)T * c.vocab, b.cand_fused, b.width, b.topk_scratch, fused * c.k, c.k, c.vocab,
-                       s));
+    if ((rc = run_pass(m, b.tree.dev(), T, 0, true, b.logits, b.g, s, kFromTree, fused))) return rc;
+    HT_HIP(launch_topk(b.logits + (size_t)T * c.vocab, b.cand_fused, b.width, b.topk_scratch, fused * c.k, c.k, b.fused_src,
+                       c.vocab, s));
     if (logits_out)
       HT_HIP(hipMemcpyAsync(logits_out, b.logits, sizeof(float) * T * c.vocab, hipMemcpyDeviceToDevice, s));
   }
@@ -670,7 +720,7 @@ int ht_accept_and_compact(ht_model* m, int32_t* n_accepted, int32_t* accepted_to
   Buffers& b = m->b;
   HT_HIP(launch_accept(b.state, b.tree.dev(), b.tok, b.g, m->T, s));
   HT_HIP(launch_compact(c.dtype, b.state, b.kc_ptrs, b.vc_ptrs, c.n_layers, m->n, c.n_kv_heads, c.head_dim, c.max_cache,
-                        b.saved_h, b.h_src, c.d_model, s));
+                        b.saved_h, (size_t)m->Mp * c.d_model, (int)m->slot_layer.size(), b.h_src, c.d_model, s));
   HT_HIP(hipMemcpyAsync(m->h_state, b.state, sizeof(StepState), hipMemcpyDeviceToHost, s));
   HT_HIP(hipStreamSynchronize(s));
   const StepState& st = *m->h_state;
@@ -701,8 +751,12 @@ int ht_get_buffer(const ht_model* m, int32_t which, int32_t layer, void** dev_pt
     case HT_BUF_DRAFT_LOGITS: p = m->b.dlogits; sz = sizeof(float) * c.k * c.vocab; break;
     case HT_BUF_CANDIDATES: p = m->b.cand; sz = sizeof(int32_t) * c.k * kMaxTopK; break;
     case HT_BUF_TREE_TOKENS: p = m->b.tok; sz = sizeof(int32_t) * m->T; break;
-    case HT_BUF_SAVED_HIDDEN: p = m->b.saved_h; sz = sizeof(float) * m->T * c.d_model; break;
-    case HT_BUF_TRANSFER_SRC: p = m->b.h_src; sz = sizeof(float) * c.d_model; break;
+    case HT_BUF_SAVED_HIDDEN:
+    case HT_BUF_TRANSFER_SRC:            // `layer` selects the distinct transfer layer (0 = lowest)
+      if (layer < 0 || layer >= (int)m->slot_layer.size()) return fail(HT_EINVAL, "transfer-layer slot %d out of range", layer);
+      if (which == HT_BUF_SAVED_HIDDEN) { p = m->b.saved_h + (size_t)layer * m->Mp * c.d_model; sz = sizeof(float) * m->T * c.d_model; }
+      else { p = m->b.h_src + (size_t)layer * c.d_model; sz = sizeof(float) * c.d_model; }
+      break;
     case HT_BUF_PSEUDO: p = m->b.pseudo; sz = sizeof(float) * c.k * c.d_model; break;
     case HT_BUF_ROOT: p = &m->b.state->root; sz = sizeof(int32_t); break;
     case HT_BUF_FUSED_DRAFT_LOGITS:

@@ -80,22 +80,24 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
                                     hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int M, int f, hipStream_t s);
 hipError_t launch_argmax(const float* z, int32_t* g, int M, int V, hipStream_t s);
-// top width[i % period + 1] entries of each of `rows` logit rows; scratch: topk_scratch_bytes(rows) bytes for
-// the per-slice survivors
+// cand[i] = top width[i % period + 1] entries of logit row src_row[i] (row i when src_row is NULL), i < rows;
+// scratch: topk_scratch_bytes(rows) bytes for the per-slice survivors
 size_t topk_scratch_bytes(int rows);
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period, int V,
-                       hipStream_t s);
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
+                       const int32_t* src_row, int V, hipStream_t s);
 hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
 hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s);
 hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
-                          int hd, int cap, const float* saved_h, float* h_src, int d, hipStream_t s);
-hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, float* h_src, int last, int d,
-                                 hipStream_t s);
+                          int hd, int cap, const float* saved_h, size_t slot_stride, int slots, float* h_src, int d,
+                          hipStream_t s);
+hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, size_t slot_stride, int slots,
+                                 float* h_src, int last, int d, hipStream_t s);
 // measurement aid: one pass over `buf` with the weight stream's access pattern; returns the bytes actually read
 size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* sink, hipStream_t s);
-// pseudo[f][i] = W_i h_f for F sources h_f = h + (src_rows ? src_rows[f] : f) * d
+// pseudo[f * row_stride + (i - i0)] = W_i h_f for steps i0 <= i < i0 + steps and F sources
+// h_f = h + (src_rows ? src_rows[f] : f) * d
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
-                           float* pseudo, int k, int d, hipStream_t s);
+                           float* pseudo, int i0, int steps, int row_stride, int d, hipStream_t s);
 hipError_t launch_convert_to_f32(int dtype, const void* src, float* dst, int n, hipStream_t s);
 // out[i] = sum_s part[s][i] in the fixed order s = 0, 1, ..
 hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, float* out, hipStream_t s);

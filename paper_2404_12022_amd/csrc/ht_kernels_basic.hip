@@ -303,7 +303,8 @@ template <bool FINAL>
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, const float* __restrict__ sv_in,
                                                    const int32_t* __restrict__ si_in, float* __restrict__ sv_out,
                                                    int32_t* __restrict__ si_out, int32_t* __restrict__ cand,
-                                                   const int32_t* __restrict__ width, int period, int V) {
+                                                   const int32_t* __restrict__ width, int period, const int32_t* __restrict__ src_row,
+                                                   int V) {
   __shared__ float sv[16];
   __shared__ int si[16];
   const int i = blockIdx.x, slice = blockIdx.y;
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, 
       float v;
       int id;
       if (FINAL) { v = sv_in[(size_t)i * kTopkSlices * kMaxTopK + j]; id = si_in[(size_t)i * kTopkSlices * kMaxTopK + j]; }
-      else { v = d[(size_t)i * V + j]; id = j; }
+      else { v = d[(size_t)(src_row ? src_row[i] : i) * V + j]; id = j; }
       const bool after = r == 0 || v < pv || (v == pv && id > pi);
       if (after && better(v, id, bv, bi)) { bv = v; bi = id; }
     }
@@ -343,14 +344,14 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, 
 }
 // scratch: float[rows][kTopkSlices][kMaxTopK] followed by int32 of the same shape
 size_t topk_scratch_bytes(int rows) { return (size_t)rows * kTopkSlices * kMaxTopK * 8; }
-hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period, int V,
-                       hipStream_t s) {
+hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
+                       const int32_t* src_row, int V, hipStream_t s) {
   float* sv = (float*)scratch;
   int32_t* si = (int32_t*)(sv + (size_t)rows * kTopkSlices * kMaxTopK);
   hipLaunchKernelGGL(topk_kernel<false>, dim3(rows, kTopkSlices), dim3(256), 0, s, d, nullptr, nullptr, sv, si, cand,
-                     width, period, V);
+                     width, period, src_row, V);
   hipLaunchKernelGGL(topk_kernel<true>, dim3(rows, 1), dim3(256), 0, s, d, sv, si, nullptr, nullptr, cand, width,
-                     period, V);
+                     period, src_row, V);
   return hipGetLastError();
 }
 
@@ -398,7 +399,8 @@ hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const 
 template <typename T>
 __global__ void compact_kernel(const StepState* __restrict__ st, void* const* __restrict__ kcs,
                                void* const* __restrict__ vcs, int n, int row_elems, int cap,
-                               const float* __restrict__ saved_h, float* __restrict__ h_src, int d) {
+                               const float* __restrict__ saved_h, size_t slot_stride, int slots,
+                               float* __restrict__ h_src, int d) {
   const int layer = blockIdx.y;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   const int m = st->m;
@@ -412,26 +414,32 @@ __global__ void compact_kernel(const StepState* __restrict__ st, void* const* __
       vc[(size_t)e * cap + n + j] = vc[(size_t)e * cap + n + src];
     }
   }
-  if (layer == 0 && e < d) h_src[e] = saved_h[(size_t)st->path[m - 1] * d + e];
+  if (layer < slots && e < d)       // one transfer source per distinct transfer layer (slots <= layers)
+    h_src[(size_t)layer * d + e] = saved_h[layer * slot_stride + (size_t)st->path[m - 1] * d + e];
 }
 hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
-                          int hd, int cap, const float* saved_h, float* h_src, int d, hipStream_t s) {
+                          int hd, int cap, const float* saved_h, size_t slot_stride, int slots, float* h_src, int d,
+                          hipStream_t s) {
   const int row = Hkv * hd;
   const int cols = row > d ? row : d;
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(compact_kernel<T>, dim3((cols + 255) / 256, L), dim3(256), 0, s, st, kc,
-                                              vc, n, row, cap, saved_h, h_src, d);)
+                                              vc, n, row, cap, saved_h, slot_stride, slots, h_src, d);)
   return hipGetLastError();
 }
 
+// saved_h holds one [rows, d] residual image per distinct transfer layer (`slot_stride` floats apart); the
+// transfer sources h_src[slot][d] become the images' row `last`.  blockIdx.y = slot.
 __global__ void prefill_finish_kernel(StepState* __restrict__ st, const int32_t* __restrict__ g,
-                                      const float* __restrict__ saved_h, float* __restrict__ h_src, int last, int d) {
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < d) h_src[e] = saved_h[(size_t)last * d + e];
-  if (e == 0) { st->root = g[last]; st->next_root = g[last]; st->m = 0; }
+                                      const float* __restrict__ saved_h, size_t slot_stride, float* __restrict__ h_src,
+                                      int last, int d) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x, slot = blockIdx.y;
+  if (e < d) h_src[(size_t)slot * d + e] = saved_h[slot * slot_stride + (size_t)last * d + e];
+  if (e == 0 && slot == 0) { st->root = g[last]; st->next_root = g[last]; st->m = 0; }
 }
-hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, float* h_src, int last, int d,
-                                 hipStream_t s) {
-  hipLaunchKernelGGL(prefill_finish_kernel, dim3((d + 255) / 256), dim3(256), 0, s, st, g, saved_h, h_src, last, d);
+hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, size_t slot_stride, int slots,
+                                 float* h_src, int last, int d, hipStream_t s) {
+  hipLaunchKernelGGL(prefill_finish_kernel, dim3((d + 255) / 256, slots), dim3(256), 0, s, st, g, saved_h, slot_stride,
+                     h_src, last, d);
   return hipGetLastError();
 }
 
@@ -440,11 +448,13 @@ hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* s
 // when src_rows is NULL).  One wavefront per output feature; the weight row is read fully coalesced (16 bytes
 // per lane) once per group of four sources (one source alone has its own instance), the sources stay in L2.  Every (source, output) sum runs in the
 // same order whatever F is, so one source alone and the same source among several give the same bits.
-// grid = (d / 4, k), block = 256.
+// Steps i0 .. i0 + gridDim.y - 1 are computed; the output row of (f, i) is f * row_stride + (i - i0).
+// grid = (d / 4, steps), block = 256.
 template <typename T, int NF>
 __global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __restrict__ src_rows, int F,
-                                const void* const* __restrict__ ws, float* __restrict__ pseudo, int k, int d) {
-  const int i = blockIdx.y;
+                                const void* const* __restrict__ ws, float* __restrict__ pseudo, int i0, int row_stride,
+                                int d) {
+  const int i = i0 + blockIdx.y;
   const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (o >= d) return;
@@ -477,18 +487,18 @@ __global__ void transfer_kernel(const float* __restrict__ h, const int32_t* __re
 #pragma unroll
     for (int j = 0; j < NF; ++j) {
       const float v = wave_sum(acc[j]);
-      if (lane == 0 && f0 + j < F) pseudo[((size_t)(f0 + j) * k + i) * d + o] = v;
+      if (lane == 0 && f0 + j < F) pseudo[((size_t)(f0 + j) * row_stride + (i - i0)) * d + o] = v;
     }
   }
 }
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
-                           float* pseudo, int k, int d, hipStream_t s) {
+                           float* pseudo, int i0, int steps, int row_stride, int d, hipStream_t s) {
   if (F == 1) {
-    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 1>), dim3((d + 3) / 4, k), dim3(256), 0, s, h,
-                                                src_rows, F, w_dev, pseudo, k, d);)
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 1>), dim3((d + 3) / 4, steps), dim3(256), 0, s, h,
+                                                src_rows, F, w_dev, pseudo, i0, row_stride, d);)
   } else {
-    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 4>), dim3((d + 3) / 4, k), dim3(256), 0, s, h,
-                                                src_rows, F, w_dev, pseudo, k, d);)
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 4>), dim3((d + 3) / 4, steps), dim3(256), 0, s, h,
+                                                src_rows, F, w_dev, pseudo, i0, row_stride, d);)
   }
   return hipGetLastError();
 }

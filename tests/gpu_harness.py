@@ -86,8 +86,10 @@ class StepCompare:
         assert self.gpu.ht_cache_len() == len(self.prompt) == self.ora.n
         root = int(self.gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item())
         assert root == self.ora.root
-        h = cpu(self.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC))
-        assert_close(h, self.ora.h_src[wl.transfer_layers[0]], wl.dtype, "prefill transfer source", tol=None if wl.dtype != "f32" else 1e-4)
+        for slot, t in enumerate(sorted(set(wl.transfer_layers))):
+            h = cpu(self.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC, slot))
+            assert_close(h, self.ora.h_src[t], wl.dtype, f"prefill transfer source of layer {t}",
+                         tol=None if wl.dtype != "f32" else 1e-4)
         self.check_cache("prefill")
 
     def check_cache(self, what):
@@ -102,6 +104,7 @@ class StepCompare:
         wl, ora, gpu = self.wl, self.ora, self.gpu
         res = ora.step(forced_tokens=forced)
         drafts = self.in_pass_drafts
+        root_gpu = int(gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item())      # pending root: the greedy token after the last accepted node
         if forced is None and drafts is not None:
             gpu.ht_transfer(None, None)                  # nothing left to do: the last verify pass drafted already
             gpu.ht_tree_verify_step(None, self.g_gpu, self.z_gpu)
@@ -128,8 +131,7 @@ class StepCompare:
             want_cand = [[]] + [O.top_candidates(d[e - 1], ora.width[e]) for e in range(1, len(ora.width))]
             for e in range(1, len(ora.width)):
                 assert list(cand[e - 1][:ora.width[e]]) == want_cand[e], f"top-k at depth {e}"
-            root = res["tok"][0]
-            want_tok = [root] + [want_cand[ora.depth[v]][ora.rank[v]] for v in range(1, self.T)]
+            want_tok = [root_gpu] + [want_cand[ora.depth[v]][ora.rank[v]] for v in range(1, self.T)]
             assert tok_gpu == want_tok, "tree build"
             for e in range(1, len(ora.width)):           # margin of the oracle's own candidate order
                 srt = np.sort(res["D"][e - 1])[::-1][:ora.width[e] + 1]
@@ -149,9 +151,8 @@ class StepCompare:
         assert emitted == [tok_gpu[v] for v in path]
         self.in_pass_drafts = None
         if path[-1] in self.fused:                       # keep what the pass drafted for the node it ended on
-            f = self.fused.index(path[-1])
-            self.in_pass_drafts = (cpu(gpu.ht_get_buffer(B.HT_BUF_FUSED_DRAFT_LOGITS)[f]),
-                                   gpu.ht_get_buffer(B.HT_BUF_FUSED_CANDIDATES)[f].cpu().numpy())
+            z, cand = gpu.fused_drafts(self.fused.index(path[-1]))
+            self.in_pass_drafts = (cpu(z), cand.cpu().numpy())
         if require_same_tokens:
             assert (path, emitted, root) == (res["path"], res["emitted"], res["root"])
             assert gpu.ht_cache_len() == ora.n

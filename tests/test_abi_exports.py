@@ -44,5 +44,7 @@ def test_binding_names_match_the_header():
     from ht_inputs import WORKLOADS
     good = B.make_config(WORKLOADS["llama7b"])
     assert B.ht_workspace_bytes(good) > 32 * 2 * 1024 * 4096 * 2          # at least the KV cache
-    good.transfer_layer[1] = 25
-    assert B.lib.ht_workspace_bytes(ctypes.byref(good), ctypes.byref(out)) == B.HT_EUNSUPPORTED
+    good.transfer_layer[1] = 25                                            # 24, 25, 24: layers may not decrease
+    assert B.lib.ht_workspace_bytes(ctypes.byref(good), ctypes.byref(out)) == B.HT_EINVAL
+    good.transfer_layer[2] = 30                                            # 24, 25, 30 is fine
+    assert B.lib.ht_workspace_bytes(ctypes.byref(good), ctypes.byref(out)) == B.HT_OK

@@ -144,7 +144,7 @@ def test_tree_attention_at_the_op_workload_size():
 
 
 # ------------------------------------------------------------------ end to end, tiny model
-@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_full7"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_full7", "tiny_t123", "tiny_t112"])
 def test_tiny_fp32_sixteen_steps_match_oracle_and_greedy(name):
     H = _H()
     wl = WORKLOADS[name]
@@ -174,7 +174,7 @@ def _rank0_chain(parent, rank):
 
 
 @pytest.mark.parametrize("name,which", [("tiny", "all"), ("tiny_k3", "all"), ("tiny_full7", "all"), ("tiny", "root"),
-                                        ("tiny_k3", "chain")])
+                                        ("tiny_k3", "chain"), ("tiny_t123", "all"), ("tiny_t112", "chain")])
 def test_tiny_fp32_drafting_inside_the_verify_pass(name, which):
     """Pseudo rows of chosen tree nodes ride along in the verify pass (Fig. 2 caption, end of Sec. 3.4).  The draft
     distributions they give must equal the oracle's, which drafts after acceptance, and the decoded text must
@@ -197,22 +197,23 @@ def test_tiny_fp32_drafting_inside_the_verify_pass(name, which):
     sc.gpu.close()
 
 
-def test_tiny_bf16_sixteen_steps():
+@pytest.mark.parametrize("name,fused", [("tiny_bf16", False), ("tiny_t123_bf16", False), ("tiny_t123_bf16", True)])
+def test_tiny_bf16_sixteen_steps(name, fused):
     H = _H()
-    wl = WORKLOADS["tiny_bf16"]
-    say("end-to-end tiny_bf16")
-    sc = H.StepCompare(wl)
+    wl = WORKLOADS[name]
+    say(f"end-to-end {name}" + (" with in-pass drafts" if fused else ""))
+    sc = H.StepCompare(wl, fused=_rank0_chain(*tree_of(wl)) if fused else None)
     sc.check_prefill()
     same = 0
     for step in range(16):
         r = sc.step(require_same_tokens=False)
         same += r["emitted"] == r["oracle"]["emitted"]
-        if r["emitted"] != r["oracle"]["emitted"]:
+        if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
             break                                                   # sequences diverged at a near-tie: stop comparing
     assert same >= 4
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_bf16"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_bf16", "tiny_t123"])
 def test_forced_acceptance_every_root_path(name):
     H = _H()
     wl = WORKLOADS[name]
@@ -352,6 +353,9 @@ def test_error_codes():
     with pytest.raises(B.HTError) as e:
         gpu.ht_set_fused_nodes([0])                                 # no valid tree yet
     assert e.value.code == B.HT_ESTATE
+    with pytest.raises(B.HTError) as e:
+        H.gpu_model(WORKLOADS["tiny_t123"].with_(transfer_layers=(2, 1, 3)))   # transfer layers must not decrease
+    assert e.value.code == B.HT_EINVAL
     gpu.ht_set_tree(parent, rank)
     with pytest.raises(B.HTError) as e:
         gpu.ht_set_fused_nodes([0])                                 # 8 + 2 rows > max_tree = 8
