@@ -199,6 +199,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tree-sizes", default="",
                     help="comma-separated tree sizes: adds a `sweep` list of verify-pass latencies at the same cache")
+    ap.add_argument("--cache-lens", default="",
+                    help="comma-separated cache lengths: adds a `cache_sweep` list (verify and one-token pass after a "
+                         "prefill of that many random tokens)")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
     ap.add_argument("--roofline-only", action="store_true",
@@ -224,9 +227,10 @@ def main():
         print(json.dumps({"kernel_ms": k["ms"], "bytes": k["bytes"], "GBps": k["bytes"] / (k["ms"] * 1e-3) / 1e9}))
         return
     sweep_sizes = [int(t) for t in args.tree_sizes.split(",") if t]
+    cache_lens = [int(t) for t in args.cache_lens.split(",") if t]
     fused_rows = (wl.k + 1) * wl.k                      # pseudo rows under the rank-0 chain
     headroom = 2 * (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size + fused_rows] + sweep_sizes)
-    wl = wl.with_(max_cache=(wl.prompt_len + headroom + 7) // 8 * 8)
+    wl = wl.with_(max_cache=(max([wl.prompt_len] + cache_lens) + headroom + 7) // 8 * 8)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     T, n0 = wl.tree_size, wl.prompt_len
     parent, rank = prune_tree(wl.branching, T)
@@ -336,6 +340,18 @@ def main():
         sweep.append({"T": ts, "verify_pass_ms": round(ms_t, 4), "hbm_GBps": round(by / (ms_t * 1e-3) / 1e9, 1),
                       "hbm_frac_of_peak": round(by / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
     model.ht_set_tree(parent, rank)
+    cache_sweep = []
+    for n_c in cache_lens:
+        long_prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n_c, wl.vocab)]
+        model.ht_prefill(long_prompt)
+        ms_v = time_verify(parent, rank, max(5, args.steps // 2))
+        ms_1 = time_verify([-1], [0], max(5, args.steps // 2))
+        by = model_bytes(wl, T, n_c)
+        cache_sweep.append({"cache_len": n_c, "verify_pass_ms": round(ms_v, 4), "one_token_step_ms": round(ms_1, 4),
+                            "verify_over_one_token": round(ms_v / ms_1, 4),
+                            "verify_hbm_GBps": round(by / (ms_v * 1e-3) / 1e9, 1),
+                            "kv_read_share_of_bytes": round(1 - model_bytes(wl, T, 0) / by, 4)})
+    model.ht_set_tree(parent, rank)
 
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)
     achieved = kern["bytes"] / (kern["ms"] * 1e-3) / 1e9
@@ -372,6 +388,8 @@ def main():
     }
     if sweep:
         res["sweep"] = sweep
+    if cache_sweep:
+        res["cache_sweep"] = cache_sweep
     if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     print(json.dumps(res))
