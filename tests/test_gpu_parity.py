@@ -45,7 +45,8 @@ def test_generators_give_the_same_bits_on_the_gpu():
 # ------------------------------------------------------------------ skinny product, op level
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (3, 208, 200), (8, 1024, 256), (16, 768, 688), (17, 4096, 1024),
-                                   (64, 8192, 512), (64, 1024, 4096), (100, 256, 11008), (128, 12288, 128)])
+                                   (64, 8192, 512), (64, 1024, 4096), (76, 2064, 688), (84, 4096, 1024), (96, 22016, 256),
+                                   (100, 256, 11008), (128, 12288, 128)])
 def test_skinny_product_matches_textbook_product(dtype, M, N, K):
     B, H = _B(), _H()
     say(f"gemm {dtype} M={M} N={N} K={K}")
@@ -64,6 +65,20 @@ def test_skinny_product_matches_textbook_product(dtype, M, N, K):
     # inputs are exact in both paths; only fp32 accumulation order differs
     bound = 2e-5 * np.sqrt(K) * np.abs(H.cpu(a[:M])).max() * 0.05 * 8 + 1e-6
     assert np.max(np.abs(got - want)) <= bound, (np.max(np.abs(got - want)), bound)
+
+
+def test_stream_read_probe_reads_whole_passes_and_rejects_bad_buffers():
+    B, H = _B(), _H()
+    buf = torch.zeros(40 << 20, dtype=torch.uint8, device=H.DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    assert B.ht_stream_read_probe(buf, sink) == 40 << 20            # 256 workgroups x 5 x 32 KiB
+    assert B.ht_stream_read_probe(buf[:(20 << 20) + 4096], sink) == 16 << 20
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0
+    for bad in (buf[:1 << 20], buf[8:(9 << 20)]):                   # under one pass; misaligned
+        with pytest.raises(B.HTError) as e:
+            B.ht_stream_read_probe(bad, sink)
+        assert e.value.code == B.HT_EINVAL
 
 
 # ------------------------------------------------------------------ tree attention, op level
