@@ -202,6 +202,9 @@ def main():
     ap.add_argument("--cache-lens", default="",
                     help="comma-separated cache lengths: adds a `cache_sweep` list (verify and one-token pass after a "
                          "prefill of that many random tokens)")
+    ap.add_argument("--fused-counts", default="",
+                    help="comma-separated numbers of tree nodes (taken in node order) that carry pseudo rows in the "
+                         "verify pass: adds a `fused_sweep` list of verify-pass latencies")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
     ap.add_argument("--roofline-only", action="store_true",
@@ -228,7 +231,8 @@ def main():
         return
     sweep_sizes = [int(t) for t in args.tree_sizes.split(",") if t]
     cache_lens = [int(t) for t in args.cache_lens.split(",") if t]
-    fused_rows = (wl.k + 1) * wl.k                      # pseudo rows under the rank-0 chain
+    fused_counts = [int(t) for t in args.fused_counts.split(",") if t]
+    fused_rows = max([wl.k + 1] + fused_counts) * wl.k   # pseudo rows under the rank-0 chain (or the largest sweep entry)
     headroom = 2 * (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size + fused_rows] + sweep_sizes)
     wl = wl.with_(max_cache=(max([wl.prompt_len] + cache_lens) + headroom + 7) // 8 * 8)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
@@ -340,6 +344,24 @@ def main():
         sweep.append({"T": ts, "verify_pass_ms": round(ms_t, 4), "hbm_GBps": round(by / (ms_t * 1e-3) / 1e9, 1),
                       "hbm_frac_of_peak": round(by / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
     model.ht_set_tree(parent, rank)
+    fused_sweep = []
+    for cnt in fused_counts:                     # verify pass with explicit tokens and `cnt` nodes drafting in-pass
+        if T + cnt * wl.k > 128:
+            continue
+        model.ht_set_tree(parent, rank)
+        model.ht_set_fused_nodes(list(range(cnt)))
+        toks = torch.tensor(prompt[:T], dtype=torch.int32, device=dev)
+        for _ in range(3):
+            model.ht_tree_verify_step(toks)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            model.ht_tree_verify_step(toks)
+        e1.record(stream)
+        e1.synchronize()
+        fused_sweep.append({"fused_nodes": cnt, "rows_in_upper_blocks": T + cnt * wl.k,
+                            "verify_pass_ms": round(e0.elapsed_time(e1) / reps, 4)})
+    model.ht_set_tree(parent, rank)
     cache_sweep = []
     for n_c in cache_lens:
         long_prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n_c, wl.vocab)]
@@ -390,6 +412,8 @@ def main():
         res["sweep"] = sweep
     if cache_sweep:
         res["cache_sweep"] = cache_sweep
+    if fused_sweep:
+        res["fused_sweep"] = fused_sweep
     if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     print(json.dumps(res))
