@@ -207,6 +207,8 @@ def main():
                          "verify pass: adds a `fused_sweep` list of verify-pass latencies")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the HIP-graph launch medians (counter collection under rocprofv3 does not survive graph launches)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop plus a device copy of known size (for rocprofv3 runs)")
     args = ap.parse_args()
@@ -334,8 +336,10 @@ def main():
     reps = max(5, args.steps)
     ms_verify = time_verify(parent, rank, reps)
     ms_one = time_verify([-1], [0], reps)
-    ms_verify_graph = time_verify_graph(parent, rank)
-    ms_one_graph = time_verify_graph([-1], [0])
+    ms_verify_graph = ms_one_graph = None
+    if not args.no_graph:
+        ms_verify_graph = time_verify_graph(parent, rank)
+        ms_one_graph = time_verify_graph([-1], [0])
     sweep = []
     for ts in sweep_sizes:
         tp, tr = prune_tree(wl.branching, ts)
@@ -391,9 +395,9 @@ def main():
         "step_ms_draft_after_accept": round(ms_step_s1, 4),
         "verify_pass_ms": round(ms_verify, 4), "one_token_step_ms": round(ms_one, 4),
         "verify_over_one_token": round(ms_verify / ms_one, 4),
-        "graph_launch_median": {"verify_pass_ms": round(ms_verify_graph, 4), "one_token_step_ms": round(ms_one_graph, 4),
-                                "verify_over_one_token": round(ms_verify_graph / ms_one_graph, 4),
-                                "launches": 100, "warmup_launches": 20},
+        "graph_launch_median": None if ms_verify_graph is None else {
+            "verify_pass_ms": round(ms_verify_graph, 4), "one_token_step_ms": round(ms_one_graph, 4),
+            "verify_over_one_token": round(ms_verify_graph / ms_one_graph, 4), "launches": 100, "warmup_launches": 20},
         "candidate_tokens_per_s": round(T / (ms_verify * 1e-3), 1),
         "accepted_tokens_per_step": round(accepted / args.steps, 3),
         "verify_hbm_GBps": round(verify_bytes / (ms_verify * 1e-3) / 1e9, 1),
