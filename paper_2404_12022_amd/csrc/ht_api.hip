@@ -273,7 +273,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       pstride = (size_t)M * d;
     }
     if (M == 0) continue;
-    if (m->qkv_fused) {
+    if (m->qkv_fused && !qkv_prefer_split(M, qd + 2 * kvd)) {
       QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
                      c.max_cache};
       HT_HIP(launch_gemm_packed_qkv(b.u, b.p_qkv[l], M, qe, s));
@@ -286,8 +286,9 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
         WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
         if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
       }
+      // weights packed for the fused epilogue keep their rotary-pair column order in the plain product's output
       HT_HIP(launch_rope_append(c.dtype, b.qkv, qsplit, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads,
-                                c.head_dim, c.max_cache, s));
+                                c.head_dim, c.max_cache, m->qkv_fused, s));
     }
     if ((rc = attention(m, l, n, M, tree, s))) return rc;
     if (m->packed) {

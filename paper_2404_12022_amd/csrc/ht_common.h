@@ -74,7 +74,7 @@ hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, s
 hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s);
 // qkv may be `nsplit` split-K partial sums of [M][(Hq + 2 Hkv) hd] each
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
-                              int n, int M, int Hq, int Hkv, int hd, int cap, hipStream_t s);
+                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s);
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
                                     void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
                                     hipStream_t s);
@@ -129,6 +129,7 @@ struct QkvEpilogue {
   int32_t n, Hq, Hkv, hd, cap;
 };
 bool qkv_fusable(int head_dim);
+bool qkv_prefer_split(int M, int N);
 hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s);
 
 // attention over cache + tree rows; out[m][h*hd+e] in dtype

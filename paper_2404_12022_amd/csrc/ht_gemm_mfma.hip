@@ -302,12 +302,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   }
 }
 
-// Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 90 workgroups, else R = 1.
+// Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 80 workgroups, else R = 1.
 // Every workgroup re-reads the whole activation panel, and a compute unit ingests only ~45 GB/s (measured,
 // weights + panel), so the fastest grid is the one closest to one workgroup on each of the 256 compute
 // units: 3 wavefronts (6 row blocks) per workgroup when that gives <= 260 workgroups, else 4 (8 row
 // blocks); split-K (gemm_mfma_splits) tops small-N grids up to about 256.
-int rows_per_wave(int N) { return N / 16 / 8 >= 90 ? 2 : 1; }
+int rows_per_wave(int N) { return N / 16 / 8 >= 80 ? 2 : 1; }
 int waves_per_group(int n_rb) { return (n_rb + 5) / 6 <= 260 ? 3 : 4; }
 
 template <int MT>
@@ -398,6 +398,11 @@ hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, h
 }
 
 bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
+
+// The fused q|k|v product cannot split K, so its workgroups are two wavefronts on four row blocks; with few row
+// blocks (70B-shaped grouped-query projections: 160 workgroups) the wider split-K workgroups plus a separate
+// rotary/append kernel are faster once the token panel is large (measured 41 us against 28 + 7 us at M = 64).
+bool qkv_prefer_split(int M, int N) { return M > 16 && N / 16 / 4 < 176; }
 
 hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s) {
   return launch_any(a, w, M, nullptr, 1, EPI_QKV, qe, s);

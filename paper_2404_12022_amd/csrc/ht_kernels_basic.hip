@@ -183,17 +183,21 @@ template <typename T, typename TIN>
 __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in,
                                    int k_stride, const TIN* __restrict__ v_in, int v_stride, int nsplit,
                                    size_t split_stride, const float2* __restrict__ cs, T* __restrict__ q,
-                                   T* __restrict__ kc, T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap) {
+                                   T* __restrict__ kc, T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap,
+                                   int paired) {
   const int m = blockIdx.x, hh = blockIdx.y, j = threadIdx.x, half = hd / 2;
   if (j >= half) return;
   const float2 c = cs[(size_t)m * half + j];
   if (hh < Hq + Hkv) {
     const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
                              : k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd;
-    float a = Conv<TIN>::load(src + j), b = Conv<TIN>::load(src + j + half);
+    // paired: the q and k columns of a head come in the packed projection's order, every block of 16 features
+    // followed by the block of their rotary partners
+    const int ja = paired ? 32 * (j >> 4) + (j & 15) : j, jb = paired ? ja + 16 : j + half;
+    float a = Conv<TIN>::load(src + ja), b = Conv<TIN>::load(src + jb);
     for (int sp = 1; sp < nsplit; ++sp) {
-      a += Conv<TIN>::load(src + sp * split_stride + j);
-      b += Conv<TIN>::load(src + sp * split_stride + j + half);
+      a += Conv<TIN>::load(src + sp * split_stride + ja);
+      b += Conv<TIN>::load(src + sp * split_stride + jb);
     }
     const float ra = a * c.x - b * c.y, rb = b * c.x + a * c.y;
     T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
@@ -212,12 +216,13 @@ __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, c
   }
 }
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
-                              int n, int M, int Hq, int Hkv, int hd, int cap, hipStream_t s) {
+                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s) {
   const int stride = (Hq + 2 * Hkv) * hd;
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
                                               s, qkv, stride, qkv + (size_t)Hq * hd, stride,
                                               qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride,
-                                              (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap);)
+                                              (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap,
+                                              paired ? 1 : 0);)
   return hipGetLastError();
 }
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
@@ -226,7 +231,7 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
                                               (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
                                               Hkv * hd, 1, (size_t)0, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,
-                                              cap);)
+                                              cap, 0);)
   return hipGetLastError();
 }
 
