@@ -135,7 +135,8 @@ def ht_tree_attention_scratch_bytes(T: int, Hq: int, hd: int) -> int:
 def ht_tree_attention(q, k_new, v_new, k_cache, v_cache, cap, n, T, parent, Hq, Hkv, hd, dtype, rope_base, out, scratch,
                       stream=None) -> None:
     _check(lib.ht_tree_attention(_ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), cap, n, T,
-                                 _i32(parent), Hq, Hkv, hd, dtype, rope_base, _ptr(out), _ptr(scratch),
+                                 None if parent is None else _i32(parent), Hq, Hkv, hd, dtype, rope_base, _ptr(out),
+                                 _ptr(scratch),
                                  scratch.numel() * scratch.element_size(), _stream_ptr(stream)))
 
 

@@ -813,28 +813,34 @@ size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd) {
 int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache, int32_t cap,
                       int32_t n, int32_t T, const int32_t* parent, int32_t Hq, int32_t Hkv, int32_t hd, int32_t dtype,
                       float rope_base, void* out, void* scratch, size_t scratch_bytes, void* stream) {
-  if (!q || !k_cache || !v_cache || !parent || !out || !scratch) return fail(HT_EINVAL, "NULL argument");
+  if (!q || !k_cache || !v_cache || !out || !scratch) return fail(HT_EINVAL, "NULL argument");
   if ((k_new == nullptr) != (v_new == nullptr)) return fail(HT_EINVAL, "k_new and v_new must both be given or both be NULL");
   if (dtype != HT_F32 && dtype != HT_BF16) return fail(HT_EINVAL, "bad dtype");
   if (Hq < 1 || Hkv < 1 || Hq % Hkv || hd < 2 || hd % 2 || hd > 256) return fail(HT_EINVAL, "bad head shape");
   if (n < 0 || cap < 8 || cap % 8) return fail(HT_EINVAL, "cap must be a positive multiple of 8 and n >= 0");
-  int rc = validate_tree(T, parent, nullptr, kMaxTree, kMaxTree);
-  if (rc) return rc;
+  int rc;
+  if (parent) {
+    if ((rc = validate_tree(T, parent, nullptr, kMaxTree, kMaxTree))) return rc;
+  } else if (T < 1 || T > kMaxTree) {
+    return fail(HT_ETREE, "tree size %d outside 1..%d", T, kMaxTree);
+  }
   if (n + T > cap) return fail(HT_ECAPACITY, "n + T = %d exceeds cap %d", n + T, cap);
   if (scratch_bytes < ht_tree_attention_scratch_bytes(T, Hq, hd)) return fail(HT_EINVAL, "scratch too small");
   if ((uintptr_t)scratch % 256) return fail(HT_EINVAL, "scratch must be 256-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  if (!g_op_stage) {
-    HT_HIP(hipHostMalloc((void**)&g_op_stage, sizeof(int32_t) * kTableInts, hipHostMallocDefault));
-    HT_HIP(hipEventCreateWithFlags(&g_op_event, hipEventDisableTiming));
-  } else {
-    HT_HIP(hipEventSynchronize(g_op_event));   // the previous call's upload must have left the staging buffer
-  }
-  fill_tables(T, parent, nullptr, g_op_stage);
   AttnScratch a = attn_scratch_layout((char*)scratch, T, Hq, hd, elem_size(dtype));
   TreeTables tt{a.parent, a.depth, a.rank, a.anc};
-  if ((rc = upload_tables(tt, g_op_stage, s))) return rc;
-  HT_HIP(hipEventRecord(g_op_event, s));
+  if (parent) {                          // NULL: the tables an earlier call left in `scratch` are used again
+    if (!g_op_stage) {
+      HT_HIP(hipHostMalloc((void**)&g_op_stage, sizeof(int32_t) * kTableInts, hipHostMallocDefault));
+      HT_HIP(hipEventCreateWithFlags(&g_op_event, hipEventDisableTiming));
+    } else {
+      HT_HIP(hipEventSynchronize(g_op_event));   // the previous call's upload must have left the staging buffer
+    }
+    fill_tables(T, parent, nullptr, g_op_stage);
+    if ((rc = upload_tables(tt, g_op_stage, s))) return rc;
+    HT_HIP(hipEventRecord(g_op_event, s));
+  }
   const void* qq = q;
   if (k_new) {
     HT_HIP(launch_rope_table(a.cs, a.depth, n, T, hd, rope_base, s));

@@ -215,9 +215,87 @@ __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, c
     Conv<T>::store(vc + ((size_t)h * hd + j + half) * cap + n + m, b);
   }
 }
+// The same, four feature pairs per thread (hd % 8 == 0): 16-byte loads of the partial sums, 8-byte stores of q
+// and k.  blockIdx.x = row, 256 threads cover 256 / (hd / 8) heads.
+template <typename TIN> __device__ inline void load4(const TIN* p, float (&v)[4]);
+template <> __device__ inline void load4<float>(const float* p, float (&v)[4]) {
+  const float4 t = *(const float4*)p;
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <> __device__ inline void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  const uint2 t = *(const uint2*)p;
+  const bf16_t* h = (const bf16_t*)&t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = bf16_to_float(h[i]);
+}
+template <typename T> __device__ inline void store4(T* p, const float (&v)[4]);
+template <> __device__ inline void store4<float>(float* p, const float (&v)[4]) {
+  *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ inline void store4<bf16_t>(bf16_t* p, const float (&v)[4]) {
+  bf16_t h[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) h[i] = float_to_bf16(v[i]);
+  *(uint2*)p = *(const uint2*)h;
+}
+
+template <typename T, typename TIN>
+__global__ __launch_bounds__(256) void rope_append_vec_kernel(
+    const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in, int k_stride, const TIN* __restrict__ v_in,
+    int v_stride, int nsplit, size_t split_stride, const float* __restrict__ cs, T* __restrict__ q, T* __restrict__ kc,
+    T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap, int paired) {
+  const int m = blockIdx.x, half = hd / 2, per_head = half / 4;
+  const int unit = blockIdx.y * 256 + threadIdx.x;
+  const int hh = unit / per_head, j = (unit % per_head) * 4;
+  if (hh >= Hq + 2 * Hkv) return;
+  const bool is_v = hh >= Hq + Hkv;
+  const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
+                 : !is_v ? k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd
+                         : v_in + (size_t)m * v_stride + (size_t)(hh - Hq - Hkv) * hd;
+  const int ja = (paired && !is_v) ? 32 * (j >> 4) + (j & 15) : j, jb = (paired && !is_v) ? ja + 16 : j + half;
+  float a[4], b[4];
+  load4<TIN>(src + ja, a);
+  load4<TIN>(src + jb, b);
+  for (int sp = 1; sp < nsplit; ++sp) {
+    float a2[4], b2[4];
+    load4<TIN>(src + sp * split_stride + ja, a2);
+    load4<TIN>(src + sp * split_stride + jb, b2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] += a2[i]; b[i] += b2[i]; }
+  }
+  if (!is_v) {
+    float c[4], sn[4];
+    {
+      const float4 c01 = *(const float4*)(cs + ((size_t)m * half + j) * 2), c23 = *(const float4*)(cs + ((size_t)m * half + j) * 2 + 4);
+      c[0] = c01.x; sn[0] = c01.y; c[1] = c01.z; sn[1] = c01.w; c[2] = c23.x; sn[2] = c23.y; c[3] = c23.z; sn[3] = c23.w;
+    }
+    float ra[4], rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { ra[i] = a[i] * c[i] - b[i] * sn[i]; rb[i] = b[i] * c[i] + a[i] * sn[i]; }
+    T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
+    store4<T>(dst + j, ra);
+    store4<T>(dst + j + half, rb);
+  } else {
+    const int h = hh - Hq - Hkv;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Conv<T>::store(vc + ((size_t)h * hd + j + i) * cap + n + m, a[i]);
+      Conv<T>::store(vc + ((size_t)h * hd + j + half + i) * cap + n + m, b[i]);
+    }
+  }
+}
+
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
                               int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s) {
   const int stride = (Hq + 2 * Hkv) * hd;
+  if (hd % 8 == 0) {
+    const int units = (Hq + 2 * Hkv) * (hd / 8);
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, float>), dim3(M, (units + 255) / 256), dim3(256),
+                                                0, s, qkv, stride, qkv + (size_t)Hq * hd, stride,
+                                                qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride, cs,
+                                                (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap, paired ? 1 : 0);)
+    return hipGetLastError();
+  }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
                                               s, qkv, stride, qkv + (size_t)Hq * hd, stride,
                                               qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride,
@@ -228,6 +306,14 @@ hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const flo
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
                                     void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
                                     hipStream_t s) {
+  if (hd % 8 == 0) {
+    const int units = (Hq + 2 * Hkv) * (hd / 8);
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, T>), dim3(M, (units + 255) / 256), dim3(256), 0,
+                                                s, (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
+                                                Hkv * hd, 1, (size_t)0, cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap,
+                                                0);)
+    return hipGetLastError();
+  }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
                                               (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
                                               Hkv * hd, 1, (size_t)0, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,

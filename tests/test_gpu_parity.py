@@ -108,6 +108,13 @@ def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=Tru
                             B.HT_F32 if dtype == "f32" else B.HT_BF16, base, out, scratch)
         qq, kk, vv = H.cpu(q), H.cpu(kn), H.cpu(vn)
     torch.cuda.synchronize()
+    if not rotate:                              # parent = None: the tables left in scratch serve the same tree again
+        first = out.clone()
+        out.fill_(float("nan"))
+        B.ht_tree_attention(q, None, None, kc, vc, cap, n, T, None, Hq, Hkv, hd,
+                            B.HT_F32 if dtype == "f32" else B.HT_BF16, base, out, scratch)
+        torch.cuda.synchronize()
+        assert torch.equal(first, out), "reusing the uploaded tree tables changed the result"
     vis = np.concatenate([np.ones((T, n), dtype=bool), O.ancestor_matrix(parent)], axis=1)
     want = O.masked_attention(qq, np.concatenate([k_old, kk]), np.concatenate([v_old, vv]), vis).reshape(T, Hq * hd)
     got = H.cpu(out)
