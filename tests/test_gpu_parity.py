@@ -219,6 +219,26 @@ def test_tiny_fp32_drafting_inside_the_verify_pass(name, which):
     sc.gpu.close()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_trees_with_random_drafting_nodes(seed):
+    """Irregular trees (random attachment, depth up to k) with a random subset of nodes drafting inside the verify
+    pass, on the model with a transfer layer per step: tables, joins and candidate maps for arbitrary shapes."""
+    H = _H()
+    wl = WORKLOADS["tiny_t123"]
+    T = 5 + 2 * seed
+    parent, rank = random_tree(100 + seed, T, wl.k)
+    pick = np.random.default_rng(seed).permutation(T)[: 1 + seed % 4]
+    fused = sorted(int(v) for v in pick)
+    say(f"random tree seed {seed}: T={T} parent={parent} drafting nodes {fused}")
+    sc = H.StepCompare(wl, tree=(parent, rank), fused=fused)
+    out = []
+    for step in range(8):
+        out += sc.step()["emitted"]
+    assert out == sc.model.ar_greedy(sc.prompt, len(out))
+    sc.check_cache("after 8 steps")
+    sc.gpu.close()
+
+
 @pytest.mark.parametrize("name,fused", [("tiny_bf16", False), ("tiny_t123_bf16", False), ("tiny_t123_bf16", True)])
 def test_tiny_bf16_sixteen_steps(name, fused):
     H = _H()
