@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
 // same keys, so the workgroup stages 64-key tiles of K ([key][e]) and V^T ([e][key]) in LDS with fully
 // coalesced loads (whole 128/256-byte runs per row) and each wavefront reads its MFMA operands from there.
 // The 16-byte pieces of a row are XOR-swizzled so that the 16 rows a fragment read touches fall into
-// different banks.  The tile after next is in flight in registers while the current one is multiplied.
+// different banks.  The next tile is in flight in registers while the current one is multiplied.
 // Tiles that lie entirely inside the cache (keys < n) run a loop body without any mask or tail code; only
 // the last one to three tiles evaluate the ancestor masks and zero the V columns past the last tree row.
 
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   constexpr int KROWS = THREADS / PK;    // key rows covered by one pass of K pieces
   constexpr int VROWS = THREADS / (TK / 8);
   constexpr int KBYTES = TK * HD * 2, VBYTES = HD * TK * 2;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][KBYTES + VBYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[1][KBYTES + VBYTES];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
   const int h = blockIdx.x, hk = h / (Hq / Hkv);
@@ -357,9 +357,9 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   }
   static_assert(VROWS % 16 == 0, "the V swizzle of a thread's piece is the same in every pass");
   const int vlds0 = KBYTES + ve0 * (TK * 2) + ((vpc ^ ((ve0 >> 1) & 7)) << 4);     // pass i adds i * VROWS rows
-  // The tile after next is in flight in registers while the current one is multiplied out of LDS and the next
-  // one sits in the other LDS stage (a second register set, two tiles in flight, measured slower: the
-  // staging side already runs near the streaming rate of the memory system).
+  // The next tile is in flight in registers while the current one is multiplied out of LDS (a second register
+  // set, two tiles in flight, measured slower: the staging side already runs near the streaming rate of the
+  // memory system).
   u32x4_t kreg[KP], vreg[VP];
   auto load_tile = [&](int t) __attribute__((always_inline)) {
     const int j0 = t * TK;
@@ -486,11 +486,13 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
       }
     }
   };
+  // One LDS stage of 32 KB: a second one (writing tile t + 1 while tile t is multiplied) measured slightly slower,
+  // because it halves the workgroups a compute unit can hold, and other workgroups fill the two barriers' gaps.
   auto step = [&](auto masked, int t) __attribute__((always_inline)) {
-    const int stage = (t - ts) & 1;
-    if (t + 1 < te) store_tile(stage ^ 1, t + 1);
+    if (m0 < M) process(masked, 0, t);          // wavefronts past the last row only help staging
+    __syncthreads();                            // everyone is done reading tile t
+    if (t + 1 < te) store_tile(0, t + 1);
     if (t + 2 < te) load_tile(t + 2);
-    if (m0 < M) process(masked, stage, t);      // wavefronts past the last row only help staging
     __syncthreads();
   };
 
