@@ -576,7 +576,8 @@ AttnPlan plan_attention(int M, int Hq, int S) {
   p.groups = p.tiled ? (M + p.waves * p.qb * 16 - 1) / (p.waves * p.qb * 16) : 1;
   const int units = p.tiled ? (S + 63) / 64 : (S + 31) / 32;     // tiles or chunks
   int s = (512 + Hq * p.groups - 1) / (Hq * p.groups);           // about two workgroups per compute unit
-  const int min_units = p.tiled ? 2 : 4;                          // per slice, so that every wavefront has work
+  // per slice: every wavefront has work; slices of under four tiles only pay off on short caches (measured)
+  const int min_units = !p.tiled ? 4 : (units >= 16 ? 4 : 2);
   if (s > units / min_units) s = units / min_units;
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
