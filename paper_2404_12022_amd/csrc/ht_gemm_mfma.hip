@@ -310,13 +310,28 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 int rows_per_wave(int N) { return N / 16 / 8 >= 80 ? 2 : 1; }
 int waves_per_group(int n_rb) { return (n_rb + 5) / 6 <= 260 ? 3 : 4; }
 
+// With a token panel of more than 16 rows the panel a workgroup re-reads is no longer small beside its weight
+// rows (64 weight rows against a 64-row panel: half of what it ingests).  When K is long enough to give every
+// split 2048 columns, 128-row workgroups (R = 2, four wavefronts) on a deeper split-K halve that share at the
+// same grid size: measured at M = 64, N x K = 5120 x 13824: 28.1 -> 25.5 us, 8192 x 28672: 83.7 -> 74.8 us,
+// 10240 x 8192: 30.1 -> 28.1 us; at 4096 x 4096 and 4096 x 11008 (512 / 1376 columns per split) it loses or ties.
+int wide_split(int M, int N, int K) {
+  if (M <= 16) return 0;
+  const int tiles = (N / 16 + 7) / 8;
+  const int s = (256 + tiles / 2) / tiles;
+  return s >= 2 && s <= kMaxSplitK && K / s >= 2048 ? s : 0;
+}
+
 template <int MT>
 hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
                      hipStream_t s) {
   const int n_rb = w.N / 16;
   const int KS = w.Kp / 32;
   constexpr int KC = MT == 1 ? 128 : kChunkCols;     // the chunk must give every thread at least one 16-byte piece
-  if (epi == EPI_SILU || (epi == EPI_F32 && rows_per_wave(w.N) == 2)) {
+  if (epi == EPI_F32 && wide_split(M, w.N, w.K)) {
+    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a,
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
+  } else if (epi == EPI_SILU || (epi == EPI_F32 && rows_per_wave(w.N) == 2)) {
     const bool three = waves_per_group(n_rb) == 3;
     const dim3 grid(three ? (n_rb + 5) / 6 : (n_rb + 7) / 8, epi == EPI_SILU ? 1 : nsplit);
     if (epi == EPI_SILU) {
@@ -367,7 +382,7 @@ size_t packed_weight_bytes(int N, int K) {
 }
 
 int gemm_mfma_splits(int M, int N, int K) {
-  (void)M;
+  if (const int wide = wide_split(M, N, K)) return wide;
   const int n_rb = N / 16;
   const int per_wg = rows_per_wave(N) == 2 ? 2 * waves_per_group(n_rb) : 4;      // row blocks per workgroup
   const int tiles = (n_rb + per_wg - 1) / per_wg;

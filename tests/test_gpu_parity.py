@@ -46,7 +46,8 @@ def test_generators_give_the_same_bits_on_the_gpu():
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (3, 208, 200), (8, 1024, 256), (16, 768, 688), (17, 4096, 1024),
                                    (64, 8192, 512), (64, 1024, 4096), (76, 2064, 688), (84, 4096, 1024), (96, 22016, 256),
-                                   (100, 256, 11008), (128, 12288, 128)])
+                                   (100, 256, 11008), (128, 12288, 128),
+                                   (40, 5120, 13824), (67, 5136, 12296)])   # 128-row workgroups, six K splits
 def test_skinny_product_matches_textbook_product(dtype, M, N, K):
     B, H = _B(), _H()
     say(f"gemm {dtype} M={M} N={N} K={K}")
