@@ -60,27 +60,20 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, i
   const int rb = tile * kTileBlocks + rbt;
   uint4 v = make_uint4(0, 0, 0, 0);
   if (rb < n_rb) {
-    int seg, src_rb;
+    int grow = rb * 16 + (lane & 15);       // source row in the concatenated segments
     if (mode == 1) {               // two equal segments interleaved block by block (gate, up)
-      seg = rb & 1;
-      src_rb = rb >> 1;
-    } else if (mode == 2) {        // q | k | v: inside every q and k head, block p is followed by block p + hb/2
-      const int hb = head_blocks;  // (the rotary partner rows), v heads keep their order
+      grow = (rb & 1) * w.rows[0] + (rb >> 1) * 16 + (lane & 15);
+    } else if (mode == 2) {        // q | k | v: block b of a q or k head holds features 8b .. 8b+7 (rows 0..7) and
+      const int hb = head_blocks;  // their rotary partners hd/2 + 8b .. (rows 8..15); v heads keep their order
       const int qk_rbs = (w.rows[0] + w.rows[1]) / 16;
-      int r2 = rb;
       if (rb < qk_rbs) {
-        const int in_head = rb % hb, head0 = rb - in_head;
-        r2 = head0 + (in_head >> 1) + (in_head & 1) * (hb / 2);
+        const int in_head = rb % hb, r = lane & 15;
+        grow = (rb - in_head) * 16 + (r < 8 ? 8 * in_head + r : 8 * hb + 8 * in_head + r - 8);
       }
-      seg = 0;
-      src_rb = r2;
-      while (seg + 1 < w.nseg && src_rb * 16 >= w.rows[seg]) { src_rb -= w.rows[seg] / 16; ++seg; }
-    } else {                       // natural order over the concatenated segments
-      seg = 0;
-      src_rb = rb;
-      while (seg + 1 < w.nseg && src_rb * 16 >= w.rows[seg]) { src_rb -= w.rows[seg] / 16; ++seg; }
     }
-    const int row = src_rb * 16 + (lane & 15);
+    int seg = 0;
+    while (seg + 1 < w.nseg && grow >= w.rows[seg]) { grow -= w.rows[seg]; ++seg; }
+    const int row = grow;
     const int k = j * 32 + (lane >> 4) * 8;
     if (k < K) v = *(const uint4*)((const bf16_t*)w.w[seg] + (size_t)row * K + k);
   }
@@ -91,7 +84,7 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, i
 // The hot loop is straight-line code (no predicated loads, no data-dependent branches) so that the
 // compiler can keep exact outstanding-load counts and the weight ring really stays in flight: chunk
 // indices past the end of this block's K range are clamped to its last chunk (a redundant, in-bounds
-// reload that is never used), rows past N are clamped to the last row block (never stored), and
+// reload that is never used), wavefront slots without a row block re-read one fragment (never stored), and
 // activation columns past K are clamped into the row (they meet zero-padded weights).
 template <int MT, int R, int WAVES, int EPI, int KC = kChunkCols, int PD = kRingDepth>
 __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
@@ -113,11 +106,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   const int c0 = (int)((long long)chunks * blockIdx.y / nsplit);
   const int c1 = (int)((long long)chunks * (blockIdx.y + 1) / nsplit);
   const int n_rb = N / 16;
-  // The grid's workgroups share the row blocks evenly: workgroup b owns blocks [b n_rb / G, (b+1) n_rb / G) (in whole pairs for the fused epilogues), at
+  // The grid's workgroups share the row blocks evenly: workgroup b owns blocks [b n_rb / G, (b+1) n_rb / G) (in whole pairs for the SiLU epilogue), at
   // most R * WAVES of them (the launcher's choice of G), R consecutive ones per wavefront.  A slot past the end of
   // the workgroup's range re-reads one fragment of its first block over and over (stride 0: cache hits, no HBM
   // traffic, same instruction stream) and stores nothing.
-  constexpr int U = EPI == EPI_F32 ? 1 : 2;              // the fused epilogues need both blocks of a pair
+  constexpr int U = EPI == EPI_SILU ? 2 : 1;             // the SiLU epilogue needs both blocks of a (gate, up) pair
   const int units = (n_rb + U - 1) / U;
   const int wg0 = U * (int)((long long)units * blockIdx.x / gridDim.x);
   const int wg1 = U * (int)((long long)units * (blockIdx.x + 1) / gridDim.x);
@@ -261,51 +254,51 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
       }
     }
   } else {
-    // q | k | v rows packed so that a wavefront holds features j (block rb0) and j + hd/2 (block rb0 + 1) of one
-    // q or k head: rotate the pair by the row's position and store q, or append k to the cache; v rows are
-    // appended to the slot-contiguous value cache.
-    if (rb0 + 1 < wg1) {
-      const int hd = qe.hd, half = hd / 2, pp = hd / 32;       // pp: block pairs per head
-      int P = rb0 / 2;
-      const int q_pairs = qe.Hq * pp, k_pairs = qe.Hkv * pp;
-      if (P < q_pairs + k_pairs) {
-        const bool is_q = P < q_pairs;
-        if (!is_q) P -= q_pairs;
-        const int h = P / pp, j = (P % pp) * 16 + g * 4;
+    // q | k | v rows.  Block b of a q or k head holds features 8b .. 8b+7 of the head in MFMA rows 0..7 and their
+    // rotary partners (feature + hd/2) in rows 8..15, so lanes 0..31 end with the low halves and the lane 32 further
+    // on with the partner of the same feature: one exchange, rotate by the row's position, store q or append k to
+    // the cache.  v rows are appended to the slot-contiguous value cache.
+    const int hd = qe.hd, half = hd / 2, hb = hd / 16;
+    const int q_blocks = qe.Hq * hb, qk_blocks = q_blocks + qe.Hkv * hb;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int rb = rb0 + r;
+      if (rb >= wg1) continue;                                  // uniform over the wavefront
+      if (rb < qk_blocks) {
+        const bool is_q = rb < q_blocks, upper = g >= 2;
+        const int hrb = is_q ? rb : rb - q_blocks;
+        const int h = hrb / hb, j = (hrb % hb) * 8 + (g & 1) * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const int m = mt * 16 + r16;
+          float other[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(acc[r][mt][i], 32, 64);
           if (m < M) {
             const float4 c01 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2);
             const float4 c23 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2 + 4);
             const float cs_[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
-            bf16_t lo[4], hi[4];
+            bf16_t o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float x = acc[0][mt][i], y = acc[1][mt][i], co = cs_[2 * i], si = cs_[2 * i + 1];
-              lo[i] = float_to_bf16(x * co - y * si);
-              hi[i] = float_to_bf16(y * co + x * si);
+              const float x = upper ? other[i] : acc[r][mt][i], y = upper ? acc[r][mt][i] : other[i];
+              const float co = cs_[2 * i], si = cs_[2 * i + 1];
+              o[i] = float_to_bf16(upper ? y * co + x * si : x * co - y * si);
             }
             bf16_t* dst = is_q ? qe.q + ((size_t)m * qe.Hq + h) * hd + j
                                : qe.kc + ((size_t)(qe.n + m) * qe.Hkv + h) * hd + j;
-            *(uint2*)dst = *(const uint2*)lo;
-            *(uint2*)(dst + half) = *(const uint2*)hi;
+            *(uint2*)(dst + (upper ? half : 0)) = *(const uint2*)o;
           }
         }
       } else {
-        P -= q_pairs + k_pairs;
-        const int hb = hd / 16;
+        const int vb = rb - qk_blocks, h = vb / hb, e0 = (vb % hb) * 16 + g * 4;
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-          const int vb = 2 * P + r, h = vb / hb, e0 = (vb % hb) * 16 + g * 4;
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = mt * 16 + r16;
+          if (m < M) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const int m = mt * 16 + r16;
-            if (m < M) {
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                qe.vc[((size_t)h * hd + e0 + i) * qe.cap + qe.n + m] = float_to_bf16(acc[r][mt][i]);
-            }
+            for (int i = 0; i < 4; ++i)
+              qe.vc[((size_t)h * hd + e0 + i) * qe.cap + qe.n + m] = float_to_bf16(acc[r][mt][i]);
           }
         }
       }
@@ -365,8 +358,18 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
                            out, nsplit, qe);
     }
   } else if (epi == EPI_QKV) {
-    hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 2, EPI_QKV, KC>), dim3((n_rb + 3) / 4, 1), dim3(128), 0, s, a, w.p,
-                       M, w.N, w.K, KS, out, 1, qe);
+    // no split-K here, so one row block per wavefront and three or four wavefronts: 768 row blocks (a 4096-wide
+    // model with full-size K/V heads) fill 256 workgroups exactly; measured 23.4 -> 21.6 us against two blocks
+    // per wavefront in 192 workgroups of two
+    const bool four = n_rb > 3 * 256;
+    int gx = four ? (n_rb + 3) / 4 : (n_rb + 2) / 3;
+    if (gx < 256 && n_rb >= 256) gx = 256;
+    if (four)
+      hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_QKV, KC>), dim3(gx, 1), dim3(256), 0, s, a, w.p, M, w.N, w.K,
+                         KS, out, 1, qe);
+    else
+      hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 3, EPI_QKV, KC>), dim3(gx, 1), dim3(192), 0, s, a, w.p, M, w.N, w.K,
+                         KS, out, 1, qe);
   } else {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32, KC>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a,
                        w.p, M, w.N, w.K, KS, out, nsplit, qe);

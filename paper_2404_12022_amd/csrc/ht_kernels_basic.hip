@@ -191,9 +191,9 @@ __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, c
   if (hh < Hq + Hkv) {
     const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
                              : k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd;
-    // paired: the q and k columns of a head come in the packed projection's order, every block of 16 features
-    // followed by the block of their rotary partners
-    const int ja = paired ? 32 * (j >> 4) + (j & 15) : j, jb = paired ? ja + 16 : j + half;
+    // paired: the q and k columns of a head come in the packed projection's order, every run of 8 features
+    // followed by the run of their rotary partners
+    const int ja = paired ? 16 * (j >> 3) + (j & 7) : j, jb = paired ? ja + 8 : j + half;
     float a = Conv<TIN>::load(src + ja), b = Conv<TIN>::load(src + jb);
     for (int sp = 1; sp < nsplit; ++sp) {
       a += Conv<TIN>::load(src + sp * split_stride + ja);
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256) void rope_append_vec_kernel(
   const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
                  : !is_v ? k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd
                          : v_in + (size_t)m * v_stride + (size_t)(hh - Hq - Hkv) * hd;
-  const int ja = (paired && !is_v) ? 32 * (j >> 4) + (j & 15) : j, jb = (paired && !is_v) ? ja + 16 : j + half;
+  const int ja = (paired && !is_v) ? 16 * (j >> 3) + (j & 7) : j, jb = (paired && !is_v) ? ja + 8 : j + half;
   float a[4], b[4];
   load4<TIN>(src + ja, a);
   load4<TIN>(src + jb, b);
