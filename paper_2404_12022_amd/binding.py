@@ -259,6 +259,19 @@ class HTModel:
         _check(lib.ht_accept_and_compact(self.handle, C.byref(m), toks, C.byref(root), path, _stream_ptr(stream)))
         return m.value, list(toks[:m.value]), root.value, list(path[:m.value])
 
+    def decode(self, max_new_tokens: int, stream=None):
+        """Calls transfer / verify / accept until at least `max_new_tokens` tokens are out or the cache is full
+        (after `ht_set_tree` and `ht_prefill`).  Returns the emitted tokens: the greedy continuation of the prompt.
+        A loop over the ABI calls and nothing else."""
+        rows = max(self.T + len(getattr(self, "fused", [])) * self.cfg.k, self.cfg.k)
+        out = []
+        while len(out) < max_new_tokens and self.ht_cache_len() + rows <= self.cfg.max_cache:
+            self.ht_transfer(None, None, stream)
+            self.ht_tree_verify_step(None, None, None, stream)
+            _, emitted, _, _ = self.ht_accept_and_compact(stream)
+            out += emitted
+        return out
+
     def fused_drafts(self, f: int):
         """(draft logits [k, vocab], candidates [k, HT_MAX_TOPK]) that the last verify pass produced for fused node
         number f.  The pass holds pseudo rows in the order they joined: transfer-layer slot by slot, node by node,

@@ -211,6 +211,32 @@ def test_tiny_fp32_decode_reproduces_the_stored_trace(name):
     gpu.close()
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_decode_loop_gives_the_greedy_continuation_until_the_cache_is_full(fused):
+    """`HTModel.decode` (the ABI calls in a loop) on the tiny workload: the text is the oracle's greedy
+    autoregressive continuation (Sec. 4.1: verification keeps the output of plain greedy decoding), with and
+    without pseudo rows riding in the verify pass, and the loop stops before a pass would overflow the cache."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["tiny"].with_(max_cache=80)
+    parent, rank = tree_of(wl)
+    nodes = _rank0_chain(parent, rank) if fused else []
+    say(f"decode loop, fused nodes {nodes}")
+    gpu = H.gpu_model(wl, max_tree=len(parent) + len(nodes) * wl.k)
+    gpu.ht_set_tree(parent, rank)
+    if nodes:
+        gpu.ht_set_fused_nodes(nodes)
+    prompt = prompt_of(wl)
+    gpu.ht_prefill(prompt)
+    out = gpu.decode(20)
+    assert len(out) >= 20
+    assert out == oracle_model(wl).ar_greedy(prompt, len(out))
+    more = gpu.decode(10 ** 6)                               # runs into the capacity check, never past it
+    rows = len(parent) + len(nodes) * wl.k
+    assert gpu.ht_cache_len() + rows > wl.max_cache >= gpu.ht_cache_len()
+    assert out + more == oracle_model(wl).ar_greedy(prompt, len(out) + len(more))
+    gpu.close()
+
+
 def _rank0_chain(parent, rank):
     chain, cur = [0], 0
     while True:
