@@ -291,6 +291,100 @@ def test_random_trees_with_random_drafting_nodes(seed):
     sc.gpu.close()
 
 
+def _random_shape(seed):
+    """A small model with dimensions drawn at random from what the configuration check allows: odd head counts and
+    group sizes, head sizes with and without a matrix-core attention kernel, widths that do and do not fit the
+    packed weight layout, 1..4 transfer steps at non-decreasing random layers, a random tree with random drafting
+    nodes, a prompt that is not a multiple of anything."""
+    rng = np.random.default_rng(4000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    hd = int(rng.choice([16, 32, 64, 128] if dtype == "bf16" else [8, 16, 32, 64]))
+    hkv = int(rng.choice([1, 2, 3]))
+    hq = hkv * int(rng.choice([1, 2, 4]))
+    d = int(rng.choice([64, 96, 136, 160, 256]))
+    f = int(rng.choice([72, 128, 200, 344]))
+    vocab = int(rng.choice([128, 250, 512, 1000]))
+    layers = int(rng.integers(2, 5))
+    k = int(rng.integers(1, 5))
+    t = tuple(sorted(int(x) for x in rng.integers(1, layers, size=k)))
+    T = int(rng.integers(2, 41))
+    parent, rank = random_tree(4000 + seed, T, k)
+    n_fused = int(rng.integers(0, min(T, (128 - T) // k) + 1))
+    fused = sorted(int(v) for v in rng.permutation(T)[:min(n_fused, 6)])
+    prompt_len = int(rng.integers(3, 71))
+    rows = T + len(fused) * k
+    max_cache = (prompt_len + 5 * (k + 1) + rows + 7) // 8 * 8
+    branching = tuple(1 + max(rank[v] for v in range(T) if len(_path_to(parent, v)) - 1 == e) for e in range(1, k + 1)
+                      if any(len(_path_to(parent, v)) - 1 == e for v in range(T)))
+    wl = small_workload(name=f"fuzz{seed}", n_layers=layers, d_model=d, n_heads=hq, n_kv_heads=hkv, head_dim=hd, d_ffn=f,
+                        vocab=vocab, k=k, transfer_layers=t, dtype=dtype, prompt_len=prompt_len, max_cache=max_cache,
+                        tree_size=T, branching=branching, seed=7000 + seed)
+    return wl, (parent, rank), fused
+
+
+def _path_to(parent, v):
+    p = []
+    while v >= 0:
+        p.append(v)
+        v = parent[v]
+    return p
+
+
+def _random_packed_shape(seed):
+    """Random bf16 shapes that all run on the matrix-core kernels (packed projections, fused q|k|v epilogue or its
+    split fallback, both attention kernels): widths in multiples of 16, heads of 64 or 128, up to 128 rows a pass."""
+    rng = np.random.default_rng(5000 + seed)
+    hd = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3, 5]))
+    hq = hkv * int(rng.choice([1, 2, 4]))
+    d = 16 * int(rng.integers(8, 49))
+    f = 16 * int(rng.integers(6, 90))
+    vocab = 16 * int(rng.integers(20, 130))
+    layers = int(rng.integers(2, 4))
+    k = int(rng.integers(1, 6))
+    t = tuple(sorted(int(x) for x in rng.integers(1, layers, size=k)))
+    T = min(int(rng.choice([1, 3, 16, 17, 33, 64, 65, 90, 120])), 1 + 40 * k)     # a parent offers at most 64 candidates
+    parent, rank = random_tree(5000 + seed, T, k) if T > 1 else ([-1], [0])
+    room = (128 - T) // k
+    fused = sorted(int(v) for v in rng.permutation(T)[:int(rng.integers(0, min(T, room) + 1))])
+    prompt_len = int(rng.integers(1, 200))
+    rows = max(T + len(fused) * k, k)
+    max_cache = (prompt_len + 4 * (k + 1) + rows + 7) // 8 * 8
+    wl = small_workload(name=f"packed{seed}", n_layers=layers, d_model=d, n_heads=hq, n_kv_heads=hkv, head_dim=hd, d_ffn=f,
+                        vocab=vocab, k=k, transfer_layers=t, dtype="bf16", prompt_len=prompt_len, max_cache=max_cache,
+                        tree_size=T, branching=(1,) * k, seed=8000 + seed)
+    return wl, (parent, rank), fused
+
+
+@pytest.mark.parametrize("seed", [f"any{i}" for i in range(12)] + [f"packed{i}" for i in range(12)])
+def test_random_model_shapes_against_oracle(seed):
+    H = _H()
+    wl, tree, fused = _random_shape(int(seed[3:])) if seed.startswith("any") else _random_packed_shape(int(seed[6:]))
+    say(f"random shape {seed}: {wl.dtype} layers={wl.n_layers} d={wl.d_model} heads={wl.n_heads}/{wl.n_kv_heads}x{wl.head_dim} "
+        f"ffn={wl.d_ffn} vocab={wl.vocab} k={wl.k} t={wl.transfer_layers} T={wl.tree_size} drafting nodes {fused} "
+        f"prompt {wl.prompt_len} cache {wl.max_cache}")
+    sc = H.StepCompare(wl, tree=tree, fused=fused)
+    sc.check_prefill()
+    full = 0
+    for step in range(4):
+        r = sc.step(require_same_tokens=False)
+        if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
+            break                       # a near-tie took the two decodes apart: what follows is not comparable
+        full += 1
+    say(f"  steps compared in full: {full}")
+    if full == 4:
+        sc.check_cache("after 4 steps")
+    sc.gpu.close()
+    if wl.dtype == "f32":
+        assert full >= 1
+    else:
+        # bf16 decisions may part at a near-tie before a verify pass was compared: one more pass on given tokens,
+        # which compares all T logit rows whatever was drafted
+        sc = H.StepCompare(wl, tree=tree, fused=fused)
+        sc.step(forced=[(7 + 13 * v) % wl.vocab for v in range(wl.tree_size)], require_same_tokens=False)
+        sc.gpu.close()
+
+
 @pytest.mark.parametrize("name,fused", [("tiny_bf16", False), ("tiny_t123_bf16", False), ("tiny_t123_bf16", True)])
 def test_tiny_bf16_sixteen_steps(name, fused):
     H = _H()
