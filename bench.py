@@ -212,6 +212,10 @@ def main():
     ap.add_argument("--fused-counts", default="",
                     help="comma-separated numbers of tree nodes (taken in node order) that carry pseudo rows in the "
                          "verify pass: adds a `fused_sweep` list of verify-pass latencies")
+    ap.add_argument("--k-values", default="",
+                    help="comma-separated numbers of transfer steps k (= tree depth) to time the step at, same T: "
+                         "a fresh model per value (transfer maps for k steps at the workload's first transfer layer, "
+                         "tree prune_tree([10] * k, T))")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
     ap.add_argument("--no-graph", action="store_true",
@@ -386,6 +390,43 @@ def main():
                             "kv_read_share_of_bytes": round(1 - model_bytes(wl, T, 0) / by, 4)})
     model.ht_set_tree(parent, rank)
 
+    # ---- the step against the number of transfer steps k = depth of the tree, T fixed (a model per value: the
+    # same decoder weights, k transfer maps, a k-level tree; both schedules as above)
+    depth_sweep = []
+    for kk in [int(t) for t in args.k_values.split(",") if t]:
+        if param_bytes > 100e9:
+            break
+        wl_k = wl.with_(k=kk, transfer_layers=(wl.transfer_layers[0],) * kk, branching=(10,) * kk)
+        w_k = dict(weights)
+        w_k["w_transfer"] = make_weights(wl_k, wl.seed, dev, tdt, layers=[])["w_transfer"]
+        p_k, r_k = prune_tree(wl_k.branching, T)
+        chain_k, cur = [0], 0
+        while True:
+            kids = [v for v in range(T) if p_k[v] == cur and r_k[v] == 0]
+            if not kids:
+                break
+            cur = kids[0]
+            chain_k.append(cur)
+        m_k = B.HTModel(B.make_config(wl_k, max_tree=min(128, T + len(chain_k) * kk)), w_k, dev)
+        m_k.ht_set_tree(p_k, r_k)
+        m_k.ht_prefill(prompt)
+        row = {"k": kk, "tree_depth": max(len(chain_k) - 1, 0)}
+        for label, nodes in (("step_ms_draft_after_accept", []), ("step_ms_draft_in_verify_pass", chain_k)):
+            m_k.ht_set_fused_nodes(nodes)
+            for _ in range(args.warmup):
+                m_k.ht_transfer(); m_k.ht_tree_verify_step(); m_k.ht_accept_and_compact()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                m_k.ht_transfer(); m_k.ht_tree_verify_step(); m_k.ht_accept_and_compact()
+            torch.cuda.synchronize()
+            row[label] = round((time.perf_counter() - t0) * 1e3 / args.steps, 4)
+        row["pseudo_rows_in_verify_pass"] = len(chain_k) * kk
+        depth_sweep.append(row)
+        m_k.close()
+        del m_k, w_k
+        torch.cuda.empty_cache()
+
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)
     achieved = kern["bytes"] / (kern["ms"] * 1e-3) / 1e9
     verify_bytes = model_bytes(wl, T, n_now)
@@ -413,8 +454,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic() if wl.name == "llama7b" else None,
-                     "kernel": (f"gemm_packed_kernel<MT=4,R=2,WAVES=3,EPI_F32,KC=128> at the gate/up projection shape "
-                                f"M={kern['M']} N={kern['N']} K={kern['K']}"),
+                     "kernel": (("gemm_packed_kernel<MT=4,R=2,WAVES=3,EPI_F32,KC=128>" if (kern["N"] // 16 + 5) // 6 <= 260
+                                 else "gemm_packed_kernel<MT=4,R=2,WAVES=4,EPI_F32,KC=64>") +
+                                f" at the gate/up projection shape M={kern['M']} N={kern['N']} K={kern['K']}"),
                      "bytes_per_launch": kern["bytes"], "ms_per_launch": round(kern["ms"], 5),
                      "measured_stream_read_GBps": round(kern["stream_GBps"], 1),
                      "frac_of_measured_stream": round(achieved / kern["stream_GBps"], 4)},
@@ -425,6 +467,8 @@ def main():
         res["cache_sweep"] = cache_sweep
     if fused_sweep:
         res["fused_sweep"] = fused_sweep
+    if depth_sweep:
+        res["depth_sweep"] = depth_sweep
     if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     print(json.dumps(res))
