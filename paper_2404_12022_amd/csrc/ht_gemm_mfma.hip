@@ -15,7 +15,8 @@
 // coalesced 1 KiB that drops straight into MFMA operand registers: no LDS transpose, no partially used
 // cache lines, sequential DRAM pages, and no two workgroups marching through memory at the same
 // power-of-two stride (row-block-major order measured up to 15 % slower on a pure streaming test).  Row blocks can be ordered freely at pack time,
-// which is how gate and up rows meet in one wavefront for the fused SiLU epilogue.
+// and rows inside a block too: that is how gate and up rows meet in one wavefront for the fused SiLU epilogue and
+// how a q or k feature meets its rotary partner inside one row block.
 //
 // The activation chunk (M x 64 columns) is staged once per workgroup in LDS (rows padded by 16 bytes:
 // conflict-free 128-bit reads) and shared by the four wavefronts; a ring of PD weight chunks per
@@ -432,9 +433,9 @@ hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, h
 
 bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
 
-// The fused q|k|v product cannot split K, so its workgroups are two wavefronts on four row blocks; with few row
-// blocks (70B-shaped grouped-query projections: 160 workgroups) the wider split-K workgroups plus a separate
-// rotary/append kernel are faster once the token panel is large (measured 41 us against 28 + 7 us at M = 64).
+// The fused q|k|v product cannot split K, so its workgroups stay small (three or four row blocks); with few row
+// blocks (70B-shaped grouped-query projections: 640) the 128-row split-K workgroups plus a separate rotary/append
+// kernel are faster once the token panel is large (measured 41 us against 28 + 7 us at M = 64).
 bool qkv_prefer_split(int M, int N) { return M > 16 && N / 16 / 4 < 176; }
 
 hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s) {
