@@ -186,8 +186,8 @@ def test_tiny_fp32_sixteen_steps_match_oracle_and_greedy(name):
     assert sc.min_margin > H.FP32_LOGIT_TOL and sc.min_margin > 10 * sc.max_err, (sc.min_margin, sc.max_err)
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_t123"])
-def test_tiny_fp32_decode_reproduces_the_stored_trace(name):
+@pytest.mark.parametrize("name,side_stream", [("tiny", False), ("tiny_t123", False), ("tiny", True)])
+def test_tiny_fp32_decode_reproduces_the_stored_trace(name, side_stream):
     """The same decode as the trace under tests/golden/ (written from the oracle alone), through the C ABI only:
     tree tokens, accepted path, emitted tokens, pending root and cache length of all 16 steps."""
     from test_golden import read_trace
@@ -197,17 +197,23 @@ def test_tiny_fp32_decode_reproduces_the_stored_trace(name):
     say(f"stored trace {name}")
     parent, rank = tree_of(wl)
     gpu = H.gpu_model(wl, max_tree=len(parent))
-    gpu.ht_set_tree(parent, rank)
-    gpu.ht_prefill(prompt_of(wl))
-    assert int(gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item()) == want["root"]
-    for s, st in enumerate(want["steps"]):
-        gpu.ht_transfer(None, None)
-        gpu.ht_tree_verify_step(None, None, None)
-        tok = [int(t) for t in gpu.ht_get_buffer(B.HT_BUF_TREE_TOKENS).cpu()]
-        assert tok == st["tok"], f"step {s}: tree tokens"
-        m, emitted, root, path = gpu.ht_accept_and_compact()
-        assert (m, path, emitted) == (len(st["path"]), st["path"], st["emitted"]), f"step {s}: acceptance"
-        assert (root, gpu.ht_cache_len()) == (st["next_root"], st["cache_len"]), f"step {s}: state"
+    torch.cuda.synchronize()
+    # every call takes the stream it is to run on; with side_stream all of them go to one that is not the default
+    stream = torch.cuda.Stream() if side_stream else torch.cuda.current_stream()
+    with torch.cuda.stream(stream):
+        gpu.ht_set_tree(parent, rank, stream)
+        gpu.ht_prefill(prompt_of(wl), stream)
+        stream.synchronize()
+        assert int(gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item()) == want["root"]
+        for s, st in enumerate(want["steps"]):
+            gpu.ht_transfer(None, None, stream)
+            gpu.ht_tree_verify_step(None, None, None, stream)
+            stream.synchronize()
+            tok = [int(t) for t in gpu.ht_get_buffer(B.HT_BUF_TREE_TOKENS).cpu()]
+            assert tok == st["tok"], f"step {s}: tree tokens"
+            m, emitted, root, path = gpu.ht_accept_and_compact(stream)
+            assert (m, path, emitted) == (len(st["path"]), st["path"], st["emitted"]), f"step {s}: acceptance"
+            assert (root, gpu.ht_cache_len()) == (st["next_root"], st["cache_len"]), f"step {s}: state"
     gpu.close()
 
 
