@@ -70,6 +70,7 @@ struct Buffers {
   float* h_src;        // transfer sources [slots][d]
   float* pseudo;       // [k, d]
   float* cs;           // rotary table [Mp, hd/2] (cos, sin)
+  float* ss;           // packed path: sums of squares of the rows of u, kNormParts parts per row [Mp][kNormParts]
   int32_t *tok, *g, *cand, *width, *prompt;
   int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
   int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
@@ -111,6 +112,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.h_src = cv.take<float>((size_t)c.k * d);
   b.pseudo = cv.take<float>((size_t)c.k * d);
   b.cs = cv.take<float>(Mp * c.head_dim);
+  b.ss = cv.take<float>(Mp * kNormParts);
   b.tok = cv.take<int32_t>(Mp);
   b.g = cv.take<int32_t>(Mp);
   b.cand = cv.take<int32_t>((size_t)kMaxTransfer * kMaxTopK);
@@ -248,11 +250,20 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   const int joining = join == kFromTree ? F * c.k : join == kFromBuffer ? c.k : 0;
   HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + joining, c.head_dim, c.rope_base, s));
   int pending = 0;
+  // Residual add + RMSNorm.  On packed weights the row is split over kNormParts workgroups (one workgroup per row
+  // takes in its 80 KB at the pace of a single compute unit) and the 1/rms factor moves into the epilogue of the
+  // product that reads u; everywhere else one workgroup normalises the whole row.
+  const bool parts = m->packed && d % (4 * kNormParts) == 0;
+  const RowScale rs = parts ? RowScale{b.ss, 1.0f / (float)d, c.rms_eps} : RowScale{};
+  auto add_norm = [&](float* x, int nsplit, size_t stride, const void* gain, void* u, float* save, float* ss, int rows) {
+    return parts ? launch_add_norm_parts(x, b.part, nsplit, stride, gain, u, save, ss, rows, d, s)
+                 : launch_add_norm(c.dtype, x, b.part, nsplit, stride, gain, u, save, rows, d, c.rms_eps, s);
+  };
   for (int l = layer_from; l < c.n_layers; ++l) {
     const int slot = m->slot_of_layer[l];
     if (M > 0) {
       float* save = (save_hidden && slot >= 0) ? b.saved_h + slot * slot_stride : nullptr;
-      HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->attn_norm[l], b.u, save, M, d, c.rms_eps, s));
+      HT_HIP(add_norm(b.x, pending, pstride, m->attn_norm[l], b.u, save, b.ss, M));
     }
     if (join != kNoJoin && slot >= 0) {
       // the residual after l blocks is complete now: make the rows of this layer's transfer steps, normalise
@@ -267,8 +278,8 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
         extra = cnt;
         HT_HIP(launch_load_rows(b.pseudo + (size_t)i0 * d, b.x + (size_t)M * d, cnt, d, s));
       }
-      HT_HIP(launch_add_norm(c.dtype, b.x + (size_t)M * d, b.part, 0, 0, m->attn_norm[l], (char*)b.u + (size_t)M * d * es,
-                             nullptr, extra, d, c.rms_eps, s));
+      HT_HIP(add_norm(b.x + (size_t)M * d, 0, 0, m->attn_norm[l], (char*)b.u + (size_t)M * d * es, nullptr,
+                      b.ss + (size_t)M * kNormParts, extra));
       M += extra;
       pstride = (size_t)M * d;
     }
@@ -276,12 +287,12 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
     if (m->qkv_fused && !qkv_prefer_split(M, qd + 2 * kvd)) {
       QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
                      c.max_cache};
-      HT_HIP(launch_gemm_packed_qkv(b.u, b.p_qkv[l], M, qe, s));
+      HT_HIP(launch_gemm_packed_qkv(b.u, b.p_qkv[l], M, qe, s, rs));
     } else {
       int qsplit = 1;
       if (m->packed) {
         qsplit = gemm_mfma_splits(M, qd + 2 * kvd, d);
-        HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, qsplit, s));
+        HT_HIP(launch_gemm_packed(b.u, b.p_qkv[l], M, b.qkv, qsplit, s, rs));
       } else {
         WeightSegs qkv{{m->wq[l], m->wk[l], m->wv[l]}, {qd, kvd, kvd}, 3};
         if ((rc = product(m, b.u, qkv, M, qd + 2 * kvd, d, b.qkv, s))) return rc;
@@ -298,9 +309,9 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       pending = 1;
       if ((rc = product(m, b.attn, segs1(m->wo[l], d), M, d, qd, b.part, s))) return rc;
     }
-    HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->ffn_norm[l], b.u, nullptr, M, d, c.rms_eps, s));
+    HT_HIP(add_norm(b.x, pending, pstride, m->ffn_norm[l], b.u, nullptr, b.ss, M));
     if (m->packed) {
-      HT_HIP(launch_gemm_packed_silu(b.u, b.p_gu[l], M, b.act, s));
+      HT_HIP(launch_gemm_packed_silu(b.u, b.p_gu[l], M, b.act, s, rs));
       pending = gemm_mfma_splits(M, d, f);
       HT_HIP(launch_gemm_packed(b.act, b.p_down[l], M, b.part, pending, s));
     } else {
@@ -311,11 +322,10 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       if ((rc = product(m, b.act, segs1(m->w_down[l], d), M, d, f, b.part, s))) return rc;
     }
   }
-  HT_HIP(launch_add_norm(c.dtype, b.x, b.part, pending, pstride, m->final_norm, logits ? b.u : nullptr, nullptr, M, d,
-                         c.rms_eps, s));
+  HT_HIP(add_norm(b.x, pending, pstride, m->final_norm, logits ? b.u : nullptr, nullptr, b.ss, M));
   if (logits) {
     if (m->packed) {
-      HT_HIP(launch_gemm_packed(b.u, b.p_head, M, logits, 1, s));      // vocab-sized N: never split
+      HT_HIP(launch_gemm_packed(b.u, b.p_head, M, logits, 1, s, rs));      // vocab-sized N: never split
     } else if ((rc = product(m, b.u, segs1(m->lm_head, c.vocab), M, c.vocab, d, logits, s))) {
       return rc;
     }

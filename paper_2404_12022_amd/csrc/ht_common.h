@@ -71,6 +71,17 @@ hipError_t launch_load_rows(const float* src, float* x, int M, int d, hipStream_
 // x[m] += sum_s part[s][m]; optional save; u[m] = rmsnorm(x[m]) * gain
 hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
                            void* u, float* save_h, int M, int d, float eps, hipStream_t s);
+// The same with kNormParts workgroups per row (d a multiple of 4 kNormParts): each adds and stores its part of the
+// row, leaves the sum of squares of that part in ss[m][part] and writes u[m] = x[m] * gain WITHOUT the 1/rms factor;
+// the product that consumes u multiplies its output rows by RowScale::of(m) instead (bf16 only).
+constexpr int kNormParts = 4;
+hipError_t launch_add_norm_parts(float* x, const float* part, int nsplit, size_t part_stride, const void* gain, void* u,
+                                 float* save_h, float* ss, int M, int d, hipStream_t s);
+// 1 / rms of the rows of an activation panel written by launch_add_norm_parts; ss == NULL: rows are used as they are
+struct RowScale {
+  const float* ss = nullptr;
+  float inv_d = 0.f, eps = 0.f;
+};
 hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s);
 // qkv may be `nsplit` split-K partial sums of [M][(Hq + 2 Hkv) hd] each
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
@@ -118,9 +129,10 @@ int gemm_mfma_splits(int M, int N, int K);
 // every q and k head the 16-row block p is followed by its rotary partner block p + head_dim/32
 hipError_t launch_repack(WeightSegs w, int K, int mode, int head_dim, void* dst, hipStream_t s);
 // out[s][m][n], s < nsplit (split-K partial sums, fp32)
-hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s);
+hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s,
+                              RowScale rs = RowScale{});
 // w packed with mode 1 from (gate, up): act[m][j] = silu(a.gate_j) * (a.up_j), bf16 [M][N/2]
-hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s);
+hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s, RowScale rs = RowScale{});
 // w packed with mode 2 from (q, k, v): rotary at the row's position, q rows to `q`, k/v rows appended to the
 // caches at slot n + m (all bf16); cs is the (cos, sin) table [M][hd/2]
 struct QkvEpilogue {
@@ -130,7 +142,8 @@ struct QkvEpilogue {
 };
 bool qkv_fusable(int head_dim);
 bool qkv_prefer_split(int M, int N);
-hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s);
+hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s,
+                                  RowScale rs = RowScale{});
 
 // attention over cache + tree rows; out[m][h*hd+e] in dtype
 hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,

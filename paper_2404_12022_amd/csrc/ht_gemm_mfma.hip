@@ -91,7 +91,7 @@ template <int MT, int R, int WAVES, int EPI, int KC = kChunkCols, int PD = kRing
 __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
                                                                  const bf16_t* __restrict__ wp, int M, int N, int K,
                                                                  int KS, void* __restrict__ outp, int nsplit,
-                                                                 QkvEpilogue qe) {
+                                                                 QkvEpilogue qe, RowScale rs) {
   constexpr int STEPS = KC / 32;                         // MFMA steps per chunk
   constexpr int ROWB = KC * 2 + 16;                      // LDS row stride in bytes (padded: conflict-free b128 reads)
   constexpr int THREADS = 64 * WAVES;
@@ -170,6 +170,19 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
+  // Rows of a panel that was stored without its 1/rms factor: the factor multiplies the finished sums instead
+  // (every K split scales its partial sums by the same factor).  The sums of squares are fetched here, ahead of
+  // the weight stream (they are the oldest loads, so no wait ever stalls on them), and turned into factors in the
+  // epilogue.
+  float4 row_ss[MT];
+  if (rs.ss) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 16 + r16;
+      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
+    }
+  }
+
   // Loads retire in issue order, so everything is issued oldest-needed-first: at chunk c the ring holds
   // weights of chunks c .. c+PD-1 and activations of chunks c+1 .. c+PD; each iteration consumes the
   // oldest of both and issues activation chunk c+PD+1, then weight chunk c+PD.
@@ -221,6 +234,15 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   for (int p = 0; p < PD - 1; ++p)
     if (c + p < c1) body(wreg[p], areg[p], c + p);                // uniform tail
 
+  if (rs.ss) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const float4 q4 = row_ss[mt];
+      const float sc = 1.0f / sqrtf((q4.x + q4.y + q4.z + q4.w) * rs.inv_d + rs.eps);
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[r][mt] *= sc;
+    }
+  }
   if (EPI == EPI_F32) {
     float* dst = (float*)outp + (size_t)blockIdx.y * M * N;
 #pragma unroll
@@ -329,13 +351,13 @@ int wide_split(int M, int N, int K) {
 
 template <int MT>
 hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
-                     hipStream_t s) {
+                     const RowScale& rs, hipStream_t s) {
   const int n_rb = w.N / 16;
   const int KS = w.Kp / 32;
   constexpr int KC = MT == 1 ? 128 : kChunkCols;     // the chunk must give every thread at least one 16-byte piece
   if (epi == EPI_F32 && wide_split(M, w.N, w.K)) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs);
   } else if (epi == EPI_SILU || (epi == EPI_F32 && rows_per_wave(w.N) == 2)) {
     const bool three = waves_per_group(n_rb) == 3;
     // a grid just short of the 256 compute units is topped up to 256 (the kernel shares the row blocks evenly):
@@ -346,17 +368,17 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
     if (epi == EPI_SILU) {
       if (three)
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_SILU, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, 1, qe);
+                           out, 1, qe, rs);
       else
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, 1, qe);
+                           out, 1, qe, rs);
     } else {
       if (three)
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_F32, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, nsplit, qe);
+                           out, nsplit, qe, rs);
       else
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, nsplit, qe);
+                           out, nsplit, qe, rs);
     }
   } else if (epi == EPI_QKV) {
     // no split-K here, so one row block per wavefront and three or four wavefronts: 768 row blocks (a 4096-wide
@@ -367,26 +389,26 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
     if (gx < 256 && n_rb >= 256) gx = 256;
     if (four)
       hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_QKV, KC>), dim3(gx, 1), dim3(256), 0, s, a, w.p, M, w.N, w.K,
-                         KS, out, 1, qe);
+                         KS, out, 1, qe, rs);
     else
       hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 3, EPI_QKV, KC>), dim3(gx, 1), dim3(192), 0, s, a, w.p, M, w.N, w.K,
-                         KS, out, 1, qe);
+                         KS, out, 1, qe, rs);
   } else {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32, KC>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit, qe);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
-                      hipStream_t s) {
+                      const RowScale& rs, hipStream_t s) {
   const bf16_t* ap = (const bf16_t*)a;
-  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, s);
-  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, s);
-  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, s);
-  if (M <= 80) return launch_mt<5>(ap, w, M, out, nsplit, epi, qe, s);      // a 64-node tree plus a few pseudo rows
-  if (M <= 96) return launch_mt<6>(ap, w, M, out, nsplit, epi, qe, s);
-  return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, s);
+  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, rs, s);
+  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, rs, s);
+  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, rs, s);
+  if (M <= 80) return launch_mt<5>(ap, w, M, out, nsplit, epi, qe, rs, s);      // a 64-node tree plus a few pseudo rows
+  if (M <= 96) return launch_mt<6>(ap, w, M, out, nsplit, epi, qe, rs, s);
+  return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, rs, s);
 }
 
 }  // namespace
@@ -423,12 +445,12 @@ hipError_t launch_repack(WeightSegs w, int K, int mode, int head_dim, void* dst,
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s) {
-  return launch_any(a, w, M, out, nsplit, EPI_F32, QkvEpilogue{}, s);
+hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s, RowScale rs) {
+  return launch_any(a, w, M, out, nsplit, EPI_F32, QkvEpilogue{}, rs, s);
 }
 
-hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s) {
-  return launch_any(a, w, M, act, 1, EPI_SILU, QkvEpilogue{}, s);
+hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, hipStream_t s, RowScale rs) {
+  return launch_any(a, w, M, act, 1, EPI_SILU, QkvEpilogue{}, rs, s);
 }
 
 bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
@@ -438,8 +460,8 @@ bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
 // kernel are faster once the token panel is large (measured 41 us against 28 + 7 us at M = 64).
 bool qkv_prefer_split(int M, int N) { return M > 16 && N / 16 / 4 < 176; }
 
-hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s) {
-  return launch_any(a, w, M, nullptr, 1, EPI_QKV, qe, s);
+hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s, RowScale rs) {
+  return launch_any(a, w, M, nullptr, 1, EPI_QKV, qe, rs, s);
 }
 
 }  // namespace ht

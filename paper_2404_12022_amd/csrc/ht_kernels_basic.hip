@@ -139,6 +139,61 @@ __global__ void add_norm_kernel(float* __restrict__ x, const float* __restrict__
     }
   }
 }
+// kNormParts blocks per row: block (m, q) owns columns q dq .. (q + 1) dq - 1, dq = d / kNormParts.
+template <int NS>
+__global__ void add_norm_parts_kernel(float* __restrict__ x, const float* __restrict__ part, size_t part_stride,
+                                      const bf16_t* __restrict__ gain, bf16_t* __restrict__ u,
+                                      float* __restrict__ save_h, float* __restrict__ ss_out, int d) {
+  __shared__ float red[16];
+  const int m = blockIdx.x, dq = d / kNormParts, c0 = blockIdx.y * dq;
+  float* xr = x + (size_t)m * d;
+  const float* pr = part + (size_t)m * d;
+  float ss = 0.f;
+  constexpr int MAXP = 4;                       // dq <= MAXP * 4 * blockDim.x (checked by the launcher)
+#pragma unroll
+  for (int p = 0; p < MAXP; ++p) {
+    const int cl = (p * blockDim.x + threadIdx.x) * 4;
+    if (cl < dq) {
+      const int c = c0 + cl;
+      float4 v = *(const float4*)(xr + c);
+      float4 pv[NS > 0 ? NS : 1];
+#pragma unroll
+      for (int sp = 0; sp < NS; ++sp) pv[sp] = *(const float4*)(pr + sp * part_stride + c);
+#pragma unroll
+      for (int sp = 0; sp < NS; ++sp) { v.x += pv[sp].x; v.y += pv[sp].y; v.z += pv[sp].z; v.w += pv[sp].w; }
+      if (NS) *(float4*)(xr + c) = v;
+      if (save_h) *(float4*)(save_h + (size_t)m * d + c) = v;
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      if (u) {
+        bf16_t o[4] = {float_to_bf16(v.x * bf16_to_float(gain[c + 0])), float_to_bf16(v.y * bf16_to_float(gain[c + 1])),
+                       float_to_bf16(v.z * bf16_to_float(gain[c + 2])), float_to_bf16(v.w * bf16_to_float(gain[c + 3]))};
+        *(uint2*)(u + (size_t)m * d + c) = *(const uint2*)o;
+      }
+    }
+  }
+  ss = block_sum_any(ss, red);
+  if (threadIdx.x == 0 && ss_out) ss_out[(size_t)m * kNormParts + blockIdx.y] = ss;
+}
+hipError_t launch_add_norm_parts(float* x, const float* part, int nsplit, size_t part_stride, const void* gain, void* u,
+                                 float* save_h, float* ss, int M, int d, hipStream_t s) {
+  if (d % (4 * kNormParts) || nsplit < 0 || nsplit > kMaxSplitK) return hipErrorInvalidValue;
+  const int dq = d / kNormParts;
+  int nt = 64;
+  while (nt < 1024 && nt * 4 < dq) nt *= 2;
+  if (dq > 16 * nt) return hipErrorInvalidValue;
+#define HT_ADD_NORM_PARTS(NS)                                                                                      \
+  case NS:                                                                                                         \
+    hipLaunchKernelGGL((add_norm_parts_kernel<NS>), dim3(M, kNormParts), dim3(nt), 0, s, x, part, part_stride,     \
+                       (const bf16_t*)gain, (bf16_t*)u, save_h, ss, d);                                            \
+    break;
+  switch (nsplit) {
+    HT_ADD_NORM_PARTS(0) HT_ADD_NORM_PARTS(1) HT_ADD_NORM_PARTS(2) HT_ADD_NORM_PARTS(3) HT_ADD_NORM_PARTS(4)
+    HT_ADD_NORM_PARTS(5) HT_ADD_NORM_PARTS(6) HT_ADD_NORM_PARTS(7) HT_ADD_NORM_PARTS(8)
+  }
+#undef HT_ADD_NORM_PARTS
+  return hipGetLastError();
+}
+
 hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, size_t part_stride, const void* gain,
                            void* u, float* save_h, int M, int d, float eps, hipStream_t s) {
   if (d % 4 || nsplit < 0 || nsplit > kMaxSplitK) return hipErrorInvalidValue;

@@ -85,7 +85,16 @@ class StepCompare:
         wl = self.wl
         assert self.gpu.ht_cache_len() == len(self.prompt) == self.ora.n
         root = int(self.gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item())
-        assert root == self.ora.root
+        if root != self.ora.root:
+            # only a bf16 near-tie may do this: the two tokens' exact logits must be closer than the two passes may
+            # differ; either token is then a legitimate outcome and the comparison goes on from the GPU's
+            assert wl.dtype != "f32", f"prefill root {root}, oracle {self.ora.root}"
+            z = self.model.causal_forward(self.prompt)[0][-1]
+            gap, bound = float(z[self.ora.root] - z[root]), 2 * BF16_REL_TOL * float(np.max(np.abs(z)))
+            print(f"prefill root {root} vs oracle {self.ora.root}: exact logit gap {gap:.3e}, bf16 bound {bound:.3e}",
+                  flush=True)
+            assert 0 <= gap <= bound, f"prefill root {root} vs {self.ora.root}: logit gap {gap:.3e} above {bound:.3e}"
+            self.ora.root = root
         for slot, t in enumerate(sorted(set(wl.transfer_layers))):
             h = cpu(self.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC, slot))
             assert_close(h, self.ora.h_src[t], wl.dtype, f"prefill transfer source of layer {t}",
