@@ -38,12 +38,14 @@ __device__ inline float block_max_256(float v, float* red) {
 // ------------------------------------------------------------------------------------------------ embed
 template <typename T>
 __global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tok, float* __restrict__ x, int d) {
-  const int m = blockIdx.x;
+  const int m = blockIdx.x;                     // blockIdx.y: which share of the row's columns
   const T* row = emb + (size_t)tok[m] * d;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) x[(size_t)m * d + c] = Conv<T>::load(row + c);
+  for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < d; c += gridDim.y * blockDim.x)
+    x[(size_t)m * d + c] = Conv<T>::load(row + c);
 }
 hipError_t launch_embed(int dtype, const void* emb, const int32_t* tok, float* x, int M, int d, hipStream_t s) {
-  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, s, (const T*)emb, tok, x, d);)
+  const int shares = d >= 2048 ? 4 : 1;         // a few workgroups per row: a row is one dependent round trip per pass
+  HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(M, shares), dim3(256), 0, s, (const T*)emb, tok, x, d);)
   return hipGetLastError();
 }
 
