@@ -150,6 +150,20 @@ int ht_tree_verify_step(ht_model *m, const int32_t *tree_tokens, int32_t *argmax
 int ht_accept_and_compact(ht_model *m, int32_t *n_accepted, int32_t *accepted_tokens, int32_t *next_root,
                           int32_t *path_out, void *stream);
 
+/* `steps` whole decode steps without a host round trip in between: each step is ht_transfer, the draft pass,
+ * ht_tree_verify_step on the drafted tree and ht_accept_and_compact (Sec. 3.2 - 3.4, drafting after acceptance),
+ * but the cache length lives on the device: every kernel reads it there, the acceptance advances it, and this
+ * call waits for `stream` once, after the last step.  Same tokens as the same number of single steps.
+ * n_accepted: HOST [steps] or NULL; accepted_tokens: HOST [steps * (k + 1)] or NULL, the emitted tokens of all
+ * steps back to back (sum of n_accepted entries are written); next_root: HOST or NULL.
+ * HT_EINVAL unless 1 <= steps <= HT_MAX_LOOP_STEPS; HT_ESTATE without tree or prefill, between a verify step and
+ * its ht_accept_and_compact, or while ht_set_fused_nodes lists nodes (the loop cannot take the data-dependent
+ * branch that skips the draft pass); HT_ECAPACITY unless n + steps * (k + 1) + max(T, k) <= max_cache (the worst
+ * case is checked up front: nothing on the device can report an overflow mid-loop). */
+enum { HT_MAX_LOOP_STEPS = 64 };
+int ht_decode_steps(ht_model *m, int32_t steps, int32_t *n_accepted, int32_t *accepted_tokens, int32_t *next_root,
+                    void *stream);
+
 int32_t ht_cache_len(const ht_model *m);      /* n */
 const char *ht_last_error(void);
 

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "libht.so")
 HT_OK, HT_EINVAL, HT_ECAPACITY, HT_ETREE, HT_ESTATE, HT_EHIP, HT_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 HT_F32, HT_BF16 = 0, 1
 HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_TOPK = 8, 128, 64
+HT_MAX_LOOP_STEPS = 64
 (HT_BUF_DRAFT_LOGITS, HT_BUF_CANDIDATES, HT_BUF_TREE_TOKENS, HT_BUF_SAVED_HIDDEN, HT_BUF_TRANSFER_SRC,
  HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT, HT_BUF_FUSED_DRAFT_LOGITS,
  HT_BUF_FUSED_CANDIDATES) = range(11)
@@ -24,7 +25,7 @@ EXPORTS = [
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
-    "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe",
+    "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
 ]
 
 
@@ -70,6 +71,7 @@ def _load() -> C.CDLL:
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
         "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "ht_accept_and_compact": (C.c_int, [vp, i32p, i32p, i32p, i32p, vp]),
+        "ht_decode_steps": (C.c_int, [vp, C.c_int32, i32p, i32p, i32p, vp]),
         "ht_cache_len": (C.c_int32, [vp]),
         "ht_last_error": (C.c_char_p, []),
         "ht_get_buffer": (C.c_int, [vp, C.c_int32, C.c_int32, C.POINTER(vp), C.POINTER(sz)]),
@@ -258,6 +260,15 @@ class HTModel:
         toks, path = (C.c_int32 * k1)(), (C.c_int32 * k1)()
         _check(lib.ht_accept_and_compact(self.handle, C.byref(m), toks, C.byref(root), path, _stream_ptr(stream)))
         return m.value, list(toks[:m.value]), root.value, list(path[:m.value])
+
+    def ht_decode_steps(self, steps: int, stream=None):
+        """(accepted count per step, emitted tokens of every step as one list, pending root)."""
+        counts = (C.c_int32 * steps)()
+        toks = (C.c_int32 * (steps * (self.cfg.k + 1)))()
+        root = C.c_int32(0)
+        _check(lib.ht_decode_steps(self.handle, steps, counts, toks, C.byref(root), _stream_ptr(stream)))
+        counts = list(counts)
+        return counts, list(toks[:sum(counts)]), root.value
 
     def decode(self, max_new_tokens: int, stream=None):
         """Calls transfer / verify / accept until at least `max_new_tokens` tokens are out or the cache is full

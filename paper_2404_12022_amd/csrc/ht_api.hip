@@ -77,6 +77,7 @@ struct Buffers {
   int32_t* fused_src;    // logits row (past the tree rows) that holds the draft of (fused node, step) [kMaxTree]
   TreeTables tree, chain;
   StepState* state;
+  StepLog* log;        // steps of the device-resident loop [kMaxLoopSteps]
   void** kc_ptrs;      // device array [L]
   void** vc_ptrs;
   void** wt_ptrs;      // device array [k]
@@ -128,6 +129,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
     t->anc = cv.take<uint64_t>((size_t)kMaxTree * kMaskWords);
   }
   b.state = cv.take<StepState>(1);
+  b.log = cv.take<StepLog>(kMaxLoopSteps);
   b.kc_ptrs = cv.take<void*>(c.n_layers);
   b.vc_ptrs = cv.take<void*>(c.n_layers);
   b.wt_ptrs = cv.take<void*>(kMaxTransfer);
@@ -205,6 +207,8 @@ struct ht_model {
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
   StepState* h_state = nullptr;
+  // device-resident loop: while set, the kernels of a pass read the cache length here and `n` is an upper bound
+  const int32_t* n_dev = nullptr;
 };
 
 namespace {
@@ -221,10 +225,10 @@ int attention(ht_model* m, int layer, int n, int M, const TreeDev& tree, hipStre
   Buffers& b = m->b;
   if (c.dtype == HT_BF16 && m->use_mfma && attn_mfma_supported(M, c.n_heads, c.n_kv_heads, c.head_dim)) {
     HT_HIP(launch_attn_mfma(b.q, b.kc[layer], b.vc[layer], c.max_cache, n, M, tree, c.n_heads, c.n_kv_heads, c.head_dim,
-                            b.attn, b.attn_scratch, s));
+                            b.attn, b.attn_scratch, s, m->n_dev));
   } else {
     HT_HIP(launch_attn_simple(c.dtype, b.q, b.kc[layer], b.vc[layer], c.max_cache, n, M, tree, c.n_heads, c.n_kv_heads,
-                              c.head_dim, b.attn, s));
+                              c.head_dim, b.attn, s, m->n_dev));
   }
   return HT_OK;
 }
@@ -248,7 +252,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   const int n = m->n;
   int rc;
   const int joining = join == kFromTree ? F * c.k : join == kFromBuffer ? c.k : 0;
-  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + joining, c.head_dim, c.rope_base, s));
+  HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + joining, c.head_dim, c.rope_base, s, m->n_dev));
   int pending = 0;
   // Residual add + RMSNorm.  On packed weights the row is split over kNormParts workgroups (one workgroup per row
   // takes in its 80 KB at the pace of a single compute unit) and the 1/rms factor moves into the epilogue of the
@@ -286,7 +290,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
     if (M == 0) continue;
     if (m->qkv_fused && !qkv_prefer_split(M, qd + 2 * kvd)) {
       QkvEpilogue qe{b.cs, (bf16_t*)b.q, (bf16_t*)b.kc[l], (bf16_t*)b.vc[l], n, c.n_heads, c.n_kv_heads, c.head_dim,
-                     c.max_cache};
+                     c.max_cache, m->n_dev};
       HT_HIP(launch_gemm_packed_qkv(b.u, b.p_qkv[l], M, qe, s, rs));
     } else {
       int qsplit = 1;
@@ -299,7 +303,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       }
       // weights packed for the fused epilogue keep their rotary-pair column order in the plain product's output
       HT_HIP(launch_rope_append(c.dtype, b.qkv, qsplit, b.cs, b.q, b.kc[l], b.vc[l], n, M, c.n_heads, c.n_kv_heads,
-                                c.head_dim, c.max_cache, m->qkv_fused, s));
+                                c.head_dim, c.max_cache, m->qkv_fused, s, m->n_dev));
     }
     if ((rc = attention(m, l, n, M, tree, s))) return rc;
     if (m->packed) {
@@ -747,6 +751,74 @@ int ht_accept_and_compact(ht_model* m, int32_t* n_accepted, int32_t* accepted_to
     if (accepted_tokens) accepted_tokens[j] = st.emitted[j];
     if (path_out) path_out[j] = st.path[j];
   }
+  return HT_OK;
+}
+
+// Device-resident loop (schedule: draft after acceptance).  Every kernel reads the cache length from the step state
+// on the device, the acceptance kernel advances it and logs the step, and the host only waits once, at the end.
+int ht_decode_steps(ht_model* m, int32_t steps, int32_t* n_accepted, int32_t* accepted_tokens, int32_t* next_root,
+                    void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
+  if (!m->has_prefill) return fail(HT_ESTATE, "empty cache: call ht_prefill first");
+  if (m->verify_done) return fail(HT_ESTATE, "a verify pass is waiting for ht_accept_and_compact");
+  if (!m->fused.empty()) return fail(HT_ESTATE, "the loop drafts after acceptance: clear ht_set_fused_nodes first");
+  if (steps < 1 || steps > kMaxLoopSteps) return fail(HT_EINVAL, "steps must be in 1..%d", kMaxLoopSteps);
+  const ht_config& c = m->cfg;
+  Buffers& b = m->b;
+  const int T = m->T, rows = T > c.k ? T : c.k, n0 = m->n;
+  if (n0 + steps * (c.k + 1) + rows > c.max_cache)
+    return fail(HT_ECAPACITY, "cache_len %d + %d steps of up to %d tokens + %d rows exceeds max_cache %d", n0, steps,
+                c.k + 1, rows, c.max_cache);
+  hipStream_t s = (hipStream_t)stream;
+  HT_HIP(hipStreamSynchronize(s));                     // the staging buffer below may still be in use
+  int32_t* init = m->h_stage;
+  init[0] = n0;                                        // n_old
+  init[1] = n0;                                        // n
+  init[2] = 0;                                         // log_count
+  HT_HIP(hipMemcpyAsync(&b.state->n_old, init, 3 * sizeof(int32_t), hipMemcpyHostToDevice, s));
+  struct Guard {
+    ht_model* m;
+    int n;
+    ~Guard() { m->n_dev = nullptr; m->n = n; }
+  } guard{m, n0};
+  m->n_dev = &b.state->n;
+  const int slots = (int)m->slot_layer.size();
+  int rc;
+  for (int st = 0; st < steps; ++st) {
+    m->n = n0 + st * (c.k + 1);                        // upper bound of the cache length at this step: sizes grids only
+    for (int g = 0; g < slots; ++g)
+      HT_HIP(launch_transfer(c.dtype, b.h_src + (size_t)g * c.d_model, nullptr, 1, (const void* const*)b.wt_ptrs,
+                             b.pseudo + (size_t)m->slot_first[g] * c.d_model, m->slot_first[g], m->slot_count[g], 0,
+                             c.d_model, s));
+    if ((rc = run_pass(m, b.chain.dev(), 0, c.transfer_layer[0], false, b.dlogits, nullptr, s, kFromBuffer))) return rc;
+    HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, nullptr, c.vocab, s));
+    HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
+    HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
+    if ((rc = run_pass(m, b.tree.dev(), T, 0, true, b.logits, b.g, s))) return rc;
+    HT_HIP(launch_accept(b.state, b.tree.dev(), b.tok, b.g, T, s, b.log));
+    HT_HIP(launch_compact(c.dtype, b.state, b.kc_ptrs, b.vc_ptrs, c.n_layers, 0, c.n_kv_heads, c.head_dim, c.max_cache,
+                          b.saved_h, (size_t)m->Mp * c.d_model, slots, b.h_src, c.d_model, s, true));
+  }
+  StepLog* h_log = (StepLog*)m->h_stage;
+  HT_HIP(hipMemcpyAsync(h_log, b.log, sizeof(StepLog) * steps, hipMemcpyDeviceToHost, s));
+  HT_HIP(hipMemcpyAsync(m->h_state, b.state, sizeof(StepState), hipMemcpyDeviceToHost, s));
+  HT_HIP(hipStreamSynchronize(s));
+  int total = 0;
+  for (int st = 0; st < steps; ++st) {
+    const int cnt = h_log[st].m;
+    if (cnt < 1 || cnt > c.k + 1) return fail(HT_EHIP, "step %d of the loop logged an impossible count %d", st, cnt);
+    if (n_accepted) n_accepted[st] = cnt;
+    if (accepted_tokens)
+      for (int j = 0; j < cnt; ++j) accepted_tokens[total + j] = h_log[st].emitted[j];
+    total += cnt;
+  }
+  if (m->h_state->n != n0 + total || m->h_state->log_count != steps)
+    return fail(HT_EHIP, "device cache length %d after the loop, expected %d", m->h_state->n, n0 + total);
+  guard.n = n0 + total;
+  m->transfer_ready = m->verify_done = false;
+  m->drafts_of = -1;
+  if (next_root) *next_root = m->h_state->next_root;
   return HT_OK;
 }
 

@@ -48,7 +48,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
                                                         const bf16_t* __restrict__ vc, int cap, int n, int M,
                                                         const uint64_t* __restrict__ anc, int Hq, int Hkv,
                                                         bf16_t* __restrict__ out, float* __restrict__ part_o,
-                                                        float* __restrict__ part_ml, int nsplit, float scale_log2) {
+                                                        float* __restrict__ part_ml, int nsplit, float scale_log2,
+                                                        const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
   constexpr int ES = HD / 32;      // contraction steps of the score MFMAs
   constexpr int EB = HD / 16;      // 16-row blocks of O^T
   // LDS merge area: per wave, O accumulators [QB][EB][4][64], running max [QB][64], partial sums [QB][64]
@@ -295,7 +297,9 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ vc, int cap, int n, int M,
                                                             const uint64_t* __restrict__ anc, int Hq, int Hkv,
                                                             bf16_t* __restrict__ out, float* __restrict__ part_o,
-                                                            float* __restrict__ part_ml, int nsplit, float scale_log2) {
+                                                            float* __restrict__ part_ml, int nsplit, float scale_log2,
+                                                            const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
   constexpr int TK = 64;                 // keys per tile
   constexpr int ES = HD / 32, EB = HD / 16;
   constexpr int THREADS = 64 * NW;
@@ -587,12 +591,12 @@ AttnPlan plan_attention(int M, int Hq, int S) {
 
 template <int HD>
 void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
-               int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s) {
+               int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s, const int32_t* n_dev) {
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (size_t)Hq * kMaxSplits * M * HD;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const dim3 grid(Hq, p.groups, p.nsplit);
-#define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2
+#define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2, n_dev
   if (!p.tiled) hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
   else hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
 #undef HT_ATTN_ARGS
@@ -612,12 +616,12 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 }
 
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
-                            int Hkv, int hd, void* out, void* scratch, hipStream_t s) {
+                            int Hkv, int hd, void* out, void* scratch, hipStream_t s, const int32_t* n_dev) {
   if ((size_t)cap * Hkv * hd >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside a cache
   const AttnPlan p = plan_attention(M, Hq, n + M);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
-  if (hd == 128) launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s);
-  else launch_hd<64>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s);
+  if (hd == 128) launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev);
+  else launch_hd<64>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev);
   return hipGetLastError();
 }
 

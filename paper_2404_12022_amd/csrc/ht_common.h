@@ -37,6 +37,7 @@ constexpr int kMaskWords = kMaxTree / 64;
 constexpr int kMaxTopK = 64;
 constexpr int kMaxTransfer = 8;
 constexpr int kMaxSplitK = 8;
+constexpr int kMaxLoopSteps = 64;        // steps per call of the device-resident loop
 
 // Tree tables as the kernels see them (device pointers).
 struct TreeDev {
@@ -53,8 +54,19 @@ struct StepState {
   int32_t next_root;
   int32_t path[kMaxTransfer + 1];
   int32_t emitted[kMaxTransfer + 1];
-  int32_t pad[4];
+  // device-resident loop (ht_decode_steps): cache length before / after the last acceptance, steps logged so far
+  int32_t n_old, n, log_count;
+  int32_t pad[1];
 };
+// what one step of the device-resident loop leaves for the host
+struct StepLog {
+  int32_t m;
+  int32_t emitted[kMaxTransfer + 1];
+};
+
+// Cache length of a pass: kernels take the host's value `n` and, for the device-resident loop, a pointer that
+// overrides it (NULL otherwise).  The host value then only has to be an upper bound (it sizes grids and LDS).
+__device__ inline int cache_len(int n, const int32_t* n_dev) { return n_dev ? *n_dev : n; }
 
 // One weight operand made of up to three row segments sharing K (Wq|Wk|Wv, Wgate|Wup).
 struct WeightSegs {
@@ -82,10 +94,12 @@ struct RowScale {
   const float* ss = nullptr;
   float inv_d = 0.f, eps = 0.f;
 };
-hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s);
+hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s,
+                             const int32_t* n_dev = nullptr);
 // qkv may be `nsplit` split-K partial sums of [M][(Hq + 2 Hkv) hd] each
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
-                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s);
+                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s,
+                              const int32_t* n_dev = nullptr);
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
                                     void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
                                     hipStream_t s);
@@ -97,10 +111,12 @@ size_t topk_scratch_bytes(int rows);
 hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
                        const int32_t* src_row, int V, hipStream_t s);
 hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
-hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s);
+// log != NULL (device-resident loop): the step is appended to log[st->log_count++] and st->n_old / st->n advance
+hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s,
+                         StepLog* log = nullptr);
 hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
                           int hd, int cap, const float* saved_h, size_t slot_stride, int slots, float* h_src, int d,
-                          hipStream_t s);
+                          hipStream_t s, bool n_from_state = false);
 hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* saved_h, size_t slot_stride, int slots,
                                  float* h_src, int last, int d, hipStream_t s);
 // measurement aid: one pass over `buf` with the weight stream's access pattern; returns the bytes actually read
@@ -139,6 +155,7 @@ struct QkvEpilogue {
   const float* cs;
   bf16_t *q, *kc, *vc;
   int32_t n, Hq, Hkv, hd, cap;
+  const int32_t* n_dev = nullptr;            // overrides n when set (device-resident loop)
 };
 bool qkv_fusable(int head_dim);
 bool qkv_prefer_split(int M, int N);
@@ -147,10 +164,11 @@ hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue q
 
 // attention over cache + tree rows; out[m][h*hd+e] in dtype
 hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,
-                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s);
+                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s,
+                              const int32_t* n_dev = nullptr);
 bool attn_mfma_supported(int M, int Hq, int Hkv, int hd);
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd);
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
-                            int Hkv, int hd, void* out, void* scratch, hipStream_t s);
+                            int Hkv, int hd, void* out, void* scratch, hipStream_t s, const int32_t* n_dev = nullptr);
 
 }  // namespace ht

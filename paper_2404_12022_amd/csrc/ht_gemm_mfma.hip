@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
     // rotary partners (feature + hd/2) in rows 8..15, so lanes 0..31 end with the low halves and the lane 32 further
     // on with the partner of the same feature: one exchange, rotate by the row's position, store q or append k to
     // the cache.  v rows are appended to the slot-contiguous value cache.
-    const int hd = qe.hd, half = hd / 2, hb = hd / 16;
+    const int hd = qe.hd, half = hd / 2, hb = hd / 16, n_now = cache_len(qe.n, qe.n_dev);
     const int q_blocks = qe.Hq * hb, qk_blocks = q_blocks + qe.Hkv * hb;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
               o[i] = float_to_bf16(upper ? y * co + x * si : x * co - y * si);
             }
             bf16_t* dst = is_q ? qe.q + ((size_t)m * qe.Hq + h) * hd + j
-                               : qe.kc + ((size_t)(qe.n + m) * qe.Hkv + h) * hd + j;
+                               : qe.kc + ((size_t)(n_now + m) * qe.Hkv + h) * hd + j;
             *(uint2*)(dst + (upper ? half : 0)) = *(const uint2*)o;
           }
         }
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
           if (m < M) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              qe.vc[((size_t)h * hd + e0 + i) * qe.cap + qe.n + m] = float_to_bf16(acc[r][mt][i]);
+              qe.vc[((size_t)h * hd + e0 + i) * qe.cap + n_now + m] = float_to_bf16(acc[r][mt][i]);
           }
         }
       }

@@ -218,7 +218,8 @@ hipError_t launch_add_norm(int dtype, float* x, const float* part, int nsplit, s
 // ------------------------------------------------------------------------------------------------ rotary
 // cs[m][j] = (cos, sin) of (n + depth[m]) * base^(-2j/hd), evaluated in fp64 and rounded once.
 __global__ void rope_table_kernel(float2* __restrict__ cs, const int32_t* __restrict__ depth, int n, int half,
-                                  float base) {
+                                  float base, const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
   const int m = blockIdx.x;
   const int j = threadIdx.x;
   if (j >= half) return;
@@ -228,8 +229,9 @@ __global__ void rope_table_kernel(float2* __restrict__ cs, const int32_t* __rest
   sincos(pos * inv, &sn, &cn);
   cs[(size_t)m * half + j] = make_float2((float)cn, (float)sn);
 }
-hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s) {
-  hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(hd / 2), 0, s, (float2*)cs, depth, n, hd / 2, base);
+hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s,
+                             const int32_t* n_dev) {
+  hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(hd / 2), 0, s, (float2*)cs, depth, n, hd / 2, base, n_dev);
   return hipGetLastError();
 }
 
@@ -241,7 +243,8 @@ __global__ void rope_append_kernel(const TIN* __restrict__ q_in, int q_stride, c
                                    int k_stride, const TIN* __restrict__ v_in, int v_stride, int nsplit,
                                    size_t split_stride, const float2* __restrict__ cs, T* __restrict__ q,
                                    T* __restrict__ kc, T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap,
-                                   int paired) {
+                                   int paired, const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
   const int m = blockIdx.x, hh = blockIdx.y, j = threadIdx.x, half = hd / 2;
   if (j >= half) return;
   const float2 c = cs[(size_t)m * half + j];
@@ -300,7 +303,8 @@ template <typename T, typename TIN>
 __global__ __launch_bounds__(256) void rope_append_vec_kernel(
     const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in, int k_stride, const TIN* __restrict__ v_in,
     int v_stride, int nsplit, size_t split_stride, const float* __restrict__ cs, T* __restrict__ q, T* __restrict__ kc,
-    T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap, int paired) {
+    T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap, int paired, const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
   const int m = blockIdx.x, half = hd / 2, per_head = half / 4;
   const int unit = blockIdx.y * 256 + threadIdx.x;
   const int hh = unit / per_head, j = (unit % per_head) * 4;
@@ -343,21 +347,22 @@ __global__ __launch_bounds__(256) void rope_append_vec_kernel(
 }
 
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
-                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s) {
+                              int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s,
+                              const int32_t* n_dev) {
   const int stride = (Hq + 2 * Hkv) * hd;
   if (hd % 8 == 0) {
     const int units = (Hq + 2 * Hkv) * (hd / 8);
     HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, float>), dim3(M, (units + 255) / 256), dim3(256),
                                                 0, s, qkv, stride, qkv + (size_t)Hq * hd, stride,
                                                 qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride, cs,
-                                                (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap, paired ? 1 : 0);)
+                                                (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap, paired ? 1 : 0, n_dev);)
     return hipGetLastError();
   }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
                                               s, qkv, stride, qkv + (size_t)Hq * hd, stride,
                                               qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride,
                                               (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap,
-                                              paired ? 1 : 0);)
+                                              paired ? 1 : 0, n_dev);)
   return hipGetLastError();
 }
 hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_in, const void* v_in, const float* cs,
@@ -368,13 +373,13 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
     HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, T>), dim3(M, (units + 255) / 256), dim3(256), 0,
                                                 s, (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
                                                 Hkv * hd, 1, (size_t)0, cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap,
-                                                0);)
+                                                0, nullptr);)
     return hipGetLastError();
   }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
                                               (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
                                               Hkv * hd, 1, (size_t)0, (const float2*)cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd,
-                                              cap, 0);)
+                                              cap, 0, nullptr);)
   return hipGetLastError();
 }
 
@@ -519,7 +524,7 @@ hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev t
 // One wavefront: each round, every lane tests a slice of the nodes for "child of cur carrying the
 // greedy token after cur" and the lowest such node index wins.
 __global__ void accept_kernel(StepState* __restrict__ st, TreeDev tree, const int32_t* __restrict__ tok,
-                              const int32_t* __restrict__ g, int T) {
+                              const int32_t* __restrict__ g, int T, StepLog* __restrict__ log) {
   const int lane = threadIdx.x;
   int cur = 0, m = 1;
   if (lane == 0) { st->path[0] = 0; st->emitted[0] = tok[0]; }
@@ -535,10 +540,23 @@ __global__ void accept_kernel(StepState* __restrict__ st, TreeDev tree, const in
     cur = best;
     ++m;
   }
-  if (lane == 0) { st->m = m; st->next_root = g[cur]; st->root = g[cur]; }
+  if (lane == 0) {
+    st->m = m;
+    st->next_root = g[cur];
+    st->root = g[cur];
+    if (log) {                       // device-resident loop: the host reads the steps and the cache length afterwards
+      StepLog* e = log + st->log_count;
+      e->m = m;
+      for (int j = 0; j < m; ++j) e->emitted[j] = st->emitted[j];
+      st->log_count += 1;
+      st->n_old = st->n;
+      st->n += m;
+    }
+  }
 }
-hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s) {
-  hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, st, tree, tok, g, T);
+hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s,
+                         StepLog* log) {
+  hipLaunchKernelGGL(accept_kernel, dim3(1), dim3(64), 0, s, st, tree, tok, g, T, log);
   return hipGetLastError();
 }
 
@@ -548,10 +566,11 @@ template <typename T>
 __global__ void compact_kernel(const StepState* __restrict__ st, void* const* __restrict__ kcs,
                                void* const* __restrict__ vcs, int n, int row_elems, int cap,
                                const float* __restrict__ saved_h, size_t slot_stride, int slots,
-                               float* __restrict__ h_src, int d) {
+                               float* __restrict__ h_src, int d, int n_from_state) {
   const int layer = blockIdx.y;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   const int m = st->m;
+  if (n_from_state) n = st->n_old;      // device-resident loop: the cache length before this acceptance
   if (e < row_elems) {
     T* kc = (T*)kcs[layer];
     T* vc = (T*)vcs[layer];
@@ -567,11 +586,12 @@ __global__ void compact_kernel(const StepState* __restrict__ st, void* const* __
 }
 hipError_t launch_compact(int dtype, const StepState* st, void* const* kc, void* const* vc, int L, int n, int Hkv,
                           int hd, int cap, const float* saved_h, size_t slot_stride, int slots, float* h_src, int d,
-                          hipStream_t s) {
+                          hipStream_t s, bool n_from_state) {
   const int row = Hkv * hd;
   const int cols = row > d ? row : d;
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(compact_kernel<T>, dim3((cols + 255) / 256, L), dim3(256), 0, s, st, kc,
-                                              vc, n, row, cap, saved_h, slot_stride, slots, h_src, d);)
+                                              vc, n, row, cap, saved_h, slot_stride, slots, h_src, d,
+                                              n_from_state ? 1 : 0);)
   return hipGetLastError();
 }
 
@@ -742,9 +762,11 @@ hipError_t launch_gemm_simple(int dtype, const void* a, WeightSegs w, int M, int
 // every thread owns one (output element, key residue class).  Dynamic LDS: (n + M) floats + hd + 256.
 template <typename T>
 __global__ void attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc, int cap,
-                                   int n, int M, TreeDev tree, int Hq, int Hkv, int hd, T* __restrict__ out) {
+                                   int n, int M, TreeDev tree, int Hq, int Hkv, int hd, T* __restrict__ out,
+                                   const int32_t* __restrict__ n_dev) {
   extern __shared__ float smem[];
   __shared__ float red[4];
+  n = cache_len(n, n_dev);             // at most the host's n, which sized the dynamic LDS
   const int h = blockIdx.x, m = blockIdx.y, hk = h / (Hq / Hkv), tid = threadIdx.x;
   const int S = n + M;
   float* sc = smem;            // [S]
@@ -795,11 +817,11 @@ __global__ void attn_simple_kernel(const T* __restrict__ q, const T* __restrict_
   }
 }
 hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const void* vc, int cap, int n, int M,
-                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s) {
+                              TreeDev tree, int Hq, int Hkv, int hd, void* out, hipStream_t s, const int32_t* n_dev) {
   const size_t smem = (size_t)(n + M + hd + 256) * sizeof(float);
   if (smem > 64 * 1024 || hd > 256) return hipErrorInvalidValue;
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(attn_simple_kernel<T>, dim3(Hq, M), dim3(256), smem, s, (const T*)q,
-                                              (const T*)kc, (const T*)vc, cap, n, M, tree, Hq, Hkv, hd, (T*)out);)
+                                              (const T*)kc, (const T*)vc, cap, n, M, tree, Hq, Hkv, hd, (T*)out, n_dev);)
   return hipGetLastError();
 }
 

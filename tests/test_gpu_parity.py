@@ -243,6 +243,69 @@ def test_decode_loop_gives_the_greedy_continuation_until_the_cache_is_full(fused
     gpu.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "tiny_t123"])
+def test_device_resident_loop_reproduces_the_stored_trace(name):
+    """`ht_decode_steps`: 16 steps with the cache length kept on the device and one host wait at the end give the
+    tokens, counts and final state of the stored trace (16 single steps of the oracle); the state it leaves is a
+    valid starting point for ordinary single steps, checked against the oracle."""
+    from test_golden import read_trace
+    B, H = _B(), _H()
+    want = read_trace()[name]
+    wl = WORKLOADS[name]
+    say(f"device-resident loop {name}")
+    sc = H.StepCompare(wl)
+    for part in ((0, 5), (5, 16)):                                # two calls: the second starts from the first's state
+        counts, toks, root = sc.gpu.ht_decode_steps(part[1] - part[0])
+        steps = want["steps"][part[0]:part[1]]
+        assert counts == [len(st["path"]) for st in steps]
+        assert toks == [t for st in steps for t in st["emitted"]]
+        assert (root, sc.gpu.ht_cache_len()) == (steps[-1]["next_root"], steps[-1]["cache_len"])
+    for _ in range(16):                                           # bring the oracle to the same point
+        sc.ora.step()
+    assert int(sc.gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item()) == sc.ora.root
+    sc.check_cache("after the loop")
+    for _ in range(3):                                            # single steps go on from the loop's state
+        sc.step()
+    with pytest.raises(B.HTError) as e:
+        sc.gpu.ht_decode_steps(0)
+    assert e.value.code == B.HT_EINVAL
+    with pytest.raises(B.HTError) as e:
+        sc.gpu.ht_decode_steps(64)                                # 64 steps of up to k + 1 tokens do not fit the cache
+    assert e.value.code == B.HT_ECAPACITY
+    sc.gpu.close()
+
+
+def test_device_resident_loop_on_the_matrix_core_path():
+    """The loop against single steps of the same library on a 7B-wide bf16 model (2 layers): both run the same
+    kernels on the same values, so tokens, counts and the caches agree bit for bit."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), prompt_len=100, max_cache=256)
+    parent, rank = tree_of(wl)
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    say("device-resident loop, 7B width")
+    a, b = H.gpu_model(wl, tensors, max_tree=len(parent)), H.gpu_model(wl, tensors, max_tree=len(parent))
+    for g in (a, b):
+        g.ht_set_tree(parent, rank)
+        g.ht_prefill(prompt_of(wl))
+    steps = 6
+    counts, toks, root = a.ht_decode_steps(steps)
+    ref_counts, ref_toks = [], []
+    for _ in range(steps):
+        b.ht_transfer(None, None)
+        b.ht_tree_verify_step(None, None, None)
+        m, emitted, ref_root, _ = b.ht_accept_and_compact()
+        ref_counts.append(m)
+        ref_toks += emitted
+    assert (counts, toks, root) == (ref_counts, ref_toks, ref_root)
+    assert a.ht_cache_len() == b.ht_cache_len() == wl.prompt_len + sum(counts)
+    n = a.ht_cache_len()
+    for layer in (0, 1):
+        assert torch.equal(a.ht_get_buffer(B.HT_BUF_K_CACHE, layer)[:n], b.ht_get_buffer(B.HT_BUF_K_CACHE, layer)[:n])
+        assert torch.equal(a.ht_get_buffer(B.HT_BUF_V_CACHE, layer)[:, :, :n], b.ht_get_buffer(B.HT_BUF_V_CACHE, layer)[:, :, :n])
+    a.close()
+    b.close()
+
+
 def _rank0_chain(parent, rank):
     chain, cur = [0], 0
     while True:
