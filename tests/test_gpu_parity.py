@@ -454,6 +454,47 @@ def test_random_model_shapes_against_oracle(seed):
         sc.gpu.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_most_transfer_steps_the_interface_allows(dtype):
+    """k = 8 transfer steps (the interface's maximum) at four distinct layers, a tree of depth 8, drafting nodes at
+    several depths: eight pseudo rows per node join the passes in four groups."""
+    H = _H()
+    k = 8
+    parent, rank = random_tree(77, 30, k)
+    wl = small_workload(name="k8", n_layers=5, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=256, vocab=512,
+                        k=k, transfer_layers=(1, 1, 2, 2, 3, 3, 4, 4), dtype=dtype, prompt_len=37, max_cache=200,
+                        tree_size=30, branching=(1,) * k, seed=4242)
+    fused = [0, 3, 9, 17]
+    say(f"k = 8, {dtype}: tree depth {max(len(_path_to(parent, v)) for v in range(30)) - 1}, drafting nodes {fused}")
+    sc = H.StepCompare(wl, tree=(parent, rank), fused=fused)
+    sc.check_prefill()
+    for step in range(4):
+        r = sc.step(require_same_tokens=(dtype == "f32"))
+        if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
+            break
+    sc.gpu.close()
+
+
+def test_long_cache_end_to_end_with_sixteen_key_slices():
+    """A 6000-token prompt (47 prefill chunks) on a small packed bf16 model, then decode steps whose attention runs
+    over 95 key tiles in sixteen slices, the most the merge handles; the one-token pass takes its own kernel."""
+    H = _H()
+    wl = small_workload(name="long", n_layers=2, d_model=128, n_heads=2, n_kv_heads=1, head_dim=64, d_ffn=256,
+                        vocab=512, k=2, transfer_layers=(1, 1), dtype="bf16", prompt_len=6000, max_cache=6200,
+                        tree_size=64, branching=(10, 6), seed=777)
+    say("long cache: oracle prefill of 6000 tokens")
+    sc = H.StepCompare(wl)
+    sc.check_prefill()
+    for step in range(2):
+        r = sc.step(require_same_tokens=False)
+        if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
+            break
+    sc.gpu.close()
+    sc = H.StepCompare(wl, tree=([-1], [0]))                       # the plain decode step at the same length
+    sc.step(forced=[sc.ora.root], require_same_tokens=False)
+    sc.gpu.close()
+
+
 @pytest.mark.parametrize("name,fused", [("tiny_bf16", False), ("tiny_t123_bf16", False), ("tiny_t123_bf16", True)])
 def test_tiny_bf16_sixteen_steps(name, fused):
     H = _H()
