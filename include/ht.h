@@ -212,11 +212,21 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
  *                           ht_init_model does the same for every projection of a bf16 model.
  *   ht_skinny_gemm_packed : the product on packed bf16 weights; scratch (may be NULL) holds split-K partials.
  *   ht_skinny_gemm        : convenience for either dtype: packs into scratch when it can, then multiplies.
- *                           scratch >= ht_skinny_gemm_scratch_bytes(M, N, K), 256-byte aligned. */
+ *                           scratch >= ht_skinny_gemm_scratch_bytes(M, N, K), 256-byte aligned.
+ *   ht_gate_up_pack       : bf16 w_gate[f, K], w_up[f, K] (f % 16 == 0, K % 8 == 0) -> one packed matrix of 2 f
+ *                           rows with gate and up row blocks alternating; `packed` needs
+ *                           ht_weight_pack_bytes(2 f, K) bytes.
+ *   ht_gate_up_silu_packed: the feed-forward block's first half as the verify pass runs it, one kernel:
+ *                           act_out[M, f] (bf16) = silu(a . w_gate^T) * (a . w_up^T), a bf16 [M, K], fp32 sums.
+ *                           The largest projection of a decoder block, hence the kernel bench.py takes the
+ *                           roofline of.  HT_EINVAL on NULL pointers, M outside 1..HT_MAX_TREE or bad f, K. */
 int32_t ht_padded_rows(int32_t M);
 size_t ht_weight_pack_bytes(int32_t N, int32_t K);
 int ht_weight_pack(const void *w, int32_t N, int32_t K, void *packed, void *stream);
 size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+int ht_gate_up_pack(const void *w_gate, const void *w_up, int32_t f, int32_t K, void *packed, void *stream);
+int ht_gate_up_silu_packed(const void *a, const void *packed, int32_t M, int32_t f, int32_t K, void *act_out,
+                           void *stream);
 int ht_skinny_gemm_packed(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
                           void *scratch, size_t scratch_bytes, void *stream);
 

@@ -26,6 +26,7 @@ EXPORTS = [
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
     "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
+    "ht_gate_up_pack", "ht_gate_up_silu_packed",
 ]
 
 
@@ -71,6 +72,8 @@ def _load() -> C.CDLL:
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
         "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "ht_accept_and_compact": (C.c_int, [vp, i32p, i32p, i32p, i32p, vp]),
+        "ht_gate_up_pack": (C.c_int, [vp, vp, C.c_int32, C.c_int32, vp, vp]),
+        "ht_gate_up_silu_packed": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
         "ht_decode_steps": (C.c_int, [vp, C.c_int32, i32p, i32p, i32p, vp]),
         "ht_cache_len": (C.c_int32, [vp]),
         "ht_last_error": (C.c_char_p, []),
@@ -162,6 +165,14 @@ def ht_weight_pack(w, N, K, packed, stream=None) -> None:
 def ht_skinny_gemm_packed(a, packed, M, N, K, out, scratch=None, stream=None) -> None:
     sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.ht_skinny_gemm_packed(_ptr(a), _ptr(packed), M, N, K, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
+
+
+def ht_gate_up_pack(w_gate, w_up, f, K, packed, stream=None) -> None:
+    _check(lib.ht_gate_up_pack(_ptr(w_gate), _ptr(w_up), f, K, _ptr(packed), _stream_ptr(stream)))
+
+
+def ht_gate_up_silu_packed(a, packed, M, f, K, act_out, stream=None) -> None:
+    _check(lib.ht_gate_up_silu_packed(_ptr(a), _ptr(packed), M, f, K, _ptr(act_out), _stream_ptr(stream)))
 
 
 def ht_stream_read_probe(buf, sink, stream=None) -> int:

@@ -961,6 +961,24 @@ int ht_weight_pack(const void* w, int32_t N, int32_t K, void* packed, void* stre
   return HT_OK;
 }
 
+int ht_gate_up_pack(const void* w_gate, const void* w_up, int32_t f, int32_t K, void* packed, void* stream) {
+  if (!w_gate || !w_up || !packed) return fail(HT_EINVAL, "NULL argument");
+  if (f < 16 || f % 16 || !ht_weight_pack_bytes(2 * f, K))
+    return fail(HT_EINVAL, "packing needs f %% 16 == 0 and K %% 8 == 0 (f=%d K=%d)", f, K);
+  HT_HIP(launch_repack(WeightSegs{{w_gate, w_up, nullptr}, {f, f, 0}, 2}, K, 1, 0, packed, (hipStream_t)stream));
+  return HT_OK;
+}
+
+int ht_gate_up_silu_packed(const void* a, const void* packed, int32_t M, int32_t f, int32_t K, void* act_out,
+                           void* stream) {
+  if (!a || !packed || !act_out) return fail(HT_EINVAL, "NULL argument");
+  if (M < 1 || M > kMaxTree || f < 16 || f % 16 || !ht_weight_pack_bytes(2 * f, K))
+    return fail(HT_EINVAL, "bad shape M=%d f=%d K=%d", M, f, K);
+  PackedW pw{(const bf16_t*)packed, 2 * f, K, packed_cols(K)};
+  HT_HIP(launch_gemm_packed_silu(a, pw, M, act_out, (hipStream_t)stream));
+  return HT_OK;
+}
+
 size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) return 0;
   return align_up((size_t)kMaxSplitK * M * N * sizeof(float), 256) + ht_weight_pack_bytes(N, K);

@@ -68,6 +68,34 @@ def test_skinny_product_matches_textbook_product(dtype, M, N, K):
     assert np.max(np.abs(got - want)) <= bound, (np.max(np.abs(got - want)), bound)
 
 
+@pytest.mark.parametrize("M,f,K", [(1, 64, 64), (7, 208, 200), (64, 688, 256), (76, 1376, 512), (128, 4112, 136),
+                                   (64, 11008, 128)])
+def test_fused_gate_up_product_matches_its_definition(M, f, K):
+    """act = silu(a . Wg^T) * (a . Wu^T) (the feed-forward block's first half, fused into one kernel) against the
+    oracle's product and SiLU, bf16 operands; sizes with ragged row-block counts and several token tiles."""
+    B, H = _B(), _H()
+    say(f"gate/up M={M} f={f} K={K}")
+    Mp = B.ht_padded_rows(M)
+    a = torch.zeros(Mp, K, dtype=torch.bfloat16, device=H.DEV)
+    a[:M] = counter_normal(3, 31, (M, K), 1.0, device=H.DEV, dtype=torch.bfloat16)
+    wg = counter_normal(3, 32, (f, K), 0.1, device=H.DEV, dtype=torch.bfloat16)
+    wu = counter_normal(3, 33, (f, K), 0.1, device=H.DEV, dtype=torch.bfloat16)
+    packed = torch.empty(B.ht_weight_pack_bytes(2 * f, K), dtype=torch.uint8, device=H.DEV)
+    B.ht_gate_up_pack(wg, wu, f, K, packed)
+    out = torch.full((M, f), float("nan"), dtype=torch.bfloat16, device=H.DEV)
+    B.ht_gate_up_silu_packed(a, packed, M, f, K, out)
+    torch.cuda.synchronize()
+    x = H.cpu(a[:M])
+    want = O.silu(O.linear(x, H.cpu(wg))) * O.linear(x, H.cpu(wu))
+    got = H.cpu(out)
+    assert np.all(np.isfinite(got))
+    # fp32 sums of exact bf16 products, one bf16 rounding of the result (2^-9 relative)
+    assert np.max(np.abs(got - want) - 2.0 ** -8 * np.abs(want)) <= 1e-5 * np.sqrt(K) * np.abs(want).max() + 1e-6
+    with pytest.raises(B.HTError) as e:
+        B.ht_gate_up_silu_packed(a, packed, M, f + 8, K, out)
+    assert e.value.code == B.HT_EINVAL
+
+
 def test_stream_read_probe_reads_whole_passes_and_rejects_bad_buffers():
     B, H = _B(), _H()
     buf = torch.zeros(40 << 20, dtype=torch.uint8, device=H.DEV)
