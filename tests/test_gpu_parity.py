@@ -303,6 +303,24 @@ def test_device_resident_loop_reproduces_the_stored_trace(name):
     sc.gpu.close()
 
 
+def test_device_resident_loop_sixty_four_steps_give_greedy_text():
+    """The most steps one call takes, on the tiny model: the text is the greedy continuation, the counts add up."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["tiny"].with_(max_cache=256)
+    parent, rank = tree_of(wl)
+    gpu = H.gpu_model(wl, max_tree=len(parent))
+    gpu.ht_set_tree(parent, rank)
+    prompt = prompt_of(wl)
+    gpu.ht_prefill(prompt)
+    counts, toks, root = gpu.ht_decode_steps(B.HT_MAX_LOOP_STEPS)
+    assert len(counts) == 64 and all(1 <= c <= wl.k + 1 for c in counts) and sum(counts) == len(toks)
+    want = oracle_model(wl).ar_greedy(prompt, len(toks) + 1)
+    assert toks == want[:-1] and root == want[-1]
+    assert gpu.ht_cache_len() == len(prompt) + len(toks)
+    say(f"64 steps in one call: {len(toks)} tokens, {max(counts)} at most per step")
+    gpu.close()
+
+
 def test_device_resident_loop_on_the_matrix_core_path():
     """The loop against single steps of the same library on a 7B-wide bf16 model (2 layers): both run the same
     kernels on the same values, so tokens, counts and the caches agree bit for bit."""
