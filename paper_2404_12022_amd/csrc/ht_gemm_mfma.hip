@@ -238,7 +238,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const float4 q4 = row_ss[mt];
-      const float sc = 1.0f / sqrtf((q4.x + q4.y + q4.z + q4.w) * rs.inv_d + rs.eps);
+      const float sc = __builtin_amdgcn_rsqf((q4.x + q4.y + q4.z + q4.w) * rs.inv_d + rs.eps);   // 1 ulp
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[r][mt] *= sc;
     }
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gt = acc[0][mt][i], up = acc[R - 1][mt][i];
-            o[i] = float_to_bf16(gt / (1.0f + __expf(-gt)) * up);
+            o[i] = float_to_bf16(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up);   // 1 ulp reciprocal, bf16 result
           }
           *(uint2*)(dst + (size_t)m * f + j0) = *(const uint2*)o;
         }
