@@ -247,10 +247,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
         const int e0 = eb * 16 + g * 4;
         if (nsplit == 1) {
           const float inv = 1.0f / lsum;
-          bf16_t ob[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(o[i] * inv);
-          *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
+          *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) =
+              pack4_bf16(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
         } else {
           float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
           *(float4*)dst = make_float4(o[0], o[1], o[2], o[3]);
@@ -563,8 +561,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
     o.x += f * v.x; o.y += f * v.y; o.z += f * v.z; o.w += f * v.w;
   }
   const float inv = 1.0f / l;
-  bf16_t ob[4] = {float_to_bf16(o.x * inv), float_to_bf16(o.y * inv), float_to_bf16(o.z * inv), float_to_bf16(o.w * inv)};
-  *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e) = *(const uint2*)ob;
+  *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e) = pack4_bf16(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
 }
 
 // Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts of a workgroup

@@ -22,6 +22,18 @@ __host__ __device__ inline bf16_t float_to_bf16(float f) {
   return (bf16_t)(c.u >> 16);
 }
 
+// Four floats to four bf16 (8 bytes) with the gfx950 pair conversion (round-to-nearest-even, NaN stays NaN: the same
+// values as float_to_bf16).
+__device__ inline uint2 pack4_bf16(float a, float b, float c, float d) {
+  typedef float f2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+  const b2_t lo = __builtin_convertvector(f2_t{a, b}, b2_t), hi = __builtin_convertvector(f2_t{c, d}, b2_t);
+  uint2 r;
+  r.x = *(const uint32_t*)&lo;
+  r.y = *(const uint32_t*)&hi;
+  return r;
+}
+
 template <typename T> struct Conv;
 template <> struct Conv<float> {
   __device__ static inline float load(const float* p) { return *p; }

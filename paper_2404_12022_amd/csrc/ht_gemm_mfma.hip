@@ -266,13 +266,13 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
       for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r16;
         if (m < M) {
-          bf16_t o[4];
+          float o[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gt = acc[0][mt][i], up = acc[R - 1][mt][i];
-            o[i] = float_to_bf16(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up);   // 1 ulp reciprocal, bf16 result
+            o[i] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;      // 1 ulp reciprocal, bf16 result
           }
-          *(uint2*)(dst + (size_t)m * f + j0) = *(const uint2*)o;
+          *(uint2*)(dst + (size_t)m * f + j0) = pack4_bf16(o[0], o[1], o[2], o[3]);
         }
       }
     }
@@ -301,16 +301,16 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
             const float4 c01 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2);
             const float4 c23 = *(const float4*)(qe.cs + ((size_t)m * half + j) * 2 + 4);
             const float cs_[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
-            bf16_t o[4];
+            float o[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const float x = upper ? other[i] : acc[r][mt][i], y = upper ? acc[r][mt][i] : other[i];
               const float co = cs_[2 * i], si = cs_[2 * i + 1];
-              o[i] = float_to_bf16(upper ? y * co + x * si : x * co - y * si);
+              o[i] = upper ? y * co + x * si : x * co - y * si;
             }
             bf16_t* dst = is_q ? qe.q + ((size_t)m * qe.Hq + h) * hd + j
                                : qe.kc + ((size_t)(n_now + m) * qe.Hkv + h) * hd + j;
-            *(uint2*)(dst + (upper ? half : 0)) = *(const uint2*)o;
+            *(uint2*)(dst + (upper ? half : 0)) = pack4_bf16(o[0], o[1], o[2], o[3]);
           }
         }
       } else {

@@ -167,9 +167,10 @@ __global__ void add_norm_parts_kernel(float* __restrict__ x, const float* __rest
       if (save_h) *(float4*)(save_h + (size_t)m * d + c) = v;
       ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
       if (u) {
-        bf16_t o[4] = {float_to_bf16(v.x * bf16_to_float(gain[c + 0])), float_to_bf16(v.y * bf16_to_float(gain[c + 1])),
-                       float_to_bf16(v.z * bf16_to_float(gain[c + 2])), float_to_bf16(v.w * bf16_to_float(gain[c + 3]))};
-        *(uint2*)(u + (size_t)m * d + c) = *(const uint2*)o;
+        const uint2 g4 = *(const uint2*)(gain + c);
+        *(uint2*)(u + (size_t)m * d + c) =
+            pack4_bf16(v.x * __uint_as_float(g4.x << 16), v.y * __uint_as_float(g4.x & 0xffff0000u),
+                       v.z * __uint_as_float(g4.y << 16), v.w * __uint_as_float(g4.y & 0xffff0000u));
       }
     }
   }
