@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   const int split = blockIdx.z;
   const int S = n + M;
   const int chunks = (S + 31) / 32;
-  const int cs = (int)((long long)chunks * split / nsplit), ce = (int)((long long)chunks * (split + 1) / nsplit);
+  int cs, ce;
+  even_share(chunks, nsplit, split, cs, ce);
 
   // queries of this lane: token m0 + qb*16 + r16 (clamped for loads), e columns es*32 + g*8 ..
   Frag qf[QB][ES];
@@ -317,7 +318,8 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   const int split = blockIdx.z;
   const int S = n + M;
   const int tiles = (S + TK - 1) / TK;
-  const int ts = (int)((long long)tiles * split / nsplit), te = (int)((long long)tiles * (split + 1) / nsplit);
+  int ts, te;
+  even_share(tiles, nsplit, split, ts, te);
   int tmid = n / TK;                     // tiles below tmid hold cache keys only
   tmid = tmid < ts ? ts : (tmid > te ? te : tmid);
 

@@ -34,6 +34,15 @@ __device__ inline uint2 pack4_bf16(float a, float b, float c, float d) {
   return r;
 }
 
+// Share `total` items over `parts` owners as evenly as possible: owner i gets [lo, hi), the first total % parts
+// owners one item more.  One 32-bit division (a 64-bit one is a few hundred instructions in front of a kernel's
+// first load).
+__device__ inline void even_share(unsigned total, unsigned parts, unsigned i, int& lo, int& hi) {
+  const unsigned q = total / parts, rem = total - q * parts;
+  lo = (int)(i * q + (i < rem ? i : rem));
+  hi = lo + (int)q + (i < rem ? 1 : 0);
+}
+
 template <typename T> struct Conv;
 template <> struct Conv<float> {
   __device__ static inline float load(const float* p) { return *p; }

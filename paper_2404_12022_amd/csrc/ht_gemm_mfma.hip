@@ -104,17 +104,20 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
   const int chunks = KS / STEPS;                         // KS is a multiple of STEPS (weights zero-padded)
-  const int c0 = (int)((long long)chunks * blockIdx.y / nsplit);
-  const int c1 = (int)((long long)chunks * (blockIdx.y + 1) / nsplit);
+  int c0, c1;
+  even_share(chunks, nsplit, blockIdx.y, c0, c1);
   const int n_rb = N / 16;
-  // The grid's workgroups share the row blocks evenly: workgroup b owns blocks [b n_rb / G, (b+1) n_rb / G) (in whole pairs for the SiLU epilogue), at
-  // most R * WAVES of them (the launcher's choice of G), R consecutive ones per wavefront.  A slot past the end of
+  // The grid's workgroups share the row blocks evenly: workgroup b owns n_rb / G blocks, the first n_rb % G
+  // workgroups one more (in whole pairs for the SiLU epilogue), at most R * WAVES of them (the launcher's
+  // choice of G), R consecutive ones per wavefront.  A slot past the end of
   // the workgroup's range re-reads one fragment of its first block over and over (stride 0: cache hits, no HBM
   // traffic, same instruction stream) and stores nothing.
   constexpr int U = EPI == EPI_SILU ? 2 : 1;             // the SiLU epilogue needs both blocks of a (gate, up) pair
   const int units = (n_rb + U - 1) / U;
-  const int wg0 = U * (int)((long long)units * blockIdx.x / gridDim.x);
-  const int wg1 = U * (int)((long long)units * (blockIdx.x + 1) / gridDim.x);
+  int wg0, wg1;
+  even_share(units, gridDim.x, blockIdx.x, wg0, wg1);
+  wg0 *= U;
+  wg1 *= U;
   const int rb0 = wg0 + wave * R;
   if (c0 >= c1) return;                                  // uniform over the block
 
