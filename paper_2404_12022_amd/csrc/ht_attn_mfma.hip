@@ -542,11 +542,10 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
 template <int HD>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                          int nsplit, int M, int Hq, bf16_t* __restrict__ out) {
-  constexpr int LANES = HD / 4, PAIRS = 256 / LANES;
-  const int pair = blockIdx.x * PAIRS + threadIdx.x / LANES;      // pair = h * M + m, the order of the partials
+  constexpr int LANES = HD / 4, PAIRS = 256 / LANES;               // grid = (row groups of PAIRS rows, heads)
+  const int h = blockIdx.y, m = blockIdx.x * PAIRS + threadIdx.x / LANES;
   const int e = (threadIdx.x % LANES) * 4;
-  if (pair >= M * Hq) return;
-  const int h = pair / M, m = pair % M;
+  if (m >= M) return;
   float ms[kMaxSplits], mall = -INFINITY;
   for (int s = 0; s < nsplit; ++s) {
     ms[s] = part_ml[(((size_t)h * nsplit + s) * M + m) * 2];
@@ -557,12 +556,12 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < nsplit; ++s) {
     const size_t idx = ((size_t)h * nsplit + s) * M + m;
-    const float f = exp2f(ms[s] - msafe);
+    const float f = __builtin_amdgcn_exp2f(ms[s] - msafe);          // exp2(-inf) = 0 for empty slices
     l += f * part_ml[idx * 2 + 1];
     const float4 v = *(const float4*)(part_o + idx * HD + e);
     o.x += f * v.x; o.y += f * v.y; o.z += f * v.z; o.w += f * v.w;
   }
-  const float inv = 1.0f / l;
+  const float inv = __builtin_amdgcn_rcpf(l);
   *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e) = pack4_bf16(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
 }
 
@@ -600,7 +599,7 @@ void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int
   else hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
 #undef HT_ATTN_ARGS
   if (p.nsplit > 1)
-    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((M * Hq + 256 / (HD / 4) - 1) / (256 / (HD / 4))), dim3(256), 0, s,
+    hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((M + 256 / (HD / 4) - 1) / (256 / (HD / 4)), Hq), dim3(256), 0, s,
                        part_o, part_ml, p.nsplit, M, Hq, out);
 }
 
