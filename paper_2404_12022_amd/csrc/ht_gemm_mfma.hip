@@ -322,9 +322,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
         for (int mt = 0; mt < MT; ++mt) {
           const int m = mt * 16 + r16;
           if (m < M) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              qe.vc[((size_t)h * hd + e0 + i) * qe.cap + n_now + m] = float_to_bf16(acc[r][mt][i]);
+            const uint2 v4 = pack4_bf16(acc[r][mt][0], acc[r][mt][1], acc[r][mt][2], acc[r][mt][3]);
+            bf16_t* col = qe.vc + ((size_t)h * hd + e0) * qe.cap + n_now + m;      // feature e0 + i is i * cap further on
+            col[0] = (bf16_t)(v4.x & 0xffffu);
+            col[(size_t)qe.cap] = (bf16_t)(v4.x >> 16);
+            col[2 * (size_t)qe.cap] = (bf16_t)(v4.y & 0xffffu);
+            col[3 * (size_t)qe.cap] = (bf16_t)(v4.y >> 16);
           }
         }
       }

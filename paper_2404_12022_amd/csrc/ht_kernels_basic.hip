@@ -294,10 +294,7 @@ template <> __device__ inline void store4<float>(float* p, const float (&v)[4]) 
   *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
 }
 template <> __device__ inline void store4<bf16_t>(bf16_t* p, const float (&v)[4]) {
-  bf16_t h[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) h[i] = float_to_bf16(v[i]);
-  *(uint2*)p = *(const uint2*)h;
+  *(uint2*)p = pack4_bf16(v[0], v[1], v[2], v[3]);
 }
 
 template <typename T, typename TIN>
