@@ -19,6 +19,11 @@ What is written out here, and the passage each part follows:
   * Greedy verification: last accepted position, next token (Fig. 2 caption; Sec. 3.4).
   * Both inference schedules: "draft after accept" (S1) and the paper's fused
     "verify and draft in the same forward" (S2, Fig. 2 caption / Sec. 3.4 last sentence).
+  * A tree chosen anew at every step from the draft distributions (`candidate_logprobs`,
+    `dynamic_tree`).  The paper decodes with a pre-defined tree (Sec. 3.4.1) and names the choice of
+    the tree's structure as what the speed depends on and as future work (Limitation section); the
+    rule here is this build's own, defined by these two functions: the nodes a greedy verification
+    is most likely to reach if the draft distributions were the model's.
 
 Arithmetic: weights exactly as stored (fp32 or bf16 widened to fp64), every accumulation in
 fp64, no intermediate rounding.  Index conventions: positions are 0-based, the cache holds
@@ -28,10 +33,12 @@ stream after t complete blocks (t = 0 is the embedding output).
 
 Pins: every function here is pinned by tests/test_oracle_*.py (closed forms, loop-level brute
 force, the causal-path invariant, losslessness against `ar_greedy`, exhaustive acceptance
-search, S1 == S2).  Nothing here is "parity unpinned".
+search, S1 == S2; the dynamic tree against an exhaustive search over all trees of its size).
+Nothing here is "parity unpinned".
 """
 from __future__ import annotations
 
+import itertools
 from dataclasses import dataclass
 from typing import Dict, List, Optional, Sequence, Tuple
 
@@ -209,6 +216,54 @@ def top_candidates(row: np.ndarray, b: int) -> List[int]:
     return [int(j) for j in order[:b]]
 
 
+def candidate_logprobs(row: np.ndarray, b: int) -> Tuple[List[int], np.ndarray]:
+    """The b best tokens of one draft distribution (value descending, id ascending) and their log-softmax
+    values  z_j - log(sum_v exp z_v)  over the whole vocabulary."""
+    z = np.asarray(row, dtype=np.float64)
+    ids = top_candidates(z, b)
+    peak = np.max(z)
+    lse = peak + np.log(np.sum(np.exp(z - peak)))
+    return ids, np.array([z[j] - lse for j in ids])
+
+
+def dynamic_tree(lp: np.ndarray, T: int) -> Tuple[List[int], List[int]]:
+    """Tree of T nodes (root included) for one step, from lp[e - 1, r] = log-probability of the r-th best
+    candidate of pseudo position e (rows sorted best first, all values <= 0).
+
+    The drafts of the k positions do not depend on one another (Sec. 3.2: every pseudo state is made from the
+    same hidden state), so a node whose path from the root picks ranks (r_1, .., r_e) is reached by a greedy
+    verification with probability exp(score), score = lp[0, r_1] + .. + lp[e-1, r_e], if the drafts were
+    exact.  The tree is the T - 1 nodes of the complete b-ary tree of depth k that come first in the order
+    (score descending, depth ascending, rank path ascending); a child never scores above its parent, so the
+    set is closed under taking parents and maximises the expected number of accepted candidates.  Nodes are
+    numbered in that order after the root.  The score is accumulated from the root down in lp's own dtype
+    (the decision is taken in the precision of the caller's numbers); NaN counts as -inf.
+    Returns (parent, rank) as `ht_set_tree` takes them."""
+    lp = np.asarray(lp)
+    k, b = lp.shape
+    kind = lp.dtype.type
+    nodes = []
+    for e in range(1, k + 1):
+        for path in itertools.product(range(b), repeat=e):
+            score = kind(0)
+            for level, r in enumerate(path):
+                term = lp[level, r]
+                score = score + (term if term == term else kind(-np.inf))
+            nodes.append((-float(score), e, path))
+    if T < 1 or T - 1 > len(nodes):
+        raise ValueError(f"a tree of {T} nodes does not fit {k} levels of {b} candidates")
+    nodes.sort()
+    chosen = [path for _, _, path in nodes[:T - 1]]
+    index = {(): 0}
+    for v, path in enumerate(chosen, start=1):
+        index[path] = v
+    parent, rank = [-1], [0]
+    for path in chosen:
+        parent.append(index[path[:-1]])          # KeyError would mean the set is not closed under parents
+        rank.append(path[-1])
+    return parent, rank
+
+
 def accept_walk(parent: Sequence[int], tok: Sequence[int], g: Sequence[int]) -> Tuple[List[int], int]:
     """Greedy verification: follow, from the root, the first child (lowest index) whose token
     equals the model's greedy choice after its parent; stop when no child matches.
@@ -239,16 +294,20 @@ class HiddenTransferOracle:
     def __init__(self, model: OracleModel, parent: Sequence[int], rank: Sequence[int], capacity: int):
         self.m, self.cfg = model, model.cfg
         c = self.cfg
-        self.parent, self.rank = list(parent), list(rank)
-        self.depth = tree_depth(parent)
-        self.T = len(parent)
-        self.anc = ancestor_matrix(parent)
         self.capacity = capacity
         self.K = [np.zeros((capacity, c.n_kv_heads, c.head_dim)) for _ in range(c.n_layers)]
         self.V = [np.zeros((capacity, c.n_kv_heads, c.head_dim)) for _ in range(c.n_layers)]
         self.n = 0
         self.root: Optional[int] = None
         self.h_src: Dict[int, np.ndarray] = {}
+        self.set_tree(parent, rank)
+
+    def set_tree(self, parent: Sequence[int], rank: Sequence[int]) -> None:
+        """The tree of the following steps (a static tree is set once, a dynamic one before every verification)."""
+        self.parent, self.rank = list(parent), list(rank)
+        self.depth = tree_depth(parent)
+        self.T = len(parent)
+        self.anc = ancestor_matrix(parent)
         # candidates needed per depth: 1 + the largest rank used at that depth
         self.width = [0] * (max(self.depth) + 1)
         for v in range(1, self.T):
@@ -342,10 +401,16 @@ class HiddenTransferOracle:
         self.root = new_root
         return path, emitted
 
-    def step(self, forced_tokens: Optional[Sequence[int]] = None):
-        """One full S1 step.  Returns a dict of every intermediate object."""
+    def step(self, forced_tokens: Optional[Sequence[int]] = None, dynamic: Optional[Tuple[int, int]] = None):
+        """One full S1 step.  Returns a dict of every intermediate object.
+        dynamic = (T, b): the step first chooses its own tree of T nodes among the b best candidates of every
+        pseudo position (`dynamic_tree` on the fp64 log-probabilities)."""
         pseudo = self.transfer()
         d = self.draft(pseudo)
+        if dynamic is not None:
+            size, b = dynamic
+            lp = np.stack([candidate_logprobs(d[e], b)[1] for e in range(self.cfg.k)])
+            self.set_tree(*dynamic_tree(lp, size))
         cand = self.candidates(d)
         tok = list(forced_tokens) if forced_tokens is not None else self.build_tree(cand)
         z, g, saved = self.verify(tok)

@@ -1,7 +1,8 @@
 """Stored values under tests/golden/.
 
 `tree_mask_seven_nodes.txt` is typed by hand from the definition of tree attention (Sec. 3.4.1): the oracle's tree
-tables have to reproduce it.  `tiny_decode_trace.txt` is written by `tests/golden/make_golden.py` from the oracle
+tables have to reproduce it.  `dynamic_tree_two_levels.txt` is worked by hand from the product rule for independent
+draws: the oracle's tree selection has to reproduce it.  `tiny_decode_trace.txt` is written by `tests/golden/make_golden.py` from the oracle
 alone; the oracle has to keep reproducing it (a deliberate change regenerates the file and says why), and the GPU
 test in test_gpu_parity.py decodes the same tokens through the C ABI.
 """
@@ -29,6 +30,19 @@ def read_tree_fixture():
         else:
             rows[f[0]] = [int(x) for x in f[1:]]
     return rows, mask, paths
+
+
+def read_dynamic_tree_fixture():
+    prob, trees = {}, {}
+    for line in open(os.path.join(GOLDEN, "dynamic_tree_two_levels.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "prob":
+            prob[int(f[1])] = [float(x) for x in f[2:]]
+        else:
+            trees.setdefault(int(f[1]), {})[f[2]] = [float(x) if f[2] == "reach" else int(x) for x in f[3:]]
+    return prob, trees
 
 
 def read_trace():
@@ -100,3 +114,17 @@ def test_oracle_reproduces_the_stored_decode_trace():
             assert (res["root"], res["n"]) == (st["next_root"], st["cache_len"]), f"{name} step {s}: state"
         # every step emits at least the pending root, and the trace holds steps that accept drafts
         assert all(len(st["path"]) >= 1 for st in want["steps"])
+
+
+def test_hand_worked_dynamic_tree():
+    prob, trees = read_dynamic_tree_fixture()
+    lp = np.log(np.array([prob[1], prob[2]]))
+    for size, want in trees.items():
+        for kind in (np.float64, np.float32):
+            parent, rank = O.dynamic_tree(lp.astype(kind), size)
+            assert parent == want["parent"] and rank == want["rank"], (size, kind)
+        depth = O.tree_depth(parent)
+        reach = [1.0]
+        for v in range(1, size):
+            reach.append(reach[parent[v]] * prob[depth[v]][rank[v]])
+        assert abs(sum(reach[1:]) - want["reach"][0]) < 1e-12

@@ -223,3 +223,99 @@ def test_transfer_is_a_bare_matrix_product():
         h = hidden[t][-1]
         want = [sum(model.w.w_transfer[i][o, c] * h[c] for c in range(wl.d_model)) for o in range(wl.d_model)]
         assert np.allclose(ps[i], want, atol=1e-13)
+
+
+# ------------------------------------------------------------------ tree chosen from the draft distributions
+def test_candidate_logprobs_closed_forms():
+    from scipy.special import log_softmax
+    V = 37
+    ids, lp = O.candidate_logprobs(np.full(V, 3.25), 5)
+    assert ids == [0, 1, 2, 3, 4]                                  # equal values: lowest ids first
+    assert np.allclose(lp, -math.log(V), atol=1e-13)               # uniform distribution
+    rng = np.random.default_rng(5)
+    z = rng.normal(size=V) * 4
+    ids, lp = O.candidate_logprobs(z, V)
+    assert sorted(ids) == list(range(V)) and np.all(np.diff(lp) <= 0)
+    assert abs(np.sum(np.exp(lp)) - 1.0) < 1e-13                   # the whole vocabulary: a distribution
+    ids7, lp7 = O.candidate_logprobs(z, 7)
+    assert ids7 == ids[:7] and np.array_equal(lp7, lp[:7])
+    assert np.allclose(lp7, log_softmax(z)[ids7], atol=1e-13)      # library routine at the same tokens
+    _, shifted = O.candidate_logprobs(z + 1000.0, 7)               # softmax ignores a common shift
+    assert np.allclose(shifted, lp7, atol=1e-10)
+    two = np.array([0.0, math.log(3.0)])                           # probabilities 1/4 and 3/4
+    ids, lp = O.candidate_logprobs(two, 2)
+    assert ids == [1, 0] and np.allclose(np.exp(lp), [0.75, 0.25], atol=1e-15)
+
+
+def _all_nodes(k, b):
+    import itertools
+    return [p for e in range(1, k + 1) for p in itertools.product(range(b), repeat=e)]
+
+
+@pytest.mark.parametrize("k,b,sizes", [(2, 2, range(1, 8)), (2, 3, range(1, 8)), (3, 2, range(1, 8)), (3, 3, range(1, 6))])
+def test_dynamic_tree_is_the_best_tree_of_its_size(k, b, sizes):
+    """Exhaustive search: among all parent-closed node sets of the same size none is reached more often."""
+    import itertools
+    rng = np.random.default_rng(100 * k + b)
+    for trial in range(3):
+        lp = np.stack([O.candidate_logprobs(rng.normal(size=3 * b + trial) * 2, b)[1] for _ in range(k)])
+        nodes = _all_nodes(k, b)
+        reach = {p: math.exp(sum(lp[e, r] for e, r in enumerate(p))) for p in nodes}
+        for T in sizes:
+            parent, rank = O.dynamic_tree(lp, T)
+            assert len(parent) == T and parent[0] == -1
+            assert all(0 <= parent[v] < v for v in range(1, T))
+            paths = [()]
+            for v in range(1, T):
+                paths.append(paths[parent[v]] + (rank[v],))
+            assert len(set(paths)) == T                            # distinct nodes
+            got = sum(reach[p] for p in paths[1:])
+            best = 0.0
+            for pick in itertools.combinations(nodes, T - 1):
+                chosen = set(pick)
+                if all(len(p) == 1 or p[:-1] in chosen for p in pick):
+                    best = max(best, sum(reach[p] for p in pick))
+            assert abs(got - best) <= 1e-12 * max(best, 1.0), (k, b, T, got, best)
+
+
+def test_dynamic_tree_order_on_ties_and_degenerate_distributions():
+    flat = np.full((2, 2), -1.0)                                   # all equal: level by level, paths in order
+    assert O.dynamic_tree(flat, 7) == ([-1, 0, 0, 1, 1, 2, 2], [0, 0, 1, 0, 1, 0, 1])
+    assert O.dynamic_tree(flat, 4) == ([-1, 0, 0, 1], [0, 0, 1, 0])
+    assert O.dynamic_tree(flat, 1) == ([-1], [0])
+    sure = np.array([[0.0, -np.inf, -np.inf]] * 3)                 # one certain token per position: the chain first,
+    parent, rank = O.dynamic_tree(sure, 7)                         # then impossible nodes by depth and path
+    assert parent == [-1, 0, 1, 2, 0, 0, 1] and rank == [0, 0, 0, 0, 1, 2, 1]
+    nan = np.array([[-0.1, np.nan], [-0.2, -0.3]])                 # NaN counts as -inf
+    assert O.dynamic_tree(nan, 5) == ([-1, 0, 1, 1, 0], [0, 0, 0, 1, 1])
+    with pytest.raises(ValueError):
+        O.dynamic_tree(flat, 8)                                    # 2 + 4 nodes below the root at most
+    # a strictly better second level beats a worse first-level sibling: depth is only a tie-break
+    lp = np.log(np.array([[0.9, 0.05], [0.8, 0.1]]))
+    assert O.dynamic_tree(lp, 4) == ([-1, 0, 1, 1], [0, 0, 0, 1])  # 0.9, 0.72, 0.09 before 0.05
+
+
+def test_dynamic_tree_decides_in_the_precision_of_its_input():
+    c = -(0.5 - 2.0 ** -25)                                        # -0.5 + c = -(1 - 2^-25): rounds to -1 in float32
+    lp32 = np.array([[-0.5, -1.0], [c, -10.0]], dtype=np.float32)
+    assert float(lp32[1, 0]) == c
+    assert O.dynamic_tree(lp32, 3) == ([-1, 0, 0], [0, 0, 1])      # float32: a tie, the shallower node first
+    assert O.dynamic_tree(lp32.astype(np.float64), 3) == ([-1, 0, 1], [0, 0, 0])   # float64: the child is ahead
+
+
+def test_oracle_step_with_a_dynamic_tree_stays_lossless():
+    """Whatever tree a step picks, the emitted tokens are the greedy continuation (Sec. 4.1)."""
+    wl = small_workload(k=2, transfer_layers=(1, 1), max_cache=64)
+    model = oracle_model(wl)
+    dec = O.HiddenTransferOracle(model, [-1], [0], wl.max_cache)
+    prompt = [int(t) for t in counter_tokens(wl.seed, 1, wl.prompt_len, wl.vocab)]
+    dec.prefill(prompt)
+    out, shapes = [], set()
+    for _ in range(6):
+        res = dec.step(dynamic=(6, 3))
+        assert len(dec.parent) == 6
+        shapes.add(tuple(dec.parent))
+        out += res["emitted"]
+    want = model.ar_greedy(prompt, len(out))
+    assert out == want[:len(out)]
+    assert len(shapes) > 1                                         # the tree really changes between steps
