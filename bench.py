@@ -308,6 +308,11 @@ def main():
     model.ht_decode_steps(loop_steps)
     torch.cuda.synchronize()
     ms_step_loop = (time.perf_counter() - t0) * 1e3 / loop_steps
+    # the same schedule with the tree chosen anew at every step among the best candidates of every pseudo position
+    dyn_b = wl.branching[0]
+    model.ht_set_dynamic_tree(T, dyn_b)
+    ms_step_dynamic, _ = timed_steps()
+    model.ht_set_tree(parent, rank)
     chain, cur = [0], 0
     while True:
         kids = [v for v in range(T) if parent[v] == cur and rank[v] == 0]
@@ -453,6 +458,7 @@ def main():
                                f"pseudo rows of the rank-0 chain riding in the verify pass"},
         "step_ms_draft_after_accept": round(ms_step_s1, 4),
         "step_ms_draft_after_accept_device_resident_loop": round(ms_step_loop, 4),
+        "step_ms_draft_after_accept_dynamic_tree": {"ms": round(ms_step_dynamic, 4), "candidates_per_position": dyn_b},
         "verify_pass_ms": round(ms_verify, 4), "one_token_step_ms": round(ms_one, 4),
         "verify_over_one_token": round(ms_verify / ms_one, 4),
         "graph_launch_median": None if ms_verify_graph is None else {

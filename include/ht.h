@@ -99,6 +99,20 @@ int ht_free_model(ht_model *m);
  * before return.  HT_ETREE if malformed. */
 int ht_set_tree(ht_model *m, int32_t T, const int32_t *parent /*host*/, const int32_t *rank /*host*/, void *stream);
 
+/* A tree chosen anew at every step instead of a fixed one.  The paper decodes with a pre-defined tree (Sec. 3.4.1)
+ * and names the tree's structure as what the speed hangs on (Limitation section); this rule is the library's own.
+ * After every draft the b best candidates of each of the k pseudo positions get their log-probability (log-softmax
+ * over the whole vocabulary, float32).  A node that picks ranks r_1 .. r_e along its path scores
+ * lp[1][r_1] + .. + lp[e][r_e], added in float32 from the root down (NaN counts as -inf): the draws of the k
+ * positions do not depend on one another (Sec. 3.2), so exp(score) is how likely a greedy verification reaches the
+ * node if the drafts were exact.  The tree is the root plus the T - 1 nodes that come first in the order (score
+ * descending, depth ascending, rank path ascending), numbered in that order; it is closed under taking parents.
+ * From this call on `ht_tree_verify_step(tree_tokens = NULL)` and `ht_decode_steps` build it on the device before
+ * each verify pass (views HT_BUF_TREE_PARENT, HT_BUF_TREE_RANK, HT_BUF_CANDIDATE_LOGPROBS show the last one);
+ * forced tree tokens and `ht_set_fused_nodes` are HT_ESTATE in this mode; `ht_set_tree` returns to a fixed tree.
+ * HT_ETREE unless 1 <= T <= max_tree, 1 <= b <= HT_MAX_TOPK and T - 1 <= b + b^2 + .. + b^k. */
+int ht_set_dynamic_tree(ht_model *m, int32_t T, int32_t b, void *stream);
+
 /* Draft inside the verify pass (Fig. 2 caption and the end of Sec. 3.4: one forward verifies the current
  * candidates and produces the next ones; Sec. 5 names the price, a longer input sequence).  Every listed
  * tree node v gets k pseudo rows: when the pass reaches the transfer layer, row (v, i) = W_i applied to v's
@@ -179,7 +193,9 @@ enum { HT_BUF_DRAFT_LOGITS = 0 /* float [k, vocab] */, HT_BUF_CANDIDATES = 1 /* 
        HT_BUF_PSEUDO = 7 /* float [k, d] */, HT_BUF_ROOT = 8 /* int32 [1] pending root token */,
        HT_BUF_FUSED_DRAFT_LOGITS = 9 /* float [fused nodes * k, vocab] of the last verify pass, rows in the order
                                         they joined it: slot by slot, node by node, step by step */,
-       HT_BUF_FUSED_CANDIDATES = 10 /* int32 [fused nodes, k, HT_MAX_TOPK] */ };
+       HT_BUF_FUSED_CANDIDATES = 10 /* int32 [fused nodes, k, HT_MAX_TOPK] */,
+       HT_BUF_CANDIDATE_LOGPROBS = 11 /* float [k, HT_MAX_TOPK], dynamic tree only: entries 0..b-1 of every row */,
+       HT_BUF_TREE_PARENT = 12 /* int32 [T] */, HT_BUF_TREE_RANK = 13 /* int32 [T] */ };
 int ht_get_buffer(const ht_model *m, int32_t which, int32_t layer, void **dev_ptr, size_t *bytes);
 
 /* ---- op-level entry points (same kernels as the model path) -------------------------------------- */
@@ -220,6 +236,18 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
  *                           act_out[M, f] (bf16) = silu(a . w_gate^T) * (a . w_up^T), a bf16 [M, K], fp32 sums.
  *                           The largest projection of a decoder block, hence the kernel bench.py takes the
  *                           roofline of.  HT_EINVAL on NULL pointers, M outside 1..HT_MAX_TREE or bad f, K. */
+/* The two steps of `ht_set_dynamic_tree`'s rule on their own (all pointers DEVICE).
+ * ht_candidate_logprobs: d [rows, V] float32 logits, cand [rows, HT_MAX_TOPK] token ids of which the first b per row
+ *   are read; lp [rows, HT_MAX_TOPK]: lp[i][r] = d[i][cand[i][r]] - log(sum_v exp d[i][v]) for r < b.
+ *   HT_EINVAL unless 1 <= rows <= HT_MAX_TREE, 1 <= b <= HT_MAX_TOPK, V >= 1.
+ * ht_dynamic_tree: lp, cand [k, HT_MAX_TOPK] (first b per row read), root [1]; writes parent, depth, rank [T],
+ *   anc [T, HT_MAX_TREE / 64] (bit u of row v: u is v or an ancestor of v) and tokens [T] (the root token, then
+ *   cand[depth - 1][rank] of every node).  HT_EINVAL / HT_ETREE as for `ht_set_dynamic_tree`. */
+int ht_candidate_logprobs(const float *d, const int32_t *cand, int32_t rows, int32_t b, int32_t V, float *lp,
+                          void *stream);
+int ht_dynamic_tree(const float *lp, const int32_t *cand, const int32_t *root, int32_t k, int32_t b, int32_t T,
+                    int32_t *parent, int32_t *depth, int32_t *rank, uint64_t *anc, int32_t *tokens, void *stream);
+
 int32_t ht_padded_rows(int32_t M);
 size_t ht_weight_pack_bytes(int32_t N, int32_t K);
 int ht_weight_pack(const void *w, int32_t N, int32_t K, void *packed, void *stream);

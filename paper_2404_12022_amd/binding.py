@@ -18,7 +18,7 @@ HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_TOPK = 8, 128, 64
 HT_MAX_LOOP_STEPS = 64
 (HT_BUF_DRAFT_LOGITS, HT_BUF_CANDIDATES, HT_BUF_TREE_TOKENS, HT_BUF_SAVED_HIDDEN, HT_BUF_TRANSFER_SRC,
  HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT, HT_BUF_FUSED_DRAFT_LOGITS,
- HT_BUF_FUSED_CANDIDATES) = range(11)
+ HT_BUF_FUSED_CANDIDATES, HT_BUF_CANDIDATE_LOGPROBS, HT_BUF_TREE_PARENT, HT_BUF_TREE_RANK) = range(14)
 
 EXPORTS = [
     "ht_workspace_bytes", "ht_init_model", "ht_free_model", "ht_set_tree", "ht_prefill", "ht_transfer",
@@ -26,7 +26,7 @@ EXPORTS = [
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
     "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
-    "ht_gate_up_pack", "ht_gate_up_silu_packed",
+    "ht_gate_up_pack", "ht_gate_up_silu_packed", "ht_set_dynamic_tree", "ht_candidate_logprobs", "ht_dynamic_tree",
 ]
 
 
@@ -67,6 +67,9 @@ def _load() -> C.CDLL:
         "ht_free_model": (C.c_int, [vp]),
         "ht_set_tree": (C.c_int, [vp, C.c_int32, i32p, i32p, vp]),
         "ht_set_fused_nodes": (C.c_int, [vp, C.c_int32, i32p, vp]),
+        "ht_set_dynamic_tree": (C.c_int, [vp, C.c_int32, C.c_int32, vp]),
+        "ht_candidate_logprobs": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
+        "ht_dynamic_tree": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp]),
         "ht_stream_read_probe": (C.c_int, [vp, sz, vp, C.POINTER(sz), vp]),
         "ht_prefill": (C.c_int, [vp, i32p, C.c_int32, vp]),
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
@@ -175,6 +178,18 @@ def ht_gate_up_silu_packed(a, packed, M, f, K, act_out, stream=None) -> None:
     _check(lib.ht_gate_up_silu_packed(_ptr(a), _ptr(packed), M, f, K, _ptr(act_out), _stream_ptr(stream)))
 
 
+def ht_candidate_logprobs(d, cand, b, lp, stream=None) -> None:
+    """d [rows, V] float32, cand [rows, HT_MAX_TOPK] int32, lp [rows, HT_MAX_TOPK] float32 (device tensors)."""
+    _check(lib.ht_candidate_logprobs(_ptr(d), _ptr(cand), d.shape[0], b, d.shape[1], _ptr(lp), _stream_ptr(stream)))
+
+
+def ht_dynamic_tree(lp, cand, root, k, b, T, parent, depth, rank, anc, tokens, stream=None) -> None:
+    """All arguments but k, b, T are device tensors: lp, cand [k, HT_MAX_TOPK], root [1]; outputs parent, depth, rank,
+    tokens [T] int32 and anc [T, HT_MAX_TREE // 64] int64."""
+    _check(lib.ht_dynamic_tree(_ptr(lp), _ptr(cand), _ptr(root), k, b, T, _ptr(parent), _ptr(depth), _ptr(rank),
+                               _ptr(anc), _ptr(tokens), _stream_ptr(stream)))
+
+
 def ht_stream_read_probe(buf, sink, stream=None) -> int:
     """One streaming pass over the tensor `buf`; returns the bytes read."""
     got = C.c_size_t(0)
@@ -249,6 +264,11 @@ class HTModel:
     def ht_set_tree(self, parent: Sequence[int], rank: Sequence[int], stream=None) -> None:
         _check(lib.ht_set_tree(self.handle, len(parent), _i32(parent), _i32(rank), _stream_ptr(stream)))
         self.T = len(parent)
+        self.fused = []
+
+    def ht_set_dynamic_tree(self, T: int, b: int, stream=None) -> None:
+        _check(lib.ht_set_dynamic_tree(self.handle, T, b, _stream_ptr(stream)))
+        self.T = T
         self.fused = []
 
     def ht_set_fused_nodes(self, nodes: Sequence[int], stream=None) -> None:
@@ -329,7 +349,9 @@ class HTModel:
             return raw.view(torch.float32).view(-1, c.vocab)
         if which == HT_BUF_FUSED_CANDIDATES:
             return raw.view(torch.int32).view(-1, c.k, HT_MAX_TOPK)
-        if which in (HT_BUF_TREE_TOKENS, HT_BUF_ROOT):
+        if which == HT_BUF_CANDIDATE_LOGPROBS:
+            return raw.view(torch.float32).view(c.k, HT_MAX_TOPK)
+        if which in (HT_BUF_TREE_TOKENS, HT_BUF_ROOT, HT_BUF_TREE_PARENT, HT_BUF_TREE_RANK):
             return raw.view(torch.int32)
         if which == HT_BUF_SAVED_HIDDEN:
             return raw.view(torch.float32).view(-1, c.d_model)

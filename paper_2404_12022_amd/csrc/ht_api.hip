@@ -53,6 +53,7 @@ struct TreeTables {
   int32_t *parent, *depth, *rank;
   uint64_t* anc;
   TreeDev dev() const { return TreeDev{parent, depth, rank, anc}; }
+  TreeOut out() const { return TreeOut{parent, depth, rank, anc}; }
 };
 
 struct Buffers {
@@ -71,6 +72,7 @@ struct Buffers {
   float* pseudo;       // [k, d]
   float* cs;           // rotary table [Mp, hd/2] (cos, sin)
   float* ss;           // packed path: sums of squares of the rows of u, kNormParts parts per row [Mp][kNormParts]
+  float* lp;           // log-probabilities of the candidates of the last draft [kMaxTransfer][kMaxTopK] (dynamic tree)
   int32_t *tok, *g, *cand, *width, *prompt;
   int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
   int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
@@ -114,6 +116,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.pseudo = cv.take<float>((size_t)c.k * d);
   b.cs = cv.take<float>(Mp * c.head_dim);
   b.ss = cv.take<float>(Mp * kNormParts);
+  b.lp = cv.take<float>((size_t)kMaxTransfer * kMaxTopK);
   b.tok = cv.take<int32_t>(Mp);
   b.g = cv.take<int32_t>(Mp);
   b.cand = cv.take<int32_t>((size_t)kMaxTransfer * kMaxTopK);
@@ -204,6 +207,7 @@ struct ht_model {
   std::vector<int> slot_layer, slot_first, slot_count, slot_of_layer;
   std::vector<int32_t> fused;   // tree nodes with pseudo rows in the verify pass (empty: draft after accept only)
   int drafts_of = -1;           // index into `fused` of the node the last acceptance ended on, -1 if none
+  int dyn_b = 0;                // > 0: every drafting step chooses its own tree among the dyn_b best candidates per level
   // pinned host staging
   int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
   StepState* h_state = nullptr;
@@ -399,6 +403,20 @@ int validate_tree(int T, const int32_t* parent, const int32_t* rank, int max_dep
   return HT_OK;
 }
 
+// Tokens of the tree from the candidates of the last draft: into the fixed tree, or (ht_set_dynamic_tree) into the
+// tree this step chooses from the candidates' log-probabilities, which also rewrites the tree tables.
+int build_tree(ht_model* m, hipStream_t s) {
+  Buffers& b = m->b;
+  const ht_config& c = m->cfg;
+  if (!m->dyn_b) {
+    HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, m->T, s));
+    return HT_OK;
+  }
+  HT_HIP(launch_cand_logprob(b.dlogits, b.cand, c.k, m->dyn_b, c.vocab, b.lp, s));
+  HT_HIP(launch_tree_dynamic(&b.state->root, b.cand, b.lp, c.k, m->dyn_b, m->T, b.tree.out(), b.tok, s));
+  return HT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -576,6 +594,41 @@ int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* ra
   m->rank.assign(rank, rank + T);
   m->fused.clear();
   m->drafts_of = -1;
+  m->dyn_b = 0;
+  m->T = T;
+  m->has_tree = true;
+  m->verify_done = false;
+  return HT_OK;
+}
+
+int ht_set_dynamic_tree(ht_model* m, int32_t T, int32_t b, void* stream) {
+  if (!m) return fail(HT_EINVAL, "model is NULL");
+  const ht_config& c = m->cfg;
+  if (T < 1 || T > c.max_tree || T > kMaxTree) return fail(HT_ETREE, "tree size %d outside 1..%d", T, c.max_tree);
+  if (b < 1 || b > kMaxTopK) return fail(HT_ETREE, "%d candidates per level outside 1..%d", b, kMaxTopK);
+  long long room = 0, level = 1;                       // nodes below the root of the complete tree, capped
+  for (int e = 0; e < c.k && room < kMaxTree; ++e) {
+    level = level * b > kMaxTree ? kMaxTree : level * b;
+    room += level;
+  }
+  if (T - 1 > room) return fail(HT_ETREE, "%d levels of %d candidates hold %lld nodes, fewer than the %d asked for", c.k, b, room, T - 1);
+  hipStream_t s = (hipStream_t)stream;
+  HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
+  // until the first step has chosen a tree the tables hold the root alone
+  const int32_t root_parent = -1, root_rank = 0;
+  fill_tables(1, &root_parent, &root_rank, m->h_stage);
+  int32_t* width = m->h_stage + kTableInts;
+  for (int e = 0; e < kMaxTransfer + 2; ++e) width[e] = e >= 1 && e <= c.k ? b : 0;
+  int rc;
+  if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
+  HT_HIP(hipMemcpyAsync(m->b.width, width, sizeof(int32_t) * (kMaxTransfer + 2), hipMemcpyHostToDevice, s));
+  HT_HIP(hipStreamSynchronize(s));
+  m->depth.clear();
+  m->parent.clear();
+  m->rank.clear();
+  m->fused.clear();
+  m->drafts_of = -1;
+  m->dyn_b = b;
   m->T = T;
   m->has_tree = true;
   m->verify_done = false;
@@ -586,6 +639,7 @@ int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* s
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
   if (count < 0 || (count > 0 && !nodes)) return fail(HT_EINVAL, "bad node list");
+  if (m->dyn_b && count) return fail(HT_ESTATE, "a tree chosen anew at every step has no fixed nodes to draft from");
   const ht_config& c = m->cfg;
   const int T = m->T, rows = T + count * c.k;
   if (rows > c.max_tree || rows > kMaxTree)
@@ -687,6 +741,7 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
   if (!m->has_prefill) return fail(HT_ESTATE, "empty cache: call ht_prefill first");
   if (!tree_tokens && !m->transfer_ready && m->drafts_of < 0)
     return fail(HT_ESTATE, "drafting needs a preceding ht_transfer");
+  if (tree_tokens && m->dyn_b) return fail(HT_ESTATE, "a dynamic tree is drafted by the step itself: forced tokens need ht_set_tree");
   const ht_config& c = m->cfg;
   const int T = m->T, fused = (int)m->fused.size(), Mall = T + fused * c.k;
   const int rows = Mall > c.k ? Mall : c.k;
@@ -705,7 +760,7 @@ int ht_tree_verify_step(ht_model* m, const int32_t* tree_tokens, int32_t* argmax
     // slots n.. and are overwritten by the verify pass below
     if ((rc = run_pass(m, b.chain.dev(), 0, c.transfer_layer[0], false, b.dlogits, nullptr, s, kFromBuffer))) return rc;
     HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, nullptr, c.vocab, s));
-    HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
+    if ((rc = build_tree(m, s))) return rc;
   }
   HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
   if (!fused) {
@@ -793,7 +848,7 @@ int ht_decode_steps(ht_model* m, int32_t steps, int32_t* n_accepted, int32_t* ac
                              c.d_model, s));
     if ((rc = run_pass(m, b.chain.dev(), 0, c.transfer_layer[0], false, b.dlogits, nullptr, s, kFromBuffer))) return rc;
     HT_HIP(launch_topk(b.dlogits, b.cand, b.width, b.topk_scratch, c.k, c.k, nullptr, c.vocab, s));
-    HT_HIP(launch_tree_build(b.state, b.cand, b.tree.dev(), b.tok, T, s));
+    if ((rc = build_tree(m, s))) return rc;
     HT_HIP(launch_embed(c.dtype, m->tok_emb, b.tok, b.x, T, c.d_model, s));
     if ((rc = run_pass(m, b.tree.dev(), T, 0, true, b.logits, b.g, s))) return rc;
     HT_HIP(launch_accept(b.state, b.tree.dev(), b.tok, b.g, T, s, b.log));
@@ -847,6 +902,9 @@ int ht_get_buffer(const ht_model* m, int32_t which, int32_t layer, void** dev_pt
       sz = sizeof(float) * m->fused.size() * c.k * c.vocab;
       break;
     case HT_BUF_FUSED_CANDIDATES: p = m->b.cand_fused; sz = sizeof(int32_t) * m->fused.size() * c.k * kMaxTopK; break;
+    case HT_BUF_CANDIDATE_LOGPROBS: p = m->b.lp; sz = sizeof(float) * c.k * kMaxTopK; break;
+    case HT_BUF_TREE_PARENT: p = m->b.tree.parent; sz = sizeof(int32_t) * m->T; break;
+    case HT_BUF_TREE_RANK: p = m->b.tree.rank; sz = sizeof(int32_t) * m->T; break;
     case HT_BUF_K_CACHE:
     case HT_BUF_V_CACHE:
       if (layer < 0 || layer >= c.n_layers) return fail(HT_EINVAL, "layer %d out of range", layer);
@@ -1016,6 +1074,29 @@ int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K
     return ht_skinny_gemm_packed(a, scratch, M, N, K, out, (char*)scratch + pb, scratch_bytes - pb, stream);
   }
   HT_HIP(launch_gemm_simple(dtype, a, segs1(w, N), M, N, K, out, s));
+  return HT_OK;
+}
+
+int ht_candidate_logprobs(const float* d, const int32_t* cand, int32_t rows, int32_t b, int32_t V, float* lp, void* stream) {
+  if (!d || !cand || !lp) return fail(HT_EINVAL, "NULL argument");
+  if (rows < 1 || rows > kMaxTree || b < 1 || b > kMaxTopK || V < 1) return fail(HT_EINVAL, "bad shape rows=%d b=%d V=%d", rows, b, V);
+  HT_HIP(launch_cand_logprob(d, cand, rows, b, V, lp, (hipStream_t)stream));
+  return HT_OK;
+}
+
+int ht_dynamic_tree(const float* lp, const int32_t* cand, const int32_t* root, int32_t k, int32_t b, int32_t T,
+                    int32_t* parent, int32_t* depth, int32_t* rank, uint64_t* anc, int32_t* tokens, void* stream) {
+  if (!lp || !cand || !root || !parent || !depth || !rank || !anc || !tokens) return fail(HT_EINVAL, "NULL argument");
+  if (k < 1 || k > kMaxTransfer) return fail(HT_EINVAL, "k = %d outside 1..%d", k, kMaxTransfer);
+  if (T < 1 || T > kMaxTree) return fail(HT_ETREE, "tree size %d outside 1..%d", T, kMaxTree);
+  if (b < 1 || b > kMaxTopK) return fail(HT_ETREE, "%d candidates per level outside 1..%d", b, kMaxTopK);
+  long long room = 0, level = 1;
+  for (int e = 0; e < k && room < kMaxTree; ++e) {
+    level = level * b > kMaxTree ? kMaxTree : level * b;
+    room += level;
+  }
+  if (T - 1 > room) return fail(HT_ETREE, "%d levels of %d candidates hold %lld nodes, fewer than the %d asked for", k, b, room, T - 1);
+  HT_HIP(launch_tree_dynamic(root, cand, lp, k, b, T, TreeOut{parent, depth, rank, anc}, tokens, (hipStream_t)stream));
   return HT_OK;
 }
 

@@ -132,6 +132,17 @@ size_t topk_scratch_bytes(int rows);
 hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
                        const int32_t* src_row, int V, hipStream_t s);
 hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
+// Tree chosen from the draft distributions: lp[k][kMaxTopK] = log-probabilities of the b best candidates of every
+// draft row (whole-row log-softmax); then the T - 1 best nodes by (summed lp desc, depth asc, rank path asc) fill
+// the tree tables and the token row.  T <= kMaxTree, 1 <= b <= kMaxTopK, 1 <= k <= kMaxTransfer and
+// T - 1 <= b + b^2 + .. + b^k are the caller's to check.
+struct TreeOut {
+  int32_t *parent, *depth, *rank;
+  uint64_t* anc;
+};
+hipError_t launch_cand_logprob(const float* d, const int32_t* cand, int rows, int b, int V, float* lp, hipStream_t s);
+hipError_t launch_tree_dynamic(const int32_t* root /*device*/, const int32_t* cand, const float* lp, int k, int b, int T,
+                               TreeOut tree, int32_t* tok, hipStream_t s);
 // log != NULL (device-resident loop): the step is appended to log[st->log_count++] and st->n_old / st->n advance
 hipError_t launch_accept(StepState* st, TreeDev tree, const int32_t* tok, const int32_t* g, int T, hipStream_t s,
                          StepLog* log = nullptr);

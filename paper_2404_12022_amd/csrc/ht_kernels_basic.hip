@@ -519,6 +519,160 @@ hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev t
   return hipGetLastError();
 }
 
+// ---- tree chosen from the draft distributions
+// lp[i][r] = log-softmax value of candidate r of draft row i:  z - (max + log(sum exp(z - max))) over the whole row.
+// One block of 1024 threads per row; 16-byte loads when the row allows.
+__global__ __launch_bounds__(1024) void cand_logprob_kernel(const float* __restrict__ d, const int32_t* __restrict__ cand,
+                                                            int b, int V, int vec, float* __restrict__ lp) {
+  __shared__ float red[16];
+  const float* row = d + (size_t)blockIdx.x * V;
+  const int v4 = vec ? (V & ~3) : 0;
+  float peak = -INFINITY;
+  for (int j = threadIdx.x * 4; j < v4; j += blockDim.x * 4) {
+    const float4 q = *(const float4*)(row + j);
+    peak = fmaxf(fmaxf(peak, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
+  }
+  for (int j = v4 + threadIdx.x; j < V; j += blockDim.x) peak = fmaxf(peak, row[j]);
+  peak = wave_max(peak);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = peak;
+  __syncthreads();
+  peak = red[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) peak = fmaxf(peak, red[w]);
+  float sum = 0.f;
+  for (int j = threadIdx.x * 4; j < v4; j += blockDim.x * 4) {      // second pass: the row is in L2 now
+    const float4 q = *(const float4*)(row + j);
+    sum += (expf(q.x - peak) + expf(q.y - peak)) + (expf(q.z - peak) + expf(q.w - peak));
+  }
+  for (int j = v4 + threadIdx.x; j < V; j += blockDim.x) sum += expf(row[j] - peak);
+  sum = block_sum_any(sum, red);
+  const float lse = peak + logf(sum);
+  if ((int)threadIdx.x < b) lp[blockIdx.x * kMaxTopK + threadIdx.x] = row[cand[blockIdx.x * kMaxTopK + threadIdx.x]] - lse;
+}
+hipError_t launch_cand_logprob(const float* d, const int32_t* cand, int rows, int b, int V, float* lp, hipStream_t s) {
+  const int vec = !((uintptr_t)d & 15) && !(V & 3);
+  hipLaunchKernelGGL(cand_logprob_kernel, dim3(rows), dim3(1024), 0, s, d, cand, b, V, vec, lp);
+  return hipGetLastError();
+}
+
+// The T - 1 best nodes of the complete b-ary candidate tree of depth k in the order (score descending, depth
+// ascending, rank path ascending), score = sum of lp along the path accumulated in float from the root down.
+// A node never scores above its parent or its previous sibling, and each of the two comes first in that order, so
+// the order is produced by a best-first walk: the frontier holds, for every node taken so far, its next sibling
+// and (once) its first child; the best frontier entry becomes the next node.  The frontier never holds more than
+// T <= 128 entries: slot j lives in the registers of lane j % 64 (two slots per lane), a round is one wave-wide
+// maximum of the lanes' best scores, a ballot that names the winner (a second reduction over depth and path only
+// when several lanes hold the best score), and register updates in two lanes: no barrier and no memory traffic
+// inside the walk but the log-probability table in LDS.  Tables and tokens are written by all lanes at the end.
+__device__ inline float not_nan(float v) { return v == v ? v : -INFINITY; }
+
+__device__ inline float wave_max_dpp(float x) {
+  // quads, half rows and rows by data-parallel-primitive moves, then rows and halves of the wave by lane swaps
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true)));    // lanes 1 0 3 2
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true)));    // lanes 2 3 0 1
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true)));   // half row mirrored
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true)));   // row mirrored
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  u = __float_as_uint(x);
+  auto r2 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r2[0]), __uint_as_float(r2[1]));
+}
+
+// (depth, path) order of two frontier entries with equal scores
+__device__ inline bool tie_first(int depth_a, uint64_t path_a, int depth_b, uint64_t path_b) {
+  return depth_a != depth_b ? depth_a < depth_b : path_a < path_b;
+}
+
+__global__ __launch_bounds__(64) void tree_dynamic_kernel(const int32_t* __restrict__ root, const int32_t* __restrict__ cand,
+                                                          const float* __restrict__ lp, int k, int b, int T,
+                                                          TreeOut tree, int32_t* __restrict__ tok) {
+  __shared__ float lp_s[kMaxTransfer * kMaxTopK];
+  __shared__ int cand_s[kMaxTransfer * kMaxTopK];
+  __shared__ int n_parent[kMaxTree], n_depth[kMaxTree], n_rank[kMaxTree];
+  const int lane = threadIdx.x;
+  for (int i = lane; i < k * kMaxTopK; i += 64) {
+    const bool used = i % kMaxTopK < b;
+    lp_s[i] = used ? not_nan(lp[i]) : -INFINITY;
+    cand_s[i] = used ? cand[i] : 0;
+  }
+  for (int v = lane; v < kMaxTree; v += 64) {      // rows the walk does not reach (none, if the sizes were checked) hang under the root
+    n_parent[v] = v ? 0 : -1;
+    n_depth[v] = v ? 1 : 0;
+    n_rank[v] = 0;
+  }
+  __syncthreads();
+  // frontier slot: score, score of the parent, depth (0: empty), parent node, path = ranks from the root down, 6 bits
+  // each, the last rank in the lowest digit
+  float fs0 = -INFINITY, fs1 = -INFINITY, fb0 = 0.f, fb1 = 0.f;
+  int fd0 = 0, fd1 = 0, fp0 = 0, fp1 = 0;
+  uint64_t fq0 = 0, fq1 = 0;
+  if (lane == 0) { fs0 = lp_s[0]; fd0 = 1; }      // first candidate of the first level, under the root
+  int count = 1;
+  for (int v = 1; v < T; ++v) {
+    const bool second = fd1 != 0 && (fd0 == 0 || fs1 > fs0 || (fs1 == fs0 && tie_first(fd1, fq1, fd0, fq0)));
+    const float s = second ? fs1 : fs0;
+    const int d = second ? fd1 : fd0;
+    const uint64_t q = second ? fq1 : fq0;
+    const int par_l = second ? fp1 : fp0;
+    const float best = wave_max_dpp(d ? s : -INFINITY);
+    const bool top = d != 0 && s == best;
+    uint64_t tied = __ballot(top);
+    if (tied == 0) break;                          // frontier exhausted: uniform
+    if (tied & (tied - 1)) {                       // several lanes hold the best score: depth, then path decide
+      uint64_t key = top ? ((uint64_t)d << 48 | q) : ~0ull;
+      uint64_t low = key;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t other = __shfl_xor((unsigned long long)low, o, 64);
+        low = other < low ? other : low;
+      }
+      tied = __ballot(key == low);
+    }
+    const int win = __builtin_amdgcn_readfirstlane(__builtin_ctzll(tied));
+    const int depth = __builtin_amdgcn_readlane(d, win);
+    const int par = __builtin_amdgcn_readlane(par_l, win);
+    const float score = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), win));
+    const uint64_t path = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(q >> 32), win) << 32 |
+                          (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)q, win);
+    const int r = (int)(path & 63);
+    if (lane == 0) { n_parent[v] = par; n_depth[v] = depth; n_rank[v] = r; }
+    if (lane == win) {                             // the next sibling takes the slot over
+      const bool more = r + 1 < b;
+      const float sib = more ? lp_s[(depth - 1) * kMaxTopK + r + 1] : 0.f;
+      if (second) { fs1 = fb1 + sib; fq1 += 1; fd1 = more ? fd1 : 0; }
+      else { fs0 = fb0 + sib; fq0 += 1; fd0 = more ? fd0 : 0; }
+    }
+    if (depth < k) {                               // the first child goes to a new slot
+      if (lane == (count & 63)) {
+        const float cs = score + lp_s[depth * kMaxTopK];
+        if (count >> 6) { fs1 = cs; fb1 = score; fd1 = depth + 1; fp1 = v; fq1 = path << 6; }
+        else { fs0 = cs; fb0 = score; fd0 = depth + 1; fp0 = v; fq0 = path << 6; }
+      }
+      ++count;
+    }
+  }
+  __syncthreads();
+  for (int v = lane; v < T; v += 64) {
+    const int depth = n_depth[v], r = n_rank[v];
+    tree.parent[v] = n_parent[v];
+    tree.depth[v] = depth;
+    tree.rank[v] = r;
+    tok[v] = v ? cand_s[(depth - 1) * kMaxTopK + r] : *root;
+    uint64_t mask[kMaskWords];
+    for (int w = 0; w < kMaskWords; ++w) mask[w] = 0;
+    for (int u = v, hop = 0; u >= 0 && hop <= kMaxTransfer; u = n_parent[u], ++hop)
+      for (int w = 0; w < kMaskWords; ++w) mask[w] |= w == (u >> 6) ? 1ull << (u & 63) : 0ull;
+    for (int w = 0; w < kMaskWords; ++w) tree.anc[(size_t)v * kMaskWords + w] = mask[w];
+  }
+}
+hipError_t launch_tree_dynamic(const int32_t* root, const int32_t* cand, const float* lp, int k, int b, int T,
+                               TreeOut tree, int32_t* tok, hipStream_t s) {
+  hipLaunchKernelGGL(tree_dynamic_kernel, dim3(1), dim3(64), 0, s, root, cand, lp, k, b, T, tree, tok);
+  return hipGetLastError();
+}
+
 // One wavefront: each round, every lane tests a slice of the nodes for "child of cur carrying the
 // greedy token after cur" and the lowest such node index wins.
 __global__ void accept_kernel(StepState* __restrict__ st, TreeDev tree, const int32_t* __restrict__ tok,

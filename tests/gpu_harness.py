@@ -58,16 +58,21 @@ def cpu(t):
 class StepCompare:
     """Runs oracle and HIP path side by side, one decode step at a time."""
 
-    def __init__(self, wl, tensors_gpu=None, tensors_cpu=None, tree=None, prompt=None, fused=None):
+    def __init__(self, wl, tensors_gpu=None, tensors_cpu=None, tree=None, prompt=None, fused=None, dynamic=None):
         """fused: tree nodes that get pseudo rows inside the verify pass (`ht_set_fused_nodes`).  The oracle keeps
-        drafting after acceptance; the two schedules give the same distributions (a CPU test pins that)."""
+        drafting after acceptance; the two schedules give the same distributions (a CPU test pins that).
+        dynamic = (T, b): every step chooses its tree (`ht_set_dynamic_tree`); use `step_dynamic`."""
         self.wl = wl
         self.model = oracle_model(wl, tensors_cpu)
-        self.parent, self.rank = tree or tree_of(wl)
+        self.dynamic = dynamic
+        self.parent, self.rank = ([-1] + [0] * (dynamic[0] - 1), [0] * dynamic[0]) if dynamic else (tree or tree_of(wl))
         self.ora = O.HiddenTransferOracle(self.model, self.parent, self.rank, wl.max_cache)
         self.fused = list(fused or [])
         self.gpu = gpu_model(wl, tensors_gpu, max_tree=max(len(self.parent) + len(self.fused) * wl.k, 1))
-        self.gpu.ht_set_tree(self.parent, self.rank)
+        if dynamic:
+            self.gpu.ht_set_dynamic_tree(*dynamic)
+        else:
+            self.gpu.ht_set_tree(self.parent, self.rank)
         if self.fused:
             self.gpu.ht_set_fused_nodes(self.fused)
         self.in_pass_drafts = None      # (logits [k, V], candidates) of the node the last acceptance ended on
@@ -166,3 +171,55 @@ class StepCompare:
             assert (path, emitted, root) == (res["path"], res["emitted"], res["root"])
             assert gpu.ht_cache_len() == ora.n
         return dict(oracle=res, emitted=emitted, path=path, root=root, m=m)
+
+    def step_dynamic(self, exact=True):
+        """One step in which the GPU chooses its tree.  Every float stage is compared with the fp64 oracle; every
+        integer stage must be the oracle's rule applied to the GPU's own numbers; the oracle then verifies the
+        GPU's tree.  exact (fp32 model): the oracle's own choices must be the same.  Otherwise (bf16) a choice may
+        differ where the oracle's numbers are closer than the two may differ, and the oracle follows the GPU's."""
+        wl, ora, gpu = self.wl, self.ora, self.gpu
+        T, b = self.dynamic
+        d_o = ora.draft(ora.transfer())
+        root_gpu = int(gpu.ht_get_buffer(B.HT_BUF_ROOT)[0].item())
+        assert root_gpu == ora.root
+        pseudo = torch.empty(wl.k, wl.d_model, dtype=torch.float32, device=DEV)
+        gpu.ht_transfer(None, pseudo)
+        gpu.ht_tree_verify_step(None, self.g_gpu, self.z_gpu)
+        torch.cuda.synchronize()
+        d = cpu(gpu.ht_get_buffer(B.HT_BUF_DRAFT_LOGITS))
+        self.max_err = max(self.max_err, assert_close(d, d_o, wl.dtype, "draft logits"))
+        cand = gpu.ht_get_buffer(B.HT_BUF_CANDIDATES).cpu().numpy()[:, :b]
+        lp = gpu.ht_get_buffer(B.HT_BUF_CANDIDATE_LOGPROBS).cpu().numpy()[:, :b]
+        want_lp = []
+        for e in range(wl.k):
+            ids, vals = O.candidate_logprobs(d[e], b)
+            assert list(cand[e]) == ids, f"top-{b} at depth {e + 1}"
+            want_lp.append(vals)
+        lp_err = float(np.max(np.abs(lp.astype(np.float64) - np.stack(want_lp))))
+        assert lp_err <= 2e-5, f"candidate log-probabilities off by {lp_err:.2e}"
+        parent = [int(x) for x in gpu.ht_get_buffer(B.HT_BUF_TREE_PARENT).cpu()]
+        rank = [int(x) for x in gpu.ht_get_buffer(B.HT_BUF_TREE_RANK).cpu()]
+        assert (parent, rank) == O.dynamic_tree(lp, T), "tree choice from the GPU's own log-probabilities"
+        own = O.dynamic_tree(np.stack([O.candidate_logprobs(d_o[e], b)[1] for e in range(wl.k)]), T)
+        if exact:
+            assert (parent, rank) == own, "tree differs from the fp64 oracle's"
+        ora.set_tree(parent, rank)
+        depth = ora.depth
+        tok_gpu = [int(t) for t in gpu.ht_get_buffer(B.HT_BUF_TREE_TOKENS).cpu()]
+        assert tok_gpu == [root_gpu] + [int(cand[depth[v] - 1][rank[v]]) for v in range(1, T)], "tree tokens"
+        z_o, g_o, saved = ora.verify(tok_gpu)
+        z = cpu(self.z_gpu)
+        self.max_err = max(self.max_err, assert_close(z, z_o, wl.dtype, "verify logits"))
+        g = [int(t) for t in self.g_gpu.cpu()]
+        assert g == [int(j) for j in np.argmax(z, axis=1)], "row arg-max of the GPU's own logits"
+        if exact:
+            assert g == g_o
+        else:
+            for v in range(T):
+                gap, bound = float(z_o[v][g_o[v]] - z_o[v][g[v]]), 2 * BF16_REL_TOL * float(np.max(np.abs(z_o[v])))
+                assert 0 <= gap <= bound, f"node {v}: greedy token {g[v]} vs {g_o[v]}, logit gap {gap:.3e} above {bound:.3e}"
+        m, emitted, root, path = gpu.ht_accept_and_compact()
+        want_path, want_emitted = ora.accept_and_compact(tok_gpu, g, saved)
+        assert (path, emitted, root, m) == (want_path, want_emitted, ora.root, len(want_path))
+        assert gpu.ht_cache_len() == ora.n
+        return dict(parent=parent, rank=rank, emitted=emitted, path=path, root=root, m=m, own_tree=own)
