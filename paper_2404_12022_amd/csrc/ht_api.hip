@@ -403,6 +403,16 @@ int validate_tree(int T, const int32_t* parent, const int32_t* rank, int max_dep
   return HT_OK;
 }
 
+// Nodes below the root of the complete b-ary tree of depth k, counted up to kMaxTree (more never matter).
+int candidate_tree_room(int k, int b) {
+  int room = 0, level = 1;
+  for (int e = 0; e < k && room < kMaxTree; ++e) {
+    level = level * b > kMaxTree ? kMaxTree : level * b;
+    room += level;
+  }
+  return room < kMaxTree ? room : kMaxTree;
+}
+
 // Tokens of the tree from the candidates of the last draft: into the fixed tree, or (ht_set_dynamic_tree) into the
 // tree this step chooses from the candidates' log-probabilities, which also rewrites the tree tables.
 int build_tree(ht_model* m, hipStream_t s) {
@@ -606,12 +616,9 @@ int ht_set_dynamic_tree(ht_model* m, int32_t T, int32_t b, void* stream) {
   const ht_config& c = m->cfg;
   if (T < 1 || T > c.max_tree || T > kMaxTree) return fail(HT_ETREE, "tree size %d outside 1..%d", T, c.max_tree);
   if (b < 1 || b > kMaxTopK) return fail(HT_ETREE, "%d candidates per level outside 1..%d", b, kMaxTopK);
-  long long room = 0, level = 1;                       // nodes below the root of the complete tree, capped
-  for (int e = 0; e < c.k && room < kMaxTree; ++e) {
-    level = level * b > kMaxTree ? kMaxTree : level * b;
-    room += level;
-  }
-  if (T - 1 > room) return fail(HT_ETREE, "%d levels of %d candidates hold %lld nodes, fewer than the %d asked for", c.k, b, room, T - 1);
+  if (T - 1 > candidate_tree_room(c.k, b))
+    return fail(HT_ETREE, "%d levels of %d candidates hold %d nodes, fewer than the %d asked for", c.k, b,
+                candidate_tree_room(c.k, b), T - 1);
   hipStream_t s = (hipStream_t)stream;
   HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
   // until the first step has chosen a tree the tables hold the root alone
@@ -1090,12 +1097,9 @@ int ht_dynamic_tree(const float* lp, const int32_t* cand, const int32_t* root, i
   if (k < 1 || k > kMaxTransfer) return fail(HT_EINVAL, "k = %d outside 1..%d", k, kMaxTransfer);
   if (T < 1 || T > kMaxTree) return fail(HT_ETREE, "tree size %d outside 1..%d", T, kMaxTree);
   if (b < 1 || b > kMaxTopK) return fail(HT_ETREE, "%d candidates per level outside 1..%d", b, kMaxTopK);
-  long long room = 0, level = 1;
-  for (int e = 0; e < k && room < kMaxTree; ++e) {
-    level = level * b > kMaxTree ? kMaxTree : level * b;
-    room += level;
-  }
-  if (T - 1 > room) return fail(HT_ETREE, "%d levels of %d candidates hold %lld nodes, fewer than the %d asked for", k, b, room, T - 1);
+  if (T - 1 > candidate_tree_room(k, b))
+    return fail(HT_ETREE, "%d levels of %d candidates hold %d nodes, fewer than the %d asked for", k, b,
+                candidate_tree_room(k, b), T - 1);
   HT_HIP(launch_tree_dynamic(root, cand, lp, k, b, T, TreeOut{parent, depth, rank, anc}, tokens, (hipStream_t)stream));
   return HT_OK;
 }
