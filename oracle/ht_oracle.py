@@ -19,6 +19,10 @@ What is written out here, and the passage each part follows:
   * Greedy verification: last accepted position, next token (Fig. 2 caption; Sec. 3.4).
   * Both inference schedules: "draft after accept" (S1) and the paper's fused
     "verify and draft in the same forward" (S2, Fig. 2 caption / Sec. 3.4 last sentence).
+  * The forward pass of the training stage and its distillation loss for one transfer step
+    (Sec. 3.3: the doubled sequence of hidden and pseudo hidden states, its attention mask and
+    position ids, the KL term per position): `training_forward`.  Forward only; the paper trains
+    the maps with this loss, which needs its dataset and is outside this build.
   * A tree chosen anew at every step from the draft distributions (`candidate_logprobs`,
     `dynamic_tree`).  The paper decodes with a pre-defined tree (Sec. 3.4.1) and names the choice of
     the tree's structure as what the speed depends on and as future work (Limitation section); the
@@ -33,7 +37,9 @@ stream after t complete blocks (t = 0 is the embedding output).
 
 Pins: every function here is pinned by tests/test_oracle_*.py (closed forms, loop-level brute
 force, the causal-path invariant, losslessness against `ar_greedy`, exhaustive acceptance
-search, S1 == S2; the dynamic tree against an exhaustive search over all trees of its size).
+search, S1 == S2; the dynamic tree against an exhaustive search over all trees of its size; the
+training forward row by row against single-row passes over stored keys, and for step 1 against
+the inference-time draft).
 Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -189,6 +195,49 @@ class OracleModel:
             z, _, _, _ = self.causal_forward(seq)
             seq.append(int(np.argmax(z[-1])))
         return seq[len(prompt):]
+
+
+# ------------------------------------------------------------------------------------ training stage (Sec. 3.3)
+def kl_divergence(za: np.ndarray, zb: np.ndarray) -> float:
+    """KL(A || B) = sum_v A_v (log A_v - log B_v) of the softmax distributions of two logit rows."""
+    la = za - np.max(za)
+    la = la - np.log(np.sum(np.exp(la)))
+    lb = zb - np.max(zb)
+    lb = lb - np.log(np.sum(np.exp(lb)))
+    return float(np.sum(np.exp(la) * (la - lb)))
+
+
+def training_forward(model: OracleModel, tokens: Sequence[int], step: int):
+    """Forward pass of the training stage for transfer step `step` (1-based i of Sec. 3.3) over n tokens.
+
+    The tokens run causally up to the transfer layer t_i; every hidden state h_j becomes a pseudo state
+    W_i h_j; the 2n rows (hidden states, then pseudo states) go on through blocks t_i+1..L.  Hidden states
+    attend causally among themselves.  Pseudo state j (0-based; it stands for position j + i) has position
+    id j + i and attends to the hidden states of positions 0 .. j+i-1 and to itself, to no other pseudo
+    state.  All rows pass the original LM head.  The loss adds KL(P~_j || P_{j+i}), the pseudo state's
+    distribution against that of the hidden state it stands for, with the first argument weighting the
+    log ratio, over the paper's index range q = 1 .. n-i-1 (1-based), i.e. j = 0 .. n-i-2.
+    Returns dict(Z[n, V] logits of the hidden states, Zp[n, V] logits of the pseudo states, kl[n-i-1], loss)."""
+    c = model.cfg
+    n, i = len(tokens), step
+    t = c.transfer_layers[i - 1]
+    _, hidden, _, _ = model.causal_forward(tokens)
+    h = hidden[t]
+    x = np.concatenate([h, linear(h, model.w.w_transfer[i - 1])], axis=0)
+    pos = np.concatenate([np.arange(n), np.arange(n) + i])
+    vis = np.zeros((2 * n, 2 * n), dtype=bool)
+    for a in range(n):
+        vis[a, :a + 1] = True                               # hidden state a: positions 0 .. a
+        vis[n + a, :min(a + i, n)] = True                   # pseudo state a: hidden states 0 .. a+i-1
+        vis[n + a, n + a] = True                            # and itself
+    empty = np.zeros((0, c.n_kv_heads, c.head_dim))
+    none_vis = np.zeros((2 * n, 0), dtype=bool)
+    for layer in range(t, c.n_layers):
+        x, _, _ = model.block(layer, x, pos, empty, empty, none_vis, vis)
+    z_all = model.logits(x)
+    z, zp = z_all[:n], z_all[n:]
+    kl = np.array([kl_divergence(zp[j], z[j + i]) for j in range(max(n - i - 1, 0))])
+    return dict(Z=z, Zp=zp, kl=kl, loss=float(np.sum(kl)))
 
 
 # ------------------------------------------------------------------------------------ tree helpers

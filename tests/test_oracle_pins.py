@@ -319,3 +319,60 @@ def test_oracle_step_with_a_dynamic_tree_stays_lossless():
     want = model.ar_greedy(prompt, len(out))
     assert out == want[:len(out)]
     assert len(shapes) > 1                                         # the tree really changes between steps
+
+
+# ------------------------------------------------------------------ training-stage forward (Sec. 3.3)
+def test_kl_divergence_closed_forms_and_argument_order():
+    a, b = np.log(np.array([0.75, 0.25])), np.log(np.array([0.5, 0.5]))
+    assert abs(O.kl_divergence(a, b) - (0.75 * math.log(1.5) + 0.25 * math.log(0.5))) < 1e-14      # first argument weights
+    assert abs(O.kl_divergence(b, a) - (0.5 * math.log(2 / 3) + 0.5 * math.log(2.0))) < 1e-14
+    assert O.kl_divergence(a + 7.5, b - 3.0) == pytest.approx(O.kl_divergence(a, b), abs=1e-13)  # logits, not log-probs
+    rng = np.random.default_rng(3)
+    from scipy.special import rel_entr, softmax
+    for _ in range(5):
+        za, zb = rng.normal(size=33) * 3, rng.normal(size=33) * 3
+        assert O.kl_divergence(za, za) == 0.0
+        assert O.kl_divergence(za, zb) == pytest.approx(float(np.sum(rel_entr(softmax(za), softmax(zb)))), abs=1e-12)
+        assert O.kl_divergence(za, zb) > 0
+
+
+@pytest.mark.parametrize("layers", [(1, 1, 1), (0, 1, 2)])
+def test_training_forward_rows_are_single_row_passes_over_the_stored_keys(layers):
+    """The doubled sequence with its mask, written out row by row: the pseudo state of position j, step i, is one row
+    at position j + i over the keys and values the causal pass stored for positions 0 .. j+i-1 (Sec. 3.3)."""
+    wl = small_workload(k=3, n_layers=3, transfer_layers=layers)
+    model = oracle_model(wl)
+    c = model.cfg
+    n = 9
+    toks = [int(t) for t in counter_tokens(wl.seed, 1, n, wl.vocab)]
+    z_causal, hidden, ks, vs = model.causal_forward(toks)
+    for i in (1, 2, 3):
+        res = O.training_forward(model, toks, i)
+        assert np.max(np.abs(res["Z"] - z_causal)) < 1e-9             # hidden states never see a pseudo state
+        t = layers[i - 1]
+        for j in range(n):
+            x = (model.w.w_transfer[i - 1] @ hidden[t][j])[None, :]
+            seen = min(j + i, n)
+            for layer in range(t, c.n_layers):
+                x, _, _ = model.block(layer, x, np.array([j + i]), ks[layer][:seen], vs[layer][:seen],
+                                      np.ones((1, seen), dtype=bool), np.ones((1, 1), dtype=bool))
+            assert np.max(np.abs(model.logits(x)[0] - res["Zp"][j])) < 1e-9, (i, j)
+        assert len(res["kl"]) == n - i - 1                             # the paper's index range q = 1 .. n-i-1
+        want = [O.kl_divergence(res["Zp"][j], z_causal[j + i]) for j in range(n - i - 1)]
+        assert np.allclose(res["kl"], want, atol=1e-14) and res["loss"] == pytest.approx(sum(want), abs=1e-13)
+        assert np.all(res["kl"] > 0)
+
+
+def test_training_forward_of_step_one_is_the_draft_of_inference():
+    """For the first transfer step the training mask and position are those of inference (Sec. 3.3 sets the position
+    id so that the two stages agree): the pseudo state of position j gives the draft distribution the decoder
+    computes after a prompt of j + 1 tokens."""
+    wl = small_workload(k=2, transfer_layers=(1, 1), max_cache=32)
+    model = oracle_model(wl)
+    toks = [int(t) for t in counter_tokens(wl.seed, 1, 8, wl.vocab)]
+    res = O.training_forward(model, toks, 1)
+    for j in (0, 3, 7):
+        dec = O.HiddenTransferOracle(model, [-1], [0], wl.max_cache)
+        dec.prefill(toks[:j + 1])
+        d = dec.draft(dec.transfer())
+        assert np.max(np.abs(d[0] - res["Zp"][j])) < 1e-9
