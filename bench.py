@@ -219,6 +219,9 @@ def main():
                     help="comma-separated numbers of transfer steps k (= tree depth) to time the step at, same T: "
                          "a fresh model per value (transfer maps for k steps at the workload's first transfer layer, "
                          "tree prune_tree([10] * k, T))")
+    ap.add_argument("--training-forward", type=int, default=0, metavar="N",
+                    help="also time the forward pass of the training stage with its KL loss over N tokens for the "
+                         "first transfer step (`training_forward` object)")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
     ap.add_argument("--no-graph", action="store_true",
@@ -250,7 +253,11 @@ def main():
     fused_counts = [int(t) for t in args.fused_counts.split(",") if t]
     fused_rows = max([wl.k + 1] + fused_counts) * wl.k   # pseudo rows under the rank-0 chain (or the largest sweep entry)
     headroom = 4 * (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size + fused_rows] + sweep_sizes)
-    wl = wl.with_(max_cache=(max([wl.prompt_len] + cache_lens) + headroom + 7) // 8 * 8)
+    if args.training_forward:
+        sweep_sizes_model = sweep_sizes + [128]      # 128-row passes: 63 positions, their pseudo rows, one of lookahead
+    else:
+        sweep_sizes_model = sweep_sizes
+    wl = wl.with_(max_cache=(max([wl.prompt_len, args.training_forward] + cache_lens) + headroom + 7) // 8 * 8)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     T, n0 = wl.tree_size, wl.prompt_len
     parent, rank = prune_tree(wl.branching, T)
@@ -263,7 +270,7 @@ def main():
         weights = make_weights(wl, wl.seed, dev, tdt, layers=[])
         head = weights["lm_head"]
         weights["lm_head"] = None
-        model = B.HTModel(B.make_config(wl, max_tree=min(128, max([T + fused_rows] + sweep_sizes))), weights, dev)
+        model = B.HTModel(B.make_config(wl, max_tree=min(128, max([T + fused_rows] + sweep_sizes_model))), weights, dev)
         for layer in range(wl.n_layers):
             lw = layer_weights(wl, wl.seed, layer, dev, tdt)
             model.ht_load_layer(layer, lw)
@@ -274,7 +281,7 @@ def main():
         del head
     else:
         weights = make_weights(wl, wl.seed, dev, tdt)
-        model = B.HTModel(B.make_config(wl, max_tree=min(128, max([T + fused_rows] + sweep_sizes))), weights, dev)
+        model = B.HTModel(B.make_config(wl, max_tree=min(128, max([T + fused_rows] + sweep_sizes_model))), weights, dev)
     model.ht_set_tree(parent, rank)
     model.ht_prefill(prompt)
     stream = torch.cuda.current_stream()
@@ -443,6 +450,37 @@ def main():
         del m_k, w_k
         torch.cuda.empty_cache()
 
+    # ---- forward pass of the training stage (Sec. 3.3) over N tokens, first transfer step: chunks of
+    # (max_tree - 1) / 2 positions, every chunk one pass over all the weights
+    training = None
+    if args.training_forward:
+        n_tr, step_tr = args.training_forward, 1
+        toks_tr = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n_tr, wl.vocab)]
+        model.ht_training_forward(step_tr, toks_tr)
+        reps_tr = 3
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps_tr):
+            _, loss_tr = model.ht_training_forward(step_tr, toks_tr)
+        ms_tr = (time.perf_counter() - t0) * 1e3 / reps_tr
+        chunk = (model.cfg.max_tree - step_tr) // 2
+        passes = (n_tr + chunk - 1) // chunk
+        t_layer = wl.transfer_layers[step_tr - 1]
+        per_layer = 2 * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim + wl.n_heads * wl.head_dim * wl.d_model +
+                         3 * wl.d_model * wl.d_ffn)                       # bytes of one block's matrices (bf16)
+        head = 2 * wl.vocab * wl.d_model
+        byts = passes * (wl.n_layers * per_layer + head)                  # weights once per pass; K/V reads left out
+        pseudo_rows = n_tr - step_tr + 1
+        rows_low, rows_up = n_tr + passes * step_tr, n_tr + passes * step_tr + pseudo_rows     # lookahead rows run twice
+        flops = per_layer * (t_layer * rows_low + (wl.n_layers - t_layer) * rows_up) + head * rows_up   # 2 flops per bf16 weight byte / 2
+        training = {"tokens": n_tr, "transfer_step": step_tr, "ms": round(ms_tr, 3), "tokens_per_s": round(n_tr / (ms_tr * 1e-3), 1),
+                    "passes": passes, "positions_per_pass": chunk, "loss": loss_tr,
+                    "weight_bytes_streamed": byts, "hbm_GBps": round(byts / (ms_tr * 1e-3) / 1e9, 1),
+                    "hbm_frac_of_peak": round(byts / (ms_tr * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "matrix_TFLOPs": round(flops / (ms_tr * 1e-3) / 1e12, 1),
+                    "matrix_frac_of_bf16_peak": round(flops / (ms_tr * 1e-3) / 2.5e15, 4)}
+        model.ht_prefill(prompt)
+
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)
     achieved = kern["bytes"] / (kern["ms"] * 1e-3) / 1e9
     verify_bytes = model_bytes(wl, T, n_now)
@@ -487,6 +525,8 @@ def main():
         res["fused_sweep"] = fused_sweep
     if depth_sweep:
         res["depth_sweep"] = depth_sweep
+    if training:
+        res["training_forward"] = training
     if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     print(json.dumps(res))

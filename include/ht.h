@@ -133,6 +133,25 @@ int ht_set_fused_nodes(ht_model *m, int32_t count, const int32_t *nodes /*host*/
  * layer-t residual of the last prompt token as the transfer source.  Resets any previous cache. */
 int ht_prefill(ht_model *m, const int32_t *tokens /*host*/, int32_t n, void *stream);
 
+/* Forward pass of the training stage for transfer step `step` (1-based i of Sec. 3.3) and its distillation loss.
+ * The n tokens (HOST array) run causally; at layer t_i every hidden state h_j becomes a pseudo state W_i h_j that
+ * goes on through blocks t_i+1..L at position id j + i, attending to the hidden states of positions 0 .. j+i-1 and
+ * to itself (no other pseudo state); all rows pass the LM head.  The loss is the sum over j = 0 .. n-i-2 (the index
+ * range of the loss equation, 0-based) of KL(P~_j || P_{j+i}), the pseudo state's distribution against that of the
+ * hidden state it stands for, the first argument weighting the log ratio; float32 per term, summed in double in
+ * index order on the host.  Forward only: the maps are not updated.
+ * The sequence is processed in chunks: a pass holds (max_tree - step) / 2 positions with their pseudo rows and
+ * `step` hidden rows of lookahead, so the weights are streamed once per chunk.
+ * kl_out: HOST [n - step - 1] or NULL; loss_out: HOST or NULL; logits_hidden_out: DEVICE [n, vocab] float32 or NULL;
+ * logits_pseudo_out: DEVICE [n - step + 1, vocab] float32 or NULL (pseudo states exist for j <= n - step, the
+ * positions whose visible hidden states all lie inside the sequence).  Waits for `stream`.
+ * The KV cache afterwards holds the n tokens, but no pending root: decoding needs a new ht_prefill.  The tree set
+ * by ht_set_tree / ht_set_dynamic_tree is kept.
+ * HT_EINVAL unless 1 <= step <= k, n >= step + 2 and all tokens lie in the vocabulary; HT_ECAPACITY unless
+ * max_tree >= step + 2 and n + (max_tree - step) / 2 <= max_cache; HT_ESTATE while deferred weights are missing. */
+int ht_training_forward(ht_model *m, int32_t step, const int32_t *tokens /*host*/, int32_t n, float *kl_out /*host*/,
+                        double *loss_out /*host*/, float *logits_hidden_out, float *logits_pseudo_out, void *stream);
+
 /* Hidden transfer (Sec. 3.2; equation of Sec. 3.3): pseudo[i] = W_i h, i = 0..k-1, a bare matrix
  * product of the layer-t_i hidden state.  h_src: [slots, d] in the model dtype (one vector per distinct transfer
  * layer, lowest first), or NULL to use the saved residuals of the last
@@ -243,6 +262,11 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
  * ht_dynamic_tree: lp, cand [k, HT_MAX_TOPK] (first b per row read), root [1]; writes parent, depth, rank [T],
  *   anc [T, HT_MAX_TREE / 64] (bit u of row v: u is v or an ancestor of v) and tokens [T] (the root token, then
  *   cand[depth - 1][rank] of every node).  HT_EINVAL / HT_ETREE as for `ht_set_dynamic_tree`. */
+/* The loss term of `ht_training_forward` on its own (all pointers DEVICE): z holds rows of V float32 logits;
+ * kl[p] = KL(softmax(z[row_a + p]) || softmax(z[row_b + p])) for p < pairs, the first argument weighting the log
+ * ratio (Sec. 3.3).  HT_EINVAL unless 1 <= pairs <= 65535, V >= 1 and the row indices are >= 0. */
+int ht_kl_divergence_rows(const float *z, int32_t row_a, int32_t row_b, int32_t pairs, int32_t V, float *kl,
+                          void *stream);
 int ht_candidate_logprobs(const float *d, const int32_t *cand, int32_t rows, int32_t b, int32_t V, float *lp,
                           void *stream);
 int ht_dynamic_tree(const float *lp, const int32_t *cand, const int32_t *root, int32_t k, int32_t b, int32_t T,

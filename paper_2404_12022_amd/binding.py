@@ -27,6 +27,7 @@ EXPORTS = [
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
     "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
     "ht_gate_up_pack", "ht_gate_up_silu_packed", "ht_set_dynamic_tree", "ht_candidate_logprobs", "ht_dynamic_tree",
+    "ht_training_forward", "ht_kl_divergence_rows",
 ]
 
 
@@ -68,6 +69,8 @@ def _load() -> C.CDLL:
         "ht_set_tree": (C.c_int, [vp, C.c_int32, i32p, i32p, vp]),
         "ht_set_fused_nodes": (C.c_int, [vp, C.c_int32, i32p, vp]),
         "ht_set_dynamic_tree": (C.c_int, [vp, C.c_int32, C.c_int32, vp]),
+        "ht_kl_divergence_rows": (C.c_int, [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
+        "ht_training_forward": (C.c_int, [vp, C.c_int32, i32p, C.c_int32, f32p, C.POINTER(C.c_double), vp, vp, vp]),
         "ht_candidate_logprobs": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
         "ht_dynamic_tree": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp]),
         "ht_stream_read_probe": (C.c_int, [vp, sz, vp, C.POINTER(sz), vp]),
@@ -178,6 +181,11 @@ def ht_gate_up_silu_packed(a, packed, M, f, K, act_out, stream=None) -> None:
     _check(lib.ht_gate_up_silu_packed(_ptr(a), _ptr(packed), M, f, K, _ptr(act_out), _stream_ptr(stream)))
 
 
+def ht_kl_divergence_rows(z, row_a, row_b, pairs, kl, stream=None) -> None:
+    """z [rows, V] float32, kl [pairs] float32 (device tensors): kl[p] = KL(softmax z[row_a + p] || softmax z[row_b + p])."""
+    _check(lib.ht_kl_divergence_rows(_ptr(z), row_a, row_b, pairs, z.shape[1], _ptr(kl), _stream_ptr(stream)))
+
+
 def ht_candidate_logprobs(d, cand, b, lp, stream=None) -> None:
     """d [rows, V] float32, cand [rows, HT_MAX_TOPK] int32, lp [rows, HT_MAX_TOPK] float32 (device tensors)."""
     _check(lib.ht_candidate_logprobs(_ptr(d), _ptr(cand), d.shape[0], b, d.shape[1], _ptr(lp), _stream_ptr(stream)))
@@ -270,6 +278,17 @@ class HTModel:
         _check(lib.ht_set_dynamic_tree(self.handle, T, b, _stream_ptr(stream)))
         self.T = T
         self.fused = []
+
+    def ht_training_forward(self, step: int, tokens: Sequence[int], logits_hidden=None, logits_pseudo=None, stream=None):
+        """Returns (kl list of n - step - 1 floats, loss).  logits_hidden [n, vocab], logits_pseudo [n - step + 1, vocab]:
+        optional float32 device tensors that receive the logits."""
+        n = len(tokens)
+        kl = (C.c_float * max(n - step - 1, 1))()
+        loss = C.c_double(0.0)
+        _check(lib.ht_training_forward(self.handle, step, _i32(tokens), n, kl, C.byref(loss),
+                                       _ptr(logits_hidden) if logits_hidden is not None else None,
+                                       _ptr(logits_pseudo) if logits_pseudo is not None else None, _stream_ptr(stream)))
+        return [float(v) for v in kl[:max(n - step - 1, 0)]], loss.value
 
     def ht_set_fused_nodes(self, nodes: Sequence[int], stream=None) -> None:
         _check(lib.ht_set_fused_nodes(self.handle, len(nodes), _i32(nodes) if len(nodes) else None, _stream_ptr(stream)))

@@ -72,12 +72,14 @@ struct Buffers {
   float* pseudo;       // [k, d]
   float* cs;           // rotary table [Mp, hd/2] (cos, sin)
   float* ss;           // packed path: sums of squares of the rows of u, kNormParts parts per row [Mp][kNormParts]
+  float* kl;           // training forward: KL term per position [max_cache]
+  int32_t* train_rows; // training forward: source row of every pseudo row of the pass [kMaxTree]
   float* lp;           // log-probabilities of the candidates of the last draft [kMaxTransfer][kMaxTopK] (dynamic tree)
   int32_t *tok, *g, *cand, *width, *prompt;
   int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
   int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
   int32_t* fused_src;    // logits row (past the tree rows) that holds the draft of (fused node, step) [kMaxTree]
-  TreeTables tree, chain;
+  TreeTables tree, chain, train;   // the decoding tree; a chain (prefill, draft pass); the rows of a training pass
   StepState* state;
   StepLog* log;        // steps of the device-resident loop [kMaxLoopSteps]
   void** kc_ptrs;      // device array [L]
@@ -117,6 +119,8 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.cs = cv.take<float>(Mp * c.head_dim);
   b.ss = cv.take<float>(Mp * kNormParts);
   b.lp = cv.take<float>((size_t)kMaxTransfer * kMaxTopK);
+  b.kl = cv.take<float>(c.max_cache);
+  b.train_rows = cv.take<int32_t>(kMaxTree);
   b.tok = cv.take<int32_t>(Mp);
   b.g = cv.take<int32_t>(Mp);
   b.cand = cv.take<int32_t>((size_t)kMaxTransfer * kMaxTopK);
@@ -125,7 +129,7 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.fused_rows = cv.take<int32_t>(kMaxTree);
   b.cand_fused = cv.take<int32_t>((size_t)kMaxTree * kMaxTopK);
   b.fused_src = cv.take<int32_t>(kMaxTree);
-  for (TreeTables* t : {&b.tree, &b.chain}) {
+  for (TreeTables* t : {&b.tree, &b.chain, &b.train}) {
     t->parent = cv.take<int32_t>(kMaxTree);
     t->depth = cv.take<int32_t>(kMaxTree);
     t->rank = cv.take<int32_t>(kMaxTree);
@@ -241,13 +245,15 @@ int attention(ht_model* m, int layer, int n, int M, const TreeDev& tree, hipStre
 // every transfer step, W_i applied to the node's residual at layer t_i (Sec. 3.2), created when the pass reaches
 // t_i: verification and the next candidates then come out of one forward (Fig. 2 caption, Sec. 3.4).
 // kFromBuffer: the k rows of b.pseudo (draft pass after acceptance), row i joining at layer t_i.
-enum JoinMode { kNoJoin = 0, kFromTree = 1, kFromBuffer = 2 };
+// kTrainStep: one pseudo row per listed row (b.train_rows), made by the map of transfer step `step` alone when the
+// pass reaches that step's layer (training stage, Sec. 3.3).
+enum JoinMode { kNoJoin = 0, kFromTree = 1, kFromBuffer = 2, kTrainStep = 3 };
 
 // Rows already in b.x (M of them, possibly none) go through blocks layer_from+1 .. L (0-based index
 // layer_from .. L-1) together with the rows that join on the way, then the final norm and, if `logits` is given,
 // the LM head and the row arg-max.  `tree` must describe all rows the pass ends with.
 int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_hidden, float* logits, int32_t* gout,
-             hipStream_t s, JoinMode join = kNoJoin, int F = 0) {
+             hipStream_t s, JoinMode join = kNoJoin, int F = 0, int step = 0) {
   const ht_config& c = m->cfg;
   Buffers& b = m->b;
   const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn;
@@ -255,7 +261,7 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
   size_t pstride = (size_t)M * d;
   const int n = m->n;
   int rc;
-  const int joining = join == kFromTree ? F * c.k : join == kFromBuffer ? c.k : 0;
+  const int joining = join == kFromTree ? F * c.k : join == kFromBuffer ? c.k : join == kTrainStep ? F : 0;
   HT_HIP(launch_rope_table(b.cs, tree.depth, n, M + joining, c.head_dim, c.rope_base, s, m->n_dev));
   int pending = 0;
   // Residual add + RMSNorm.  On packed weights the row is split over kNormParts workgroups (one workgroup per row
@@ -273,7 +279,16 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       float* save = (save_hidden && slot >= 0) ? b.saved_h + slot * slot_stride : nullptr;
       HT_HIP(add_norm(b.x, pending, pstride, m->attn_norm[l], b.u, save, b.ss, M));
     }
-    if (join != kNoJoin && slot >= 0) {
+    if (join == kTrainStep) {
+      if (l == c.transfer_layer[step]) {
+        HT_HIP(launch_transfer(c.dtype, b.x, b.train_rows, F, (const void* const*)b.wt_ptrs, b.x + (size_t)M * d, step, 1,
+                               1, d, s));
+        HT_HIP(add_norm(b.x + (size_t)M * d, 0, 0, m->attn_norm[l], (char*)b.u + (size_t)M * d * es, nullptr,
+                        b.ss + (size_t)M * kNormParts, F));
+        M += F;
+        pstride = (size_t)M * d;
+      }
+    } else if (join != kNoJoin && slot >= 0) {
       // the residual after l blocks is complete now: make the rows of this layer's transfer steps, normalise
       // them, go on wider
       const int i0 = m->slot_first[slot], cnt = m->slot_count[slot];
@@ -723,6 +738,86 @@ int ht_prefill(ht_model* m, const int32_t* tokens, int32_t n, void* stream) {
   return HT_OK;
 }
 
+int ht_training_forward(ht_model* m, int32_t step, const int32_t* tokens, int32_t n, float* kl_out, double* loss_out,
+                        float* logits_hidden_out, float* logits_pseudo_out, void* stream) {
+  if (!m || !tokens) return fail(HT_EINVAL, "NULL argument");
+  const ht_config& c = m->cfg;
+  if (!all_loaded(m)) return fail(HT_ESTATE, "deferred weights: ht_load_layer / ht_load_lm_head have not supplied every layer");
+  if (step < 1 || step > c.k) return fail(HT_EINVAL, "transfer step %d outside 1..%d", step, c.k);
+  if (n < step + 2) return fail(HT_EINVAL, "%d tokens give no loss term for step %d (at least %d needed)", n, step, step + 2);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(HT_EINVAL, "token %d at %d outside the vocabulary", tokens[i], i);
+  // A pass holds C hidden rows whose K/V stay in the cache, `step` more hidden rows of lookahead (the pseudo rows of
+  // the chunk see up to step - 1 positions ahead, the loss pairs up to `step`; the next pass computes them again)
+  // and the chunk's C pseudo rows.
+  const int room = c.max_tree < kMaxTree ? c.max_tree : kMaxTree;
+  const int C = (room - step) / 2;
+  if (C < 1) return fail(HT_ECAPACITY, "max_tree %d leaves no room for a chunk at step %d", c.max_tree, step);
+  if (n + C > c.max_cache) return fail(HT_ECAPACITY, "%d tokens + %d pseudo rows exceed max_cache %d", n, C, c.max_cache);
+  hipStream_t s = (hipStream_t)stream;
+  Buffers& b = m->b;
+  HT_HIP(hipStreamSynchronize(s));
+  memcpy(m->h_stage, tokens, sizeof(int32_t) * n);
+  HT_HIP(hipMemcpyAsync(b.prompt, m->h_stage, sizeof(int32_t) * n, hipMemcpyHostToDevice, s));
+  HT_HIP(hipStreamSynchronize(s));           // the staging buffer takes the row tables next
+  m->n = 0;
+  m->has_prefill = m->transfer_ready = m->verify_done = false;
+  m->drafts_of = -1;
+  const int last_pseudo = n - step;          // pseudo rows exist for positions j <= n - step: all they may see is there
+  const int terms = n - step - 1;            // loss terms j = 0 .. n - step - 2 (Sec. 3.3, upper limit of the sum)
+  int shape_real = -1, shape_pseudo = -1, rc;
+  std::vector<int32_t> parent, rows;
+  for (int c0 = 0; c0 < n; c0 += C) {
+    const int real = n - c0 < C + step ? n - c0 : C + step;
+    int pseudo = last_pseudo - c0 + 1;
+    pseudo = pseudo < 0 ? 0 : pseudo > C ? C : pseudo;
+    if (real != shape_real || pseudo != shape_pseudo) {
+      // hidden rows form a chain; the pseudo row of in-pass position f hangs under hidden row f + step - 1: it then
+      // sees hidden rows 0 .. f + step - 1 and itself and sits at position c0 + f + step (Sec. 3.3)
+      parent.assign(real + pseudo, 0);
+      rows.assign(pseudo > 0 ? pseudo : 1, 0);
+      for (int r = 0; r < real; ++r) parent[r] = r - 1;
+      for (int f = 0; f < pseudo; ++f) {
+        parent[real + f] = f + step - 1;
+        rows[f] = f;
+      }
+      HT_HIP(hipStreamSynchronize(s));       // earlier uploads have left the staging buffer
+      fill_tables(real + pseudo, parent.data(), nullptr, m->h_stage);
+      if ((rc = upload_tables(b.train, m->h_stage, s))) return rc;
+      int32_t* rows_stage = m->h_stage + kTableInts;
+      memcpy(rows_stage, rows.data(), sizeof(int32_t) * rows.size());
+      HT_HIP(hipMemcpyAsync(b.train_rows, rows_stage, sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice, s));
+      shape_real = real;
+      shape_pseudo = pseudo;
+    }
+    HT_HIP(launch_embed(c.dtype, m->tok_emb, b.prompt + c0, b.x, real, c.d_model, s));
+    if ((rc = run_pass(m, b.train.dev(), real, 0, false, b.logits, nullptr, s, pseudo ? kTrainStep : kNoJoin, pseudo,
+                       step - 1)))
+      return rc;
+    int pairs = terms - c0;
+    pairs = pairs < 0 ? 0 : pairs > pseudo ? pseudo : pairs;
+    if (pairs) HT_HIP(launch_kl_rows(b.logits, real, step, pairs, c.vocab, b.kl + c0, s));
+    if (logits_hidden_out)
+      HT_HIP(hipMemcpyAsync(logits_hidden_out + (size_t)c0 * c.vocab, b.logits, sizeof(float) * real * c.vocab,
+                            hipMemcpyDeviceToDevice, s));
+    if (logits_pseudo_out && pseudo)
+      HT_HIP(hipMemcpyAsync(logits_pseudo_out + (size_t)c0 * c.vocab, b.logits + (size_t)real * c.vocab,
+                            sizeof(float) * pseudo * c.vocab, hipMemcpyDeviceToDevice, s));
+    m->n += real < C ? real : C;             // the lookahead rows are overwritten by the next pass
+  }
+  float* h_kl = (float*)m->h_stage;
+  HT_HIP(hipStreamSynchronize(s));
+  HT_HIP(hipMemcpyAsync(h_kl, b.kl, sizeof(float) * terms, hipMemcpyDeviceToHost, s));
+  HT_HIP(hipStreamSynchronize(s));
+  double loss = 0.0;
+  for (int j = 0; j < terms; ++j) {
+    loss += (double)h_kl[j];
+    if (kl_out) kl_out[j] = h_kl[j];
+  }
+  if (loss_out) *loss_out = loss;
+  return HT_OK;
+}
+
 int ht_transfer(ht_model* m, const void* h_src, float* pseudo_out, void* stream) {
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!h_src && !m->has_prefill) return fail(HT_ESTATE, "no saved hidden state: call ht_prefill first or pass h_src");
@@ -1081,6 +1176,13 @@ int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K
     return ht_skinny_gemm_packed(a, scratch, M, N, K, out, (char*)scratch + pb, scratch_bytes - pb, stream);
   }
   HT_HIP(launch_gemm_simple(dtype, a, segs1(w, N), M, N, K, out, s));
+  return HT_OK;
+}
+
+int ht_kl_divergence_rows(const float* z, int32_t row_a, int32_t row_b, int32_t pairs, int32_t V, float* kl, void* stream) {
+  if (!z || !kl) return fail(HT_EINVAL, "NULL argument");
+  if (row_a < 0 || row_b < 0 || pairs < 1 || pairs > 65535 || V < 1) return fail(HT_EINVAL, "bad shape pairs=%d V=%d", pairs, V);
+  HT_HIP(launch_kl_rows(z, row_a, row_b, pairs, V, kl, (hipStream_t)stream));
   return HT_OK;
 }
 

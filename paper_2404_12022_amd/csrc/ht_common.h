@@ -132,6 +132,8 @@ size_t topk_scratch_bytes(int rows);
 hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
                        const int32_t* src_row, int V, hipStream_t s);
 hipError_t launch_tree_build(const StepState* st, const int32_t* cand, TreeDev tree, int32_t* tok, int T, hipStream_t s);
+// kl[p] = KL(softmax(z[row_a + p]) || softmax(z[row_b + p])), p < pairs, z rows of V floats (Sec. 3.3 loss term)
+hipError_t launch_kl_rows(const float* z, int row_a, int row_b, int pairs, int V, float* kl, hipStream_t s);
 // Tree chosen from the draft distributions: lp[k][kMaxTopK] = log-probabilities of the b best candidates of every
 // draft row (whole-row log-softmax); then the T - 1 best nodes by (summed lp desc, depth asc, rank path asc) fill
 // the tree tables and the token row.  T <= kMaxTree, 1 <= b <= kMaxTopK, 1 <= k <= kMaxTransfer and

@@ -673,6 +673,57 @@ hipError_t launch_tree_dynamic(const int32_t* root, const int32_t* cand, const f
   return hipGetLastError();
 }
 
+// ---- distillation term of the training stage (Sec. 3.3)
+// kl[p] = KL(softmax(z[row_a + p]) || softmax(z[row_b + p])) = sum_v A_v (log A_v - log B_v) for pairs p of logit
+// rows.  One block of 1024 threads per pair: the two maxima, then the two sums of exponentials and the A-weighted sum
+// of the shifted logit differences in one more pass.
+__global__ __launch_bounds__(1024) void kl_rows_kernel(const float* __restrict__ z, int row_a, int row_b, int V, int vec,
+                                                       float* __restrict__ kl) {
+  __shared__ float red[16];
+  const float* za = z + (size_t)(row_a + blockIdx.x) * V;
+  const float* zb = z + (size_t)(row_b + blockIdx.x) * V;
+  const int v4 = vec ? (V & ~3) : 0;
+  float ma = -INFINITY, mb = -INFINITY;
+  for (int j = threadIdx.x * 4; j < v4; j += blockDim.x * 4) {
+    const float4 a = *(const float4*)(za + j), b = *(const float4*)(zb + j);
+    ma = fmaxf(fmaxf(ma, fmaxf(a.x, a.y)), fmaxf(a.z, a.w));
+    mb = fmaxf(fmaxf(mb, fmaxf(b.x, b.y)), fmaxf(b.z, b.w));
+  }
+  for (int j = v4 + threadIdx.x; j < V; j += blockDim.x) { ma = fmaxf(ma, za[j]); mb = fmaxf(mb, zb[j]); }
+  auto block_max = [&](float v) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = red[0];
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t = fmaxf(t, red[w]);
+    return t;
+  };
+  ma = block_max(ma);
+  mb = block_max(mb);
+  float sa = 0.f, sb = 0.f, cross = 0.f;
+  auto term = [&](float a, float b) {
+    const float ea = expf(a - ma);
+    sa += ea;
+    sb += expf(b - mb);
+    cross += ea * ((a - ma) - (b - mb));
+  };
+  for (int j = threadIdx.x * 4; j < v4; j += blockDim.x * 4) {
+    const float4 a = *(const float4*)(za + j), b = *(const float4*)(zb + j);
+    term(a.x, b.x); term(a.y, b.y); term(a.z, b.z); term(a.w, b.w);
+  }
+  for (int j = v4 + threadIdx.x; j < V; j += blockDim.x) term(za[j], zb[j]);
+  sa = block_sum_any(sa, red);
+  sb = block_sum_any(sb, red);
+  cross = block_sum_any(cross, red);
+  if (threadIdx.x == 0) kl[blockIdx.x] = cross / sa - logf(sa) + logf(sb);
+}
+hipError_t launch_kl_rows(const float* z, int row_a, int row_b, int pairs, int V, float* kl, hipStream_t s) {
+  const int vec = !((uintptr_t)z & 15) && !(V & 3);
+  hipLaunchKernelGGL(kl_rows_kernel, dim3(pairs), dim3(1024), 0, s, z, row_a, row_b, V, vec, kl);
+  return hipGetLastError();
+}
+
 // One wavefront: each round, every lane tests a slice of the nodes for "child of cur carrying the
 // greedy token after cur" and the lowest such node index wins.
 __global__ void accept_kernel(StepState* __restrict__ st, TreeDev tree, const int32_t* __restrict__ tok,
