@@ -142,7 +142,9 @@ int ht_prefill(ht_model *m, const int32_t *tokens /*host*/, int32_t n, void *str
  * index order on the host.  Forward only: the maps are not updated.
  * The sequence is processed in chunks: a pass holds (max_tree - step) / 2 positions with their pseudo rows and
  * `step` hidden rows of lookahead, so the weights are streamed once per chunk.
- * kl_out: HOST [n - step - 1] or NULL; loss_out: HOST or NULL; logits_hidden_out: DEVICE [n, vocab] float32 or NULL;
+ * kl_out: HOST [n - step - 1] or NULL; loss_out: HOST or NULL; logits_hidden_out: DEVICE [n, vocab] float32 or NULL
+ * (a lookahead row is computed by two passes, which in bf16 may round it differently: the row returned is the one
+ * the loss used);
  * logits_pseudo_out: DEVICE [n - step + 1, vocab] float32 or NULL (pseudo states exist for j <= n - step, the
  * positions whose visible hidden states all lie inside the sequence).  Waits for `stream`.
  * The KV cache afterwards holds the n tokens, but no pending root: decoding needs a new ht_prefill.  The tree set

@@ -797,9 +797,12 @@ int ht_training_forward(ht_model* m, int32_t step, const int32_t* tokens, int32_
     int pairs = terms - c0;
     pairs = pairs < 0 ? 0 : pairs > pseudo ? pseudo : pairs;
     if (pairs) HT_HIP(launch_kl_rows(b.logits, real, step, pairs, c.vocab, b.kl + c0, s));
-    if (logits_hidden_out)
-      HT_HIP(hipMemcpyAsync(logits_hidden_out + (size_t)c0 * c.vocab, b.logits, sizeof(float) * real * c.vocab,
-                            hipMemcpyDeviceToDevice, s));
+    // the first `step` rows of a later pass were the lookahead of the pass before, whose loss terms used them: the
+    // copy keeps that first version (in bf16 the two passes may round a row differently)
+    const int seen = c0 > 0 ? step : 0;
+    if (logits_hidden_out && real > seen)
+      HT_HIP(hipMemcpyAsync(logits_hidden_out + (size_t)(c0 + seen) * c.vocab, b.logits + (size_t)seen * c.vocab,
+                            sizeof(float) * (real - seen) * c.vocab, hipMemcpyDeviceToDevice, s));
     if (logits_pseudo_out && pseudo)
       HT_HIP(hipMemcpyAsync(logits_pseudo_out + (size_t)c0 * c.vocab, b.logits + (size_t)real * c.vocab,
                             sizeof(float) * pseudo * c.vocab, hipMemcpyDeviceToDevice, s));

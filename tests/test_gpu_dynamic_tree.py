@@ -274,3 +274,25 @@ def test_llama7b_width_two_layers_with_a_tree_chosen_every_step():
         say(f"  step {step}: depth profile {np.bincount(O.tree_depth(r['parent'])).tolist()}, accepted {r['m']}, "
             f"tree equals the fp64 oracle's own: {(r['parent'], r['rank']) == r['own_tree']}")
     sc.gpu.close()
+
+
+@pytest.mark.parametrize("seed", [f"any{i}" for i in range(6)] + [f"packed{i}" for i in range(6)])
+def test_random_model_shapes_with_a_tree_chosen_every_step(seed):
+    """The random shapes of the fixed-tree suite (grouped heads, odd widths, 1..5 transfer steps at different layers,
+    both kernel families), decoding with a tree of the same size chosen at every step."""
+    from test_gpu_parity import _random_shape, _random_packed_shape
+    H = _H()
+    wl, _, _ = _random_shape(int(seed[3:])) if seed.startswith("any") else _random_packed_shape(int(seed[6:]))
+    b = 2
+    while sum(b ** e for e in range(1, wl.k + 1)) < wl.tree_size - 1:
+        b += 1
+    b = min(b + 1, 64, wl.vocab)
+    wl = wl.with_(max_cache=wl.max_cache + 64)
+    say(f"dynamic tree, random shape {seed}: {wl.dtype} layers={wl.n_layers} d={wl.d_model} heads={wl.n_heads}/{wl.n_kv_heads}x"
+        f"{wl.head_dim} vocab={wl.vocab} k={wl.k} t={wl.transfer_layers} T={wl.tree_size} b={b} prompt {wl.prompt_len}")
+    sc = H.StepCompare(wl, dynamic=(wl.tree_size, b))
+    sc.check_prefill()
+    for step in range(4):
+        sc.step_dynamic(exact=False)
+    sc.check_cache("after 4 steps")
+    sc.gpu.close()

@@ -2,8 +2,9 @@
 the oracle, through the C ABI.  Needs a real MI355X.
 
 Float stages (logits of the hidden states and of the pseudo states) are compared with the fp64 oracle at the model's
-tolerance; the KL terms are compared with the oracle's formula applied to the GPU's own logits (<= 2e-5 absolute:
-float32 sums over the vocabulary) and, on fp32 models, with the oracle's own terms.
+tolerance; the KL terms are compared with the oracle's formula applied to the GPU's own logits (<= 2e-5 + 1e-5 |KL|:
+the kernel works in float32, three sums over the vocabulary and a difference of two logarithms whose size grows with
+the spread of the logits) and, on fp32 models, with the oracle's own terms.
 """
 import numpy as np
 import pytest
@@ -45,7 +46,7 @@ def test_kl_rows_match_the_definition(rows, V):
     got = kl.cpu().numpy().astype(np.float64)
     want = np.array([O.kl_divergence(zn[1 + p], zn[rows + 2 + p]) for p in range(rows)])
     say(f"kl rows V={V}: max-abs error {np.max(np.abs(got - want)):.2e}, values {want[1]:.3f}..")
-    assert np.max(np.abs(got - want)) <= 2e-5 and abs(got[0]) <= 1e-6
+    assert np.all(np.abs(got - want) <= 2e-5 + 1e-5 * np.abs(want)) and abs(got[0]) <= 1e-6
 
 
 def _compare(wl, tensors_gpu, tensors_cpu, n, step, max_tree, exact):
@@ -65,13 +66,15 @@ def _compare(wl, tensors_gpu, tensors_cpu, n, step, max_tree, exact):
     assert len(kl) == n - step - 1 == len(res["kl"])
     own = np.array([O.kl_divergence(zpc[j], zc[j + step]) for j in range(n - step - 1)])
     err_own = float(np.max(np.abs(np.array(kl) - own))) if len(kl) else 0.0
-    assert err_own <= 2e-5, f"KL terms off the definition on the GPU's own logits by {err_own:.2e}"
+    assert np.all(np.abs(np.array(kl) - own) <= 2e-5 + 1e-5 * np.abs(own)), \
+        f"KL terms off the definition on the GPU's own logits by {err_own:.2e} (largest term {np.max(own):.3f})"
     assert abs(loss - float(np.sum(np.array(kl, dtype=np.float64)))) <= 1e-9 * max(1.0, abs(loss))
     if exact:
         err = float(np.max(np.abs(np.array(kl) - res["kl"]))) if len(kl) else 0.0
         assert err <= 2e-5 + 1e-3 * float(np.max(res["kl"])), f"KL terms differ from the oracle's by {err:.2e}"
         assert abs(loss - res["loss"]) <= 2e-5 * len(kl) + 1e-3 * res["loss"]
-    say(f"  {wl.name} n={n} step={step} rows/pass<={max_tree}: logits {e1:.2e} / {e2:.2e}, KL vs definition {err_own:.2e}, "
+    say(f"  {wl.name} n={n} step={step} rows/pass<={max_tree}: logits {e1:.2e} / {e2:.2e}, KL vs definition {err_own:.2e} "
+        f"(largest term {float(np.max(own)) if len(own) else 0.0:.3f}), "
         f"loss {loss:.6f} (oracle {res['loss']:.6f})")
     gpu.close()
 
@@ -144,3 +147,19 @@ def test_training_forward_state_and_error_codes():
         out += gpu.ht_accept_and_compact()[1]
     assert out == oracle_model(wl).ar_greedy(toks, len(out))
     gpu.close()
+
+
+@pytest.mark.parametrize("seed", [f"any{i}" for i in range(6)] + [f"packed{i}" for i in range(6)])
+def test_random_model_shapes_training_forward(seed):
+    """The random shapes of the decoding suite (grouped heads, odd widths and vocabularies, several transfer layers,
+    both kernel families), every transfer step, a random sequence length and rows per pass."""
+    from test_gpu_parity import _random_shape, _random_packed_shape
+    wl, _, _ = _random_shape(int(seed[3:])) if seed.startswith("any") else _random_packed_shape(int(seed[6:]))
+    rng = np.random.default_rng(int(seed[-1]) + 17)
+    n = int(rng.integers(wl.k + 2, 90))
+    max_tree = int(rng.integers(wl.k + 2, 129))
+    wl = wl.with_(max_cache=(n + 64 + 7) // 8 * 8)
+    say(f"training forward, random shape {seed}: {wl.dtype} layers={wl.n_layers} d={wl.d_model} heads={wl.n_heads}/"
+        f"{wl.n_kv_heads}x{wl.head_dim} vocab={wl.vocab} k={wl.k} t={wl.transfer_layers} n={n} rows/pass<={max_tree}")
+    for step in range(1, wl.k + 1):
+        _compare(wl, None, None, n, step, max_tree, exact=wl.dtype == "f32")
