@@ -296,3 +296,50 @@ def test_random_model_shapes_with_a_tree_chosen_every_step(seed):
         sc.step_dynamic(exact=False)
     sc.check_cache("after 4 steps")
     sc.gpu.close()
+
+
+def test_drafting_step_with_a_chosen_tree_replayed_from_a_graph():
+    """Transfer, draft pass, top-k, log-probabilities, tree choice and verify pass captured in one HIP graph: every
+    replay, with eager work of the same model in between, gives the tree, tokens and logits of the eager call."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), prompt_len=90, max_cache=256)
+    T, b = 32, 6
+    model = H.gpu_model(wl, make_weights(wl, wl.seed, H.DEV, torch.bfloat16), max_tree=T)
+    model.ht_set_dynamic_tree(T, b)
+    model.ht_prefill(prompt_of(wl))
+    z_e = torch.empty(T, wl.vocab, dtype=torch.float32, device=DEV)
+    g_e = torch.empty(T, dtype=torch.int32, device=DEV)
+    z_g, g_g = torch.empty_like(z_e), torch.empty_like(g_e)
+
+    def eager():
+        model.ht_transfer(None, None)
+        model.ht_tree_verify_step(None, g_e, z_e)
+        torch.cuda.synchronize()
+        return (model.ht_get_buffer(B.HT_BUF_TREE_PARENT).clone(), model.ht_get_buffer(B.HT_BUF_TREE_RANK).clone(),
+                model.ht_get_buffer(B.HT_BUF_TREE_TOKENS).clone())
+
+    want = eager()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.ht_transfer(None, None)
+        model.ht_tree_verify_step(None, g_g, z_g)
+    say("graph replay of a drafting step with a chosen tree")
+    for replay in range(4):
+        z_g.zero_()
+        g_g.zero_()
+        other = torch.full((T,), 5 + replay, dtype=torch.int32, device=DEV)
+        model.ht_set_tree(*prune_tree(wl.branching, T))          # eager work between the replays rewrites the tables
+        model.ht_tree_verify_step(other, g_e, z_e)
+        model.ht_set_dynamic_tree(T, b)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (model.ht_get_buffer(B.HT_BUF_TREE_PARENT).clone(), model.ht_get_buffer(B.HT_BUF_TREE_RANK).clone(),
+               model.ht_get_buffer(B.HT_BUF_TREE_TOKENS).clone())
+        assert all(torch.equal(a, c) for a, c in zip(got, want)), f"replay {replay}: tree or tokens differ"
+        again = eager()
+        assert all(torch.equal(a, c) for a, c in zip(again, want))
+        assert torch.equal(g_g, g_e), f"replay {replay}: arg-max differs from the eager pass"
+        assert torch.equal(z_g, z_e), f"replay {replay}: logits differ from the eager pass"
+    del graph
+    model.close()
