@@ -451,7 +451,8 @@ def main():
         torch.cuda.empty_cache()
 
     # ---- forward pass of the training stage (Sec. 3.3) over N tokens, first transfer step: chunks of
-    # (max_tree - 1) / 2 positions, every chunk one pass over all the weights
+    # (max_tree - 1) / 2 positions; the blocks above the transfer layer and the LM head are walked once per chunk,
+    # the blocks below it once per two chunks
     training = None
     if args.training_forward:
         n_tr, step_tr = args.training_forward, 1
@@ -469,12 +470,14 @@ def main():
         per_layer = 2 * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim + wl.n_heads * wl.head_dim * wl.d_model +
                          3 * wl.d_model * wl.d_ffn)                       # bytes of one block's matrices (bf16)
         head = 2 * wl.vocab * wl.d_model
-        byts = passes * (wl.n_layers * per_layer + head)                  # weights once per pass; K/V reads left out
+        passes_low = (n_tr + 2 * chunk - 1) // (2 * chunk)
+        byts = passes_low * t_layer * per_layer + passes * ((wl.n_layers - t_layer) * per_layer + head)   # K/V reads left out
         pseudo_rows = n_tr - step_tr + 1
-        rows_low, rows_up = n_tr + passes * step_tr, n_tr + passes * step_tr + pseudo_rows     # lookahead rows run twice
+        rows_low, rows_up = n_tr + passes_low * step_tr, n_tr + passes * step_tr + pseudo_rows     # lookahead rows run twice
         flops = per_layer * (t_layer * rows_low + (wl.n_layers - t_layer) * rows_up) + head * rows_up   # 2 flops per bf16 weight byte / 2
         training = {"tokens": n_tr, "transfer_step": step_tr, "ms": round(ms_tr, 3), "tokens_per_s": round(n_tr / (ms_tr * 1e-3), 1),
-                    "passes": passes, "positions_per_pass": chunk, "loss": loss_tr,
+                    "passes_upper_blocks": passes, "passes_lower_blocks": passes_low, "positions_per_pass": chunk,
+                    "loss": loss_tr,
                     "weight_bytes_streamed": byts, "hbm_GBps": round(byts / (ms_tr * 1e-3) / 1e9, 1),
                     "hbm_frac_of_peak": round(byts / (ms_tr * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                     "matrix_TFLOPs": round(flops / (ms_tr * 1e-3) / 1e12, 1),

@@ -140,8 +140,9 @@ int ht_prefill(ht_model *m, const int32_t *tokens /*host*/, int32_t n, void *str
  * range of the loss equation, 0-based) of KL(P~_j || P_{j+i}), the pseudo state's distribution against that of the
  * hidden state it stands for, the first argument weighting the log ratio; float32 per term, summed in double in
  * index order on the host.  Forward only: the maps are not updated.
- * The sequence is processed in chunks: a pass holds (max_tree - step) / 2 positions with their pseudo rows and
- * `step` hidden rows of lookahead, so the weights are streamed once per chunk.
+ * The sequence is processed in chunks of C = (max_tree - step) / 2 positions: blocks t_i+1..L and the LM head run a
+ * chunk's hidden rows, `step` hidden rows of lookahead and its pseudo rows in one pass; blocks 1..t_i, which see
+ * hidden rows only, run two chunks per pass.
  * kl_out: HOST [n - step - 1] or NULL; loss_out: HOST or NULL; logits_hidden_out: DEVICE [n, vocab] float32 or NULL
  * (a lookahead row is computed by two passes, which in bf16 may round it differently: the row returned is the one
  * the loss used);

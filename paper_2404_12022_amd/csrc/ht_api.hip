@@ -252,8 +252,10 @@ enum JoinMode { kNoJoin = 0, kFromTree = 1, kFromBuffer = 2, kTrainStep = 3 };
 // Rows already in b.x (M of them, possibly none) go through blocks layer_from+1 .. L (0-based index
 // layer_from .. L-1) together with the rows that join on the way, then the final norm and, if `logits` is given,
 // the LM head and the row arg-max.  `tree` must describe all rows the pass ends with.
+// layer_end >= 0: the pass stops after block layer_end (0-based index layer_end - 1) and leaves the finished residual
+// rows in b.x (no final norm, no logits).
 int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_hidden, float* logits, int32_t* gout,
-             hipStream_t s, JoinMode join = kNoJoin, int F = 0, int step = 0) {
+             hipStream_t s, JoinMode join = kNoJoin, int F = 0, int step = 0, int layer_end = -1) {
   const ht_config& c = m->cfg;
   Buffers& b = m->b;
   const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn;
@@ -273,7 +275,8 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
     return parts ? launch_add_norm_parts(x, b.part, nsplit, stride, gain, u, save, ss, rows, d, s)
                  : launch_add_norm(c.dtype, x, b.part, nsplit, stride, gain, u, save, rows, d, c.rms_eps, s);
   };
-  for (int l = layer_from; l < c.n_layers; ++l) {
+  const int layer_stop = layer_end >= 0 ? layer_end : c.n_layers;
+  for (int l = layer_from; l < layer_stop; ++l) {
     const int slot = m->slot_of_layer[l];
     if (M > 0) {
       float* save = (save_hidden && slot >= 0) ? b.saved_h + slot * slot_stride : nullptr;
@@ -344,6 +347,10 @@ int run_pass(ht_model* m, const TreeDev& tree, int M, int layer_from, bool save_
       pending = 1;
       if ((rc = product(m, b.act, segs1(m->w_down[l], d), M, d, f, b.part, s))) return rc;
     }
+  }
+  if (layer_end >= 0) {      // fold the last block's partial sums into the residual and stop (u is scratch here)
+    if (pending && M > 0) HT_HIP(add_norm(b.x, pending, pstride, m->attn_norm[layer_end], b.u, nullptr, b.ss, M));
+    return HT_OK;
   }
   HT_HIP(add_norm(b.x, pending, pstride, m->final_norm, logits ? b.u : nullptr, nullptr, b.ss, M));
   if (logits) {
@@ -747,9 +754,9 @@ int ht_training_forward(ht_model* m, int32_t step, const int32_t* tokens, int32_
   if (n < step + 2) return fail(HT_EINVAL, "%d tokens give no loss term for step %d (at least %d needed)", n, step, step + 2);
   for (int i = 0; i < n; ++i)
     if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(HT_EINVAL, "token %d at %d outside the vocabulary", tokens[i], i);
-  // A pass holds C hidden rows whose K/V stay in the cache, `step` more hidden rows of lookahead (the pseudo rows of
-  // the chunk see up to step - 1 positions ahead, the loss pairs up to `step`; the next pass computes them again)
-  // and the chunk's C pseudo rows.
+  // A pass through blocks t+1..L holds C hidden rows whose K/V stay in the cache, `step` more hidden rows of lookahead
+  // (the pseudo rows of the chunk see up to step - 1 positions ahead, the loss pairs up to `step`; the next pass
+  // computes them again) and the chunk's C pseudo rows.
   const int room = c.max_tree < kMaxTree ? c.max_tree : kMaxTree;
   const int C = (room - step) / 2;
   if (C < 1) return fail(HT_ECAPACITY, "max_tree %d leaves no room for a chunk at step %d", c.max_tree, step);
@@ -767,46 +774,58 @@ int ht_training_forward(ht_model* m, int32_t step, const int32_t* tokens, int32_
   const int terms = n - step - 1;            // loss terms j = 0 .. n - step - 2 (Sec. 3.3, upper limit of the sum)
   int shape_real = -1, shape_pseudo = -1, rc;
   std::vector<int32_t> parent, rows;
-  for (int c0 = 0; c0 < n; c0 += C) {
-    const int real = n - c0 < C + step ? n - c0 : C + step;
-    int pseudo = last_pseudo - c0 + 1;
-    pseudo = pseudo < 0 ? 0 : pseudo > C ? C : pseudo;
-    if (real != shape_real || pseudo != shape_pseudo) {
-      // hidden rows form a chain; the pseudo row of in-pass position f hangs under hidden row f + step - 1: it then
-      // sees hidden rows 0 .. f + step - 1 and itself and sits at position c0 + f + step (Sec. 3.3)
-      parent.assign(real + pseudo, 0);
-      rows.assign(pseudo > 0 ? pseudo : 1, 0);
-      for (int r = 0; r < real; ++r) parent[r] = r - 1;
-      for (int f = 0; f < pseudo; ++f) {
-        parent[real + f] = f + step - 1;
-        rows[f] = f;
+  const int t = c.transfer_layer[step - 1];
+  // Blocks 1..t see hidden rows only, so they take two chunks (and the lookahead of the second) in one pass of up to
+  // 2 C + step rows; their finished residual rows wait in the saved-hidden buffer while blocks t+1..L run the two
+  // chunks one after the other, each with its pseudo rows.
+  for (int b0 = 0; b0 < n; b0 += 2 * C) {
+    const int low = n - b0 < 2 * C + step ? n - b0 : 2 * C + step;
+    m->n = b0;
+    HT_HIP(launch_embed(c.dtype, m->tok_emb, b.prompt + b0, b.x, low, c.d_model, s));
+    if (t > 0 && (rc = run_pass(m, b.chain.dev(), low, 0, false, nullptr, nullptr, s, kNoJoin, 0, 0, t))) return rc;
+    HT_HIP(launch_load_rows(b.x, b.saved_h, low, c.d_model, s));
+    for (int c0 = b0; c0 < n && c0 < b0 + 2 * C; c0 += C) {
+      const int real = n - c0 < C + step ? n - c0 : C + step;
+      int pseudo = last_pseudo - c0 + 1;
+      pseudo = pseudo < 0 ? 0 : pseudo > C ? C : pseudo;
+      if (real != shape_real || pseudo != shape_pseudo) {
+        // hidden rows form a chain; the pseudo row of in-pass position f hangs under hidden row f + step - 1: it then
+        // sees hidden rows 0 .. f + step - 1 and itself and sits at position c0 + f + step (Sec. 3.3)
+        parent.assign(real + pseudo, 0);
+        rows.assign(pseudo > 0 ? pseudo : 1, 0);
+        for (int r = 0; r < real; ++r) parent[r] = r - 1;
+        for (int f = 0; f < pseudo; ++f) {
+          parent[real + f] = f + step - 1;
+          rows[f] = f;
+        }
+        HT_HIP(hipStreamSynchronize(s));       // earlier uploads have left the staging buffer
+        fill_tables(real + pseudo, parent.data(), nullptr, m->h_stage);
+        if ((rc = upload_tables(b.train, m->h_stage, s))) return rc;
+        int32_t* rows_stage = m->h_stage + kTableInts;
+        memcpy(rows_stage, rows.data(), sizeof(int32_t) * rows.size());
+        HT_HIP(hipMemcpyAsync(b.train_rows, rows_stage, sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice, s));
+        shape_real = real;
+        shape_pseudo = pseudo;
       }
-      HT_HIP(hipStreamSynchronize(s));       // earlier uploads have left the staging buffer
-      fill_tables(real + pseudo, parent.data(), nullptr, m->h_stage);
-      if ((rc = upload_tables(b.train, m->h_stage, s))) return rc;
-      int32_t* rows_stage = m->h_stage + kTableInts;
-      memcpy(rows_stage, rows.data(), sizeof(int32_t) * rows.size());
-      HT_HIP(hipMemcpyAsync(b.train_rows, rows_stage, sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice, s));
-      shape_real = real;
-      shape_pseudo = pseudo;
+      m->n = c0;
+      HT_HIP(launch_load_rows(b.saved_h + (size_t)(c0 - b0) * c.d_model, b.x, real, c.d_model, s));
+      if ((rc = run_pass(m, b.train.dev(), real, t, false, b.logits, nullptr, s, pseudo ? kTrainStep : kNoJoin, pseudo,
+                         step - 1)))
+        return rc;
+      int pairs = terms - c0;
+      pairs = pairs < 0 ? 0 : pairs > pseudo ? pseudo : pairs;
+      if (pairs) HT_HIP(launch_kl_rows(b.logits, real, step, pairs, c.vocab, b.kl + c0, s));
+      // the first `step` rows of a later pass were the lookahead of the pass before, whose loss terms used them: the
+      // copy keeps that first version (in bf16 the two passes may round a row differently)
+      const int seen = c0 > 0 ? step : 0;
+      if (logits_hidden_out && real > seen)
+        HT_HIP(hipMemcpyAsync(logits_hidden_out + (size_t)(c0 + seen) * c.vocab, b.logits + (size_t)seen * c.vocab,
+                              sizeof(float) * (real - seen) * c.vocab, hipMemcpyDeviceToDevice, s));
+      if (logits_pseudo_out && pseudo)
+        HT_HIP(hipMemcpyAsync(logits_pseudo_out + (size_t)c0 * c.vocab, b.logits + (size_t)real * c.vocab,
+                              sizeof(float) * pseudo * c.vocab, hipMemcpyDeviceToDevice, s));
+      m->n = c0 + (real < C ? real : C);       // the lookahead rows are overwritten by the next pass
     }
-    HT_HIP(launch_embed(c.dtype, m->tok_emb, b.prompt + c0, b.x, real, c.d_model, s));
-    if ((rc = run_pass(m, b.train.dev(), real, 0, false, b.logits, nullptr, s, pseudo ? kTrainStep : kNoJoin, pseudo,
-                       step - 1)))
-      return rc;
-    int pairs = terms - c0;
-    pairs = pairs < 0 ? 0 : pairs > pseudo ? pseudo : pairs;
-    if (pairs) HT_HIP(launch_kl_rows(b.logits, real, step, pairs, c.vocab, b.kl + c0, s));
-    // the first `step` rows of a later pass were the lookahead of the pass before, whose loss terms used them: the
-    // copy keeps that first version (in bf16 the two passes may round a row differently)
-    const int seen = c0 > 0 ? step : 0;
-    if (logits_hidden_out && real > seen)
-      HT_HIP(hipMemcpyAsync(logits_hidden_out + (size_t)(c0 + seen) * c.vocab, b.logits + (size_t)seen * c.vocab,
-                            sizeof(float) * (real - seen) * c.vocab, hipMemcpyDeviceToDevice, s));
-    if (logits_pseudo_out && pseudo)
-      HT_HIP(hipMemcpyAsync(logits_pseudo_out + (size_t)c0 * c.vocab, b.logits + (size_t)real * c.vocab,
-                            sizeof(float) * pseudo * c.vocab, hipMemcpyDeviceToDevice, s));
-    m->n += real < C ? real : C;             // the lookahead rows are overwritten by the next pass
   }
   float* h_kl = (float*)m->h_stage;
   HT_HIP(hipStreamSynchronize(s));
