@@ -19,6 +19,30 @@ __device__ inline float wave_max(float v) {
   return v;
 }
 
+__device__ inline float wave_max_dpp(float x) {
+  // quads, half rows and rows by data-parallel-primitive moves, then rows and halves of the wave by lane swaps
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true)));    // lanes 1 0 3 2
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true)));    // lanes 2 3 0 1
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true)));   // half row mirrored
+  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true)));   // row mirrored
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  u = __float_as_uint(x);
+  auto r2 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r2[0]), __uint_as_float(r2[1]));
+}
+__device__ inline int wave_min_dpp(int x) {
+  x = min(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true));
+  x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true));
+  x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x141, 0xf, 0xf, true));
+  x = min(x, __builtin_amdgcn_update_dpp(0, x, 0x140, 0xf, 0xf, true));
+  auto r = __builtin_amdgcn_permlane16_swap((unsigned)x, (unsigned)x, false, false);
+  x = min((int)r[0], (int)r[1]);
+  auto r2 = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+  return min((int)r2[0], (int)r2[1]);
+}
+
 // block-wide sum for 256-thread blocks; `red` is __shared__ float[4]
 __device__ inline float block_sum_256(float v, float* red) {
   v = wave_sum(v);
@@ -493,16 +517,108 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ d, 
     __syncthreads();
   }
 }
+// The same two stages with the selection done by wavefronts on register-resident entries: every wavefront of a block
+// takes a quarter of the block's entries (E per lane), picks its best b one by one (a wave-wide maximum by DPP moves,
+// a ballot, the lowest id among equal values), the four lists meet in LDS and the first wavefront picks the best b
+// of them the same way.  No block-wide barrier inside the rounds and no re-reading of the row.  The order is the
+// total order (value descending, id ascending), so the result is that of `topk_kernel` bit for bit.
+constexpr int kNoEntry = 0x7fffffff;       // id of an empty slot: loses against every real entry of the same value
+
+template <int E>
+__device__ inline void wave_select(float (&v)[E], int (&id)[E], int b, float* out_v, int* out_i) {
+  const int lane = threadIdx.x & 63;
+  for (int r = 0; r < b; ++r) {
+    float bv = v[0];
+    int bi = id[0];
+#pragma unroll
+    for (int e = 1; e < E; ++e)
+      if (better(v[e], id[e], bv, bi)) { bv = v[e]; bi = id[e]; }
+    const float top = wave_max_dpp(bv);
+    const bool tie = bv == top;
+    const uint64_t mask = __ballot(tie);
+    int pick;
+    if (mask & (mask - 1)) pick = wave_min_dpp(tie ? bi : kNoEntry);
+    else pick = __builtin_amdgcn_readlane(bi, __builtin_amdgcn_readfirstlane(__builtin_ctzll(mask)));
+    if (lane == 0) { out_v[r] = top; out_i[r] = pick; }
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (id[e] == pick) { v[e] = -INFINITY; id[e] = kNoEntry; }
+  }
+}
+
+template <int E, bool FINAL>
+__global__ __launch_bounds__(256) void topk_wave_kernel(const float* __restrict__ d, const float* __restrict__ sv_in,
+                                                        const int32_t* __restrict__ si_in, float* __restrict__ sv_out,
+                                                        int32_t* __restrict__ si_out, int32_t* __restrict__ cand,
+                                                        const int32_t* __restrict__ width, int period,
+                                                        const int32_t* __restrict__ src_row, int V) {
+  __shared__ float list_v[5][kMaxTopK];
+  __shared__ int list_i[5][kMaxTopK];
+  const int i = blockIdx.x, slice = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int b = width[i % period + 1];      // row i drafts the tree level i % period + 1
+  if (b <= 0) return;                       // uniform over the block
+  int lo, hi;
+  if (FINAL) { lo = 0; hi = kTopkSlices * b; }
+  else {
+    const int per = (V + kTopkSlices - 1) / kTopkSlices;
+    lo = slice * per;
+    hi = lo + per < V ? lo + per : V;
+  }
+  const int quarter = (hi - lo + 3) / 4;
+  const int w0 = lo + wave * quarter, w1 = w0 + quarter < hi ? w0 + quarter : hi;
+  const size_t base = FINAL ? (size_t)i * kTopkSlices * kMaxTopK : (size_t)(src_row ? src_row[i] : i) * V;
+  float v[E];
+  int id[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int j = w0 + lane + 64 * e;
+    v[e] = -INFINITY;
+    id[e] = kNoEntry;
+    if (j < w1) {
+      const float x = FINAL ? sv_in[base + j] : d[base + j];
+      const int xi = FINAL ? si_in[base + j] : j;
+      if (x == x && xi != kNoEntry) { v[e] = x; id[e] = xi; }      // NaN never wins
+    }
+  }
+  wave_select<E>(v, id, b, list_v[wave], list_i[wave]);
+  __syncthreads();
+  if (wave) return;
+  float v2[4];
+  int id2[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    v2[e] = lane < b ? list_v[e][lane] : -INFINITY;
+    id2[e] = lane < b ? list_i[e][lane] : kNoEntry;
+  }
+  wave_select<4>(v2, id2, b, list_v[4], list_i[4]);
+  if (lane < b) {                           // one wavefront: its LDS writes are ordered before these reads
+    if (FINAL) cand[i * kMaxTopK + lane] = list_i[4][lane] == kNoEntry ? 0 : list_i[4][lane];
+    else {
+      sv_out[(size_t)i * kTopkSlices * kMaxTopK + slice * b + lane] = list_v[4][lane];
+      si_out[(size_t)i * kTopkSlices * kMaxTopK + slice * b + lane] = list_i[4][lane];
+    }
+  }
+}
+
 // scratch: float[rows][kTopkSlices][kMaxTopK] followed by int32 of the same shape
 size_t topk_scratch_bytes(int rows) { return (size_t)rows * kTopkSlices * kMaxTopK * 8; }
 hipError_t launch_topk(const float* d, int32_t* cand, const int32_t* width, void* scratch, int rows, int period,
                        const int32_t* src_row, int V, hipStream_t s) {
   float* sv = (float*)scratch;
   int32_t* si = (int32_t*)(sv + (size_t)rows * kTopkSlices * kMaxTopK);
-  hipLaunchKernelGGL(topk_kernel<false>, dim3(rows, kTopkSlices), dim3(256), 0, s, d, nullptr, nullptr, sv, si, cand,
-                     width, period, src_row, V);
-  hipLaunchKernelGGL(topk_kernel<true>, dim3(rows, 1), dim3(256), 0, s, d, sv, si, nullptr, nullptr, cand, width,
-                     period, src_row, V);
+  // entries per lane of the first stage: a quarter of a slice over 64 lanes; of the second: a quarter of
+  // kTopkSlices * b <= 2048 survivors
+  const int per_lane = (((V + kTopkSlices - 1) / kTopkSlices + 3) / 4 + 63) / 64;
+  const dim3 g1(rows, kTopkSlices), g2(rows, 1);
+#define HT_TOPK_ARGS(in_v, in_i, out_v, out_i) d, in_v, in_i, out_v, out_i, cand, width, period, src_row, V
+  if (per_lane <= 4)
+    hipLaunchKernelGGL((topk_wave_kernel<4, false>), g1, dim3(256), 0, s, HT_TOPK_ARGS(nullptr, nullptr, sv, si));
+  else if (per_lane <= 16)
+    hipLaunchKernelGGL((topk_wave_kernel<16, false>), g1, dim3(256), 0, s, HT_TOPK_ARGS(nullptr, nullptr, sv, si));
+  else          // very large vocabularies: block-wide selection, any row length
+    hipLaunchKernelGGL(topk_kernel<false>, g1, dim3(256), 0, s, HT_TOPK_ARGS(nullptr, nullptr, sv, si));
+  hipLaunchKernelGGL((topk_wave_kernel<8, true>), g2, dim3(256), 0, s, HT_TOPK_ARGS(sv, si, nullptr, nullptr));
+#undef HT_TOPK_ARGS
   return hipGetLastError();
 }
 
@@ -565,20 +681,6 @@ hipError_t launch_cand_logprob(const float* d, const int32_t* cand, int rows, in
 // when several lanes hold the best score), and register updates in two lanes: no barrier and no memory traffic
 // inside the walk but the log-probability table in LDS.  Tables and tokens are written by all lanes at the end.
 __device__ inline float not_nan(float v) { return v == v ? v : -INFINITY; }
-
-__device__ inline float wave_max_dpp(float x) {
-  // quads, half rows and rows by data-parallel-primitive moves, then rows and halves of the wave by lane swaps
-  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true)));    // lanes 1 0 3 2
-  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true)));    // lanes 2 3 0 1
-  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true)));   // half row mirrored
-  x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true)));   // row mirrored
-  unsigned u = __float_as_uint(x);
-  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-  u = __float_as_uint(x);
-  auto r2 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(r2[0]), __uint_as_float(r2[1]));
-}
 
 // (depth, path) order of two frontier entries with equal scores
 __device__ inline bool tie_first(int depth_a, uint64_t path_a, int depth_b, uint64_t path_b) {

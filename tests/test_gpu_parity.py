@@ -784,3 +784,21 @@ def test_llama7b_width_two_layers_against_oracle():
     sc.check_prefill()
     r = sc.step(require_same_tokens=False)
     say(f"7B-width 2 layers: emitted {r['emitted']} oracle {r['oracle']['emitted']}")
+
+
+@pytest.mark.parametrize("vocab", [33000, 50000, 140000])
+def test_candidate_selection_on_large_vocabularies(vocab):
+    """Vocabularies past 32768 use the sixteen-entries-per-lane instance of the candidate selection, past 131072 its
+    block-wide fallback: three steps of a very small model, candidates and tokens against the oracle's rule."""
+    H = _H()
+    wl = small_workload(name=f"vocab{vocab}", n_layers=2, d_model=64, n_heads=2, n_kv_heads=1, head_dim=32, d_ffn=72,
+                        vocab=vocab, k=2, transfer_layers=(1, 1), prompt_len=9, max_cache=64, tree_size=12,
+                        branching=(5, 4), seed=31 + vocab)
+    say(f"large vocabulary {vocab}")
+    sc = H.StepCompare(wl)
+    sc.check_prefill()
+    out = []
+    for step in range(3):
+        out += sc.step()["emitted"]
+    assert out == sc.model.ar_greedy(sc.prompt, len(out))
+    sc.gpu.close()
