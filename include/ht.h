@@ -21,8 +21,12 @@
  *     stated otherwise.  One model is used from one stream at a time; calls are not re-entrant.
  *   - Positions are 0-based: the cache holds positions 0..n-1, the tree root sits at position n and a
  *     node of depth e at n+e.  "Layer t" is the residual stream after t complete blocks.
- *   - Return value: HT_OK (0) or a negative error; on error nothing has been enqueued and no state
- *     changed.  `ht_last_error()` gives a thread-local message.  No exception crosses this boundary.
+ *   - Return value: HT_OK (0) or a negative error.  Arguments and state are checked before anything is
+ *     enqueued: HT_EINVAL, HT_ECAPACITY, HT_ETREE, HT_ESTATE and HT_EUNSUPPORTED leave the model and the
+ *     stream as they were.  HT_EHIP reports a failed HIP call, which may come after part of the work was
+ *     enqueued: the model is then in an undefined state and needs a new ht_prefill (ht_decode_steps also
+ *     returns it when the device's own step log is inconsistent).  `ht_last_error()` gives a thread-local
+ *     message.  No exception crosses this boundary.
  */
 #ifndef HT_H_
 #define HT_H_
@@ -122,8 +126,8 @@ int ht_set_dynamic_tree(ht_model *m, int32_t T, int32_t b, void *stream);
  * tree from those rows and needs no `ht_transfer` and no draft pass (an `ht_transfer(m, NULL, NULL, ..)` in
  * between returns at once); if it ends elsewhere the step drafts after acceptance as without this call.
  * Either way the tokens are the same (the two schedules compute the same distributions).
- * nodes: host array of `count` distinct node ids of the current tree, count = 0 switches the feature off;
- * `ht_set_tree` also switches it off.  The pass then has T + count * k rows, which must fit max_tree (and
+ * nodes: host array of `count` distinct node ids of the current tree, count = 0 switches the feature off (always
+ * allowed, also after ht_set_dynamic_tree, where any other count is HT_ESTATE); `ht_set_tree` also switches it off.  The pass then has T + count * k rows, which must fit max_tree (and
  * n + T + count * k must fit max_cache at every step): HT_ECAPACITY otherwise; HT_ETREE for bad ids;
  * HT_ESTATE without a tree. */
 int ht_set_fused_nodes(ht_model *m, int32_t count, const int32_t *nodes /*host*/, void *stream);

@@ -38,8 +38,9 @@ stream after t complete blocks (t = 0 is the embedding output).
 Pins: every function here is pinned by tests/test_oracle_*.py (closed forms, loop-level brute
 force, the causal-path invariant, losslessness against `ar_greedy`, exhaustive acceptance
 search, S1 == S2; the dynamic tree against an exhaustive search over all trees of its size; the
-training forward row by row against single-row passes over stored keys, and for step 1 against
-the inference-time draft).
+training forward row by row against single-row passes over stored keys, for step 1 against
+the inference-time draft, and for every step against the causal logits when the map sends each hidden
+state to the true hidden state of the position it stands for).
 Nothing here is "parity unpinned".
 """
 from __future__ import annotations

@@ -668,7 +668,13 @@ int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* s
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!m->has_tree) return fail(HT_ESTATE, "no tree: call ht_set_tree first");
   if (count < 0 || (count > 0 && !nodes)) return fail(HT_EINVAL, "bad node list");
-  if (m->dyn_b && count) return fail(HT_ESTATE, "a tree chosen anew at every step has no fixed nodes to draft from");
+  if (m->dyn_b) {
+    // the tables belong to the tree of the last step and the host keeps no copy of it: nothing to rebuild
+    if (count) return fail(HT_ESTATE, "a tree chosen anew at every step has no fixed nodes to draft from");
+    m->fused.clear();
+    m->drafts_of = -1;
+    return HT_OK;
+  }
   const ht_config& c = m->cfg;
   const int T = m->T, rows = T + count * c.k;
   if (rows > c.max_tree || rows > kMaxTree)

@@ -24,6 +24,38 @@ def oracle_model(wl: Workload, tensors=None) -> OracleModel:
     return OracleModel(oracle_config(wl), OracleWeights(tensors))
 
 
+class WidenedOnRead:
+    """Stored matrices (one per layer) that are handed out as fp64 copies, made when an entry is read and kept only
+    until another entry is read: the oracle then runs a model whose fp64 copy would not fit the host memory, with its
+    arithmetic untouched (it reads `w.wq[layer]` and gets the same fp64 matrix as from an `OracleWeights`)."""
+
+    def __init__(self, stored):
+        self.stored, self.at, self.wide = list(stored), None, None
+
+    def __len__(self):
+        return len(self.stored)
+
+    def __getitem__(self, layer):
+        if self.at != layer:
+            self.wide = None
+            self.wide = self.stored[layer].detach().to("cpu").double().numpy()
+            self.at = layer
+        return self.wide
+
+
+def layerwise_oracle_model(wl: Workload, tensors) -> OracleModel:
+    """`oracle_model` for a model too large to widen at once: the seven projections of a block are widened to fp64
+    when the oracle reaches that block; embedding, head, gains and transfer maps are widened up front."""
+    small = {k: v for k, v in tensors.items()}
+    heavy = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+    for name in heavy:
+        small[name] = []
+    w = OracleWeights(small)
+    for name in heavy:
+        setattr(w, name, WidenedOnRead(tensors[name]))
+    return OracleModel(oracle_config(wl), w)
+
+
 def prompt_of(wl: Workload, length=None):
     return [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, length or wl.prompt_len, wl.vocab)]
 

@@ -240,6 +240,9 @@ def test_switching_between_fixed_and_chosen_trees_and_error_codes():
     with pytest.raises(B.HTError) as e:
         gpu.ht_set_fused_nodes([0])
     assert e.value.code == B.HT_ESTATE
+    before = gpu.ht_get_buffer(B.HT_BUF_TREE_PARENT).tolist()
+    gpu.ht_set_fused_nodes([])                                       # switching it off is always allowed and changes nothing
+    assert gpu.ht_get_buffer(B.HT_BUF_TREE_PARENT).tolist() == before
     gpu.ht_transfer(None, None)
     with pytest.raises(B.HTError) as e:
         gpu.ht_tree_verify_step(torch.zeros(7, dtype=torch.int32, device=DEV), None, None)

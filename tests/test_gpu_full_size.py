@@ -1,8 +1,9 @@
 """Full-size checks of the HIP path in the launch configuration the benchmark times (llama7b workload:
 32 layers, cache 512, 64-node tree), through the C ABI.  Needs a real MI355X.
 
-A 32-layer fp64 oracle pass at this size takes far too long on the host, so these tests use properties that
-hold at any size and need no oracle values:
+The first test holds one whole step (prefill of 512 tokens, draft pass, 64-node verify pass at all 32 layers)
+against the fp64 oracle at the stated bf16 tolerance; the oracle widens the weights of one block at a time.  The
+others use properties that hold at any size and need no oracle values:
 
 * Sec. 3.4.1 (tree attention): the logits of a tree node equal those of a plain causal pass over the tokens
   on its root-to-node path.  The plain pass here is the library's own one-token decode step (a different
@@ -40,6 +41,38 @@ def _rank0_chain(parent, rank):
             return chain
         cur = kids[0]
         chain.append(cur)
+
+
+def test_llama7b_full_depth_step_against_the_oracle():
+    """Config 3 as the benchmark runs it (32 layers, 512 cached tokens, 64-node tree, k = 3 after layer 24) against
+    the fp64 oracle: prefill state, draft logits, all 64 verify-logit rows (Sec. 3.4.1: a node's logits are those of
+    the causal pass over its path), greedy tokens, acceptance, and the K cache of every fourth layer, whose error
+    shows how the bf16 rounding grows with depth."""
+    from helpers import layerwise_oracle_model
+    B, H = _mods()
+    wl = WORKLOADS["llama7b"].with_(max_cache=640)
+    T = wl.tree_size
+    say("7B full depth vs oracle: generating weights")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    say("7B full depth vs oracle: oracle prefill of 512 tokens through 32 blocks + GPU prefill")
+    sc = H.StepCompare(wl, tensors_gpu=tensors, model=layerwise_oracle_model(wl, cpu_tensors))
+    del tensors
+    n = sc.ora.n
+    curve = []
+    for layer in list(range(0, wl.n_layers, 4)) + [wl.n_layers - 1]:
+        kc = H.cpu(sc.gpu.ht_get_buffer(B.HT_BUF_K_CACHE, layer))[:n]
+        curve.append((layer, H.within_bf16(kc, sc.ora.K[layer][:n])[1]))
+    say("  K cache of the prompt, worst error / bound by layer: " + ", ".join(f"{l}: {r:.3f}" for l, r in curve))
+    sc.check_prefill()
+    say("7B full depth vs oracle: one step (draft pass, 64-node verify pass)")
+    r = sc.step(require_same_tokens=False)
+    say(f"  emitted {r['emitted']} oracle {r['oracle']['emitted']}; verify passes compared {sc.verify_passes_compared} "
+        f"({sc.steps_on_gpu_tree} on the GPU's own tree); worst logit error / bound {sc.max_err:.3f}")
+    assert sc.verify_passes_compared == 1
+    if r["emitted"] == r["oracle"]["emitted"]:
+        sc.check_cache("after the step", layers=(0, wl.transfer_layers[0], wl.n_layers - 1))
+    sc.gpu.close()
 
 
 def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_accepted():

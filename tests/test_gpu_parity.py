@@ -194,6 +194,12 @@ def test_tree_attention_at_the_op_workload_size():
                     a["seed"], cap=a["cache_len"] + a["tree_size"], base=a["rope_base"])
 
 
+def test_tree_attention_grouped_queries_over_a_long_cache():
+    """The 70B-shaped attention: 64 query heads on 8 key/value heads, 4096 cached keys, a 64-node tree."""
+    say("attention bf16 Hq 64 / Hkv 8, n = 4096, T = 64")
+    _attention_case("bf16", 64, 4096, 64, 8, 128, random_tree(70, 64, 4)[0], 70, cap=4160)
+
+
 # ------------------------------------------------------------------ end to end, tiny model
 @pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_full7", "tiny_t123", "tiny_t112"])
 def test_tiny_fp32_sixteen_steps_match_oracle_and_greedy(name):
@@ -554,7 +560,10 @@ def test_tiny_bf16_sixteen_steps(name, fused):
         same += r["emitted"] == r["oracle"]["emitted"]
         if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
             break                                                   # sequences diverged at a near-tie: stop comparing
-    assert same >= 4
+    say(f"{name}: {same} steps with the oracle's tokens, {sc.verify_passes_compared} verify passes compared "
+        f"({sc.steps_on_gpu_tree} on the GPU's own tree), worst logit error / bound {sc.max_err:.3f}")
+    assert same >= 4 and sc.verify_passes_compared >= same
+    sc.gpu.close()
 
 
 @pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_bf16", "tiny_t123"])
@@ -748,7 +757,11 @@ def _shallow_case(name, prompt_len, tree_size=None, cache=None, fused_chain=Fals
         say(f"{name}: emitted {r['emitted']} oracle {r['oracle']['emitted']} worst logit error / bound {sc.max_err:.3f}")
         if r["emitted"] != r["oracle"]["emitted"] or r["root"] != r["oracle"]["root"]:
             break                                       # a bf16 near-tie sent the two sequences apart: stop comparing
-    sc.check_cache("after the steps")
+    else:
+        sc.check_cache("after the steps")
+    say(f"{name}: verify passes with all {T} logit rows held against the oracle: {sc.verify_passes_compared} "
+        f"({sc.steps_on_gpu_tree} on the GPU's own tree)")
+    assert sc.verify_passes_compared >= 1
     if fused_chain:
         say(f"{name}: {sc.steps_without_draft_pass} step(s) built their tree from in-pass drafts")
         assert sc.steps_without_draft_pass >= 1
@@ -758,6 +771,11 @@ def _shallow_case(name, prompt_len, tree_size=None, cache=None, fused_chain=Fals
 @pytest.mark.parametrize("tree_size", [1, 16, 32, 64, 128])
 def test_llama13b_width_tree_size_sweep(tree_size):
     _shallow_case("llama13b", 96, tree_size=tree_size)
+
+
+def test_llama13b_width_at_the_full_cache_length():
+    """Config 4 at its own cache length: 2048 cached tokens (the key-slice paths of both attention kernels), T = 64."""
+    _shallow_case("llama13b", 2048, cache=2048 + 2 * 64 + 16)
 
 
 def test_llama70b_width_grouped_query_attention():
@@ -783,7 +801,10 @@ def test_llama7b_width_two_layers_against_oracle():
     sc = H.StepCompare(wl, tensors_gpu=tensors, tensors_cpu=cpu_tensors)
     sc.check_prefill()
     r = sc.step(require_same_tokens=False)
-    say(f"7B-width 2 layers: emitted {r['emitted']} oracle {r['oracle']['emitted']}")
+    say(f"7B-width 2 layers: emitted {r['emitted']} oracle {r['oracle']['emitted']}, verify passes compared "
+        f"{sc.verify_passes_compared}, worst logit error / bound {sc.max_err:.3f}")
+    assert sc.verify_passes_compared == 1
+    sc.gpu.close()
 
 
 @pytest.mark.parametrize("vocab", [33000, 50000, 140000])

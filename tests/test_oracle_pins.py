@@ -376,3 +376,37 @@ def test_training_forward_of_step_one_is_the_draft_of_inference():
         dec.prefill(toks[:j + 1])
         d = dec.draft(dec.transfer())
         assert np.max(np.abs(d[0] - res["Zp"][j])) < 1e-9
+
+
+@pytest.mark.parametrize("layers", [(1, 1, 1), (0, 1, 2)])
+def test_training_forward_fed_true_hidden_states_reproduces_the_causal_logits(layers):
+    """Mask and position id of the pseudo states, pinned without typing them again: with a map that sends every
+    hidden state h_j to the true hidden state of position j + i (solved for, the h_j being linearly independent),
+    pseudo state j is the real state of position j + i at position id j + i seeing positions 0 .. j+i-1 and itself,
+    i.e. the causal pass, so its logits must be those of position j + i and every loss term must vanish (Sec. 3.3).
+    The same map used for another step (wrong offset between position and content) must not do that."""
+    wl = small_workload(k=3, n_layers=3, transfer_layers=layers, d_model=16)
+    model = oracle_model(wl, make_weights(wl, wl.seed, sigma=0.4))
+    n = 9
+    toks = [int(t) for t in counter_tokens(wl.seed, 1, n, wl.vocab)]
+    z_causal, hidden, _, _ = model.causal_forward(toks)
+    for i in (1, 2, 3):
+        h = hidden[layers[i - 1]]
+        src, dst = h[:n - i], h[i:]                                  # W src_j = dst_j for j = 0 .. n-i-1
+        assert np.linalg.matrix_rank(src) == n - i
+        w_true = np.linalg.lstsq(src, dst, rcond=None)[0].T
+        assert np.max(np.abs(src @ w_true.T - dst)) < 1e-9
+        kept = model.w.w_transfer[i - 1]
+        model.w.w_transfer[i - 1] = w_true
+        res = O.training_forward(model, toks, i)
+        assert np.max(np.abs(res["Zp"][:n - i] - z_causal[i:])) < 1e-7, i
+        assert np.max(np.abs(res["kl"])) < 1e-12
+        other = i % 3 + 1                                            # the map of step i under the position ids of another step
+        if layers[other - 1] == layers[i - 1]:
+            kept_other = model.w.w_transfer[other - 1]
+            model.w.w_transfer[other - 1] = w_true
+            off = O.training_forward(model, toks, other)
+            m = n - max(i, other)
+            assert np.max(np.abs(off["Zp"][:m] - z_causal[i:i + m])) > 1e-4
+            model.w.w_transfer[other - 1] = kept_other
+        model.w.w_transfer[i - 1] = kept
