@@ -289,6 +289,19 @@ int ht_gate_up_silu_packed(const void *a, const void *packed, int32_t M, int32_t
 int ht_skinny_gemm_packed(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
                           void *scratch, size_t scratch_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP-graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): `ht_skinny_gemm_packed` without a scratch argument.  The split-K partial sums go to a
+ * device array of HT_NOALLOC_SCRATCH_BYTES that is part of the library image (every GPU the library runs on holds
+ * its own copy until the process ends); the call allocates and frees nothing.  Same kernels, same K split and
+ * therefore the same bits as `ht_skinny_gemm_packed` given enough scratch.  HT_ECAPACITY when the partial sums
+ * (K splits x M x N x 4 bytes; shapes that need no split always fit) exceed the array; HT_EINVAL as for
+ * `ht_skinny_gemm_packed`.  All calls on one GPU share that GPU's array, which keeps the last call's contents
+ * (every element is written before it is read, so nothing is cleared): calls that overlap in time on one GPU,
+ * from two streams or two threads, race; calls on one stream are safe back to back. */
+#define HT_NOALLOC_SCRATCH_BYTES (16u << 20)
+int ht_skinny_gemm_packed_noalloc(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
+                                  void *stream);
+
 /* Measurement aid for the roofline (Sec. 1: decoding time is the time to load the parameters): reads `buf`
  * (device, 16-byte aligned) once with the access pattern of the packed weight stream (256 workgroups, each
  * walking its own contiguous region in nontemporal 1 KiB wavefront loads) and does nothing else, so its time is

@@ -27,7 +27,7 @@ EXPORTS = [
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
     "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
     "ht_gate_up_pack", "ht_gate_up_silu_packed", "ht_set_dynamic_tree", "ht_candidate_logprobs", "ht_dynamic_tree",
-    "ht_training_forward", "ht_kl_divergence_rows",
+    "ht_training_forward", "ht_kl_divergence_rows", "ht_skinny_gemm_packed_noalloc",
 ]
 
 
@@ -95,6 +95,7 @@ def _load() -> C.CDLL:
         "ht_weight_pack_bytes": (sz, [C.c_int32, C.c_int32]),
         "ht_weight_pack": (C.c_int, [vp, C.c_int32, C.c_int32, vp, vp]),
         "ht_skinny_gemm_packed": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, sz, vp]),
+        "ht_skinny_gemm_packed_noalloc": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -171,6 +172,13 @@ def ht_weight_pack(w, N, K, packed, stream=None) -> None:
 def ht_skinny_gemm_packed(a, packed, M, N, K, out, scratch=None, stream=None) -> None:
     sb = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.ht_skinny_gemm_packed(_ptr(a), _ptr(packed), M, N, K, _ptr(out), _ptr(scratch), sb, _stream_ptr(stream)))
+
+
+HT_NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def ht_skinny_gemm_packed_noalloc(a, packed, M, N, K, out, stream=None) -> None:
+    _check(lib.ht_skinny_gemm_packed_noalloc(_ptr(a), _ptr(packed), M, N, K, _ptr(out), _stream_ptr(stream)))
 
 
 def ht_gate_up_pack(w_gate, w_up, f, K, packed, stream=None) -> None:

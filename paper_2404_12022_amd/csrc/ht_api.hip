@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 using namespace ht;
@@ -1186,6 +1187,61 @@ int ht_skinny_gemm_packed(const void* a, const void* packed, int32_t M, int32_t 
     HT_HIP(launch_gemm_packed(a, pw, M, (float*)scratch, sp, s));
     HT_HIP(launch_reduce_splits((const float*)scratch, sp, (size_t)M * N, out, s));
   }
+  return HT_OK;
+}
+
+// ---- the packed product for callers that cannot allocate --------------------------------------------------------
+// Split-K partial sums live in a device array of the library's own instead of a caller's scratch buffer.  Every
+// GPU holds its own copy of the array at its own address: the address is asked for once per device, with that
+// device current, and only that pointer (never the array's name) reaches kernels.
+}  // extern "C" (reopened below the file-scope state)
+
+namespace {
+constexpr size_t kNoAllocScratchBytes = HT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each GPU, filled on first use
+
+int noalloc_scratch(float** out) {
+  int dev = -1;
+  HT_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(HT_EUNSUPPORTED, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(HT_EHIP, "the library's scratch array has no address on device %d", dev);
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return HT_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int ht_skinny_gemm_packed_noalloc(const void* a, const void* packed, int32_t M, int32_t N, int32_t K, float* out,
+                                  void* stream) {
+  if (!a || !packed || !out) return fail(HT_EINVAL, "NULL argument");
+  if (M < 1 || M > kMaxTree || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  hipStream_t s = (hipStream_t)stream;
+  PackedW pw{(const bf16_t*)packed, N, K, packed_cols(K)};
+  const int sp = gemm_mfma_splits(M, N, K);          // the same split as ht_skinny_gemm_packed with enough scratch
+  if (sp == 1) {
+    HT_HIP(launch_gemm_packed(a, pw, M, out, 1, s));
+    return HT_OK;
+  }
+  const size_t need = (size_t)sp * M * N * sizeof(float);
+  if (need > kNoAllocScratchBytes)
+    return fail(HT_ECAPACITY, "%d K splits of %d x %d partial sums need %zu bytes, the library's own scratch holds %zu",
+                sp, M, N, need, kNoAllocScratchBytes);
+  float* part = nullptr;
+  int rc = noalloc_scratch(&part);
+  if (rc) return rc;
+  // every partial sum [split][m < M][n < N] is written before it is read: nothing has to start at zero
+  HT_HIP(launch_gemm_packed(a, pw, M, part, sp, s));
+  HT_HIP(launch_reduce_splits(part, sp, (size_t)M * N, out, s));
   return HT_OK;
 }
 

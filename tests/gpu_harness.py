@@ -17,6 +17,16 @@ FP32_LOGIT_TOL = 1e-4          # max-abs, fp32 model
 BF16_REL_TOL = 3e-2            # bf16 model: per row, max|a-b| <= tol * max|b| and ||a-b|| <= tol * ||b||
 
 
+def bf16_tol_after(blocks: int) -> float:
+    """The bf16 bound for a value that has come through `blocks` decoder blocks of rounded activations.  Every block
+    rounds its normalised rows, q, K, V, the attention output and the feed-forward activations to bf16 (2^-9
+    relative each), and those errors add up like a random walk over the depth: measured on the 7B shape against
+    the fp64 oracle, the worst row's error is 0.55 sqrt(blocks) times the one-block bound BF16_REL_TOL (1.1 x at
+    4 blocks, 2.3 x at 16, 3.0 x at 32).  The bound is that curve with a third of headroom, and never below the
+    plain tolerance, which is what every test of up to three blocks uses."""
+    return BF16_REL_TOL * max(1.0, 0.75 * float(np.sqrt(blocks)))
+
+
 def within_bf16(got: np.ndarray, want: np.ndarray, tol=BF16_REL_TOL):
     """bf16 criterion, per row (last axis): max-abs error <= tol * max-abs reference, and relative L2 error <= tol.
     Returns (ok, worst error / bound)."""
@@ -86,6 +96,7 @@ class StepCompare:
         self.g_gpu = torch.empty(self.T, dtype=torch.int32, device=DEV)
         self.min_margin = float("inf")
         self.max_err = 0.0          # largest logit error seen (fp32: absolute; bf16: fraction of the bound)
+        self.tol = None             # bf16 bound of the float comparisons (None: BF16_REL_TOL); fp32 models ignore it
         self.verify_passes_compared = 0     # verify passes whose T logit rows were all held against the oracle
         self.steps_on_gpu_tree = 0          # of those, passes in which the oracle verified the GPU's tree, not its own
 
@@ -98,7 +109,7 @@ class StepCompare:
             # differ; either token is then a legitimate outcome and the comparison goes on from the GPU's
             assert wl.dtype != "f32", f"prefill root {root}, oracle {self.ora.root}"
             z = self.model.causal_forward(self.prompt)[0][-1]
-            gap, bound = float(z[self.ora.root] - z[root]), 2 * BF16_REL_TOL * float(np.max(np.abs(z)))
+            gap, bound = float(z[self.ora.root] - z[root]), 2 * (self.tol or BF16_REL_TOL) * float(np.max(np.abs(z)))
             print(f"prefill root {root} vs oracle {self.ora.root}: exact logit gap {gap:.3e}, bf16 bound {bound:.3e}",
                   flush=True)
             assert 0 <= gap <= bound, f"prefill root {root} vs {self.ora.root}: logit gap {gap:.3e} above {bound:.3e}"
@@ -106,7 +117,7 @@ class StepCompare:
         for slot, t in enumerate(sorted(set(wl.transfer_layers))):
             h = cpu(self.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC, slot))
             assert_close(h, self.ora.h_src[t], wl.dtype, f"prefill transfer source of layer {t}",
-                         tol=None if wl.dtype != "f32" else 1e-4)
+                         tol=self.tol if wl.dtype != "f32" else 1e-4)
         self.check_cache("prefill")
 
     def check_cache(self, what, layers=None):
@@ -114,8 +125,9 @@ class StepCompare:
         for layer in layers or (0, wl.n_layers - 1):
             kc = cpu(self.gpu.ht_get_buffer(B.HT_BUF_K_CACHE, layer))[:n]
             vc = cpu(self.gpu.ht_get_buffer(B.HT_BUF_V_CACHE, layer))[:, :, :n]
-            assert_close(kc, self.ora.K[layer][:n], wl.dtype, f"{what}: K cache layer {layer}")
-            assert_close(np.transpose(vc, (2, 0, 1)), self.ora.V[layer][:n], wl.dtype, f"{what}: V cache layer {layer}")
+            tol = self.tol if wl.dtype != "f32" else None
+            assert_close(kc, self.ora.K[layer][:n], wl.dtype, f"{what}: K cache layer {layer}", tol=tol)
+            assert_close(np.transpose(vc, (2, 0, 1)), self.ora.V[layer][:n], wl.dtype, f"{what}: V cache layer {layer}", tol=tol)
 
     def step(self, forced=None, require_same_tokens=True):
         """One step on both sides.  The oracle drafts its own tree; the verify pass, however, is always compared on
@@ -123,6 +135,7 @@ class StepCompare:
         than the oracle's, the oracle verifies the GPU's tree (any tree keeps the output greedy, Sec. 4.1), so all
         T logit rows are compared in every step and `verify_passes_compared` counts them."""
         wl, ora, gpu = self.wl, self.ora, self.gpu
+        ftol = self.tol if wl.dtype != "f32" else None
         pseudo_o = ora.transfer()
         d_o = ora.draft(pseudo_o)
         cand_o = ora.candidates(d_o)
@@ -145,12 +158,12 @@ class StepCompare:
         g = [int(t) for t in self.g_gpu.cpu()]
         if forced is None:
             if drafts is None:
-                assert_close(cpu(pseudo), np.stack(pseudo_o), wl.dtype, "pseudo hidden states")
+                assert_close(cpu(pseudo), np.stack(pseudo_o), wl.dtype, "pseudo hidden states", tol=ftol)
                 d = cpu(gpu.ht_get_buffer(B.HT_BUF_DRAFT_LOGITS))
                 cand = gpu.ht_get_buffer(B.HT_BUF_CANDIDATES).cpu().numpy()
             else:
                 d, cand = drafts
-            self.max_err = max(self.max_err, assert_close(d, d_o, wl.dtype, "draft logits"))
+            self.max_err = max(self.max_err, assert_close(d, d_o, wl.dtype, "draft logits", tol=ftol))
             # integer stages: the oracle's rules applied to the GPU's own logits must give the GPU's integers
             want_cand = [[]] + [O.top_candidates(d[e - 1], ora.width[e]) for e in range(1, len(ora.width))]
             for e in range(1, len(ora.width)):
@@ -169,12 +182,12 @@ class StepCompare:
             self.steps_on_gpu_tree += 1
         # the oracle verifies the tree the GPU verified (its own, unless a near-tie changed a candidate)
         z_o, g_o, saved = ora.verify(tok_gpu)
-        self.max_err = max(self.max_err, assert_close(z, z_o, wl.dtype, "verify logits"))
+        self.max_err = max(self.max_err, assert_close(z, z_o, wl.dtype, "verify logits", tol=ftol))
         self.verify_passes_compared += 1
         assert g == [int(j) for j in np.argmax(z, axis=1)], "row arg-max of the GPU's own logits"
         if wl.dtype != "f32":
             for v in range(self.T):                      # another greedy token only where the exact logits nearly tie
-                gap, bound = float(z_o[v][g_o[v]] - z_o[v][g[v]]), 2 * BF16_REL_TOL * float(np.max(np.abs(z_o[v])))
+                gap, bound = float(z_o[v][g_o[v]] - z_o[v][g[v]]), 2 * (ftol or BF16_REL_TOL) * float(np.max(np.abs(z_o[v])))
                 assert 0 <= gap <= bound, f"node {v}: greedy token {g[v]} vs {g_o[v]}, logit gap {gap:.3e} above {bound:.3e}"
         top2 = np.sort(z_o, axis=1)[:, -2:]
         self.min_margin = min(self.min_margin, float(np.min(top2[:, 1] - top2[:, 0])))
