@@ -43,7 +43,8 @@ typedef struct ht_model ht_model; /* opaque, host side, owned by the library */
 enum { HT_OK = 0, HT_EINVAL = -1, HT_ECAPACITY = -2, HT_ETREE = -3, HT_ESTATE = -4, HT_EHIP = -5,
        HT_EUNSUPPORTED = -6 };
 enum { HT_F32 = 0, HT_BF16 = 1 };
-enum { HT_MAX_TRANSFER = 8, HT_MAX_TREE = 128, HT_MAX_TOPK = 64 };
+enum { HT_MAX_TRANSFER = 8, HT_MAX_TREE = 128 /* nodes of a tree */, HT_MAX_ROWS = 256 /* rows of a pass */,
+       HT_MAX_TOPK = 64 };
 
 /* Llama-style decoder shape plus the hidden-transfer hyper-parameters (Sec. 3.3: the number of
  * transfer steps k and the transfer layers t_i; Sec. 4.1 uses a different layer for every step).  The layers must
@@ -57,7 +58,9 @@ typedef struct {
   int32_t transfer_layer[HT_MAX_TRANSFER];   /* 1 <= t_1 <= .. <= t_k < n_layers: residual after t_i blocks */
   int32_t max_cache;                         /* KV slots per layer (multiple of 8) */
   int32_t max_tree;                          /* most rows of a pass: tree nodes (root included) plus pseudo
-                                                rows riding in the verify pass; <= HT_MAX_TREE */
+                                                rows riding in the verify pass; <= HT_MAX_ROWS (a tree itself has
+                                                at most HT_MAX_TREE nodes).  Projections run 128 rows per launch:
+                                                a pass of more rows streams the weights twice. */
 } ht_config;
 
 /* Borrowed weight pointers (device).  They must outlive the model.  Per-layer arrays are host arrays
@@ -98,7 +101,7 @@ int ht_init_model(const ht_config *cfg, const ht_weights *weights, void *workspa
 int ht_free_model(ht_model *m);
 
 /* Static candidate tree (Sec. 3.4.1 "pre-defined tree structure"): T nodes, root included.
- * parent[0] = -1, 0 <= parent[v] < v, depth <= k; rank[v] (v >= 1) selects the rank-th best candidate
+ * T <= min(max_tree, HT_MAX_TREE); parent[0] = -1, 0 <= parent[v] < v, depth <= k; rank[v] (v >= 1) selects the rank-th best candidate
  * of pseudo position depth[v], 0 <= rank < HT_MAX_TOPK, distinct among siblings.  Host arrays, copied
  * before return.  HT_ETREE if malformed. */
 int ht_set_tree(ht_model *m, int32_t T, const int32_t *parent /*host*/, const int32_t *rank /*host*/, void *stream);
@@ -114,7 +117,7 @@ int ht_set_tree(ht_model *m, int32_t T, const int32_t *parent /*host*/, const in
  * From this call on `ht_tree_verify_step(tree_tokens = NULL)` and `ht_decode_steps` build it on the device before
  * each verify pass (views HT_BUF_TREE_PARENT, HT_BUF_TREE_RANK, HT_BUF_CANDIDATE_LOGPROBS show the last one);
  * forced tree tokens and `ht_set_fused_nodes` are HT_ESTATE in this mode; `ht_set_tree` returns to a fixed tree.
- * HT_ETREE unless 1 <= T <= max_tree, 1 <= b <= HT_MAX_TOPK and T - 1 <= b + b^2 + .. + b^k. */
+ * HT_ETREE unless 1 <= T <= min(max_tree, HT_MAX_TREE), 1 <= b <= HT_MAX_TOPK and T - 1 <= b + b^2 + .. + b^k. */
 int ht_set_dynamic_tree(ht_model *m, int32_t T, int32_t b, void *stream);
 
 /* Draft inside the verify pass (Fig. 2 caption and the end of Sec. 3.4: one forward verifies the current
@@ -245,7 +248,7 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
                       int32_t hd, int32_t dtype, float rope_base, void *out, void *scratch, size_t scratch_bytes,
                       void *stream);
 
-/* Skinny weight-streaming product out[M, N] (float32) = a[M, K] . w[N, K]^T with M <= HT_MAX_TREE rows,
+/* Skinny weight-streaming product out[M, N] (float32) = a[M, K] . w[N, K]^T with M <= HT_MAX_ROWS rows,
  * the contraction every projection of the verify step uses (Sec. 1: decoding time goes to loading the
  * parameters).  a must be readable up to ht_padded_rows(M) rows.
  *   ht_weight_pack        : bf16 w[N, K] (N % 16 == 0, K % 8 == 0) -> the library's streaming layout
@@ -261,13 +264,13 @@ int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void 
  *   ht_gate_up_silu_packed: the feed-forward block's first half as the verify pass runs it, one kernel:
  *                           act_out[M, f] (bf16) = silu(a . w_gate^T) * (a . w_up^T), a bf16 [M, K], fp32 sums.
  *                           The largest projection of a decoder block, hence the kernel bench.py takes the
- *                           roofline of.  HT_EINVAL on NULL pointers, M outside 1..HT_MAX_TREE or bad f, K. */
+ *                           roofline of.  HT_EINVAL on NULL pointers, M outside 1..HT_MAX_ROWS or bad f, K. */
 /* The two steps of `ht_set_dynamic_tree`'s rule on their own (all pointers DEVICE).
  * ht_candidate_logprobs: d [rows, V] float32 logits, cand [rows, HT_MAX_TOPK] token ids of which the first b per row
  *   are read; lp [rows, HT_MAX_TOPK]: lp[i][r] = d[i][cand[i][r]] - log(sum_v exp d[i][v]) for r < b.
- *   HT_EINVAL unless 1 <= rows <= HT_MAX_TREE, 1 <= b <= HT_MAX_TOPK, V >= 1.
+ *   HT_EINVAL unless 1 <= rows <= HT_MAX_ROWS, 1 <= b <= HT_MAX_TOPK, V >= 1.
  * ht_dynamic_tree: lp, cand [k, HT_MAX_TOPK] (first b per row read), root [1]; writes parent, depth, rank [T],
- *   anc [T, HT_MAX_TREE / 64] (bit u of row v: u is v or an ancestor of v) and tokens [T] (the root token, then
+ *   anc [T, HT_MAX_ROWS / 64] (bit u of row v: u is v or an ancestor of v) and tokens [T] (the root token, then
  *   cand[depth - 1][rank] of every node).  HT_EINVAL / HT_ETREE as for `ht_set_dynamic_tree`. */
 /* The loss term of `ht_training_forward` on its own (all pointers DEVICE): z holds rows of V float32 logits;
  * kl[p] = KL(softmax(z[row_a + p]) || softmax(z[row_b + p])) for p < pairs, the first argument weighting the log

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libht.so")
 
 HT_OK, HT_EINVAL, HT_ECAPACITY, HT_ETREE, HT_ESTATE, HT_EHIP, HT_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 HT_F32, HT_BF16 = 0, 1
-HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_TOPK = 8, 128, 64
+HT_MAX_TRANSFER, HT_MAX_TREE, HT_MAX_ROWS, HT_MAX_TOPK = 8, 128, 256, 64
 HT_MAX_LOOP_STEPS = 64
 (HT_BUF_DRAFT_LOGITS, HT_BUF_CANDIDATES, HT_BUF_TREE_TOKENS, HT_BUF_SAVED_HIDDEN, HT_BUF_TRANSFER_SRC,
  HT_BUF_K_CACHE, HT_BUF_V_CACHE, HT_BUF_PSEUDO, HT_BUF_ROOT, HT_BUF_FUSED_DRAFT_LOGITS,
@@ -201,7 +201,7 @@ def ht_candidate_logprobs(d, cand, b, lp, stream=None) -> None:
 
 def ht_dynamic_tree(lp, cand, root, k, b, T, parent, depth, rank, anc, tokens, stream=None) -> None:
     """All arguments but k, b, T are device tensors: lp, cand [k, HT_MAX_TOPK], root [1]; outputs parent, depth, rank,
-    tokens [T] int32 and anc [T, HT_MAX_TREE // 64] int64."""
+    tokens [T] int32 and anc [T, HT_MAX_ROWS // 64] int64."""
     _check(lib.ht_dynamic_tree(_ptr(lp), _ptr(cand), _ptr(root), k, b, T, _ptr(parent), _ptr(depth), _ptr(rank),
                                _ptr(anc), _ptr(tokens), _stream_ptr(stream)))
 

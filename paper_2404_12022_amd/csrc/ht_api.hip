@@ -34,7 +34,7 @@ int fail(int code, const char* fmt, ...) {
 size_t elem_size(int dtype) { return dtype == HT_F32 ? 4 : 2; }
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int padded_rows(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128; }
+int padded_rows(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256; }
 
 // Bump allocator over the workspace; with base == nullptr it only measures.
 struct Carver {
@@ -78,8 +78,8 @@ struct Buffers {
   float* lp;           // log-probabilities of the candidates of the last draft [kMaxTransfer][kMaxTopK] (dynamic tree)
   int32_t *tok, *g, *cand, *width, *prompt;
   int32_t* fused_rows;   // tree nodes that get pseudo rows inside the verify pass [kMaxTree]
-  int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK]
-  int32_t* fused_src;    // logits row (past the tree rows) that holds the draft of (fused node, step) [kMaxTree]
+  int32_t* cand_fused;   // their candidates [fused node][k][kMaxTopK], at most kMaxRows (node, step) pairs
+  int32_t* fused_src;    // logits row (past the tree rows) that holds the draft of (fused node, step) [kMaxRows]
   TreeTables tree, chain, train;   // the decoding tree; a chain (prefill, draft pass); the rows of a training pass
   StepState* state;
   StepLog* log;        // steps of the device-resident loop [kMaxLoopSteps]
@@ -128,20 +128,20 @@ void carve(const ht_config& c, Carver& cv, Buffers& b) {
   b.width = cv.take<int32_t>(kMaxTransfer + 2);
   b.prompt = cv.take<int32_t>(c.max_cache);
   b.fused_rows = cv.take<int32_t>(kMaxTree);
-  b.cand_fused = cv.take<int32_t>((size_t)kMaxTree * kMaxTopK);
-  b.fused_src = cv.take<int32_t>(kMaxTree);
+  b.cand_fused = cv.take<int32_t>((size_t)kMaxRows * kMaxTopK);
+  b.fused_src = cv.take<int32_t>(kMaxRows);
   for (TreeTables* t : {&b.tree, &b.chain, &b.train}) {
-    t->parent = cv.take<int32_t>(kMaxTree);
-    t->depth = cv.take<int32_t>(kMaxTree);
-    t->rank = cv.take<int32_t>(kMaxTree);
-    t->anc = cv.take<uint64_t>((size_t)kMaxTree * kMaskWords);
+    t->parent = cv.take<int32_t>(kMaxRows);
+    t->depth = cv.take<int32_t>(kMaxRows);
+    t->rank = cv.take<int32_t>(kMaxRows);
+    t->anc = cv.take<uint64_t>((size_t)kMaxRows * kMaskWords);
   }
   b.state = cv.take<StepState>(1);
   b.log = cv.take<StepLog>(kMaxLoopSteps);
   b.kc_ptrs = cv.take<void*>(c.n_layers);
   b.vc_ptrs = cv.take<void*>(c.n_layers);
   b.wt_ptrs = cv.take<void*>(kMaxTransfer);
-  b.topk_scratch = cv.take_bytes(topk_scratch_bytes(kMaxTree));
+  b.topk_scratch = cv.take_bytes(topk_scratch_bytes(kMaxRows));
   b.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes((int)Mp, c.n_heads, c.head_dim));
   b.kc.resize(c.n_layers);
   b.vc.resize(c.n_layers);
@@ -184,7 +184,7 @@ int check_config(const ht_config* c) {
     if (i && c->transfer_layer[i] < c->transfer_layer[i - 1])
       return fail(HT_EINVAL, "transfer layers must not decrease (t_1 <= t_2 <= ..)");
   }
-  if (c->max_tree < 1 || c->max_tree > HT_MAX_TREE) return fail(HT_EINVAL, "max_tree must be in 1..%d", HT_MAX_TREE);
+  if (c->max_tree < 1 || c->max_tree > HT_MAX_ROWS) return fail(HT_EINVAL, "max_tree must be in 1..%d", HT_MAX_ROWS);
   if (c->max_cache < 8 || c->max_cache % 8) return fail(HT_EINVAL, "max_cache must be a positive multiple of 8");
   if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return fail(HT_EINVAL, "rms_eps must be > 0 and rope_base > 1");
   return HT_OK;
@@ -214,7 +214,7 @@ struct ht_model {
   int drafts_of = -1;           // index into `fused` of the node the last acceptance ended on, -1 if none
   int dyn_b = 0;                // > 0: every drafting step chooses its own tree among the dyn_b best candidates per level
   // pinned host staging
-  int32_t* h_stage = nullptr;     // [max(max_cache, 8 * kMaxTree)]
+  int32_t* h_stage = nullptr;     // [max(max_cache, two table images)] + the pointer tables
   StepState* h_state = nullptr;
   // device-resident loop: while set, the kernels of a pass read the cache length here and `n` is an upper bound
   const int32_t* n_dev = nullptr;
@@ -386,10 +386,10 @@ bool all_loaded(const ht_model* m) {
 // host-side tree tables: depth, ancestor-or-self bit masks
 void fill_tables(int T, const int32_t* parent, const int32_t* rank, int32_t* stage) {
   int32_t* sp = stage;                       // parent
-  int32_t* sd = stage + kMaxTree;            // depth
-  int32_t* sr = stage + 2 * kMaxTree;        // rank
-  uint64_t* sa = (uint64_t*)(stage + 3 * kMaxTree);
-  memset(stage, 0, sizeof(int32_t) * 3 * kMaxTree + sizeof(uint64_t) * kMaxTree * kMaskWords);
+  int32_t* sd = stage + kMaxRows;            // depth
+  int32_t* sr = stage + 2 * kMaxRows;        // rank
+  uint64_t* sa = (uint64_t*)(stage + 3 * kMaxRows);
+  memset(stage, 0, sizeof(int32_t) * 3 * kMaxRows + sizeof(uint64_t) * kMaxRows * kMaskWords);
   for (int v = 0; v < T; ++v) {
     sp[v] = parent[v];
     sr[v] = rank ? rank[v] : 0;
@@ -398,13 +398,13 @@ void fill_tables(int T, const int32_t* parent, const int32_t* rank, int32_t* sta
     sa[v * kMaskWords + (v >> 6)] |= 1ull << (v & 63);
   }
 }
-constexpr size_t kTableInts = 3 * kMaxTree + 2 * kMaxTree * kMaskWords;   // int32 units of one table image
+constexpr size_t kTableInts = 3 * kMaxRows + 2 * kMaxRows * kMaskWords;   // int32 units of one table image
 
 int upload_tables(const TreeTables& t, const int32_t* stage, hipStream_t s) {
-  HT_HIP(hipMemcpyAsync(t.parent, stage, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
-  HT_HIP(hipMemcpyAsync(t.depth, stage + kMaxTree, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
-  HT_HIP(hipMemcpyAsync(t.rank, stage + 2 * kMaxTree, sizeof(int32_t) * kMaxTree, hipMemcpyHostToDevice, s));
-  HT_HIP(hipMemcpyAsync(t.anc, stage + 3 * kMaxTree, sizeof(uint64_t) * kMaxTree * kMaskWords, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.parent, stage, sizeof(int32_t) * kMaxRows, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.depth, stage + kMaxRows, sizeof(int32_t) * kMaxRows, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.rank, stage + 2 * kMaxRows, sizeof(int32_t) * kMaxRows, hipMemcpyHostToDevice, s));
+  HT_HIP(hipMemcpyAsync(t.anc, stage + 3 * kMaxRows, sizeof(uint64_t) * kMaxRows * kMaskWords, hipMemcpyHostToDevice, s));
   return HT_OK;
 }
 
@@ -561,9 +561,9 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   }
 
   // chain tables (prefill chunks and pseudo rows): row i has depth i and sees rows 0..i
-  std::vector<int32_t> cp(kMaxTree);
-  for (int i = 0; i < kMaxTree; ++i) cp[i] = i - 1;
-  fill_tables(kMaxTree, cp.data(), nullptr, m->h_stage);
+  std::vector<int32_t> cp(kMaxRows);
+  for (int i = 0; i < kMaxRows; ++i) cp[i] = i - 1;
+  fill_tables(kMaxRows, cp.data(), nullptr, m->h_stage);
   if ((rc = upload_tables(m->b.chain, m->h_stage, s))) return cleanup(rc);
   // pointer tables
   void** hp = (void**)(m->h_stage + 2 * kTableInts);
@@ -609,14 +609,14 @@ int ht_free_model(ht_model* m) {
 int ht_set_tree(ht_model* m, int32_t T, const int32_t* parent, const int32_t* rank, void* stream) {
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!rank) return fail(HT_EINVAL, "rank is NULL");
-  int rc = validate_tree(T, parent, rank, m->cfg.k, m->cfg.max_tree);
+  int rc = validate_tree(T, parent, rank, m->cfg.k, m->cfg.max_tree < kMaxTree ? m->cfg.max_tree : kMaxTree);
   if (rc) return rc;
   hipStream_t s = (hipStream_t)stream;
   HT_HIP(hipStreamSynchronize(s));           // staging buffer may still feed an earlier copy
   fill_tables(T, parent, rank, m->h_stage);
   int32_t* width = m->h_stage + kTableInts;
   for (int e = 0; e < kMaxTransfer + 2; ++e) width[e] = 0;
-  const int32_t* depth = m->h_stage + kMaxTree;
+  const int32_t* depth = m->h_stage + kMaxRows;
   for (int v = 1; v < T; ++v)
     if (rank[v] + 1 > width[depth[v]]) width[depth[v]] = rank[v] + 1;
   if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
@@ -678,7 +678,7 @@ int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* s
   }
   const ht_config& c = m->cfg;
   const int T = m->T, rows = T + count * c.k;
-  if (rows > c.max_tree || rows > kMaxTree)
+  if (rows > c.max_tree || rows > kMaxRows)
     return fail(HT_ECAPACITY, "%d tree rows + %d x %d pseudo rows exceed max_tree %d", T, count, c.k, c.max_tree);
   for (int f = 0; f < count; ++f) {
     if (nodes[f] < 0 || nodes[f] >= T) return fail(HT_ETREE, "fused node %d outside the tree", nodes[f]);
@@ -706,7 +706,7 @@ int ht_set_fused_nodes(ht_model* m, int32_t count, const int32_t* nodes, void* s
   int rc;
   if ((rc = upload_tables(m->b.tree, m->h_stage, s))) return rc;
   int32_t* rows_stage = m->h_stage + kTableInts;
-  int32_t* src_stage = rows_stage + kMaxTree;      // logits row, counted from the first pseudo row, of (node, step)
+  int32_t* src_stage = rows_stage + kMaxRows;      // logits row, counted from the first pseudo row, of (node, step)
   for (int f = 0; f < count; ++f) {
     rows_stage[f] = nodes[f];
     for (int i = 0; i < c.k; ++i) src_stage[f * c.k + i] = row_of(f, i) - T;
@@ -737,8 +737,9 @@ int ht_prefill(ht_model* m, const int32_t* tokens, int32_t n, void* stream) {
   m->has_prefill = m->transfer_ready = m->verify_done = false;
   const TreeDev chain = m->b.chain.dev();
   int rc;
-  for (int start = 0; start < n; start += m->Mp) {
-    const int rows = n - start < m->Mp ? n - start : m->Mp;
+  const int chunk = m->Mp < 128 ? m->Mp : 128;          // more rows a pass would only stream the weights twice
+  for (int start = 0; start < n; start += chunk) {
+    const int rows = n - start < chunk ? n - start : chunk;
     const bool last = start + rows == n;
     HT_HIP(launch_embed(c.dtype, m->tok_emb, m->b.prompt + start, m->b.x, rows, c.d_model, s));
     if ((rc = run_pass(m, chain, rows, 0, true, last ? m->b.logits : nullptr, m->b.g, s))) return rc;
@@ -1062,10 +1063,10 @@ struct AttnScratch {
 AttnScratch attn_scratch_layout(char* base, int T, int Hq, int hd, size_t es) {
   Carver cv(base);
   AttnScratch a;
-  a.parent = cv.take<int32_t>(kMaxTree);
-  a.depth = cv.take<int32_t>(kMaxTree);
-  a.rank = cv.take<int32_t>(kMaxTree);
-  a.anc = cv.take<uint64_t>((size_t)kMaxTree * kMaskWords);
+  a.parent = cv.take<int32_t>(kMaxRows);
+  a.depth = cv.take<int32_t>(kMaxRows);
+  a.rank = cv.take<int32_t>(kMaxRows);
+  a.anc = cv.take<uint64_t>((size_t)kMaxRows * kMaskWords);
   a.cs = cv.take<float>((size_t)padded_rows(T) * hd);
   a.q_rot = cv.take_bytes((size_t)padded_rows(T) * Hq * hd * es);
   a.mfma = cv.take_bytes(attn_mfma_scratch_bytes(padded_rows(T), Hq, hd));
@@ -1077,7 +1078,7 @@ hipEvent_t g_op_event = nullptr;
 }  // namespace
 
 size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd) {
-  if (T < 1 || T > kMaxTree || Hq < 1 || hd < 2) return 0;
+  if (T < 1 || T > kMaxRows || Hq < 1 || hd < 2) return 0;
   return attn_scratch_layout(nullptr, T, Hq, hd, 4).total;
 }
 
@@ -1091,9 +1092,9 @@ int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void*
   if (n < 0 || cap < 8 || cap % 8) return fail(HT_EINVAL, "cap must be a positive multiple of 8 and n >= 0");
   int rc;
   if (parent) {
-    if ((rc = validate_tree(T, parent, nullptr, kMaxTree, kMaxTree))) return rc;
-  } else if (T < 1 || T > kMaxTree) {
-    return fail(HT_ETREE, "tree size %d outside 1..%d", T, kMaxTree);
+    if ((rc = validate_tree(T, parent, nullptr, kMaxRows, kMaxRows))) return rc;
+  } else if (T < 1 || T > kMaxRows) {
+    return fail(HT_ETREE, "tree size %d outside 1..%d", T, kMaxRows);
   }
   if (n + T > cap) return fail(HT_ECAPACITY, "n + T = %d exceeds cap %d", n + T, cap);
   if (scratch_bytes < ht_tree_attention_scratch_bytes(T, Hq, hd)) return fail(HT_EINVAL, "scratch too small");
@@ -1161,7 +1162,7 @@ int ht_gate_up_pack(const void* w_gate, const void* w_up, int32_t f, int32_t K, 
 int ht_gate_up_silu_packed(const void* a, const void* packed, int32_t M, int32_t f, int32_t K, void* act_out,
                            void* stream) {
   if (!a || !packed || !act_out) return fail(HT_EINVAL, "NULL argument");
-  if (M < 1 || M > kMaxTree || f < 16 || f % 16 || !ht_weight_pack_bytes(2 * f, K))
+  if (M < 1 || M > kMaxRows || f < 16 || f % 16 || !ht_weight_pack_bytes(2 * f, K))
     return fail(HT_EINVAL, "bad shape M=%d f=%d K=%d", M, f, K);
   PackedW pw{(const bf16_t*)packed, 2 * f, K, packed_cols(K)};
   HT_HIP(launch_gemm_packed_silu(a, pw, M, act_out, (hipStream_t)stream));
@@ -1176,7 +1177,7 @@ size_t ht_skinny_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
 int ht_skinny_gemm_packed(const void* a, const void* packed, int32_t M, int32_t N, int32_t K, float* out, void* scratch,
                           size_t scratch_bytes, void* stream) {
   if (!a || !packed || !out) return fail(HT_EINVAL, "NULL argument");
-  if (M < 1 || M > kMaxTree || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  if (M < 1 || M > kMaxRows || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
   hipStream_t s = (hipStream_t)stream;
   PackedW pw{(const bf16_t*)packed, N, K, packed_cols(K)};
   int sp = gemm_mfma_splits(M, N, K);
@@ -1224,7 +1225,7 @@ extern "C" {
 int ht_skinny_gemm_packed_noalloc(const void* a, const void* packed, int32_t M, int32_t N, int32_t K, float* out,
                                   void* stream) {
   if (!a || !packed || !out) return fail(HT_EINVAL, "NULL argument");
-  if (M < 1 || M > kMaxTree || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  if (M < 1 || M > kMaxRows || !ht_weight_pack_bytes(N, K)) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
   hipStream_t s = (hipStream_t)stream;
   PackedW pw{(const bf16_t*)packed, N, K, packed_cols(K)};
   const int sp = gemm_mfma_splits(M, N, K);          // the same split as ht_skinny_gemm_packed with enough scratch
@@ -1249,7 +1250,7 @@ int ht_skinny_gemm(const void* a, const void* w, int32_t M, int32_t N, int32_t K
                    void* scratch, size_t scratch_bytes, void* stream) {
   if (!a || !w || !out) return fail(HT_EINVAL, "NULL argument");
   if (dtype != HT_F32 && dtype != HT_BF16) return fail(HT_EINVAL, "bad dtype");
-  if (M < 1 || M > kMaxTree || N < 1 || K < 1) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
+  if (M < 1 || M > kMaxRows || N < 1 || K < 1) return fail(HT_EINVAL, "bad shape M=%d N=%d K=%d", M, N, K);
   hipStream_t s = (hipStream_t)stream;
   const char* env = getenv("HT_FORCE_SIMPLE");
   const bool simple = env && env[0] == '1';
@@ -1272,7 +1273,7 @@ int ht_kl_divergence_rows(const float* z, int32_t row_a, int32_t row_b, int32_t 
 
 int ht_candidate_logprobs(const float* d, const int32_t* cand, int32_t rows, int32_t b, int32_t V, float* lp, void* stream) {
   if (!d || !cand || !lp) return fail(HT_EINVAL, "NULL argument");
-  if (rows < 1 || rows > kMaxTree || b < 1 || b > kMaxTopK || V < 1) return fail(HT_EINVAL, "bad shape rows=%d b=%d V=%d", rows, b, V);
+  if (rows < 1 || rows > kMaxRows || b < 1 || b > kMaxTopK || V < 1) return fail(HT_EINVAL, "bad shape rows=%d b=%d V=%d", rows, b, V);
   HT_HIP(launch_cand_logprob(d, cand, rows, b, V, lp, (hipStream_t)stream));
   return HT_OK;
 }

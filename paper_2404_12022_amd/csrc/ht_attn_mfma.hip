@@ -606,7 +606,7 @@ void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int
 }  // namespace
 
 bool attn_mfma_supported(int M, int Hq, int Hkv, int hd) {
-  return (hd == 64 || hd == 128) && M >= 1 && M <= kMaxTree && Hq % Hkv == 0;
+  return (hd == 64 || hd == 128) && M >= 1 && M <= kMaxRows && Hq % Hkv == 0;
 }
 
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {

@@ -53,8 +53,9 @@ template <> struct Conv<bf16_t> {
   __device__ static inline void store(bf16_t* p, float v) { *p = float_to_bf16(v); }
 };
 
-constexpr int kMaxTree = 128;            // rows per pass (tree nodes, prefill chunk, pseudo rows)
-constexpr int kMaskWords = kMaxTree / 64;
+constexpr int kMaxTree = 128;            // nodes of a tree (root included)
+constexpr int kMaxRows = 256;            // rows of a pass: tree nodes plus the pseudo rows that ride along, or a prefill chunk
+constexpr int kMaskWords = kMaxRows / 64;
 constexpr int kMaxTopK = 64;
 constexpr int kMaxTransfer = 8;
 constexpr int kMaxSplitK = 8;
@@ -65,7 +66,7 @@ struct TreeDev {
   const int32_t* parent;     // [T]
   const int32_t* depth;      // [T]
   const int32_t* rank;       // [T]
-  const uint64_t* anc;       // [T][kMaskWords] bit u set iff u is ancestor-or-self
+  const uint64_t* anc;       // [rows][kMaskWords] bit u set iff row u is the row itself or an ancestor of it
 };
 
 // Device-resident decoder state written by the accept kernel and read back by the host.
@@ -178,7 +179,8 @@ int gemm_mfma_splits(int M, int N, int K);
 // interleaved block by block (gate block i, up block i, gate block i+1, ..); mode 2: segments (q, k, v), in
 // every q and k head the 16-row block p is followed by its rotary partner block p + head_dim/32
 hipError_t launch_repack(WeightSegs w, int K, int mode, int head_dim, void* dst, hipStream_t s);
-// out[s][m][n], s < nsplit (split-K partial sums, fp32)
+// out[s][m][n], s < nsplit (split-K partial sums, fp32).  M <= kMaxRows; more than 128 rows run as two launches over
+// the same weights (rows 0..127, then the rest).
 hipError_t launch_gemm_packed(const void* a, PackedW w, int M, float* out, int nsplit, hipStream_t s,
                               RowScale rs = RowScale{});
 // w packed with mode 1 from (gate, up): act[m][j] = silu(a.gate_j) * (a.up_j), bf16 [M][N/2]

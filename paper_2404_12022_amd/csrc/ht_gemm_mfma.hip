@@ -81,162 +81,15 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, i
   *(uint4*)(dst + piece * 8) = v;
 }
 
-// --------------------------------------------------------------------------------------------- product
-// The hot loop is straight-line code (no predicated loads, no data-dependent branches) so that the
-// compiler can keep exact outstanding-load counts and the weight ring really stays in flight: chunk
-// indices past the end of this block's K range are clamped to its last chunk (a redundant, in-bounds
-// reload that is never used), wavefront slots without a row block re-read one fragment (never stored), and
-// activation columns past K are clamped into the row (they meet zero-padded weights).
-template <int MT, int R, int WAVES, int EPI, int KC = kChunkCols, int PD = kRingDepth>
-__global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
-                                                                 const bf16_t* __restrict__ wp, int M, int N, int K,
-                                                                 int KS, void* __restrict__ outp, int nsplit,
-                                                                 QkvEpilogue qe, RowScale rs) {
-  constexpr int STEPS = KC / 32;                         // MFMA steps per chunk
-  constexpr int ROWB = KC * 2 + 16;                      // LDS row stride in bytes (padded: conflict-free b128 reads)
-  constexpr int THREADS = 64 * WAVES;
-  constexpr int ROWS = MT * 16;
-  constexpr int PIECES = ROWS * (KC / 8);                // 16-byte pieces of the activation chunk
-  static_assert(PIECES >= THREADS, "every thread stages at least one piece of the activation chunk");
-  constexpr int APASS = (PIECES + THREADS - 1) / THREADS;   // surplus threads of the last pass repeat the last piece
-  constexpr int STAGE = ROWS * ROWB;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
-  const int chunks = KS / STEPS;                         // KS is a multiple of STEPS (weights zero-padded)
-  int c0, c1;
-  even_share(chunks, nsplit, blockIdx.y, c0, c1);
-  const int n_rb = N / 16;
-  // The grid's workgroups share the row blocks evenly: workgroup b owns n_rb / G blocks, the first n_rb % G
-  // workgroups one more (in whole pairs for the SiLU epilogue), at most R * WAVES of them (the launcher's
-  // choice of G), R consecutive ones per wavefront.  A slot past the end of
-  // the workgroup's range re-reads one fragment of its first block over and over (stride 0: cache hits, no HBM
-  // traffic, same instruction stream) and stores nothing.
-  constexpr int U = EPI == EPI_SILU ? 2 : 1;             // the SiLU epilogue needs both blocks of a (gate, up) pair
-  const int units = (n_rb + U - 1) / U;
-  int wg0, wg1;
-  even_share(units, gridDim.x, blockIdx.x, wg0, wg1);
-  wg0 *= U;
-  wg1 *= U;
-  const int rb0 = wg0 + wave * R;
-  if (c0 >= c1) return;                                  // uniform over the block
-
-  const u32x4_t* wbase[R];
-  size_t wstep[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const bool own = rb0 + r < wg1;
-    const int rb = own ? rb0 + r : wg0;
-    wbase[r] = (const u32x4_t*)wp + ((size_t)(rb / kTileBlocks) * KS * kTileBlocks + rb % kTileBlocks) * 64 + lane;
-    wstep[r] = own ? (size_t)kTileBlocks * 64 : 0;
-  }
-  const int last = c1 - 1;
-  // All workgroups walk K in the same order on purpose: they then pull the same activation lines from
-  // L2 at about the same time, which keeps the small panel resident while the weights stream through
-  // (a staggered walk measured 12 % slower).
-  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
-    c = c < last ? c : last;
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-      for (int s = 0; s < STEPS; ++s)
-        dst[r][s].nat = __builtin_nontemporal_load(wbase[r] + (size_t)(c * STEPS + s) * wstep[r]);
-  };
-  // activation pieces of this thread: row p / 16, 16-byte column p % 16 of the chunk
-  const bf16_t* arow[APASS];
-  int acol[APASS], alds[APASS];
-#pragma unroll
-  for (int i = 0; i < APASS; ++i) {
-    int p = tid + i * THREADS;
-    p = p < PIECES ? p : PIECES - 1;
-    arow[i] = a + (size_t)(p / (KC / 8)) * K;
-    acol[i] = (p % (KC / 8)) * 8;
-    alds[i] = (p / (KC / 8)) * ROWB + (p % (KC / 8)) * 16;
-  }
-  auto load_a = [&](u32x4_t (&dst)[APASS], int c) __attribute__((always_inline)) {
-    c = c < last ? c : last;
-#pragma unroll
-    for (int i = 0; i < APASS; ++i) {
-      int k = c * KC + acol[i];
-      k = k < K - 8 ? k : K - 8;
-      dst[i] = *(const u32x4_t*)(arow[i] + k);
-    }
-  };
-  auto store_a = [&](const u32x4_t (&src)[APASS], int stage) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < APASS; ++i) *(u32x4_t*)(&lds[stage * STAGE + alds[i]]) = src[i];
-  };
-
-  floatx4_t acc[R][MT];
-#pragma unroll
-  for (int r = 0; r < R; ++r)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-
-  // Rows of a panel that was stored without its 1/rms factor: the factor multiplies the finished sums instead
-  // (every K split scales its partial sums by the same factor).  The sums of squares are fetched here, ahead of
-  // the weight stream (they are the oldest loads, so no wait ever stalls on them), and turned into factors in the
-  // epilogue.
-  float4 row_ss[MT];
-  if (rs.ss) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 16 + r16;
-      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
-    }
-  }
-
-  // Loads retire in issue order, so everything is issued oldest-needed-first: at chunk c the ring holds
-  // weights of chunks c .. c+PD-1 and activations of chunks c+1 .. c+PD; each iteration consumes the
-  // oldest of both and issues activation chunk c+PD+1, then weight chunk c+PD.
-  Frag wreg[PD][R][STEPS];
-  u32x4_t areg[PD][APASS];
-  {
-    u32x4_t first[APASS];
-    load_a(first, c0);
-#pragma unroll
-    for (int p = 0; p < PD; ++p) {
-      load_a(areg[p], c0 + 1 + p);
-      load_w(wreg[p], c0 + p);
-    }
-    store_a(first, 0);
-  }
-  __syncthreads();
-
-  auto body = [&](Frag (&wslot)[R][STEPS], u32x4_t (&aslot)[APASS], int c) __attribute__((always_inline)) {
-    const int stage = (c - c0) & 1;
-    const unsigned char* ab = &lds[stage * STAGE + r16 * ROWB + g * 16];
-    // activation fragments are read one MFMA step ahead of their use
-    Frag b[2][MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) b[0][mt].nat = *(const u32x4_t*)(ab + mt * 16 * ROWB);
-    store_a(aslot, stage ^ 1);                 // activation chunk c+1 becomes visible after the barrier below
-    load_a(aslot, c + PD + 1);
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-      if (s + 1 < STEPS) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) b[(s + 1) & 1][mt].nat = *(const u32x4_t*)(ab + mt * 16 * ROWB + (s + 1) * 64);
-      }
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][mt].v, acc[r][mt], 0, 0, 0);
-    }
-    load_w(wslot, c + PD);
-    __syncthreads();
-  };
-
-  int c = c0;
-  for (; c + PD <= c1; c += PD) {
-#pragma unroll
-    for (int p = 0; p < PD; ++p) body(wreg[p], areg[p], c + p);
-  }
-#pragma unroll
-  for (int p = 0; p < PD - 1; ++p)
-    if (c + p < c1) body(wreg[p], areg[p], c + p);                // uniform tail
-
+// --------------------------------------------------------------------------------------------- epilogues
+// What a wavefront does with its finished sums acc[r][mt] (row block rb0 + r, token tile mt): the 1/rms factor of
+// the token rows, then fp32 partial sums, SiLU(gate) * up, or rotary + q store / K,V append.
+template <int MT, int R, int EPI>
+__device__ __forceinline__ void finish_rows(floatx4_t (&acc)[R][MT], const float4 (&row_ss)[MT], int rb0, int wg1, int M,
+                                            int N, void* __restrict__ outp, const QkvEpilogue& qe, const RowScale& rs,
+                                            int row0) {
+  const int lane = threadIdx.x & 63, g = lane >> 4;
+  const int r16 = row0 + (lane & 15);                    // token row of tile mt: mt * 16 + r16, counted over the whole pass
   if (rs.ss) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -335,6 +188,363 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   }
 }
 
+// --------------------------------------------------------------------------------------------- product
+// The hot loop is straight-line code (no predicated loads, no data-dependent branches) so that the
+// compiler can keep exact outstanding-load counts and the weight ring really stays in flight: chunk
+// indices past the end of this block's K range are clamped to its last chunk (a redundant, in-bounds
+// reload that is never used), wavefront slots without a row block re-read one fragment (never stored), and
+// activation columns past K are clamped into the row (they meet zero-padded weights).
+template <int MT, int R, int WAVES, int EPI, int KC = kChunkCols, int PD = kRingDepth>
+__global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* __restrict__ a,
+                                                                 const bf16_t* __restrict__ wp, int M, int N, int K,
+                                                                 int KS, void* __restrict__ outp, int nsplit,
+                                                                 QkvEpilogue qe, RowScale rs, int row0) {
+  constexpr int STEPS = KC / 32;                         // MFMA steps per chunk
+  constexpr int ROWB = KC * 2 + 16;                      // LDS row stride in bytes (padded: conflict-free b128 reads)
+  constexpr int THREADS = 64 * WAVES;
+  constexpr int ROWS = MT * 16;
+  constexpr int PIECES = ROWS * (KC / 8);                // 16-byte pieces of the activation chunk
+  static_assert(PIECES >= THREADS, "every thread stages at least one piece of the activation chunk");
+  constexpr int APASS = (PIECES + THREADS - 1) / THREADS;   // surplus threads of the last pass repeat the last piece
+  constexpr int STAGE = ROWS * ROWB;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  const int chunks = KS / STEPS;                         // KS is a multiple of STEPS (weights zero-padded)
+  int c0, c1;
+  even_share(chunks, nsplit, blockIdx.y, c0, c1);
+  const int n_rb = N / 16;
+  // The grid's workgroups share the row blocks evenly: workgroup b owns n_rb / G blocks, the first n_rb % G
+  // workgroups one more (in whole pairs for the SiLU epilogue), at most R * WAVES of them (the launcher's
+  // choice of G), R consecutive ones per wavefront.  A slot past the end of
+  // the workgroup's range re-reads one fragment of its first block over and over (stride 0: cache hits, no HBM
+  // traffic, same instruction stream) and stores nothing.
+  constexpr int U = EPI == EPI_SILU ? 2 : 1;             // the SiLU epilogue needs both blocks of a (gate, up) pair
+  const int units = (n_rb + U - 1) / U;
+  int wg0, wg1;
+  even_share(units, gridDim.x, blockIdx.x, wg0, wg1);
+  wg0 *= U;
+  wg1 *= U;
+  const int rb0 = wg0 + wave * R;
+  if (c0 >= c1) return;                                  // uniform over the block
+
+  const u32x4_t* wbase[R];
+  size_t wstep[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool own = rb0 + r < wg1;
+    const int rb = own ? rb0 + r : wg0;
+    wbase[r] = (const u32x4_t*)wp + ((size_t)(rb / kTileBlocks) * KS * kTileBlocks + rb % kTileBlocks) * 64 + lane;
+    wstep[r] = own ? (size_t)kTileBlocks * 64 : 0;
+  }
+  const int last = c1 - 1;
+  // All workgroups walk K in the same order on purpose: they then pull the same activation lines from
+  // L2 at about the same time, which keeps the small panel resident while the weights stream through
+  // (a staggered walk measured 12 % slower).
+  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s)
+        dst[r][s].nat = __builtin_nontemporal_load(wbase[r] + (size_t)(c * STEPS + s) * wstep[r]);
+  };
+  // activation pieces of this thread: row p / 16, 16-byte column p % 16 of the chunk
+  const bf16_t* arow[APASS];
+  int acol[APASS], alds[APASS];
+#pragma unroll
+  for (int i = 0; i < APASS; ++i) {
+    int p = tid + i * THREADS;
+    p = p < PIECES ? p : PIECES - 1;
+    arow[i] = a + (size_t)(row0 + p / (KC / 8)) * K;
+    acol[i] = (p % (KC / 8)) * 8;
+    alds[i] = (p / (KC / 8)) * ROWB + (p % (KC / 8)) * 16;
+  }
+  auto load_a = [&](u32x4_t (&dst)[APASS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
+#pragma unroll
+    for (int i = 0; i < APASS; ++i) {
+      int k = c * KC + acol[i];
+      k = k < K - 8 ? k : K - 8;
+      dst[i] = *(const u32x4_t*)(arow[i] + k);
+    }
+  };
+  auto store_a = [&](const u32x4_t (&src)[APASS], int stage) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < APASS; ++i) *(u32x4_t*)(&lds[stage * STAGE + alds[i]]) = src[i];
+  };
+
+  floatx4_t acc[R][MT];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  // Rows of a panel that was stored without its 1/rms factor: the factor multiplies the finished sums instead
+  // (every K split scales its partial sums by the same factor).  The sums of squares are fetched here, ahead of
+  // the weight stream (they are the oldest loads, so no wait ever stalls on them), and turned into factors in the
+  // epilogue.
+  float4 row_ss[MT];
+  if (rs.ss) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = row0 + mt * 16 + r16;
+      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
+    }
+  }
+
+  // Loads retire in issue order, so everything is issued oldest-needed-first: at chunk c the ring holds
+  // weights of chunks c .. c+PD-1 and activations of chunks c+1 .. c+PD; each iteration consumes the
+  // oldest of both and issues activation chunk c+PD+1, then weight chunk c+PD.
+  Frag wreg[PD][R][STEPS];
+  u32x4_t areg[PD][APASS];
+  {
+    u32x4_t first[APASS];
+    load_a(first, c0);
+#pragma unroll
+    for (int p = 0; p < PD; ++p) {
+      load_a(areg[p], c0 + 1 + p);
+      load_w(wreg[p], c0 + p);
+    }
+    store_a(first, 0);
+  }
+  __syncthreads();
+
+  auto body = [&](Frag (&wslot)[R][STEPS], u32x4_t (&aslot)[APASS], int c) __attribute__((always_inline)) {
+    const int stage = (c - c0) & 1;
+    const unsigned char* ab = &lds[stage * STAGE + r16 * ROWB + g * 16];
+    // activation fragments are read one MFMA step ahead of their use
+    Frag b[2][MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) b[0][mt].nat = *(const u32x4_t*)(ab + mt * 16 * ROWB);
+    store_a(aslot, stage ^ 1);                 // activation chunk c+1 becomes visible after the barrier below
+    load_a(aslot, c + PD + 1);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (s + 1 < STEPS) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) b[(s + 1) & 1][mt].nat = *(const u32x4_t*)(ab + mt * 16 * ROWB + (s + 1) * 64);
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][mt].v, acc[r][mt], 0, 0, 0);
+    }
+    load_w(wslot, c + PD);
+    __syncthreads();
+  };
+
+  int c = c0;
+  for (; c + PD <= c1; c += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) body(wreg[p], areg[p], c + p);
+  }
+#pragma unroll
+  for (int p = 0; p < PD - 1; ++p)
+    if (c + p < c1) body(wreg[p], areg[p], c + p);                // uniform tail
+
+  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0);
+}
+
+// --------------------------------------------------------------------------------------------- product, panel wavefront
+// The same product with the activation panel brought in by a wavefront of its own.  In gemm_packed_kernel every
+// wavefront fetches its share of each panel chunk between its weight loads; loads return in issue order, so a panel
+// piece (an L2 hit) holds its place in the queue as long as the weight loads around it (HBM misses), and at 64 token
+// rows the panel is half or more of what a workgroup takes in.  Here WW wavefronts issue weight loads only (a ring of
+// PD chunks each) and one more wavefront does nothing but move panel chunks from global memory straight into LDS
+// (16-byte LDS-direct loads, no registers in between), S stages ahead.  One barrier per chunk as before.
+//
+// LDS stage: rows of KC bf16 (KC / 8 slots of 16 bytes), slot j of row r stored at position j ^ (r & 7), so the eight
+// rows a b128 operand read touches per pass fall on eight different bank groups without padding (an LDS-direct load
+// writes 64 consecutive slots, lane l the slot l: padding is not possible, but every lane picks its source address).
+template <int N> __device__ __forceinline__ void wait_vm_then_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds_then_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int MT, int R, int WW, int EPI, int KC, int PD, int S, int PF = 0, int DIAG = 0>
+__global__ __launch_bounds__(64 * (WW + 1)) void gemm_ws_kernel(const bf16_t* __restrict__ a,
+                                                                const bf16_t* __restrict__ wp, int M, int N, int K, int KS,
+                                                                void* __restrict__ outp, int nsplit, QkvEpilogue qe,
+                                                                RowScale rs, int row0) {
+  constexpr int STEPS = KC / 32;
+  constexpr int SLOTS = KC / 8;                          // 16-byte slots per row
+  constexpr int ROWS = MT * 16;
+  constexpr int STAGE = ROWS * KC * 2;                   // bytes
+  constexpr int NL = STAGE / 1024;                       // LDS-direct loads (64 lanes x 16 bytes) per chunk
+  static_assert(STAGE % 1024 == 0 && (S - 2) * NL <= 63 && S >= 3 + PF, "stage size / ring depth");
+  static_assert(!PF || PD % 2 == 0, "operand double buffering alternates with the ring slots");
+  constexpr int AHEAD = S - 2 - PF;                      // chunks that may still be in flight at a barrier
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  const int chunks = KS / STEPS;
+  int c0, c1;
+  even_share(chunks, nsplit, blockIdx.y, c0, c1);
+  const int n_rb = N / 16;
+  constexpr int U = EPI == EPI_SILU ? 2 : 1;
+  const int units = (n_rb + U - 1) / U;
+  int wg0, wg1;
+  even_share(units, gridDim.x, blockIdx.x, wg0, wg1);
+  wg0 *= U;
+  wg1 *= U;
+  if (c0 >= c1) return;                                  // uniform over the block
+  const int last = c1 - 1, iters = c1 - c0;
+
+  if (wave == WW) {
+    // ---- panel wavefront: chunk c goes to stage (c - c0) % S; lane l of load i fills slot 64 i + l of the stage
+    const bf16_t* src[NL];
+    int col[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int slot = i * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
+      src[i] = a + (size_t)(row0 + row) * K;
+      col[i] = (pos ^ (row & 7)) * 8;
+    }
+    auto fetch = [&](int c, int stage) __attribute__((always_inline)) {
+      c = c < last ? c : last;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        int k = c * KC + col[i];
+        k = k < K - 8 ? k : K - 8;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + k),
+                                         (void __attribute__((address_space(3)))*)(lds + stage * STAGE + i * 1024), 16, 0, 0);
+      }
+    };
+#pragma unroll
+    for (int p = 0; p < S - 1; ++p) fetch(c0 + p, p);
+    wait_vm_then_barrier<AHEAD * NL>();                  // chunk c0 (and c0 + 1 with PF) has landed
+    int stage = S - 1;
+    for (int i = 0; i < iters; ++i) {
+      fetch(c0 + i + S - 1, stage);                      // the stage the others read before the last barrier
+      stage = stage + 1 == S ? 0 : stage + 1;
+      wait_vm_then_barrier<AHEAD * NL>();                // chunk c0 + i + 1 (+ PF) has landed
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // nothing may still be writing LDS when the wavefront ends
+    return;
+  }
+
+  // ---- weight wavefronts
+  const int rb0 = wg0 + wave * R;
+  const u32x4_t* wbase[R];
+  size_t wstep[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool own = rb0 + r < wg1;
+    const int rb = own ? rb0 + r : wg0;
+    wbase[r] = (const u32x4_t*)wp + ((size_t)(rb / kTileBlocks) * KS * kTileBlocks + rb % kTileBlocks) * 64 + lane;
+    wstep[r] = own ? (size_t)kTileBlocks * 64 : 0;
+  }
+  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s)
+        dst[r][s].nat = __builtin_nontemporal_load(wbase[r] + (size_t)(c * STEPS + s) * wstep[r]);
+  };
+  floatx4_t acc[R][MT];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  float4 row_ss[MT];
+  if (rs.ss) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = row0 + mt * 16 + r16;
+      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
+    }
+  }
+  Frag wreg[PD][R][STEPS];
+#pragma unroll
+  for (int p = 0; p < PD; ++p) load_w(wreg[p], c0 + p);
+  wait_lds_then_barrier();
+
+  // operand of token row mt * 16 + r16, K step s: slot s * 4 + g of that row
+  int boff[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) boff[s] = r16 * (KC * 2) + (((s * 4 + g) ^ (r16 & 7)) * 16);
+  int stage = 0;
+  if (PF) {
+    // operands of chunk c + 1 are read from LDS while the matrix cores work on chunk c: no LDS wait in front of them
+    Frag b[2][STEPS][MT];
+    auto read_b = [&](Frag (&dst)[STEPS][MT], int st) __attribute__((always_inline)) {
+      const unsigned char* ab = lds + st * STAGE;
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) dst[s][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[s]);
+    };
+    read_b(b[0], 0);
+    auto body = [&](Frag (&wslot)[R][STEPS], Frag (&cur)[STEPS][MT], Frag (&nxt)[STEPS][MT], int c) __attribute__((always_inline)) {
+      stage = stage + 1 == S ? 0 : stage + 1;
+      read_b(nxt, stage);
+      if (DIAG != 1) {
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+          for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, cur[s][mt].v, acc[r][mt], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+          for (int r = 0; r < R; ++r) acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, cur[s][0].v, acc[r][0], 0, 0, 0);
+      }
+      load_w(wslot, c + PD);
+      wait_lds_then_barrier();
+    };
+    int c = c0;
+    for (; c + PD <= c1; c += PD) {
+#pragma unroll
+      for (int p = 0; p < PD; ++p) body(wreg[p], b[p & 1], b[(p + 1) & 1], c + p);
+    }
+#pragma unroll
+    for (int p = 0; p < PD - 1; ++p)
+      if (c + p < c1) body(wreg[p], b[p & 1], b[(p + 1) & 1], c + p);
+  } else {
+  auto body = [&](Frag (&wslot)[R][STEPS], int c) __attribute__((always_inline)) {
+    const unsigned char* ab = lds + stage * STAGE;
+    stage = stage + 1 == S ? 0 : stage + 1;
+    Frag b[2][MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) b[0][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[0]);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (s + 1 < STEPS) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) b[(s + 1) & 1][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[s + 1]);
+      }
+      if (DIAG == 1 ) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][0].v, acc[r][0], 0, 0, 0);
+      } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][mt].v, acc[r][mt], 0, 0, 0);
+      }
+    }
+    load_w(wslot, c + PD);
+    wait_lds_then_barrier();
+  };
+  int c = c0;
+  for (; c + PD <= c1; c += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) body(wreg[p], c + p);
+  }
+#pragma unroll
+  for (int p = 0; p < PD - 1; ++p)
+    if (c + p < c1) body(wreg[p], c + p);                // uniform tail
+  }
+  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0);
+}
+
 // Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 80 workgroups, else R = 1.
 // Every workgroup re-reads the whole activation panel, and a compute unit ingests only ~45 GB/s (measured,
 // weights + panel), so the fastest grid is the one closest to one workgroup on each of the 256 compute
@@ -357,13 +567,13 @@ int wide_split(int M, int N, int K) {
 
 template <int MT>
 hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
-                     const RowScale& rs, hipStream_t s) {
+                     const RowScale& rs, hipStream_t s, int row0) {
   const int n_rb = w.N / 16;
   const int KS = w.Kp / 32;
   constexpr int KC = MT == 1 ? 128 : kChunkCols;     // the chunk must give every thread at least one 16-byte piece
   if (epi == EPI_F32 && wide_split(M, w.N, w.K)) {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), dim3((n_rb + 7) / 8, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs, row0);
   } else if (epi == EPI_SILU || (epi == EPI_F32 && rows_per_wave(w.N) == 2)) {
     const bool three = waves_per_group(n_rb) == 3;
     // a grid just short of the 256 compute units is topped up to 256 (the kernel shares the row blocks evenly):
@@ -374,17 +584,17 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
     if (epi == EPI_SILU) {
       if (three)
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_SILU, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, 1, qe, rs);
+                           out, 1, qe, rs, row0);
       else
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_SILU, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, 1, qe, rs);
+                           out, 1, qe, rs, row0);
     } else {
       if (three)
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 3, EPI_F32, 128>), grid, dim3(192), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, nsplit, qe, rs);
+                           out, nsplit, qe, rs, row0);
       else
         hipLaunchKernelGGL((gemm_packed_kernel<MT, 2, 4, EPI_F32, KC>), grid, dim3(256), 0, s, a, w.p, M, w.N, w.K, KS,
-                           out, nsplit, qe, rs);
+                           out, nsplit, qe, rs, row0);
     }
   } else if (epi == EPI_QKV) {
     // no split-K here, so one row block per wavefront and three or four wavefronts: 768 row blocks (a 4096-wide
@@ -395,31 +605,42 @@ hipError_t launch_mt(const bf16_t* a, const PackedW& w, int M, void* out, int ns
     if (gx < 256 && n_rb >= 256) gx = 256;
     if (four)
       hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_QKV, KC>), dim3(gx, 1), dim3(256), 0, s, a, w.p, M, w.N, w.K,
-                         KS, out, 1, qe, rs);
+                         KS, out, 1, qe, rs, row0);
     else
       hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 3, EPI_QKV, KC>), dim3(gx, 1), dim3(192), 0, s, a, w.p, M, w.N, w.K,
-                         KS, out, 1, qe, rs);
+                         KS, out, 1, qe, rs, row0);
   } else {
     hipLaunchKernelGGL((gemm_packed_kernel<MT, 1, 4, EPI_F32, KC>), dim3((n_rb + 3) / 4, nsplit), dim3(256), 0, s, a,
-                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs);
+                       w.p, M, w.N, w.K, KS, out, nsplit, qe, rs, row0);
   }
   return hipGetLastError();
 }
 
+// Rows [row0, row0 + rows) of a pass of M rows: the instance with the fewest token tiles that hold them.
+hipError_t launch_rows(const bf16_t* ap, const PackedW& w, int rows, int M, void* out, int nsplit, int epi,
+                       const QkvEpilogue& qe, const RowScale& rs, hipStream_t s, int row0) {
+  if (rows <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);
+  if (rows <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);
+  if (rows <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);
+  if (rows <= 80) return launch_mt<5>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);   // a 64-node tree plus a few pseudo rows
+  if (rows <= 96) return launch_mt<6>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);
+  return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, rs, s, row0);
+}
+
+// A workgroup holds at most 128 token rows (accumulators and the activation ring are registers): a pass of more
+// rows runs as two launches over the same weights, rows 0..127 and the rest, each writing its own rows of the
+// same outputs.  The K split is the caller's and the same for both.
 hipError_t launch_any(const void* a, const PackedW& w, int M, void* out, int nsplit, int epi, const QkvEpilogue& qe,
                       const RowScale& rs, hipStream_t s) {
   const bf16_t* ap = (const bf16_t*)a;
-  if (M <= 16) return launch_mt<1>(ap, w, M, out, nsplit, epi, qe, rs, s);
-  if (M <= 32) return launch_mt<2>(ap, w, M, out, nsplit, epi, qe, rs, s);
-  if (M <= 64) return launch_mt<4>(ap, w, M, out, nsplit, epi, qe, rs, s);
-  if (M <= 80) return launch_mt<5>(ap, w, M, out, nsplit, epi, qe, rs, s);      // a 64-node tree plus a few pseudo rows
-  if (M <= 96) return launch_mt<6>(ap, w, M, out, nsplit, epi, qe, rs, s);
-  return launch_mt<8>(ap, w, M, out, nsplit, epi, qe, rs, s);
+  if (M <= 128) return launch_rows(ap, w, M, M, out, nsplit, epi, qe, rs, s, 0);
+  const hipError_t e = launch_rows(ap, w, 128, M, out, nsplit, epi, qe, rs, s, 0);
+  return e != hipSuccess ? e : launch_rows(ap, w, M - 128, M, out, nsplit, epi, qe, rs, s, 128);
 }
 
 }  // namespace
 
-bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && M <= 128 && N % 16 == 0 && K % 8 == 0 && N >= 16; }
+bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && M <= kMaxRows && N % 16 == 0 && K % 8 == 0 && N >= 16; }
 
 int packed_cols(int K) { return (K + kPadCols - 1) / kPadCols * kPadCols; }
 

@@ -18,7 +18,7 @@ from oracle import ht_oracle as O
 from helpers import oracle_model, prompt_of, tree_of
 
 DEV = "cuda:0"
-TOPK, WORDS = 64, 2
+TOPK, WORDS = 64, 4                  # mask words per row: HT_MAX_ROWS / 64
 
 
 def _B():

@@ -47,7 +47,8 @@ def test_generators_give_the_same_bits_on_the_gpu():
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (3, 208, 200), (8, 1024, 256), (16, 768, 688), (17, 4096, 1024),
                                    (64, 8192, 512), (64, 1024, 4096), (76, 2064, 688), (84, 4096, 1024), (96, 22016, 256),
                                    (100, 256, 11008), (128, 12288, 128),
-                                   (40, 5120, 13824), (67, 5136, 12296)])   # 128-row workgroups, six K splits
+                                   (40, 5120, 13824), (67, 5136, 12296),    # 128-row workgroups, six K splits
+                                   (129, 1024, 4096), (200, 2064, 688), (256, 12288, 128), (144, 5120, 13824)])  # two launches
 def test_skinny_product_matches_textbook_product(dtype, M, N, K):
     B, H = _B(), _H()
     say(f"gemm {dtype} M={M} N={N} K={K}")
@@ -69,7 +70,7 @@ def test_skinny_product_matches_textbook_product(dtype, M, N, K):
 
 
 @pytest.mark.parametrize("M,f,K", [(1, 64, 64), (7, 208, 200), (64, 688, 256), (76, 1376, 512), (128, 4112, 136),
-                                   (64, 11008, 128)])
+                                   (64, 11008, 128), (131, 688, 256), (256, 1376, 512)])
 def test_fused_gate_up_product_matches_its_definition(M, f, K):
     """act = silu(a . Wg^T) * (a . Wu^T) (the feed-forward block's first half, fused into one kernel) against the
     oracle's product and SiLU, bf16 operands; sizes with ragged row-block counts and several token tiles."""
@@ -165,7 +166,8 @@ def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=Tru
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("case", ["random", "chain", "star", "single", "gqa", "empty_cache", "no_rotate", "ragged"])
+@pytest.mark.parametrize("case", ["random", "chain", "star", "single", "gqa", "empty_cache", "no_rotate", "ragged",
+                                  "rows200", "rows256"])
 def test_tree_attention_small(dtype, case):
     say(f"attention {dtype} {case}")
     if case == "random":
@@ -182,8 +184,12 @@ def test_tree_attention_small(dtype, case):
         _attention_case(dtype, 12, 0, 2, 2, 64, random_tree(9, 12, 3)[0], 8)
     elif case == "no_rotate":
         _attention_case(dtype, 24, 37, 4, 4, 64, random_tree(5, 24, 4)[0], 9, rotate=False)
-    else:
+    elif case == "ragged":
         _attention_case(dtype, 70, 203, 3, 3, 128, random_tree(11, 70, 6)[0], 10, cap=280)
+    elif case == "rows200":                          # more rows than a tree has nodes: four ancestor-mask words
+        _attention_case(dtype, 200, 150, 2, 1, 128, random_tree(12, 200, 9)[0], 11)
+    else:
+        _attention_case(dtype, 256, 61, 2, 2, 64, random_tree(13, 256, 12)[0], 12, rotate=False)
 
 
 def test_tree_attention_at_the_op_workload_size():
@@ -390,6 +396,70 @@ def test_tiny_fp32_drafting_inside_the_verify_pass(name, which):
     assert sc.steps_without_draft_pass >= (15 if which == "all" else 1)
     assert sc.min_margin > H.FP32_LOGIT_TOL and sc.min_margin > 10 * sc.max_err, (sc.min_margin, sc.max_err)
     sc.gpu.close()
+
+
+def _full_fused_schedule_case(wl, tensors_gpu, tensors_cpu, prompt_len):
+    """The paper's own inference schedule (Fig. 2 caption, end of Sec. 3.4): EVERY tree node carries its k pseudo rows
+    through the verify pass, T (1 + k) rows in the blocks above the transfer layer.  One pass on given tokens against
+    the oracle's `fused_verify_and_draft`: the T verify-logit rows, and the k draft distributions of every node."""
+    B, H = _B(), _H()
+    parent, rank = tree_of(wl)
+    T = len(parent)
+    model = oracle_model(wl, tensors_cpu)
+    ora = O.HiddenTransferOracle(model, parent, rank, wl.max_cache)
+    prompt = prompt_of(wl, prompt_len)
+    ora.prefill(prompt)
+    gpu = H.gpu_model(wl, tensors_gpu, max_tree=T * (1 + wl.k))
+    gpu.ht_set_tree(parent, rank)
+    gpu.ht_set_fused_nodes(list(range(T)))
+    gpu.ht_prefill(prompt)
+    tok = [ora.root] + [(11 + 17 * v) % wl.vocab for v in range(1, T)]
+    z_o, g_o, d_o = ora.fused_verify_and_draft(tok)
+    z = torch.empty(T, wl.vocab, dtype=torch.float32, device=H.DEV)
+    g = torch.empty(T, dtype=torch.int32, device=H.DEV)
+    gpu.ht_tree_verify_step(torch.tensor(tok, dtype=torch.int32, device=H.DEV), g, z)
+    torch.cuda.synchronize()
+    worst = H.assert_close(H.cpu(z), z_o, wl.dtype, "verify logits with every node drafting in the pass")
+    zc = H.cpu(z)
+    assert [int(t) for t in g.cpu()] == [int(j) for j in np.argmax(zc, axis=1)]
+    width, cands = ora.width, []
+    for v in range(T):
+        d, cand = gpu.fused_drafts(v)
+        d = H.cpu(d)
+        worst = max(worst, H.assert_close(d, d_o[v], wl.dtype, f"draft distributions of node {v}"))
+        cands.append(cand.cpu().numpy())
+        for e in range(1, len(width)):          # the oracle's candidate rule on the GPU's own draft logits
+            assert list(cands[v][e - 1][:width[e]]) == O.top_candidates(d[e - 1], width[e]), f"node {v}: candidates at depth {e}"
+    # the step after any acceptance needs neither a transfer nor a draft pass: its tree comes from these rows
+    m, emitted, root, path = gpu.ht_accept_and_compact()
+    gpu.ht_transfer(None, None)
+    gpu.ht_tree_verify_step(None, g, z)
+    torch.cuda.synchronize()
+    tok2 = [int(t) for t in gpu.ht_get_buffer(B.HT_BUF_TREE_TOKENS).cpu()]
+    mine = cands[path[-1]]
+    assert tok2 == [root] + [int(mine[ora.depth[v] - 1][ora.rank[v]]) for v in range(1, T)], "tree of the next step"
+    gpu.close()
+    return worst
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_k3", "tiny_t123"])
+def test_every_node_drafts_inside_the_verify_pass_tiny(name):
+    wl = WORKLOADS[name]
+    say(f"full fused schedule {name}: {wl.tree_size} nodes x (1 + {wl.k}) rows")
+    worst = _full_fused_schedule_case(wl, None, None, wl.prompt_len)
+    say(f"  largest logit error {worst:.3e}")
+
+
+def test_every_node_drafts_inside_the_verify_pass_llama7b_width():
+    """64 nodes x (1 + 3) = 256 rows in the upper block and the LM head at the 7B widths (2 layers, transfer after the
+    first): the projections run two launches of 128 rows over the same weights, attention four row groups."""
+    H = _H()
+    wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), prompt_len=96, max_cache=96 + 256 + 16)
+    say("full fused schedule, 7B width, 2 layers: 256 rows above the transfer layer")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    worst = _full_fused_schedule_case(wl, tensors, cpu_tensors, wl.prompt_len)
+    say(f"  worst logit error / bound {worst:.3f}")
 
 
 @pytest.mark.parametrize("seed", range(6))
