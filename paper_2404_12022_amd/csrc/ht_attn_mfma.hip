@@ -537,6 +537,254 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The tile scheme with a wavefront of its own for the loads, for long key ranges and grouped query heads.  One
+// workgroup serves one key/value head and one key slice: NCW wavefronts each own a block of 16 query columns, a column
+// being a (query head of the group, tree row) pair, so the query heads that share a key/value head also share its
+// tiles (attn_tile_kernel stages them once per query head); one more wavefront does nothing but bring 64-key tiles of
+// K and V^T from global memory straight into LDS (16-byte LDS-direct loads: no registers and no LDS stores in
+// between), a ring of kStages tiles, one or two tiles ahead of the arithmetic.  One barrier per tile.  The LDS layout
+// of a tile is that of attn_tile_kernel (XOR-swizzled 16-byte pieces); an LDS-direct load writes 64 consecutive
+// pieces, so every lane picks the global piece that belongs at its place.  Same arithmetic in the same order as
+// attn_tile_kernel: the two give the same bits.
+template <int N> __device__ __forceinline__ void attn_wait_vm_then_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void attn_wait_lds_then_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int HD> struct RingShape {
+  static constexpr int TK = 64;
+  static constexpr int KBYTES = TK * HD * 2, VBYTES = HD * TK * 2, STAGE = KBYTES + VBYTES;
+  static constexpr int NL = STAGE / 1024;                              // LDS-direct loads per tile
+  static constexpr int AHEAD = 63 / NL < 2 ? 63 / NL : 2;              // tiles that may be in flight at a barrier
+  static constexpr int STAGES = AHEAD + 2;
+  static constexpr int LDS_BYTES = STAGES * STAGE;
+};
+
+template <int HD, int NCW>
+__global__ __launch_bounds__(64 * (NCW + 1)) void attn_ring_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                                   const bf16_t* __restrict__ vc, int cap, int n, int M,
+                                                                   const uint64_t* __restrict__ anc, int Hq, int Hkv,
+                                                                   bf16_t* __restrict__ out, float* __restrict__ part_o,
+                                                                   float* __restrict__ part_ml, int nsplit, float scale_log2,
+                                                                   const int32_t* __restrict__ n_dev) {
+  n = cache_len(n, n_dev);
+  using RS = RingShape<HD>;
+  constexpr int TK = RS::TK, ES = HD / 32, EB = HD / 16, PK = HD / 8;
+  constexpr int KBYTES = RS::KBYTES, STAGE = RS::STAGE, NL = RS::NL, NLK = KBYTES / 1024, AHEAD = RS::AHEAD, ST = RS::STAGES;
+  static_assert(KBYTES % 1024 == 0 && RS::VBYTES % 1024 == 0, "whole LDS-direct loads per tile");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  const int hk = blockIdx.x, group = Hq / Hkv, split = blockIdx.z;
+  const int S = n + M;
+  const int tiles = (S + TK - 1) / TK;
+  int ts, te;
+  even_share(tiles, nsplit, split, ts, te);
+  const bool empty = ts >= te;                            // a slice without tiles still leaves its (neutral) partials
+  int tmid = n / TK;                                      // tiles below tmid hold cache keys only
+  tmid = tmid < ts ? ts : (tmid > te ? te : tmid);
+  const int iters = te - ts;
+  const bool tail_tile = te == tiles && S % TK != 0;      // the slice ends with a tile that reaches past the last tree row
+
+  if (wave == NCW) {
+    // ---- load wavefront.  Piece li < NLK of a tile is K (64 / PK key rows), the others V^T (eight rows e of 64 keys)
+    if (empty) return;
+    const bf16_t* kbase = kc + (size_t)hk * HD;
+    const bf16_t* vbase = vc + (size_t)hk * HD * cap;
+    const unsigned krow_stride = (unsigned)(Hkv * HD);
+    auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+      t = t < te - 1 ? t : te - 1;                          // past the slice: a redundant in-bounds reload, never read
+      const int j0 = t * TK;
+      unsigned char* base = ring + stage * STAGE;
+#pragma unroll
+      for (int li = 0; li < NLK; ++li) {
+        const int piece = li * 64 + lane, kl = piece / PK, pos = piece % PK;
+        const int sw = ((((kl >> 3) & 3) << 2) | (kl & 3)) & (PK - 1);
+        int key = j0 + kl;
+        key = key < cap ? key : cap - 1;
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(kbase + (unsigned)key * krow_stride + (pos ^ sw) * 8),
+            (void __attribute__((address_space(3)))*)(base + li * 1024), 16, 0, 0);
+      }
+#pragma unroll
+      for (int li = 0; li < NL - NLK; ++li) {
+        const int piece = li * 64 + lane, e = piece / (TK / 8), pos = piece % (TK / 8);
+        int kv = j0 + (pos ^ ((e >> 1) & 7)) * 8;
+        kv = kv + 8 <= cap ? kv : cap - 8;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(vbase + (size_t)e * cap + kv),
+                                         (void __attribute__((address_space(3)))*)(base + KBYTES + li * 1024), 16, 0, 0);
+      }
+    };
+    // V columns of keys past the last tree row hold whatever the cache holds there: zeroed in LDS once the tile has
+    // landed (their probabilities are zero, but zero times a stray NaN would not be)
+    auto clear_tail = [&](int stage) __attribute__((always_inline)) {
+      const int valid = S - (tiles - 1) * TK;               // keys of the tile that carry data, 1 .. TK - 1
+      unsigned char* vb = ring + stage * STAGE + KBYTES;
+      for (int idx = lane; idx < HD * (TK - valid); idx += 64) {
+        const int e = idx / (TK - valid), key = valid + idx % (TK - valid);
+        *(bf16_t*)(vb + e * (TK * 2) + (((key >> 3) ^ ((e >> 1) & 7)) << 4) + (key & 7) * 2) = 0;
+      }
+    };
+#pragma unroll
+    for (int p = 0; p < ST - 1; ++p) fetch(ts + p, p);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(AHEAD * NL) : "memory");      // tile ts has landed
+    if (tail_tile && iters == 1) clear_tail(0);
+    attn_wait_vm_then_barrier<AHEAD * NL>();
+    int stage = ST - 1;
+    for (int i = 0; i < iters; ++i) {
+      fetch(ts + i + ST - 1, stage);                        // the stage the others finished before the last barrier
+      stage = stage + 1 == ST ? 0 : stage + 1;
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(AHEAD * NL) : "memory");    // tile ts + i + 1 has landed
+      if (tail_tile && i + 2 == iters) clear_tail((i + 1) % ST);
+      attn_wait_vm_then_barrier<AHEAD * NL>();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // nothing may still be writing LDS when the wavefront ends
+    return;
+  }
+
+  // ---- arithmetic wavefronts: one block of 16 query columns each
+  const int row_blocks = (M + 15) / 16, blocks = group * row_blocks;
+  const int blk = blockIdx.y * NCW + wave;
+  const bool live = blk < blocks;
+  const int bc = live ? blk : blocks - 1;
+  const int h = hk * group + bc / row_blocks, m0 = (bc % row_blocks) * 16;
+  Frag qf[ES];
+  uint64_t amask[kMaskWords];
+  {
+    const int m = m0 + r16, mc = m < M ? m : M - 1;
+    const bf16_t* qrow = q + ((size_t)mc * Hq + h) * HD + g * 8;
+#pragma unroll
+    for (int es = 0; es < ES; ++es) qf[es].nat = *(const u32x4_t*)(qrow + es * 32);
+#pragma unroll
+    for (int wd = 0; wd < kMaskWords; ++wd) amask[wd] = m < M ? anc[(size_t)m * kMaskWords + wd] : 0ull;
+  }
+  floatx4_t oacc[EB];
+  float mrun = -INFINITY, lrun = 0.f;
+#pragma unroll
+  for (int eb = 0; eb < EB; ++eb) oacc[eb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  int kfo[2], vfo[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) kfo[b] = ((r16 >> 2) * 8 + b * 4 + (r16 & 3)) * (HD * 2);   // interleaved key order
+  const int ksw = r16 & (PK - 1);
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) vfo[sub] = KBYTES + r16 * (TK * 2) + (((sub * 4 + g) ^ ((r16 >> 1) & 7)) << 4);
+
+  auto process = [&](auto masked, int stage, int t) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked)::value;
+    const unsigned char* base = ring + stage * STAGE;
+    const int j0 = t * TK;
+    Frag kf[2][2][ES];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int es = 0; es < ES; ++es)
+          kf[sub][b][es].nat = *(const u32x4_t*)(base + kfo[b] + sub * 32 * (HD * 2) + (((es * 4 + g) ^ ksw) << 4));
+    floatx4_t s[2][2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        s[sub][b] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int es = 0; es < ES; ++es)
+          s[sub][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sub][b][es].v, qf[es].v, s[sub][b], 0, 0, 0);
+      }
+    float p[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) p[x] = s[x >> 3][(x >> 2) & 1][x & 3];
+    if (MASKED) {
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int j = j0 + (x >> 3) * 32 + g * 8 + (x & 7);
+        bool vis = j < n;
+        if (!vis && j < S) {
+          const int u = j - n;
+          vis = (amask[u >> 6] >> (u & 63)) & 1ull;
+        }
+        p[x] = vis ? p[x] : -INFINITY;
+      }
+    }
+    float cmax = p[0];
+#pragma unroll
+    for (int x = 1; x < 16; ++x) cmax = fmaxf(cmax, p[x]);
+    cmax = max_over_groups(cmax) * scale_log2;
+    const bool grow = cmax > mrun + kRescaleStep;
+    if (__any(grow)) {
+      const float mnew = grow ? cmax : mrun;
+      const float alpha = grow ? __builtin_amdgcn_exp2f(mrun - cmax) : 1.0f;
+      lrun *= alpha;
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb) oacc[eb] *= alpha;
+      mrun = mnew;
+    }
+    const float msafe = MASKED ? (mrun == -INFINITY ? 0.f : mrun) : mrun;
+    float psum = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      p[x] = __builtin_amdgcn_exp2f(fmaf(p[x], scale_log2, -msafe));
+      psum += p[x];
+    }
+    lrun += psum;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      Frag vf[EB];
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb) vf[eb].nat = *(const u32x4_t*)(base + vfo[sub] + eb * 16 * (TK * 2));
+      Frag pf;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) {
+        floatx2_t f2 = {p[sub * 8 + 2 * w2], p[sub * 8 + 2 * w2 + 1]};
+        bf16x2_t b2 = __builtin_convertvector(f2, bf16x2_t);
+        pf.u[w2] = *(const uint32_t*)&b2;
+      }
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb)
+        oacc[eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[eb].v, pf.v, oacc[eb], 0, 0, 0);
+    }
+  };
+
+  if (!empty) {
+    attn_wait_lds_then_barrier();                           // tile ts is in LDS
+    int stage = 0, t = ts;
+    for (; t < tmid; ++t) {
+      if (live) process(std::false_type{}, stage, t);
+      stage = stage + 1 == ST ? 0 : stage + 1;
+      attn_wait_lds_then_barrier();
+    }
+    for (; t < te; ++t) {                                   // the few tiles that reach past the cache
+      if (live) process(std::true_type{}, stage, t);
+      stage = stage + 1 == ST ? 0 : stage + 1;
+      attn_wait_lds_then_barrier();
+    }
+  }
+
+  const float lsum = sum_over_groups(lrun);
+  const int m = m0 + r16;
+  if (!live || m >= M) return;
+#pragma unroll
+  for (int eb = 0; eb < EB; ++eb) {
+    const int e0 = eb * 16 + g * 4;
+    if (nsplit == 1) {
+      const float inv = 1.0f / lsum;
+      bf16_t ob[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(oacc[eb][i] * inv);
+      *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
+    } else {
+      float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
+      *(float4*)dst = make_float4(oacc[eb][0], oacc[eb][1], oacc[eb][2], oacc[eb][3]);
+    }
+  }
+  if (nsplit > 1 && g == 0) {
+    float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
+    ml[0] = mrun;
+    ml[1] = lsum;
+  }
+}
+
 // out[m][h] = sum_s exp2(m_s - m*) O_s / sum_s exp2(m_s - m*) l_s, splits added in index order.
 // HD / 4 lanes per (row, head) pair, four output elements per lane; 256-thread blocks.
 template <int HD>
@@ -568,15 +816,30 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 // Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts of a workgroup
 // split the keys of the slice and fragments come straight from global memory.  More rows: the tile kernel,
 // each wavefront owning 16 rows (two row groups of workgroups above 64 rows).
-struct AttnPlan { int qb, waves, groups, nsplit; bool tiled; };
+struct AttnPlan { int qb, waves, groups, nsplit; bool tiled; int ring_waves; };
 
-AttnPlan plan_attention(int M, int Hq, int S) {
+AttnPlan plan_attention(int M, int Hq, int Hkv, int S) {
   AttnPlan p;
   p.tiled = M > 16;
   p.qb = 1;                                       // 32 rows per wavefront measured slower (one wave per SIMD)
   p.waves = 4;
+  p.ring_waves = 0;
   p.groups = p.tiled ? (M + p.waves * p.qb * 16 - 1) / (p.waves * p.qb * 16) : 1;
   const int units = p.tiled ? (S + 63) / 64 : (S + 31) / 32;     // tiles or chunks
+  // Long key ranges, or query heads that share key/value heads: the ring kernel (measured at 128-wide heads, 64 rows:
+  // 40 heads over 2112 keys 14.2 -> 13.2 us, 64 query on 8 key/value heads over 4160 keys 25.1 -> 20.7 us; 128 rows
+  // of 32 heads over 4224 keys 23.7 -> 22.8 us; over 576 keys the tile kernel stays ahead, 7.0 against 7.3 us).  Its
+  // three-tile ring fills the LDS of a compute unit, so the slices are cut for one workgroup per unit.
+  const int blocks = (Hq / Hkv) * ((M + 15) / 16);
+  if (p.tiled && units >= 24 && M <= 128) {
+    p.ring_waves = blocks >= 8 ? 8 : 4;
+    p.groups = (blocks + p.ring_waves - 1) / p.ring_waves;
+    int s = 256 / (Hkv * p.groups);
+    if (s > units / 2) s = units / 2;
+    if (s > kMaxSplits) s = kMaxSplits;
+    p.nsplit = s < 1 ? 1 : s;
+    return p;
+  }
   int s = (512 + Hq * p.groups - 1) / (Hq * p.groups);           // about two workgroups per compute unit
   // per slice: every wavefront has work; slices of under four tiles only pay off on short caches (measured)
   const int min_units = !p.tiled ? 4 : (units >= 16 ? 4 : 2);
@@ -587,20 +850,45 @@ AttnPlan plan_attention(int M, int Hq, int S) {
   return p;
 }
 
+template <int HD, int NCW>
+hipError_t launch_ring(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
+                       int Hkv, bf16_t* out, float* part_o, float* part_ml, const AttnPlan& p, float scale_log2, hipStream_t s,
+                       const int32_t* n_dev) {
+  constexpr int lds = RingShape<HD>::LDS_BYTES;            // above the 64 KB a kernel may use without asking
+  static bool allowed = false;
+  if (!allowed) {
+    const hipError_t e = hipFuncSetAttribute((const void*)attn_ring_kernel<HD, NCW>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    allowed = true;
+  }
+  hipLaunchKernelGGL((attn_ring_kernel<HD, NCW>), dim3(Hkv, p.groups, p.nsplit), dim3(64 * (NCW + 1)), lds, s, q, kc, vc, cap, n,
+                     M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2, n_dev);
+  return hipSuccess;
+}
+
 template <int HD>
-void launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
-               int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s, const int32_t* n_dev) {
+hipError_t launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
+                     int Hkv, bf16_t* out, void* scratch, const AttnPlan& p, hipStream_t s, const int32_t* n_dev) {
   float* part_o = (float*)scratch;
   float* part_ml = part_o + (size_t)Hq * kMaxSplits * M * HD;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const dim3 grid(Hq, p.groups, p.nsplit);
 #define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2, n_dev
-  if (!p.tiled) hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
-  else hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  if (p.ring_waves) {
+    const hipError_t e = p.ring_waves == 8
+        ? launch_ring<HD, 8>(q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p, scale_log2, s, n_dev)
+        : launch_ring<HD, 4>(q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p, scale_log2, s, n_dev);
+    if (e != hipSuccess) return e;
+  } else if (!p.tiled) {
+    hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  } else {
+    hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+  }
 #undef HT_ATTN_ARGS
   if (p.nsplit > 1)
     hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((M + 256 / (HD / 4) - 1) / (256 / (HD / 4)), Hq), dim3(256), 0, s,
                        part_o, part_ml, p.nsplit, M, Hq, out);
+  return hipSuccess;
 }
 
 }  // namespace
@@ -616,11 +904,11 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s, const int32_t* n_dev) {
   if ((size_t)cap * Hkv * hd >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside a cache
-  const AttnPlan p = plan_attention(M, Hq, n + M);
+  const AttnPlan p = plan_attention(M, Hq, Hkv, n + M);
   const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
-  if (hd == 128) launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev);
-  else launch_hd<64>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev);
-  return hipGetLastError();
+  const hipError_t e = hd == 128 ? launch_hd<128>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev)
+                                 : launch_hd<64>(qp, kp, vp, cap, n, M, tree.anc, Hq, Hkv, (bf16_t*)out, scratch, p, s, n_dev);
+  return e != hipSuccess ? e : hipGetLastError();
 }
 
 }  // namespace ht

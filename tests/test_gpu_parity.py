@@ -112,13 +112,17 @@ def test_stream_read_probe_reads_whole_passes_and_rejects_bad_buffers():
 
 
 # ------------------------------------------------------------------ tree attention, op level
-def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=True, base=10000.0):
+def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=True, base=10000.0, poison=False):
+    """poison: the cache slots past the last tree row hold NaN (they are never visible and must not leak)."""
     B, H = _B(), _H()
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-    cap = cap or ((n + T + 7) // 8 * 8)
+    cap = cap or ((n + T + 7) // 8 * 8 + (24 if poison else 0))
     q = counter_normal(seed, 21, (T, Hq, hd), 1.0, device=H.DEV, dtype=tdt)
     kc = counter_normal(seed, 22, (cap, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
     vc = counter_normal(seed, 23, (Hkv, hd, cap), 1.0, device=H.DEV, dtype=tdt)
+    if poison:
+        kc[n + T:] = float("nan")
+        vc[:, :, n + T:] = float("nan")
     kn = counter_normal(seed, 24, (T, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
     vn = counter_normal(seed, 25, (T, Hkv, hd), 1.0, device=H.DEV, dtype=tdt)
     out = torch.full((T, Hq * hd), float("nan"), dtype=tdt, device=H.DEV)
@@ -167,7 +171,7 @@ def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=Tru
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", ["random", "chain", "star", "single", "gqa", "empty_cache", "no_rotate", "ragged",
-                                  "rows200", "rows256"])
+                                  "rows200", "rows256", "long_ragged", "long_grouped"])
 def test_tree_attention_small(dtype, case):
     say(f"attention {dtype} {case}")
     if case == "random":
@@ -185,7 +189,11 @@ def test_tree_attention_small(dtype, case):
     elif case == "no_rotate":
         _attention_case(dtype, 24, 37, 4, 4, 64, random_tree(5, 24, 4)[0], 9, rotate=False)
     elif case == "ragged":
-        _attention_case(dtype, 70, 203, 3, 3, 128, random_tree(11, 70, 6)[0], 10, cap=280)
+        _attention_case(dtype, 70, 203, 3, 3, 128, random_tree(11, 70, 6)[0], 10, poison=True)
+    elif case == "long_ragged":                      # 33 tiles, the last one holding two keys and then NaN
+        _attention_case(dtype, 50, 2000, 4, 2, 128, random_tree(14, 50, 5)[0], 13, poison=True)
+    elif case == "long_grouped":                     # six query heads on one key/value head, 64-wide heads, ragged end
+        _attention_case(dtype, 40, 1777, 6, 1, 64, random_tree(15, 40, 4)[0], 14, poison=True)
     elif case == "rows200":                          # more rows than a tree has nodes: four ancestor-mask words
         _attention_case(dtype, 200, 150, 2, 1, 128, random_tree(12, 200, 9)[0], 11)
     else:
