@@ -190,6 +190,80 @@ def time_attention_op(dev):
                     "static tree's tables are uploaded once"}
 
 
+def time_second_workload(name, dev, tree_sizes, reps):
+    """Verify pass of another named workload at its own cache length: one model, a sweep over tree sizes (HIP events
+    on the launch stream), the one-token pass, and the whole step at the workload's own tree size in two schedules."""
+    import torch
+    from ht_inputs import WORKLOADS, make_weights, counter_tokens, prune_tree
+    from ht_inputs.generators import PROMPT_STREAM
+    import paper_2404_12022_amd.binding as B
+    wl = WORKLOADS[name]
+    T0, n0 = wl.tree_size, wl.prompt_len
+    steps = 10
+    rows = max(tree_sizes + [T0 + (wl.k + 1) * wl.k])
+    wl = wl.with_(max_cache=(n0 + 4 * (2 * steps + 8) * (wl.k + 1) + rows + 7) // 8 * 8)
+    tdt = torch.bfloat16
+    weights = make_weights(wl, wl.seed, dev, tdt)
+    model = B.HTModel(B.make_config(wl, max_tree=min(128, rows)), weights, dev)
+    prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n0, wl.vocab)]
+    parent, rank = prune_tree(wl.branching, T0)
+    model.ht_set_tree(parent, rank)
+    model.ht_prefill(prompt)
+    stream = torch.cuda.current_stream()
+
+    def verify_ms(tp, tr):
+        model.ht_set_tree(tp, tr)
+        toks = torch.tensor(prompt[:len(tp)], dtype=torch.int32, device=dev)
+        for _ in range(3):
+            model.ht_tree_verify_step(toks)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            model.ht_tree_verify_step(toks)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def step_ms(nodes):
+        model.ht_set_tree(parent, rank)
+        model.ht_set_fused_nodes(nodes)
+        for _ in range(3):
+            model.ht_transfer(); model.ht_tree_verify_step(); model.ht_accept_and_compact()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            model.ht_transfer(); model.ht_tree_verify_step(); model.ht_accept_and_compact()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_one = verify_ms([-1], [0])
+    sweep = []
+    for ts in tree_sizes:
+        tp, tr = prune_tree(wl.branching, ts)
+        ms_t = verify_ms(tp, tr)
+        by = model_bytes(wl, ts, n0)
+        sweep.append({"T": ts, "verify_pass_ms": round(ms_t, 4), "verify_over_one_token": round(ms_t / ms_one, 4),
+                      "hbm_GBps": round(by / (ms_t * 1e-3) / 1e9, 1),
+                      "hbm_frac_of_peak": round(by / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+    chain, cur = [0], 0
+    while True:
+        kids = [v for v in range(T0) if parent[v] == cur and rank[v] == 0]
+        if not kids:
+            break
+        cur = kids[0]
+        chain.append(cur)
+    ms_s1 = step_ms([])
+    ms_hybrid = step_ms(chain)
+    res = {"workload": f"{wl.name}: {wl.n_layers} layers d={wl.d_model} {wl.n_heads}x{wl.head_dim} heads ffn={wl.d_ffn}, "
+                       f"cache {n0}, k={wl.k} transfer after layer {sorted(set(wl.transfer_layers))}",
+           "one_token_step_ms": round(ms_one, 4), "tree_size_sweep": sweep, "tree_size_of_the_steps": T0,
+           "step_ms_draft_after_accept": round(ms_s1, 4), "step_ms_rank0_chain_drafts_in_verify_pass": round(ms_hybrid, 4)}
+    model.close()
+    del model, weights
+    torch.cuda.empty_cache()
+    return res
+
+
 def measured_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None."""
     path = os.path.join(ROOT, "profiles", "gemm_gateup_hbm_traffic.json")
@@ -224,6 +298,8 @@ def main():
                          "first transfer step (`training_forward` object)")
     ap.add_argument("--attention-op", action="store_true",
                     help="time the tree-attention op alone (32 heads x 128, cache 4096, random 128-node tree)")
+    ap.add_argument("--only-main", action="store_true",
+                    help="skip the objects a default run adds to the 7B line: the tree-attention op and the 13B workload")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph launch medians (counter collection under rocprofv3 does not survive graph launches)")
     ap.add_argument("--roofline-only", action="store_true",
@@ -252,7 +328,7 @@ def main():
     cache_lens = [int(t) for t in args.cache_lens.split(",") if t]
     fused_counts = [int(t) for t in args.fused_counts.split(",") if t]
     fused_rows = max([wl.k + 1] + fused_counts) * wl.k   # pseudo rows under the rank-0 chain (or the largest sweep entry)
-    headroom = 4 * (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size + fused_rows] + sweep_sizes)
+    headroom = 5 * (args.steps + args.warmup + 4) * (wl.k + 1) + max([wl.tree_size * (1 + wl.k)] + sweep_sizes)
     if args.training_forward:
         sweep_sizes_model = sweep_sizes + [128]      # 128-row passes: 63 positions, their pseudo rows, one of lookahead
     else:
@@ -281,7 +357,9 @@ def main():
         del head
     else:
         weights = make_weights(wl, wl.seed, dev, tdt)
-        model = B.HTModel(B.make_config(wl, max_tree=min(128, max([T + fused_rows] + sweep_sizes_model))), weights, dev)
+        full_rows = T * (1 + wl.k)                   # every node with its k pseudo rows: the paper's own schedule
+        rows_model = max([T + fused_rows] + sweep_sizes_model + ([full_rows] if full_rows <= B.HT_MAX_ROWS else []))
+        model = B.HTModel(B.make_config(wl, max_tree=min(B.HT_MAX_ROWS, rows_model)), weights, dev)
     model.ht_set_tree(parent, rank)
     model.ht_prefill(prompt)
     stream = torch.cuda.current_stream()
@@ -329,6 +407,11 @@ def main():
         chain.append(cur)
     model.ht_set_fused_nodes(chain)
     ms_step, accepted = timed_steps()
+    # the paper's own schedule: every node carries its k pseudo rows, T (1 + k) rows above the transfer layer
+    ms_step_full = None
+    if T * (1 + wl.k) <= model.cfg.max_tree:
+        model.ht_set_fused_nodes(list(range(T)))
+        ms_step_full, _ = timed_steps()
     model.ht_set_fused_nodes([])
 
     # ---- verify pass alone (explicit tokens, no draft) and the one-token step, HIP events on the launch stream
@@ -384,7 +467,7 @@ def main():
     model.ht_set_tree(parent, rank)
     fused_sweep = []
     for cnt in fused_counts:                     # verify pass with explicit tokens and `cnt` nodes drafting in-pass
-        if T + cnt * wl.k > 128:
+        if T + cnt * wl.k > model.cfg.max_tree:
             continue
         model.ht_set_tree(parent, rank)
         model.ht_set_fused_nodes(list(range(cnt)))
@@ -464,7 +547,7 @@ def main():
         for _ in range(reps_tr):
             _, loss_tr = model.ht_training_forward(step_tr, toks_tr)
         ms_tr = (time.perf_counter() - t0) * 1e3 / reps_tr
-        chunk = (model.cfg.max_tree - step_tr) // 2
+        chunk = (min(model.cfg.max_tree, B.HT_MAX_TREE) - step_tr) // 2
         passes = (n_tr + chunk - 1) // chunk
         t_layer = wl.transfer_layers[step_tr - 1]
         per_layer = 2 * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim + wl.n_heads * wl.head_dim * wl.d_model +
@@ -495,9 +578,14 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers d={wl.d_model} {wl.n_heads}x{wl.head_dim} heads "
                                f"ffn={wl.d_ffn} vocab={wl.vocab}, batch 1, cache {n0}, tree T={T} {list(wl.branching)}, "
                                f"k={wl.k} transfer after layer {sorted(set(wl.transfer_layers))}; step = hidden transfer + pseudo "
-                               f"rows through the upper blocks + top-k + tree build + verify + accept + compact, the "
-                               f"pseudo rows of the rank-0 chain riding in the verify pass"},
+                               f"rows through the upper blocks + top-k + tree build + verify + accept + compact.  "
+                               f"Schedule of `value`: the pseudo rows of the rank-0 chain ({len(chain)} nodes x k rows) ride in "
+                               f"the verify pass and, with random maps, every acceptance ends on that chain, so no step "
+                               f"needs a draft pass: the hybrid's best case.  The schedule that drafts after every "
+                               f"acceptance costs `step_ms_draft_after_accept`, the paper's own schedule (all {T} nodes "
+                               f"draft in the pass) `step_ms_every_node_drafts_in_verify_pass`"},
         "step_ms_draft_after_accept": round(ms_step_s1, 4),
+        "step_ms_every_node_drafts_in_verify_pass": None if ms_step_full is None else round(ms_step_full, 4),
         "step_ms_draft_after_accept_device_resident_loop": round(ms_step_loop, 4),
         "step_ms_draft_after_accept_dynamic_tree": {"ms": round(ms_step_dynamic, 4), "candidates_per_position": dyn_b},
         "verify_pass_ms": round(ms_verify, 4), "one_token_step_ms": round(ms_one, 4),
@@ -513,6 +601,11 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic() if wl.name == "llama7b" else None,
+                     "traffic_source": "FETCH_SIZE + WRITE_SIZE of this kernel from the committed rocprofv3 counter runs "
+                                       "(profiles/gemm_packed_gateup_7b_hbm_counters.md), not a counter read in this run",
+                     "whole_verify_pass": {"achieved": round(verify_bytes / (ms_verify * 1e-3) / 1e9, 1),
+                                           "frac": round(verify_bytes / (ms_verify * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                           "bytes": verify_bytes, "ms": round(ms_verify, 4)},
                      "kernel": (("gemm_packed_kernel<MT=4,R=2,WAVES=3,EPI_SILU,KC=128>" if (kern["N"] // 16 + 5) // 6 <= 260
                                  else "gemm_packed_kernel<MT=4,R=2,WAVES=4,EPI_SILU,KC=64>") +
                                 f": fused gate/up projection + SiLU*up, M={kern['M']} N={kern['N']} K={kern['K']}"),
@@ -532,6 +625,12 @@ def main():
         res["training_forward"] = training
     if not args.no_cpu_baseline and param_bytes <= 100e9:
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
+    if not args.only_main and wl.name == "llama7b":
+        model.close()
+        del model, weights
+        torch.cuda.empty_cache()
+        res["attention_op"] = time_attention_op(dev)
+        res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps))
     print(json.dumps(res))
 
 
