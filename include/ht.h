@@ -238,10 +238,11 @@ int ht_get_buffer(const ht_model *m, int32_t which, int32_t layer, void **dev_pt
  *   k_cache [cap, Hkv, hd], v_cache [Hkv, hd, cap] (key index contiguous); cap multiple of 8, n + T <= cap
  *   out    [T, Hq*hd]: row v = softmax over {cache 0..n-1} U {n+u : u ancestor-or-self of v} of q.k/sqrt(hd), times V
  *   scratch: device bytes >= ht_tree_attention_scratch_bytes(...)
- * parent is a host array; this call turns it into depth and ancestor tables, uploads them into `scratch` and for
- * that waits until the previous call's upload has left the library's staging buffer.  parent == NULL skips both: the
- * tables an earlier call with the same T left in the same `scratch` are used again (a serving loop uploads a tree
- * once).  dtype selects HT_F32 or HT_BF16 for q/k/v/out (softmax and sums in fp32). */
+ * parent is a host array; this call turns it into depth and ancestor tables and uploads them into `scratch` from
+ * pageable memory (the call may wait for the copy, and such a call cannot be captured into a HIP graph).
+ * parent == NULL skips both: the tables an earlier call with the same T left in the same `scratch` are used again (a
+ * serving loop uploads a tree once; that form is capturable and keeps no state outside its arguments, so calls from
+ * several threads on their own scratch buffers and streams do not interfere).  T <= HT_MAX_ROWS.  dtype selects HT_F32 or HT_BF16 for q/k/v/out (softmax and sums in fp32). */
 size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd);
 int ht_tree_attention(const void *q, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
                       int32_t cap, int32_t n, int32_t T, const int32_t *parent /*host*/, int32_t Hq, int32_t Hkv,

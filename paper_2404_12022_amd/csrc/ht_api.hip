@@ -1073,8 +1073,6 @@ AttnScratch attn_scratch_layout(char* base, int T, int Hq, int hd, size_t es) {
   a.total = align_up(cv.off, 256);
   return a;
 }
-int32_t* g_op_stage = nullptr;       // pinned staging for the op-level tree tables
-hipEvent_t g_op_event = nullptr;
 }  // namespace
 
 size_t ht_tree_attention_scratch_bytes(int32_t T, int32_t Hq, int32_t hd) {
@@ -1103,15 +1101,11 @@ int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void*
   AttnScratch a = attn_scratch_layout((char*)scratch, T, Hq, hd, elem_size(dtype));
   TreeTables tt{a.parent, a.depth, a.rank, a.anc};
   if (parent) {                          // NULL: the tables an earlier call left in `scratch` are used again
-    if (!g_op_stage) {
-      HT_HIP(hipHostMalloc((void**)&g_op_stage, sizeof(int32_t) * kTableInts, hipHostMallocDefault));
-      HT_HIP(hipEventCreateWithFlags(&g_op_event, hipEventDisableTiming));
-    } else {
-      HT_HIP(hipEventSynchronize(g_op_event));   // the previous call's upload must have left the staging buffer
-    }
-    fill_tables(T, parent, nullptr, g_op_stage);
-    if ((rc = upload_tables(tt, g_op_stage, s))) return rc;
-    HT_HIP(hipEventRecord(g_op_event, s));
+    // The table image lives on this call's stack and goes up from pageable memory: the copies have left it when
+    // hipMemcpyAsync returns, so the call keeps no state of its own between calls or threads.
+    std::vector<int32_t> stage(kTableInts);
+    fill_tables(T, parent, nullptr, stage.data());
+    if ((rc = upload_tables(tt, stage.data(), s))) return rc;
   }
   const void* qq = q;
   if (k_new) {

@@ -347,204 +347,6 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0);
 }
 
-// --------------------------------------------------------------------------------------------- product, panel wavefront
-// The same product with the activation panel brought in by a wavefront of its own.  In gemm_packed_kernel every
-// wavefront fetches its share of each panel chunk between its weight loads; loads return in issue order, so a panel
-// piece (an L2 hit) holds its place in the queue as long as the weight loads around it (HBM misses), and at 64 token
-// rows the panel is half or more of what a workgroup takes in.  Here WW wavefronts issue weight loads only (a ring of
-// PD chunks each) and one more wavefront does nothing but move panel chunks from global memory straight into LDS
-// (16-byte LDS-direct loads, no registers in between), S stages ahead.  One barrier per chunk as before.
-//
-// LDS stage: rows of KC bf16 (KC / 8 slots of 16 bytes), slot j of row r stored at position j ^ (r & 7), so the eight
-// rows a b128 operand read touches per pass fall on eight different bank groups without padding (an LDS-direct load
-// writes 64 consecutive slots, lane l the slot l: padding is not possible, but every lane picks its source address).
-template <int N> __device__ __forceinline__ void wait_vm_then_barrier() {
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wait_lds_then_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-template <int MT, int R, int WW, int EPI, int KC, int PD, int S, int PF = 0, int DIAG = 0>
-__global__ __launch_bounds__(64 * (WW + 1)) void gemm_ws_kernel(const bf16_t* __restrict__ a,
-                                                                const bf16_t* __restrict__ wp, int M, int N, int K, int KS,
-                                                                void* __restrict__ outp, int nsplit, QkvEpilogue qe,
-                                                                RowScale rs, int row0) {
-  constexpr int STEPS = KC / 32;
-  constexpr int SLOTS = KC / 8;                          // 16-byte slots per row
-  constexpr int ROWS = MT * 16;
-  constexpr int STAGE = ROWS * KC * 2;                   // bytes
-  constexpr int NL = STAGE / 1024;                       // LDS-direct loads (64 lanes x 16 bytes) per chunk
-  static_assert(STAGE % 1024 == 0 && (S - 2) * NL <= 63 && S >= 3 + PF, "stage size / ring depth");
-  static_assert(!PF || PD % 2 == 0, "operand double buffering alternates with the ring slots");
-  constexpr int AHEAD = S - 2 - PF;                      // chunks that may still be in flight at a barrier
-  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
-  const int chunks = KS / STEPS;
-  int c0, c1;
-  even_share(chunks, nsplit, blockIdx.y, c0, c1);
-  const int n_rb = N / 16;
-  constexpr int U = EPI == EPI_SILU ? 2 : 1;
-  const int units = (n_rb + U - 1) / U;
-  int wg0, wg1;
-  even_share(units, gridDim.x, blockIdx.x, wg0, wg1);
-  wg0 *= U;
-  wg1 *= U;
-  if (c0 >= c1) return;                                  // uniform over the block
-  const int last = c1 - 1, iters = c1 - c0;
-
-  if (wave == WW) {
-    // ---- panel wavefront: chunk c goes to stage (c - c0) % S; lane l of load i fills slot 64 i + l of the stage
-    const bf16_t* src[NL];
-    int col[NL];
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int slot = i * 64 + lane, row = slot / SLOTS, pos = slot % SLOTS;
-      src[i] = a + (size_t)(row0 + row) * K;
-      col[i] = (pos ^ (row & 7)) * 8;
-    }
-    auto fetch = [&](int c, int stage) __attribute__((always_inline)) {
-      c = c < last ? c : last;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        int k = c * KC + col[i];
-        k = k < K - 8 ? k : K - 8;
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + k),
-                                         (void __attribute__((address_space(3)))*)(lds + stage * STAGE + i * 1024), 16, 0, 0);
-      }
-    };
-#pragma unroll
-    for (int p = 0; p < S - 1; ++p) fetch(c0 + p, p);
-    wait_vm_then_barrier<AHEAD * NL>();                  // chunk c0 (and c0 + 1 with PF) has landed
-    int stage = S - 1;
-    for (int i = 0; i < iters; ++i) {
-      fetch(c0 + i + S - 1, stage);                      // the stage the others read before the last barrier
-      stage = stage + 1 == S ? 0 : stage + 1;
-      wait_vm_then_barrier<AHEAD * NL>();                // chunk c0 + i + 1 (+ PF) has landed
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // nothing may still be writing LDS when the wavefront ends
-    return;
-  }
-
-  // ---- weight wavefronts
-  const int rb0 = wg0 + wave * R;
-  const u32x4_t* wbase[R];
-  size_t wstep[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const bool own = rb0 + r < wg1;
-    const int rb = own ? rb0 + r : wg0;
-    wbase[r] = (const u32x4_t*)wp + ((size_t)(rb / kTileBlocks) * KS * kTileBlocks + rb % kTileBlocks) * 64 + lane;
-    wstep[r] = own ? (size_t)kTileBlocks * 64 : 0;
-  }
-  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
-    c = c < last ? c : last;
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-      for (int s = 0; s < STEPS; ++s)
-        dst[r][s].nat = __builtin_nontemporal_load(wbase[r] + (size_t)(c * STEPS + s) * wstep[r]);
-  };
-  floatx4_t acc[R][MT];
-#pragma unroll
-  for (int r = 0; r < R; ++r)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-  float4 row_ss[MT];
-  if (rs.ss) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = row0 + mt * 16 + r16;
-      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
-    }
-  }
-  Frag wreg[PD][R][STEPS];
-#pragma unroll
-  for (int p = 0; p < PD; ++p) load_w(wreg[p], c0 + p);
-  wait_lds_then_barrier();
-
-  // operand of token row mt * 16 + r16, K step s: slot s * 4 + g of that row
-  int boff[STEPS];
-#pragma unroll
-  for (int s = 0; s < STEPS; ++s) boff[s] = r16 * (KC * 2) + (((s * 4 + g) ^ (r16 & 7)) * 16);
-  int stage = 0;
-  if (PF) {
-    // operands of chunk c + 1 are read from LDS while the matrix cores work on chunk c: no LDS wait in front of them
-    Frag b[2][STEPS][MT];
-    auto read_b = [&](Frag (&dst)[STEPS][MT], int st) __attribute__((always_inline)) {
-      const unsigned char* ab = lds + st * STAGE;
-#pragma unroll
-      for (int s = 0; s < STEPS; ++s)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) dst[s][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[s]);
-    };
-    read_b(b[0], 0);
-    auto body = [&](Frag (&wslot)[R][STEPS], Frag (&cur)[STEPS][MT], Frag (&nxt)[STEPS][MT], int c) __attribute__((always_inline)) {
-      stage = stage + 1 == S ? 0 : stage + 1;
-      read_b(nxt, stage);
-      if (DIAG != 1) {
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s)
-#pragma unroll
-          for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, cur[s][mt].v, acc[r][mt], 0, 0, 0);
-      } else {
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s)
-#pragma unroll
-          for (int r = 0; r < R; ++r) acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, cur[s][0].v, acc[r][0], 0, 0, 0);
-      }
-      load_w(wslot, c + PD);
-      wait_lds_then_barrier();
-    };
-    int c = c0;
-    for (; c + PD <= c1; c += PD) {
-#pragma unroll
-      for (int p = 0; p < PD; ++p) body(wreg[p], b[p & 1], b[(p + 1) & 1], c + p);
-    }
-#pragma unroll
-    for (int p = 0; p < PD - 1; ++p)
-      if (c + p < c1) body(wreg[p], b[p & 1], b[(p + 1) & 1], c + p);
-  } else {
-  auto body = [&](Frag (&wslot)[R][STEPS], int c) __attribute__((always_inline)) {
-    const unsigned char* ab = lds + stage * STAGE;
-    stage = stage + 1 == S ? 0 : stage + 1;
-    Frag b[2][MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) b[0][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[0]);
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-      if (s + 1 < STEPS) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) b[(s + 1) & 1][mt].nat = *(const u32x4_t*)(ab + mt * 16 * KC * 2 + boff[s + 1]);
-      }
-      if (DIAG == 1 ) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][0].v, acc[r][0], 0, 0, 0);
-      } else {
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[s & 1][mt].v, acc[r][mt], 0, 0, 0);
-      }
-    }
-    load_w(wslot, c + PD);
-    wait_lds_then_barrier();
-  };
-  int c = c0;
-  for (; c + PD <= c1; c += PD) {
-#pragma unroll
-    for (int p = 0; p < PD; ++p) body(wreg[p], c + p);
-  }
-#pragma unroll
-  for (int p = 0; p < PD - 1; ++p)
-    if (c + p < c1) body(wreg[p], c + p);                // uniform tail
-  }
-  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0);
-}
-
 // Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 80 workgroups, else R = 1.
 // Every workgroup re-reads the whole activation panel, and a compute unit ingests only ~45 GB/s (measured,
 // weights + panel), so the fastest grid is the one closest to one workgroup on each of the 256 compute

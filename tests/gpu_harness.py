@@ -41,6 +41,15 @@ def within_bf16(got: np.ndarray, want: np.ndarray, tol=BF16_REL_TOL):
     return worst <= 1.0, worst
 
 
+def elementwise_ratio(got: np.ndarray, want: np.ndarray, tol=BF16_REL_TOL) -> float:
+    """A stricter reading of "3e-2 relative" than `within_bf16`, reported but not asserted: the worst element's error
+    over tol * max(|reference element|, rms of its row)."""
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    rms = np.sqrt(np.mean(want * want, axis=-1, keepdims=True))
+    return float(np.max(np.abs(got - want) / (tol * np.maximum(np.abs(want), rms))))
+
+
 def assert_close(got, want, dtype: str, what: str, tol=None):
     """Returns the max-abs error (fp32) or the worst error/bound ratio (bf16)."""
     got = np.asarray(got, dtype=np.float64)
@@ -96,6 +105,7 @@ class StepCompare:
         self.g_gpu = torch.empty(self.T, dtype=torch.int32, device=DEV)
         self.min_margin = float("inf")
         self.max_err = 0.0          # largest logit error seen (fp32: absolute; bf16: fraction of the bound)
+        self.max_elementwise = 0.0  # verify logits: worst element error / (3e-2 max(|element|, row rms)), not asserted
         self.tol = None             # bf16 bound of the float comparisons (None: BF16_REL_TOL); fp32 models ignore it
         self.verify_passes_compared = 0     # verify passes whose T logit rows were all held against the oracle
         self.steps_on_gpu_tree = 0          # of those, passes in which the oracle verified the GPU's tree, not its own
@@ -183,6 +193,7 @@ class StepCompare:
         # the oracle verifies the tree the GPU verified (its own, unless a near-tie changed a candidate)
         z_o, g_o, saved = ora.verify(tok_gpu)
         self.max_err = max(self.max_err, assert_close(z, z_o, wl.dtype, "verify logits", tol=ftol))
+        self.max_elementwise = max(self.max_elementwise, elementwise_ratio(z, z_o))
         self.verify_passes_compared += 1
         assert g == [int(j) for j in np.argmax(z, axis=1)], "row arg-max of the GPU's own logits"
         if wl.dtype != "f32":

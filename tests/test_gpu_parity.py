@@ -880,7 +880,8 @@ def test_llama7b_width_two_layers_against_oracle():
     sc.check_prefill()
     r = sc.step(require_same_tokens=False)
     say(f"7B-width 2 layers: emitted {r['emitted']} oracle {r['oracle']['emitted']}, verify passes compared "
-        f"{sc.verify_passes_compared}, worst logit error / bound {sc.max_err:.3f}")
+        f"{sc.verify_passes_compared}, worst logit error / bound {sc.max_err:.3f}, element-wise with rms floor "
+        f"{sc.max_elementwise:.3f} x")
     assert sc.verify_passes_compared == 1
     sc.gpu.close()
 
