@@ -87,7 +87,7 @@ __global__ void repack_kernel(WeightSegs w, int K, int KS, int n_rb, int mode, i
 template <int MT, int R, int EPI>
 __device__ __forceinline__ void finish_rows(floatx4_t (&acc)[R][MT], const float4 (&row_ss)[MT], int rb0, int wg1, int M,
                                             int N, void* __restrict__ outp, const QkvEpilogue& qe, const RowScale& rs,
-                                            int row0) {
+                                            int row0, int split) {
   const int lane = threadIdx.x & 63, g = lane >> 4;
   const int r16 = row0 + (lane & 15);                    // token row of tile mt: mt * 16 + r16, counted over the whole pass
   if (rs.ss) {
@@ -100,7 +100,7 @@ __device__ __forceinline__ void finish_rows(floatx4_t (&acc)[R][MT], const float
     }
   }
   if (EPI == EPI_F32) {
-    float* dst = (float*)outp + (size_t)blockIdx.y * M * N;
+    float* dst = (float*)outp + (size_t)split * M * N;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       if (rb0 + r >= wg1) continue;
@@ -113,11 +113,13 @@ __device__ __forceinline__ void finish_rows(floatx4_t (&acc)[R][MT], const float
       }
     }
   } else if (EPI == EPI_SILU) {
-    // row block rb0 holds gate rows, rb0 + 1 the matching up rows: act = silu(gate) * up, bf16
-    if (rb0 + 1 < wg1) {
-      bf16_t* dst = (bf16_t*)outp;
-      const int f = N / 2;
-      const int j0 = (rb0 / 2) * 16 + g * 4;
+    // row blocks come in pairs: block rb0 + 2 p holds gate rows, rb0 + 2 p + 1 the matching up rows: act = silu(gate) * up
+    bf16_t* dst = (bf16_t*)outp;
+    const int f = N / 2;
+#pragma unroll
+    for (int pr = 0; pr < R / 2; ++pr) {                  // (the launchers give this epilogue an even R)
+      if (rb0 + 2 * pr + 1 >= wg1) continue;
+      const int j0 = ((rb0 + 2 * pr) / 2) * 16 + g * 4;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r16;
@@ -125,7 +127,7 @@ __device__ __forceinline__ void finish_rows(floatx4_t (&acc)[R][MT], const float
           float o[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float gt = acc[0][mt][i], up = acc[R - 1][mt][i];
+            const float gt = acc[2 * pr][mt][i], up = acc[2 * pr + 1][mt][i];
             o[i] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;      // 1 ulp reciprocal, bf16 result
           }
           *(uint2*)(dst + (size_t)m * f + j0) = pack4_bf16(o[0], o[1], o[2], o[3]);
@@ -344,7 +346,140 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
   for (int p = 0; p < PD - 1; ++p)
     if (c + p < c1) body(wreg[p], areg[p], c + p);                // uniform tail
 
-  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0);
+  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0, blockIdx.y);
+}
+
+// --------------------------------------------------------------------------------------------- product, many rows
+// The same product tiled over the tokens as well, for passes of hundreds or thousands of rows (the forward pass of
+// the training stage): a workgroup owns 4 R row blocks of the weights (four wavefronts, R each) and MT * 16 token
+// rows, walks the whole K range, and the grid covers (row-block tiles) x (token tiles).  At R = 4, MT = 16 a
+// workgroup does 256 x 256 outputs per 64 KB it takes in (32 KB of weights, 32 KB of tokens per 64 columns), so the
+// matrix cores, not the memory path, set the pace.  Weights come straight into operand registers as before (ring of
+// two chunks), the token chunk through registers into padded LDS (two stages, the chunk after next in flight), and
+// the token operands are read from LDS four tiles at a time, one group ahead of the matrix cores.
+// Workgroups are numbered so that those of one XCD (every eighth) share weight tiles: XCD x takes the row-block
+// tiles x, x + 8, .. and runs all token tiles of one before the next, so a weight tile is fetched from HBM by one L2.
+template <int MT, int R, int EPI, int AD = 2, int OCC = 1>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void gemm_wide_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ wp, int M, int N,
+                                                        int K, int KS, void* __restrict__ outp, QkvEpilogue qe, RowScale rs,
+                                                        int n_tiles, int m_tiles) {
+  constexpr int KC = 64, STEPS = 2, PD = 2;
+  constexpr int ROWB = KC * 2 + 16, ROWS = MT * 16, STAGE = ROWS * ROWB;
+  constexpr int APASS = ROWS * (KC / 8) / 256;
+  static_assert(ROWS * (KC / 8) % 256 == 0 && MT % 4 == 0, "whole passes of pieces; token tiles in groups of four");
+  extern __shared__ __attribute__((aligned(16))) unsigned char wide_lds[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
+  // workgroup id -> (row-block tile, token tile), see above
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int tx = xcd + 8 * (slot / m_tiles), ty = slot % m_tiles;
+  if (tx >= n_tiles) return;                             // uniform over the workgroup
+  const int row0 = ty * ROWS;
+  const int n_rb = N / 16;
+  const int wg0 = tx * 4 * R, wg1 = wg0 + 4 * R < n_rb ? wg0 + 4 * R : n_rb;
+  const int rb0 = wg0 + wave * R;
+  const int chunks = KS / STEPS, last = chunks - 1;
+
+  const u32x4_t* wbase[R];
+  size_t wstep[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool own = rb0 + r < wg1;
+    const int rb = own ? rb0 + r : wg0;
+    wbase[r] = (const u32x4_t*)wp + ((size_t)(rb / kTileBlocks) * KS * kTileBlocks + rb % kTileBlocks) * 64 + lane;
+    wstep[r] = own ? (size_t)kTileBlocks * 64 : 0;
+  }
+  auto load_w = [&](Frag (&dst)[R][STEPS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s) dst[r][s].nat = *(wbase[r] + (size_t)(c * STEPS + s) * wstep[r]);
+  };
+  // token pieces of this thread: pass i covers rows i * 32 + tid / 8, 16-byte column tid % 8
+  const int arow0 = tid >> 3, acol = (tid & 7) * 8;
+  const bf16_t* abase = a + acol;
+  auto load_a = [&](u32x4_t (&dst)[APASS], int c) __attribute__((always_inline)) {
+    c = c < last ? c : last;
+    int k = c * KC;
+    k = k + acol < K - 8 ? k : K - 8 - acol;               // columns past K meet zero-padded weights: any in-bounds piece
+#pragma unroll
+    for (int i = 0; i < APASS; ++i) {
+      int m = row0 + arow0 + i * 32;
+      m = m < M ? m : M - 1;                                // rows past the pass: a valid row, results never stored
+      dst[i] = *(const u32x4_t*)(abase + (size_t)m * K + k);
+    }
+  };
+  auto store_a = [&](const u32x4_t (&src)[APASS], int stage) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < APASS; ++i)
+      *(u32x4_t*)(wide_lds + stage * STAGE + (arow0 + i * 32) * ROWB + (tid & 7) * 16) = src[i];
+  };
+
+  floatx4_t acc[R][MT];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[r][mt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  Frag wreg[PD][R][STEPS];
+  u32x4_t areg[AD][APASS];
+  {
+    u32x4_t first[APASS];
+    load_a(first, 0);
+#pragma unroll
+    for (int p = 0; p < AD; ++p) load_a(areg[p], 1 + p);
+#pragma unroll
+    for (int p = 0; p < PD; ++p) load_w(wreg[p], p);
+    store_a(first, 0);
+  }
+  __syncthreads();
+
+  auto body = [&](Frag (&wslot)[R][STEPS], u32x4_t (&aslot)[APASS], int c) __attribute__((always_inline)) {
+    const int stage = c & 1;
+    const unsigned char* ab = wide_lds + stage * STAGE + r16 * ROWB + g * 16;
+    Frag b[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[0][j].nat = *(const u32x4_t*)(ab + j * 16 * ROWB);
+    store_a(aslot, stage ^ 1);                 // token chunk c + 1 becomes visible after the barrier below
+    load_a(aslot, c + AD + 1);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+      for (int mg = 0; mg < MT / 4; ++mg) {
+        constexpr int G = MT / 4;
+        const int cur = (s * G + mg) & 1;
+        if (s * G + mg + 1 < STEPS * G) {      // the next group of four token tiles, while these multiply
+          const int ns = (s * G + mg + 1) / G, nm = (s * G + mg + 1) % G;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) b[cur ^ 1][j].nat = *(const u32x4_t*)(ab + (nm * 4 + j) * 16 * ROWB + ns * 64);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[r][mg * 4 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wslot[r][s].v, b[cur][j].v, acc[r][mg * 4 + j], 0, 0, 0);
+      }
+    load_w(wslot, c + PD);
+    __syncthreads();
+  };
+  static_assert(PD == 2 && (AD == 1 || AD == 2), "the loop below alternates two ring slots");
+  int c = 0;
+  for (; c + 2 <= chunks; c += 2) {
+    body(wreg[0], areg[0], c);
+    body(wreg[1], areg[AD - 1], c + 1);
+  }
+  if (c < chunks) body(wreg[0], areg[0], c);
+
+  float4 row_ss[MT];
+  if (rs.ss) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = row0 + mt * 16 + r16;
+      row_ss[mt] = *(const float4*)(rs.ss + (size_t)(m < M ? m : M - 1) * kNormParts);
+    }
+  }
+  finish_rows<MT, R, EPI>(acc, row_ss, rb0, wg1, M, N, outp, qe, rs, row0, 0);
 }
 
 // Workgroup shape.  R = 2 row blocks per wavefront when that still leaves >= 80 workgroups, else R = 1.
