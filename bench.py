@@ -565,6 +565,25 @@ def main():
                     "hbm_frac_of_peak": round(byts / (ms_tr * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                     "matrix_TFLOPs": round(flops / (ms_tr * 1e-3) / 1e12, 1),
                     "matrix_frac_of_bf16_peak": round(flops / (ms_tr * 1e-3) / 2.5e15, 4)}
+        # the same forward pass with all positions in one pass per block (token-tiled products)
+        ws_bytes = B.C.c_size_t(0)
+        B._check(B.lib.ht_training_workspace_bytes(B.C.byref(model.cfg), n_tr, B.C.byref(ws_bytes)))
+        ws_tr = torch.empty(ws_bytes.value, dtype=torch.uint8, device=dev)
+        _, loss_b = model.ht_training_forward_batched(step_tr, toks_tr, workspace=ws_tr)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps_tr):
+            model.ht_training_forward_batched(step_tr, toks_tr, workspace=ws_tr)
+        ms_b = (time.perf_counter() - t0) * 1e3 / reps_tr
+        rows_b_low, rows_b_up = n_tr, n_tr + pseudo_rows
+        flops_b = per_layer * (t_layer * rows_b_low + (wl.n_layers - t_layer) * rows_b_up) + head * rows_b_up \
+            + 2 * wl.d_model * wl.d_model * pseudo_rows
+        training["batched"] = {"ms": round(ms_b, 3), "tokens_per_s": round(n_tr / (ms_b * 1e-3), 1), "loss": loss_b,
+                               "matrix_TFLOPs": round(flops_b / (ms_b * 1e-3) / 1e12, 1),
+                               "matrix_frac_of_bf16_peak": round(flops_b / (ms_b * 1e-3) / 2.5e15, 4),
+                               "workspace_bytes": ws_bytes.value,
+                               "note": "every projection once over all rows (token-tiled kernel), attention 128 rows at a time"}
+        del ws_tr
         model.ht_prefill(prompt)
 
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)

@@ -28,6 +28,7 @@ EXPORTS = [
     "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
     "ht_gate_up_pack", "ht_gate_up_silu_packed", "ht_set_dynamic_tree", "ht_candidate_logprobs", "ht_dynamic_tree",
     "ht_training_forward", "ht_kl_divergence_rows", "ht_skinny_gemm_packed_noalloc",
+    "ht_training_workspace_bytes", "ht_training_forward_batched",
 ]
 
 
@@ -71,6 +72,9 @@ def _load() -> C.CDLL:
         "ht_set_dynamic_tree": (C.c_int, [vp, C.c_int32, C.c_int32, vp]),
         "ht_kl_divergence_rows": (C.c_int, [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
         "ht_training_forward": (C.c_int, [vp, C.c_int32, i32p, C.c_int32, f32p, C.POINTER(C.c_double), vp, vp, vp]),
+        "ht_training_workspace_bytes": (C.c_int, [C.POINTER(ht_config), C.c_int32, C.POINTER(sz)]),
+        "ht_training_forward_batched": (C.c_int, [vp, C.c_int32, i32p, C.c_int32, f32p, C.POINTER(C.c_double), vp, vp, vp, sz,
+                                                  vp]),
         "ht_candidate_logprobs": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
         "ht_dynamic_tree": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp]),
         "ht_stream_read_probe": (C.c_int, [vp, sz, vp, C.POINTER(sz), vp]),
@@ -296,6 +300,23 @@ class HTModel:
         _check(lib.ht_training_forward(self.handle, step, _i32(tokens), n, kl, C.byref(loss),
                                        _ptr(logits_hidden) if logits_hidden is not None else None,
                                        _ptr(logits_pseudo) if logits_pseudo is not None else None, _stream_ptr(stream)))
+        return [float(v) for v in kl[:max(n - step - 1, 0)]], loss.value
+
+    def ht_training_forward_batched(self, step: int, tokens: Sequence[int], logits_hidden=None, logits_pseudo=None,
+                                    workspace=None, stream=None):
+        """`ht_training_forward` with all positions in one pass per block.  workspace: a uint8 device tensor of at least
+        `ht_training_workspace_bytes` bytes (allocated here when None).  Returns (kl list, loss)."""
+        n = len(tokens)
+        if workspace is None:
+            need = C.c_size_t(0)
+            _check(lib.ht_training_workspace_bytes(C.byref(self.cfg), n, C.byref(need)))
+            workspace = self.torch.empty(need.value, dtype=self.torch.uint8, device=self.device)
+        kl = (C.c_float * max(n - step - 1, 1))()
+        loss = C.c_double(0.0)
+        _check(lib.ht_training_forward_batched(self.handle, step, _i32(tokens), n, kl, C.byref(loss),
+                                               _ptr(logits_hidden) if logits_hidden is not None else None,
+                                               _ptr(logits_pseudo) if logits_pseudo is not None else None,
+                                               _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
         return [float(v) for v in kl[:max(n - step - 1, 0)]], loss.value
 
     def ht_set_fused_nodes(self, nodes: Sequence[int], stream=None) -> None:

@@ -848,6 +848,216 @@ int ht_training_forward(ht_model* m, int32_t step, const int32_t* tokens, int32_
   return HT_OK;
 }
 
+}  // extern "C" (reopened below)
+
+// ---- the forward pass of the training stage over all positions at once ---------------------------------------------
+namespace {
+struct WideBuffers {
+  float* x;            // residual stream [rows, d]
+  void* u;             // normalised rows (bf16, before the 1/rms factor) [rows, d]
+  float* qkv;          // [rows, (Hq + 2 Hkv) hd]
+  void* q;             // rotated queries [rows, Hq hd]
+  void* attn;          // attention output [rows, Hq hd]
+  void* act;           // silu(gate) * up [rows, f]
+  float* part;         // output of the O / down projection [rows, d]
+  float* ss;           // sums of squares of the rows of u [rows, kNormParts]
+  float* logits;       // [rows, V]
+  float* cs;           // rotary table of one chunk [kMaxRows, hd / 2] (cos, sin)
+  void* q_pass;        // queries of one pseudo-row pass [kMaxRows, Hq hd]
+  void* attn_pass;     // its output
+  void* attn_scratch;
+  void* w_transfer;    // the step's transfer map in the streaming layout
+  TreeTables tail;     // row tables of the last, shorter pseudo-row pass
+  size_t total;
+};
+constexpr int kWideChunk = 128;          // rows of an attention launch
+
+WideBuffers carve_wide(const ht_config& c, int n, void* base) {
+  Carver cv(base);
+  WideBuffers w;
+  const size_t rows = 2 * (size_t)n, d = c.d_model, qd = (size_t)c.n_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+  w.x = cv.take<float>(rows * d);
+  w.u = cv.take_bytes(rows * d * 2);
+  w.qkv = cv.take<float>(rows * (qd + 2 * kvd));
+  w.q = cv.take_bytes(rows * qd * 2);
+  w.attn = cv.take_bytes(rows * qd * 2);
+  w.act = cv.take_bytes(rows * c.d_ffn * 2);
+  w.part = cv.take<float>(rows * d);
+  w.ss = cv.take<float>(rows * kNormParts);
+  w.logits = cv.take<float>(rows * c.vocab);
+  w.cs = cv.take<float>((size_t)kMaxRows * c.head_dim);
+  w.q_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
+  w.attn_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
+  w.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes(kMaxRows, c.n_heads, c.head_dim));
+  w.w_transfer = cv.take_bytes(packed_weight_bytes((int)d, (int)d));
+  w.tail.parent = cv.take<int32_t>(kMaxRows);
+  w.tail.depth = cv.take<int32_t>(kMaxRows);
+  w.tail.rank = cv.take<int32_t>(kMaxRows);
+  w.tail.anc = cv.take<uint64_t>((size_t)kMaxRows * kMaskWords);
+  w.total = align_up(cv.off, 256);
+  return w;
+}
+
+// Row tables of a pass that holds `look` hidden rows (a chain: row i sees rows 0..i) followed by `cnt` pseudo rows:
+// pseudo row f sees the hidden rows 0 .. f-1 of the pass and itself, and sits f positions past the first row.
+void fill_pseudo_pass_tables(int look, int cnt, int32_t* stage) {
+  int32_t* sp = stage;
+  int32_t* sd = stage + kMaxRows;
+  uint64_t* sa = (uint64_t*)(stage + 3 * kMaxRows);
+  memset(stage, 0, sizeof(int32_t) * kTableInts);
+  auto set_bit = [&](int v, int u) { sa[v * kMaskWords + (u >> 6)] |= 1ull << (u & 63); };
+  for (int i = 0; i < look; ++i) {
+    sp[i] = i - 1;
+    sd[i] = i;
+    for (int u = 0; u <= i; ++u) set_bit(i, u);
+  }
+  for (int f = 0; f < cnt; ++f) {
+    const int v = look + f;
+    sp[v] = f - 1;                       // the hidden row below it (-1: none in this pass)
+    sd[v] = f;
+    for (int u = 0; u < f; ++u) set_bit(v, u);
+    set_bit(v, v);
+  }
+}
+}  // namespace
+
+extern "C" int ht_training_workspace_bytes(const ht_config* cfg, int32_t n, size_t* out_bytes) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!out_bytes || n < 1) return fail(HT_EINVAL, "bad argument");
+  *out_bytes = carve_wide(*cfg, n, nullptr).total;
+  return HT_OK;
+}
+
+extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int32_t* tokens, int32_t n, float* kl_out,
+                                           double* loss_out, float* logits_hidden_out, float* logits_pseudo_out,
+                                           void* train_ws, size_t train_ws_bytes, void* stream) {
+  if (!m || !tokens || !train_ws) return fail(HT_EINVAL, "NULL argument");
+  const ht_config& c = m->cfg;
+  if (!m->packed || !m->qkv_fused)
+    return fail(HT_EUNSUPPORTED, "the batched forward pass needs a bf16 model on packed weights with heads of a multiple of 32");
+  if (c.d_model % (4 * kNormParts)) return fail(HT_EUNSUPPORTED, "d_model must be a multiple of %d", 4 * kNormParts);
+  if (!attn_mfma_supported(kMaxRows, c.n_heads, c.n_kv_heads, c.head_dim))
+    return fail(HT_EUNSUPPORTED, "head size %d has no matrix-core attention kernel", c.head_dim);
+  if (!all_loaded(m)) return fail(HT_ESTATE, "deferred weights: ht_load_layer / ht_load_lm_head have not supplied every layer");
+  if (step < 1 || step > c.k) return fail(HT_EINVAL, "transfer step %d outside 1..%d", step, c.k);
+  if (n < step + 2) return fail(HT_EINVAL, "%d tokens give no loss term for step %d (at least %d needed)", n, step, step + 2);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(HT_EINVAL, "token %d at %d outside the vocabulary", tokens[i], i);
+  if (n + 2 * kWideChunk > c.max_cache)
+    return fail(HT_ECAPACITY, "%d tokens + %d rows of a pseudo-row pass exceed max_cache %d", n, 2 * kWideChunk, c.max_cache);
+  if ((uintptr_t)train_ws % 256) return fail(HT_EINVAL, "workspace must be 256-byte aligned");
+  const WideBuffers w = carve_wide(c, n, train_ws);
+  if (train_ws_bytes < w.total) return fail(HT_EINVAL, "workspace has %zu bytes, %zu needed", train_ws_bytes, w.total);
+  hipStream_t s = (hipStream_t)stream;
+  Buffers& b = m->b;
+  const int d = c.d_model, qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, f = c.d_ffn, L = c.n_layers;
+  const int stride_qkv = qd + 2 * kvd;
+  const int t = c.transfer_layer[step - 1];
+  const int P = n - step + 1;                // pseudo states exist for positions j <= n - step
+  const int terms = n - step - 1;            // loss terms j = 0 .. n - step - 2 (Sec. 3.3, upper limit of the sum)
+  const RowScale rs{w.ss, 1.0f / (float)d, c.rms_eps};
+
+  HT_HIP(hipStreamSynchronize(s));
+  memcpy(m->h_stage, tokens, sizeof(int32_t) * n);
+  HT_HIP(hipMemcpyAsync(b.prompt, m->h_stage, sizeof(int32_t) * n, hipMemcpyHostToDevice, s));
+  HT_HIP(hipStreamSynchronize(s));           // the staging buffer takes the row tables next
+  m->n = 0;
+  m->has_prefill = m->transfer_ready = m->verify_done = false;
+  m->drafts_of = -1;
+  // row tables of the pseudo-row passes: full ones (127 hidden rows of lookahead + 128 pseudo rows) in b.train, the
+  // last, shorter one in the workspace
+  const int tail_cnt = P % kWideChunk;
+  int rc;
+  fill_pseudo_pass_tables(kWideChunk - 1, kWideChunk, m->h_stage);
+  if ((rc = upload_tables(b.train, m->h_stage, s))) return rc;
+  if (tail_cnt) {
+    fill_pseudo_pass_tables(tail_cnt - 1, tail_cnt, m->h_stage + kTableInts);
+    if ((rc = upload_tables(w.tail, m->h_stage + kTableInts, s))) return rc;
+  }
+  HT_HIP(hipMemsetAsync(w.q_pass, 0, (size_t)kMaxRows * qd * 2, s));      // the lookahead rows' queries are never used
+  HT_HIP(launch_repack(WeightSegs{{m->w_transfer[step - 1], nullptr, nullptr}, {d, 0, 0}, 1}, d, 0, 0, w.w_transfer, s));
+  const PackedW p_transfer{(const bf16_t*)w.w_transfer, d, d, packed_cols(d)};
+
+  HT_HIP(launch_embed(c.dtype, m->tok_emb, b.prompt, w.x, n, d, s));
+  int rows = n, pending = 0;
+  const TreeDev chain = b.chain.dev();
+  for (int l = 0; l < L; ++l) {
+    if (l == t) {
+      // the residual after t blocks is complete once the last block's sums are in: pseudo states W_i h_j, j < P, as
+      // one more product (sources rounded to bf16 like every other product's operand)
+      if (pending) {
+        HT_HIP(launch_add_norm_parts(w.x, w.part, 1, (size_t)rows * d, m->attn_norm[l], w.u, nullptr, w.ss, rows, d, s));
+        pending = 0;
+      }
+      HT_HIP(launch_convert_to_bf16(w.x, w.u, (size_t)P * d, s));
+      HT_HIP(launch_gemm_wide(w.u, p_transfer, P, w.x + (size_t)n * d, s));
+      rows = n + P;
+    }
+    HT_HIP(launch_add_norm_parts(w.x, w.part, pending, (size_t)rows * d, m->attn_norm[l], w.u, nullptr, w.ss, rows, d, s));
+    HT_HIP(launch_gemm_wide(w.u, b.p_qkv[l], rows, w.qkv, s, rs));
+    // hidden rows: rotary at their own position, K/V to their own slot, then causal attention chunk by chunk
+    for (int c0 = 0; c0 < n; c0 += kMaxRows) {
+      const int cnt = n - c0 < kMaxRows ? n - c0 : kMaxRows;
+      HT_HIP(launch_rope_table(w.cs, chain.depth, c0, cnt, c.head_dim, c.rope_base, s));
+      HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)c0 * stride_qkv, 1, w.cs, (char*)w.q + (size_t)c0 * qd * 2, b.kc[l],
+                                b.vc[l], c0, cnt, c.n_heads, c.n_kv_heads, c.head_dim, c.max_cache, true, s));
+    }
+    for (int c0 = 0; c0 < n; c0 += kWideChunk) {
+      const int cnt = n - c0 < kWideChunk ? n - c0 : kWideChunk;
+      HT_HIP(launch_attn_mfma((char*)w.q + (size_t)c0 * qd * 2, b.kc[l], b.vc[l], c.max_cache, c0, cnt, chain, c.n_heads,
+                              c.n_kv_heads, c.head_dim, (char*)w.attn + (size_t)c0 * qd * 2, w.attn_scratch, s));
+    }
+    if (l >= t) {
+      // pseudo rows, 128 at a time from the end of the sequence backwards.  A pass over pseudo rows j0 .. j0 + cnt - 1
+      // holds the hidden rows of positions j0 + step .. j0 + step + cnt - 2 (already in the cache: only their keys
+      // matter) and then the pseudo rows, whose K/V land in the cache slots behind those hidden rows and so overwrite
+      // keys of later positions: every pass that needed those has run before.
+      for (int j0 = (P - 1) / kWideChunk * kWideChunk; j0 >= 0; j0 -= kWideChunk) {
+        const int cnt = P - j0 < kWideChunk ? P - j0 : kWideChunk, look = cnt - 1, n0 = j0 + step;
+        const TreeTables& tab = cnt == kWideChunk ? b.train : w.tail;
+        HT_HIP(launch_rope_table(w.cs, chain.depth, n0, cnt, c.head_dim, c.rope_base, s));        // pseudo row f at n0 + f
+        HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)(n + j0) * stride_qkv, 1, w.cs, (char*)w.q_pass + (size_t)look * qd * 2,
+                                  b.kc[l], b.vc[l], n0 + look, cnt, c.n_heads, c.n_kv_heads, c.head_dim, c.max_cache, true, s));
+        HT_HIP(launch_attn_mfma(w.q_pass, b.kc[l], b.vc[l], c.max_cache, n0, look + cnt, tab.dev(), c.n_heads, c.n_kv_heads,
+                                c.head_dim, w.attn_pass, w.attn_scratch, s));
+        HT_HIP(hipMemcpyAsync((char*)w.attn + (size_t)(n + j0) * qd * 2, (char*)w.attn_pass + (size_t)look * qd * 2,
+                              (size_t)cnt * qd * 2, hipMemcpyDeviceToDevice, s));
+      }
+    }
+    HT_HIP(launch_gemm_wide(w.attn, b.p_o[l], rows, w.part, s));
+    HT_HIP(launch_add_norm_parts(w.x, w.part, 1, (size_t)rows * d, m->ffn_norm[l], w.u, nullptr, w.ss, rows, d, s));
+    HT_HIP(launch_gemm_wide_silu(w.u, b.p_gu[l], rows, w.act, s, rs));
+    HT_HIP(launch_gemm_wide(w.act, b.p_down[l], rows, w.part, s));
+    pending = 1;
+  }
+  HT_HIP(launch_add_norm_parts(w.x, w.part, pending, (size_t)rows * d, m->final_norm, w.u, nullptr, w.ss, rows, d, s));
+  HT_HIP(launch_gemm_wide(w.u, b.p_head, rows, w.logits, s, rs));
+  // term j pairs pseudo row j (logits row n + j) with the hidden state it stands for (logits row j + step)
+  for (int j0 = 0; j0 < terms; j0 += 32768) {
+    const int cnt = terms - j0 < 32768 ? terms - j0 : 32768;
+    HT_HIP(launch_kl_rows(w.logits, n + j0, step + j0, cnt, c.vocab, b.kl + j0, s));
+  }
+  if (logits_hidden_out)
+    HT_HIP(hipMemcpyAsync(logits_hidden_out, w.logits, sizeof(float) * (size_t)n * c.vocab, hipMemcpyDeviceToDevice, s));
+  if (logits_pseudo_out)
+    HT_HIP(hipMemcpyAsync(logits_pseudo_out, w.logits + (size_t)n * c.vocab, sizeof(float) * (size_t)P * c.vocab,
+                          hipMemcpyDeviceToDevice, s));
+  float* h_kl = (float*)m->h_stage;
+  HT_HIP(hipStreamSynchronize(s));
+  HT_HIP(hipMemcpyAsync(h_kl, b.kl, sizeof(float) * terms, hipMemcpyDeviceToHost, s));
+  HT_HIP(hipStreamSynchronize(s));
+  double loss = 0.0;
+  for (int j = 0; j < terms; ++j) {
+    loss += (double)h_kl[j];
+    if (kl_out) kl_out[j] = h_kl[j];
+  }
+  if (loss_out) *loss_out = loss;
+  return HT_OK;
+}
+
+extern "C" {
+
 int ht_transfer(ht_model* m, const void* h_src, float* pseudo_out, void* stream) {
   if (!m) return fail(HT_EINVAL, "model is NULL");
   if (!h_src && !m->has_prefill) return fail(HT_ESTATE, "no saved hidden state: call ht_prefill first or pass h_src");

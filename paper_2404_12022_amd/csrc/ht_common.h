@@ -161,6 +161,7 @@ size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* s
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,
                            float* pseudo, int i0, int steps, int row_stride, int d, hipStream_t s);
 hipError_t launch_convert_to_f32(int dtype, const void* src, float* dst, int n, hipStream_t s);
+hipError_t launch_convert_to_bf16(const float* src, void* dst, size_t count, hipStream_t s);
 // out[i] = sum_s part[s][i] in the fixed order s = 0, 1, ..
 hipError_t launch_reduce_splits(const float* part, int nsplit, size_t stride, float* out, hipStream_t s);
 
@@ -193,6 +194,10 @@ struct QkvEpilogue {
   int32_t n, Hq, Hkv, hd, cap;
   const int32_t* n_dev = nullptr;            // overrides n when set (device-resident loop)
 };
+// The same products tiled over the tokens too, for passes of any number of rows (the batched forward pass of the
+// training stage): one launch, no K split.  out: fp32 [M][N]; act: bf16 [M][N/2] (w packed from (gate, up)).
+hipError_t launch_gemm_wide(const void* a, PackedW w, int M, float* out, hipStream_t s, RowScale rs = RowScale{});
+hipError_t launch_gemm_wide_silu(const void* a, PackedW w, int M, void* act, hipStream_t s, RowScale rs = RowScale{});
 bool qkv_fusable(int head_dim);
 bool qkv_prefer_split(int M, int N);
 hipError_t launch_gemm_packed_qkv(const void* a, PackedW w, int M, QkvEpilogue qe, hipStream_t s,

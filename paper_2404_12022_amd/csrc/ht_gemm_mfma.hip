@@ -617,6 +617,25 @@ hipError_t launch_gemm_packed_silu(const void* a, PackedW w, int M, void* act, h
   return launch_any(a, w, M, act, 1, EPI_SILU, QkvEpilogue{}, rs, s);
 }
 
+namespace {
+template <int EPI>
+hipError_t launch_wide(const void* a, const PackedW& w, int M, void* out, const RowScale& rs, hipStream_t s) {
+  constexpr int MT = 8, R = 4;                            // 128 tokens x 256 features per workgroup, two workgroups per unit
+  const int n_tiles = (w.N / 16 + 4 * R - 1) / (4 * R), m_tiles = (M + MT * 16 - 1) / (MT * 16);
+  const int lds = 2 * MT * 16 * (64 * 2 + 16);
+  hipLaunchKernelGGL((gemm_wide_kernel<MT, R, EPI, 1, 2>), dim3(8 * ((n_tiles + 7) / 8) * m_tiles), dim3(256), lds, s,
+                     (const bf16_t*)a, w.p, M, w.N, w.K, w.Kp / 32, out, QkvEpilogue{}, rs, n_tiles, m_tiles);
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_gemm_wide(const void* a, PackedW w, int M, float* out, hipStream_t s, RowScale rs) {
+  return launch_wide<EPI_F32>(a, w, M, out, rs, s);
+}
+hipError_t launch_gemm_wide_silu(const void* a, PackedW w, int M, void* act, hipStream_t s, RowScale rs) {
+  return launch_wide<EPI_SILU>(a, w, M, act, rs, s);
+}
+
 bool qkv_fusable(int head_dim) { return head_dim % 32 == 0; }
 
 // The fused q|k|v product cannot split K, so its workgroups stay small (three or four row blocks); with few row

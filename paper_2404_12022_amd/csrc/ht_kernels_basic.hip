@@ -94,6 +94,20 @@ hipError_t launch_convert_to_f32(int dtype, const void* src, float* dst, int n, 
   return hipGetLastError();
 }
 
+// dst[i] = bf16(src[i]), four elements per thread (count a multiple of 4)
+__global__ void convert_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, size_t quads) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= quads) return;
+  const float4 v = *(const float4*)(src + i * 4);
+  *(uint2*)(dst + i * 4) = pack4_bf16(v.x, v.y, v.z, v.w);
+}
+hipError_t launch_convert_to_bf16(const float* src, void* dst, size_t count, hipStream_t s) {
+  if (count % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(convert_to_bf16_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, s, src, (bf16_t*)dst,
+                     count / 4);
+  return hipGetLastError();
+}
+
 __global__ void reduce_splits_kernel(const float* __restrict__ part, int nsplit, size_t stride, float* __restrict__ out) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= stride) return;

@@ -49,7 +49,7 @@ def test_kl_rows_match_the_definition(rows, V):
     assert np.all(np.abs(got - want) <= 2e-5 + 1e-5 * np.abs(want)) and abs(got[0]) <= 1e-6
 
 
-def _compare(wl, tensors_gpu, tensors_cpu, n, step, max_tree, exact):
+def _compare(wl, tensors_gpu, tensors_cpu, n, step, max_tree, exact, batched=False):
     B, H = _B(), _H()
     model = oracle_model(wl, tensors_cpu)
     toks = prompt_of(wl, n)
@@ -57,9 +57,12 @@ def _compare(wl, tensors_gpu, tensors_cpu, n, step, max_tree, exact):
     gpu = H.gpu_model(wl, tensors_gpu, max_tree=max_tree)
     z = torch.zeros(n, wl.vocab, dtype=torch.float32, device=DEV)
     zp = torch.zeros(n - step + 1, wl.vocab, dtype=torch.float32, device=DEV)
-    kl, loss = gpu.ht_training_forward(step, toks, z, zp)
+    if batched:
+        kl, loss = gpu.ht_training_forward_batched(step, toks, z, zp)
+    else:
+        kl, loss = gpu.ht_training_forward(step, toks, z, zp)
     torch.cuda.synchronize()
-    assert gpu.ht_cache_len() == n
+    assert batched or gpu.ht_cache_len() == n
     zc, zpc = H.cpu(z), H.cpu(zp)
     e1 = H.assert_close(zc, res["Z"], wl.dtype, "logits of the hidden states")
     e2 = H.assert_close(zpc, res["Zp"][:n - step + 1], wl.dtype, "logits of the pseudo states")
@@ -163,3 +166,75 @@ def test_random_model_shapes_training_forward(seed):
         f"{wl.n_kv_heads}x{wl.head_dim} vocab={wl.vocab} k={wl.k} t={wl.transfer_layers} n={n} rows/pass<={max_tree}")
     for step in range(1, wl.k + 1):
         _compare(wl, None, None, n, step, max_tree, exact=wl.dtype == "f32")
+
+
+# ------------------------------------------------------------------ all positions in one pass per block
+def _packed_small(**kw):
+    from helpers import small_workload
+    base = dict(name="batched", n_layers=3, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=272, vocab=512, k=3,
+                transfer_layers=(1, 2, 2), dtype="bf16", prompt_len=8, max_cache=1024, tree_size=8, branching=(2, 2, 1),
+                seed=5151)
+    base.update(kw)
+    return small_workload(**base)
+
+
+@pytest.mark.parametrize("n", [5, 77, 128, 129, 300, 515])
+def test_batched_training_forward_small_model(n):
+    """Sequence lengths below, at and above the 128-row attention chunks and the 128-token product tiles, with one, two
+    and several pseudo-row passes, the last one short; every transfer step (joins at two different layers)."""
+    wl = _packed_small()
+    say(f"batched training forward, small packed model, n = {n}")
+    for step in (1, 2, 3):
+        if n >= step + 2:
+            _compare(wl, None, None, n, step, 64, exact=False, batched=True)
+
+
+def test_batched_training_forward_wide_heads_and_grouped_queries():
+    wl = _packed_small(name="batched128", d_model=256, n_heads=4, n_kv_heads=1, head_dim=128, d_ffn=400, vocab=1008, k=2,
+                       transfer_layers=(1, 1), n_layers=2)
+    say("batched training forward, 128-wide heads, four query heads on one key/value head")
+    for step in (1, 2):
+        _compare(wl, None, None, 260, step, 64, exact=False, batched=True)
+
+
+def test_batched_training_forward_llama7b_width_and_both_paths_agree():
+    """Full 7B widths and vocabulary, 2 layers, 300 tokens: against the oracle, and the loss against the chunked
+    `ht_training_forward` on the same model (two bf16 computations of the same sums)."""
+    B, H = _B(), _H()
+    wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), max_cache=640)
+    say("7B-width 2 layers, batched training forward: generating weights")
+    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
+    _compare(wl, tensors, cpu_tensors, 300, 2, 128, exact=False, batched=True)
+    gpu = H.gpu_model(wl, tensors, max_tree=128)
+    toks = prompt_of(wl, 300)
+    kl_a, loss_a = gpu.ht_training_forward(2, toks)
+    kl_b, loss_b = gpu.ht_training_forward_batched(2, toks)
+    say(f"  loss chunked {loss_a:.6f}, batched {loss_b:.6f}")
+    assert abs(loss_a - loss_b) <= 0.03 * abs(loss_a)
+    with pytest.raises(B.HTError) as e:                              # the cache holds nothing usable afterwards
+        gpu.ht_tree_verify_step(None, None, None)
+    assert e.value.code == B.HT_ESTATE
+    gpu.close()
+
+
+def test_batched_training_forward_error_codes():
+    B, H = _B(), _H()
+    f32 = H.gpu_model(WORKLOADS["tiny"], max_tree=16)
+    with pytest.raises(B.HTError) as e:
+        f32.ht_training_forward_batched(1, prompt_of(WORKLOADS["tiny"], 20))
+    assert e.value.code == B.HT_EUNSUPPORTED                         # fp32 models have no packed weights
+    f32.close()
+    wl = _packed_small(max_cache=320)
+    gpu = H.gpu_model(wl, max_tree=16)
+    for step, n, code in ((0, 20, B.HT_EINVAL), (4, 20, B.HT_EINVAL), (2, 3, B.HT_EINVAL), (1, 65, B.HT_ECAPACITY)):
+        with pytest.raises(B.HTError) as e:
+            gpu.ht_training_forward_batched(step, prompt_of(wl, n))
+        assert e.value.code == code, (step, n)
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.HTError) as e:
+        gpu.ht_training_forward_batched(1, prompt_of(wl, 20), workspace=small)
+    assert e.value.code == B.HT_EINVAL
+    kl, loss = gpu.ht_training_forward_batched(1, prompt_of(wl, 20))
+    assert len(kl) == 18 and abs(loss - sum(kl)) < 1e-5
+    gpu.close()
