@@ -203,8 +203,25 @@ def time_second_workload(name, dev, tree_sizes, reps):
     rows = max(tree_sizes + [T0 + (wl.k + 1) * wl.k])
     wl = wl.with_(max_cache=(n0 + 4 * (2 * steps + 8) * (wl.k + 1) + rows + 7) // 8 * 8)
     tdt = torch.bfloat16
-    weights = make_weights(wl, wl.seed, dev, tdt)
-    model = B.HTModel(B.make_config(wl, max_tree=min(128, rows)), weights, dev)
+    param_bytes = 2 * wl.n_layers * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim +
+                                     wl.n_heads * wl.head_dim * wl.d_model + 3 * wl.d_model * wl.d_ffn)
+    if param_bytes > 100e9:                      # too large for the original and the packed copy together: layer by layer
+        from ht_inputs import layer_weights
+        weights = make_weights(wl, wl.seed, dev, tdt, layers=[])
+        head = weights["lm_head"]
+        weights["lm_head"] = None
+        model = B.HTModel(B.make_config(wl, max_tree=min(128, rows)), weights, dev)
+        for layer in range(wl.n_layers):
+            lw = layer_weights(wl, wl.seed, layer, dev, tdt)
+            model.ht_load_layer(layer, lw)
+            torch.cuda.synchronize()
+            del lw
+        model.ht_load_lm_head(head)
+        torch.cuda.synchronize()
+        del head
+    else:
+        weights = make_weights(wl, wl.seed, dev, tdt)
+        model = B.HTModel(B.make_config(wl, max_tree=min(128, rows)), weights, dev)
     prompt = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n0, wl.vocab)]
     parent, rank = prune_tree(wl.branching, T0)
     model.ht_set_tree(parent, rank)
@@ -650,6 +667,7 @@ def main():
         torch.cuda.empty_cache()
         res["attention_op"] = time_attention_op(dev)
         res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps))
+        res["llama70b"] = time_second_workload("llama70b", dev, [1, 64], max(5, args.steps // 3))
     print(json.dumps(res))
 
 

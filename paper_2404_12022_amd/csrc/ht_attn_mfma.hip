@@ -830,8 +830,12 @@ AttnPlan plan_attention(int M, int Hq, int Hkv, int S) {
   // 40 heads over 2112 keys 14.2 -> 13.2 us, 64 query on 8 key/value heads over 4160 keys 25.1 -> 20.7 us; 128 rows
   // of 32 heads over 4224 keys 23.7 -> 22.8 us; over 576 keys the tile kernel stays ahead, 7.0 against 7.3 us).  Its
   // three-tile ring fills the LDS of a compute unit, so the slices are cut for one workgroup per unit.
+  // With four or more query heads per key/value head it also takes the passes of up to 16 rows (one-token step, draft
+  // rows), whose own kernel streams the tiles once per query head.
   const int blocks = (Hq / Hkv) * ((M + 15) / 16);
-  if (p.tiled && units >= 24 && M <= 128) {
+  const int tiles = (S + 63) / 64;
+  if (tiles >= 24 && M <= 128 && (p.tiled || Hq / Hkv >= 4)) {
+    const int units = tiles;
     p.ring_waves = blocks >= 8 ? 8 : 4;
     p.groups = (blocks + p.ring_waves - 1) / p.ring_waves;
     int s = 256 / (Hkv * p.groups);

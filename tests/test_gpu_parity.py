@@ -171,7 +171,8 @@ def _attention_case(dtype, T, n, Hq, Hkv, hd, parent, seed, cap=None, rotate=Tru
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", ["random", "chain", "star", "single", "gqa", "empty_cache", "no_rotate", "ragged",
-                                  "rows200", "rows256", "long_ragged", "long_grouped"])
+                                  "rows200", "rows256", "long_ragged", "long_grouped", "long_grouped_few_rows",
+                                  "long_grouped_one_row"])
 def test_tree_attention_small(dtype, case):
     say(f"attention {dtype} {case}")
     if case == "random":
@@ -192,6 +193,10 @@ def test_tree_attention_small(dtype, case):
         _attention_case(dtype, 70, 203, 3, 3, 128, random_tree(11, 70, 6)[0], 10, poison=True)
     elif case == "long_ragged":                      # 33 tiles, the last one holding two keys and then NaN
         _attention_case(dtype, 50, 2000, 4, 2, 128, random_tree(14, 50, 5)[0], 13, poison=True)
+    elif case == "long_grouped_few_rows":            # under 17 rows with four query heads per key/value head
+        _attention_case(dtype, 5, 1900, 8, 2, 128, random_tree(16, 5, 3)[0], 15, poison=True)
+    elif case == "long_grouped_one_row":
+        _attention_case(dtype, 1, 4099, 16, 2, 64, [-1], 16, poison=True)
     elif case == "long_grouped":                     # six query heads on one key/value head, 64-wide heads, ragged end
         _attention_case(dtype, 40, 1777, 6, 1, 64, random_tree(15, 40, 4)[0], 14, poison=True)
     elif case == "rows200":                          # more rows than a tree has nodes: four ancestor-mask words
