@@ -836,7 +836,7 @@ AttnPlan plan_attention(int M, int Hq, int Hkv, int S) {
   const int tiles = (S + 63) / 64;
   if (tiles >= 24 && M <= 128 && (p.tiled || Hq / Hkv >= 4)) {
     const int units = tiles;
-    p.ring_waves = blocks >= 8 ? 8 : 4;
+    p.ring_waves = 4;      // eight wavefronts on half as many workgroups run as fast, but double the slices to merge
     p.groups = (blocks + p.ring_waves - 1) / p.ring_waves;
     int s = 256 / (Hkv * p.groups);
     if (s > units / 2) s = units / 2;
@@ -879,9 +879,7 @@ hipError_t launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int ca
   const dim3 grid(Hq, p.groups, p.nsplit);
 #define HT_ATTN_ARGS q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2, n_dev
   if (p.ring_waves) {
-    const hipError_t e = p.ring_waves == 8
-        ? launch_ring<HD, 8>(q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p, scale_log2, s, n_dev)
-        : launch_ring<HD, 4>(q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p, scale_log2, s, n_dev);
+    const hipError_t e = launch_ring<HD, 4>(q, kc, vc, cap, n, M, anc, Hq, Hkv, out, part_o, part_ml, p, scale_log2, s, n_dev);
     if (e != hipSuccess) return e;
   } else if (!p.tiled) {
     hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
