@@ -335,63 +335,90 @@ template <> __device__ inline void store4<bf16_t>(bf16_t* p, const float (&v)[4]
   *(uint2*)p = pack4_bf16(v[0], v[1], v[2], v[3]);
 }
 
+// One workgroup per (block of RB rows, head).  q and k heads: four feature pairs per thread and item, 16-byte loads,
+// 8-byte stores.  v heads: the value cache is stored key-contiguous ([head][feature][slot]), so the rows go through LDS
+// and every wavefront stores one feature of up to 64 consecutive rows at a time (a 2-byte store per row and feature
+// straight from the row-major input touches a cache line of its own each).
 template <typename T, typename TIN>
-__global__ __launch_bounds__(256) void rope_append_vec_kernel(
+__global__ __launch_bounds__(256) void rope_append_rows_kernel(
     const TIN* __restrict__ q_in, int q_stride, const TIN* __restrict__ k_in, int k_stride, const TIN* __restrict__ v_in,
     int v_stride, int nsplit, size_t split_stride, const float* __restrict__ cs, T* __restrict__ q, T* __restrict__ kc,
-    T* __restrict__ vc, int n, int Hq, int Hkv, int hd, int cap, int paired, const int32_t* __restrict__ n_dev) {
+    T* __restrict__ vc, int n, int M, int RB, int Hq, int Hkv, int hd, int cap, int paired,
+    const int32_t* __restrict__ n_dev) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char rows_lds[];
   n = cache_len(n, n_dev);
-  const int m = blockIdx.x, half = hd / 2, per_head = half / 4;
-  const int unit = blockIdx.y * 256 + threadIdx.x;
-  const int hh = unit / per_head, j = (unit % per_head) * 4;
-  if (hh >= Hq + 2 * Hkv) return;
-  const bool is_v = hh >= Hq + Hkv;
-  const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
-                 : !is_v ? k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd
-                         : v_in + (size_t)m * v_stride + (size_t)(hh - Hq - Hkv) * hd;
-  const int ja = (paired && !is_v) ? 16 * (j >> 3) + (j & 7) : j, jb = (paired && !is_v) ? ja + 8 : j + half;
-  float a[4], b[4];
-  load4<TIN>(src + ja, a);
-  load4<TIN>(src + jb, b);
-  for (int sp = 1; sp < nsplit; ++sp) {
-    float a2[4], b2[4];
-    load4<TIN>(src + sp * split_stride + ja, a2);
-    load4<TIN>(src + sp * split_stride + jb, b2);
+  const int m0 = blockIdx.x * RB, hh = blockIdx.y, half = hd / 2;
+  const int rows = M - m0 < RB ? M - m0 : RB;
+  if (hh < Hq + Hkv) {
+    const int per_row = half / 4;                          // items of four feature pairs
+    for (int item = threadIdx.x; item < rows * per_row; item += 256) {
+      const int m = m0 + item / per_row, j = (item % per_row) * 4;
+      const TIN* src = hh < Hq ? q_in + (size_t)m * q_stride + (size_t)hh * hd
+                               : k_in + (size_t)m * k_stride + (size_t)(hh - Hq) * hd;
+      // paired: the q and k columns of a head come in the packed projection's order, every run of 8 features
+      // followed by the run of their rotary partners
+      const int ja = paired ? 16 * (j >> 3) + (j & 7) : j, jb = paired ? ja + 8 : j + half;
+      float a[4], b[4];
+      load4<TIN>(src + ja, a);
+      load4<TIN>(src + jb, b);
+      for (int sp = 1; sp < nsplit; ++sp) {
+        float a2[4], b2[4];
+        load4<TIN>(src + sp * split_stride + ja, a2);
+        load4<TIN>(src + sp * split_stride + jb, b2);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { a[i] += a2[i]; b[i] += b2[i]; }
-  }
-  if (!is_v) {
-    float c[4], sn[4];
-    {
+        for (int i = 0; i < 4; ++i) { a[i] += a2[i]; b[i] += b2[i]; }
+      }
       const float4 c01 = *(const float4*)(cs + ((size_t)m * half + j) * 2), c23 = *(const float4*)(cs + ((size_t)m * half + j) * 2 + 4);
-      c[0] = c01.x; sn[0] = c01.y; c[1] = c01.z; sn[1] = c01.w; c[2] = c23.x; sn[2] = c23.y; c[3] = c23.z; sn[3] = c23.w;
-    }
-    float ra[4], rb[4];
+      const float c[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+      float ra[4], rb[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { ra[i] = a[i] * c[i] - b[i] * sn[i]; rb[i] = b[i] * c[i] + a[i] * sn[i]; }
-    T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
-    store4<T>(dst + j, ra);
-    store4<T>(dst + j + half, rb);
-  } else {
-    const int h = hh - Hq - Hkv;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      Conv<T>::store(vc + ((size_t)h * hd + j + i) * cap + n + m, a[i]);
-      Conv<T>::store(vc + ((size_t)h * hd + j + half + i) * cap + n + m, b[i]);
+      for (int i = 0; i < 4; ++i) { ra[i] = a[i] * c[i] - b[i] * sn[i]; rb[i] = b[i] * c[i] + a[i] * sn[i]; }
+      T* dst = hh < Hq ? q + ((size_t)m * Hq + hh) * hd : kc + ((size_t)(n + m) * Hkv + (hh - Hq)) * hd;
+      store4<T>(dst + j, ra);
+      store4<T>(dst + j + half, rb);
     }
+    return;
   }
+  // v head: rows into LDS (row stride hd + 2 elements: the column reads below fall on consecutive banks)
+  const int h = hh - Hq - Hkv, ldr = hd + 2;
+  T* tile = (T*)rows_lds;
+  const int per_row = hd / 4;
+  for (int item = threadIdx.x; item < rows * per_row; item += 256) {
+    const int r = item / per_row, j = (item % per_row) * 4;
+    const TIN* src = v_in + (size_t)(m0 + r) * v_stride + (size_t)h * hd + j;
+    float a[4];
+    load4<TIN>(src, a);
+    for (int sp = 1; sp < nsplit; ++sp) {
+      float a2[4];
+      load4<TIN>(src + sp * split_stride, a2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] += a2[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Conv<T>::store(tile + r * ldr + j + i, a[i]);
+  }
+  __syncthreads();
+  // RB is 16, 32 or 64: a wavefront stores 64 / RB features of RB consecutive rows at a time
+  const int r = threadIdx.x % RB, per_pass = 256 / RB;
+  for (int e = threadIdx.x / RB; e < hd; e += per_pass)
+    if (r < rows) vc[((size_t)h * hd + e) * cap + n + m0 + r] = tile[r * ldr + e];
 }
+
+// rows per workgroup of rope_append_rows_kernel: 16 (measured: blocks of 64 rows leave too few workgroups for passes of
+// 64 - 128 rows, which are latency bound)
+static int rope_rows_per_block(int dtype, int hd) { (void)dtype; (void)hd; return 16; }
 
 hipError_t launch_rope_append(int dtype, const float* qkv, int nsplit, const float* cs, void* q, void* kc, void* vc,
                               int n, int M, int Hq, int Hkv, int hd, int cap, bool paired, hipStream_t s,
                               const int32_t* n_dev) {
   const int stride = (Hq + 2 * Hkv) * hd;
   if (hd % 8 == 0) {
-    const int units = (Hq + 2 * Hkv) * (hd / 8);
-    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, float>), dim3(M, (units + 255) / 256), dim3(256),
-                                                0, s, qkv, stride, qkv + (size_t)Hq * hd, stride,
+    const int RB = rope_rows_per_block(dtype, hd);
+    const size_t lds = (size_t)RB * (hd + 2) * (dtype == 0 ? 4 : 2);
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_rows_kernel<T, float>), dim3((M + RB - 1) / RB, Hq + 2 * Hkv),
+                                                dim3(256), lds, s, qkv, stride, qkv + (size_t)Hq * hd, stride,
                                                 qkv + (size_t)(Hq + Hkv) * hd, stride, nsplit, (size_t)M * stride, cs,
-                                                (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap, paired ? 1 : 0, n_dev);)
+                                                (T*)q, (T*)kc, (T*)vc, n, M, RB, Hq, Hkv, hd, cap, paired ? 1 : 0, n_dev);)
     return hipGetLastError();
   }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, float>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0,
@@ -405,11 +432,12 @@ hipError_t launch_rope_append_split(int dtype, const void* q_in, const void* k_i
                                     void* q, void* kc, void* vc, int n, int M, int Hq, int Hkv, int hd, int cap,
                                     hipStream_t s) {
   if (hd % 8 == 0) {
-    const int units = (Hq + 2 * Hkv) * (hd / 8);
-    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_vec_kernel<T, T>), dim3(M, (units + 255) / 256), dim3(256), 0,
-                                                s, (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd, (const T*)v_in,
-                                                Hkv * hd, 1, (size_t)0, cs, (T*)q, (T*)kc, (T*)vc, n, Hq, Hkv, hd, cap,
-                                                0, nullptr);)
+    const int RB = rope_rows_per_block(dtype, hd);
+    const size_t lds = (size_t)RB * (hd + 2) * (dtype == 0 ? 4 : 2);
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_rows_kernel<T, T>), dim3((M + RB - 1) / RB, Hq + 2 * Hkv),
+                                                dim3(256), lds, s, (const T*)q_in, Hq * hd, (const T*)k_in, Hkv * hd,
+                                                (const T*)v_in, Hkv * hd, 1, (size_t)0, cs, (T*)q, (T*)kc, (T*)vc, n, M, RB, Hq,
+                                                Hkv, hd, cap, 0, nullptr);)
     return hipGetLastError();
   }
   HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((rope_append_kernel<T, T>), dim3(M, Hq + 2 * Hkv), dim3(hd / 2), 0, s,
