@@ -540,6 +540,8 @@ int ht_init_model(const ht_config* cfg, const ht_weights* w, void* workspace, si
   if (e == hipSuccess) e = hipMemsetAsync(workspace, 0, need, s);
   if (e != hipSuccess) return cleanup(fail(HT_EHIP, "init allocation/clear failed: %s", hipGetErrorString(e)));
 
+  if (e == hipSuccess && cfg->dtype == HT_BF16) e = attn_mfma_prepare(cfg->head_dim);
+  if (e != hipSuccess) return cleanup(fail(HT_EHIP, "kernel set-up failed: %s", hipGetErrorString(e)));
   m->packed = m->use_mfma && shapes_packable(*cfg);
   m->qkv_fused = m->packed && qkv_fusable(cfg->head_dim);
   m->layer_loaded.assign(L, 0);

@@ -854,17 +854,31 @@ AttnPlan plan_attention(int M, int Hq, int Hkv, int S) {
   return p;
 }
 
+// The ring's LDS is more than a kernel may use without asking: asked for once per device (attn_mfma_prepare does it
+// when a model is set up, so that no launch inside a stream capture has to).
+template <int HD, int NCW>
+hipError_t allow_ring_lds() {
+  static bool allowed[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!allowed[dev]) {
+    e = hipFuncSetAttribute((const void*)attn_ring_kernel<HD, NCW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            RingShape<HD>::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    allowed[dev] = true;
+  }
+  return hipSuccess;
+}
+
 template <int HD, int NCW>
 hipError_t launch_ring(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int n, int M, const uint64_t* anc, int Hq,
                        int Hkv, bf16_t* out, float* part_o, float* part_ml, const AttnPlan& p, float scale_log2, hipStream_t s,
                        const int32_t* n_dev) {
   constexpr int lds = RingShape<HD>::LDS_BYTES;            // above the 64 KB a kernel may use without asking
-  static bool allowed = false;
-  if (!allowed) {
-    const hipError_t e = hipFuncSetAttribute((const void*)attn_ring_kernel<HD, NCW>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    allowed = true;
-  }
+  const hipError_t ea = allow_ring_lds<HD, NCW>();
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL((attn_ring_kernel<HD, NCW>), dim3(Hkv, p.groups, p.nsplit), dim3(64 * (NCW + 1)), lds, s, q, kc, vc, cap, n,
                      M, anc, Hq, Hkv, out, part_o, part_ml, p.nsplit, scale_log2, n_dev);
   return hipSuccess;
@@ -897,6 +911,12 @@ hipError_t launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int ca
 
 bool attn_mfma_supported(int M, int Hq, int Hkv, int hd) {
   return (hd == 64 || hd == 128) && M >= 1 && M <= kMaxRows && Hq % Hkv == 0;
+}
+
+hipError_t attn_mfma_prepare(int hd) {
+  if (hd == 128) return allow_ring_lds<128, 4>();
+  if (hd == 64) return allow_ring_lds<64, 4>();
+  return hipSuccess;
 }
 
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {

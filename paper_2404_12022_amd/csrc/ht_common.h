@@ -209,6 +209,8 @@ hipError_t launch_attn_simple(int dtype, const void* q, const void* kc, const vo
                               const int32_t* n_dev = nullptr);
 bool attn_mfma_supported(int M, int Hq, int Hkv, int hd);
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd);
+// once per device before the first launch that may sit inside a stream capture (kernel attributes)
+hipError_t attn_mfma_prepare(int hd);
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s, const int32_t* n_dev = nullptr);
 

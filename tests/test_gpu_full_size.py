@@ -157,12 +157,18 @@ def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_acc
     tree.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "llama7b_2layers"])
+@pytest.mark.parametrize("name", ["tiny", "llama7b_2layers", "long_cache"])
 def test_verify_pass_replayed_from_a_graph_matches_the_eager_pass(name):
     B, H = _mods()
     if name == "tiny":
         wl = WORKLOADS["tiny"]
         dt = torch.float32
+    elif name == "long_cache":       # 1700 cached tokens: the attention kernel with the LDS ring inside the capture
+        from helpers import small_workload
+        wl = small_workload(name="graph_long", n_layers=2, d_model=128, n_heads=4, n_kv_heads=1, head_dim=64, d_ffn=256,
+                            vocab=512, k=2, transfer_layers=(1, 1), dtype="bf16", prompt_len=1700, max_cache=1800,
+                            tree_size=64, branching=(10, 6), seed=778)
+        dt = torch.bfloat16
     else:
         wl = WORKLOADS["llama7b"].with_(n_layers=2, transfer_layers=(1, 1, 1), max_cache=640)
         dt = torch.bfloat16
