@@ -864,7 +864,7 @@ struct WideBuffers {
   float* part;         // output of the O / down projection [rows, d]
   float* ss;           // sums of squares of the rows of u [rows, kNormParts]
   float* logits;       // [rows, V]
-  float* cs;           // rotary table of one chunk [kMaxRows, hd / 2] (cos, sin)
+  float* cs;           // rotary table of positions 0 .. n [n + 1, hd / 2] (cos, sin), the same for every block
   void* q_pass;        // queries of one pseudo-row pass [kMaxRows, Hq hd]
   void* attn_pass;     // its output
   void* attn_scratch;
@@ -887,7 +887,7 @@ WideBuffers carve_wide(const ht_config& c, int n, void* base) {
   w.part = cv.take<float>(rows * d);
   w.ss = cv.take<float>(rows * kNormParts);
   w.logits = cv.take<float>(rows * c.vocab);
-  w.cs = cv.take<float>((size_t)kMaxRows * c.head_dim);
+  w.cs = cv.take<float>(((size_t)n + 1) * c.head_dim);
   w.q_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
   w.attn_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
   w.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes(kMaxRows, c.n_heads, c.head_dim));
@@ -982,6 +982,7 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
   const PackedW p_transfer{(const bf16_t*)w.w_transfer, d, d, packed_cols(d)};
 
   HT_HIP(launch_embed(c.dtype, m->tok_emb, b.prompt, w.x, n, d, s));
+  HT_HIP(launch_rope_table(w.cs, nullptr, 0, n + 1, c.head_dim, c.rope_base, s));
   int rows = n, pending = 0;
   const TreeDev chain = b.chain.dev();
   for (int l = 0; l < L; ++l) {
@@ -999,12 +1000,8 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
     HT_HIP(launch_add_norm_parts(w.x, w.part, pending, (size_t)rows * d, m->attn_norm[l], w.u, nullptr, w.ss, rows, d, s));
     HT_HIP(launch_gemm_wide(w.u, b.p_qkv[l], rows, w.qkv, s, rs));
     // hidden rows: rotary at their own position, K/V to their own slot, then causal attention chunk by chunk
-    for (int c0 = 0; c0 < n; c0 += kMaxRows) {
-      const int cnt = n - c0 < kMaxRows ? n - c0 : kMaxRows;
-      HT_HIP(launch_rope_table(w.cs, chain.depth, c0, cnt, c.head_dim, c.rope_base, s));
-      HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)c0 * stride_qkv, 1, w.cs, (char*)w.q + (size_t)c0 * qd * 2, b.kc[l],
-                                b.vc[l], c0, cnt, c.n_heads, c.n_kv_heads, c.head_dim, c.max_cache, true, s));
-    }
+    HT_HIP(launch_rope_append(c.dtype, w.qkv, 1, w.cs, w.q, b.kc[l], b.vc[l], 0, n, c.n_heads, c.n_kv_heads, c.head_dim,
+                              c.max_cache, true, s));
     for (int c0 = 0; c0 < n; c0 += kWideChunk) {
       const int cnt = n - c0 < kWideChunk ? n - c0 : kWideChunk;
       HT_HIP(launch_attn_mfma((char*)w.q + (size_t)c0 * qd * 2, b.kc[l], b.vc[l], c.max_cache, c0, cnt, chain, c.n_heads,
@@ -1018,8 +1015,9 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
       for (int j0 = (P - 1) / kWideChunk * kWideChunk; j0 >= 0; j0 -= kWideChunk) {
         const int cnt = P - j0 < kWideChunk ? P - j0 : kWideChunk, look = cnt - 1, n0 = j0 + step;
         const TreeTables& tab = cnt == kWideChunk ? b.train : w.tail;
-        HT_HIP(launch_rope_table(w.cs, chain.depth, n0, cnt, c.head_dim, c.rope_base, s));        // pseudo row f at n0 + f
-        HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)(n + j0) * stride_qkv, 1, w.cs, (char*)w.q_pass + (size_t)look * qd * 2,
+        // pseudo row f sits at position n0 + f: its rotary factors are row n0 + f of the table
+        HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)(n + j0) * stride_qkv, 1, w.cs + (size_t)n0 * c.head_dim,
+                                  (char*)w.q_pass + (size_t)look * qd * 2,
                                   b.kc[l], b.vc[l], n0 + look, cnt, c.n_heads, c.n_kv_heads, c.head_dim, c.max_cache, true, s));
         HT_HIP(launch_attn_mfma(w.q_pass, b.kc[l], b.vc[l], c.max_cache, n0, look + cnt, tab.dev(), c.n_heads, c.n_kv_heads,
                                 c.head_dim, w.attn_pass, w.attn_scratch, s));

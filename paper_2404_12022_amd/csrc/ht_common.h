@@ -116,6 +116,7 @@ struct RowScale {
   const float* ss = nullptr;
   float inv_d = 0.f, eps = 0.f;
 };
+// depth == NULL: row m sits at position n + m
 hipError_t launch_rope_table(float* cs, const int32_t* depth, int n, int M, int hd, float base, hipStream_t s,
                              const int32_t* n_dev = nullptr);
 // qkv may be `nsplit` split-K partial sums of [M][(Hq + 2 Hkv) hd] each

@@ -262,7 +262,7 @@ __global__ void rope_table_kernel(float2* __restrict__ cs, const int32_t* __rest
   const int m = blockIdx.x;
   const int j = threadIdx.x;
   if (j >= half) return;
-  const double pos = (double)(n + depth[m]);
+  const double pos = (double)(n + (depth ? depth[m] : m));      // no depth table: row m at position n + m
   const double inv = exp(-(2.0 * (double)j / (double)(2 * half)) * log((double)base));
   double sn, cn;
   sincos(pos * inv, &sn, &cn);
