@@ -48,3 +48,20 @@ def test_binding_names_match_the_header():
     assert B.lib.ht_workspace_bytes(ctypes.byref(good), ctypes.byref(out)) == B.HT_EINVAL
     good.transfer_layer[2] = 30                                            # 24, 25, 30 is fine
     assert B.lib.ht_workspace_bytes(ctypes.byref(good), ctypes.byref(out)) == B.HT_OK
+
+
+def test_binding_constants_match_the_header():
+    """Limits and codes the binding re-types (it cannot include a C header) against include/ht.h."""
+    if not os.path.exists(LIB):
+        pytest.skip("library not built")
+    import paper_2404_12022_amd.binding as B
+    text = open(os.path.join(ROOT, "include", "ht.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    enums = dict((k, int(v)) for k, v in re.findall(r"\b(HT_[A-Z_0-9]+)\s*=\s*(-?\d+)", text))
+    for name in ("HT_OK", "HT_EINVAL", "HT_ECAPACITY", "HT_ETREE", "HT_ESTATE", "HT_EHIP", "HT_EUNSUPPORTED", "HT_F32", "HT_BF16",
+                 "HT_MAX_TRANSFER", "HT_MAX_TREE", "HT_MAX_ROWS", "HT_MAX_TOPK", "HT_MAX_LOOP_STEPS", "HT_BUF_DRAFT_LOGITS",
+                 "HT_BUF_K_CACHE", "HT_BUF_V_CACHE", "HT_BUF_FUSED_DRAFT_LOGITS", "HT_BUF_TREE_PARENT", "HT_BUF_TREE_RANK"):
+        assert getattr(B, name) == enums[name], name
+    m = re.search(r"#define\s+HT_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert B.HT_NOALLOC_SCRATCH_BYTES == int(m.group(1)) << int(m.group(2))
+    assert B.lib.ht_padded_rows(129) == 256 and B.lib.ht_padded_rows(256) == 256
