@@ -861,6 +861,12 @@ def test_llama13b_width_at_the_full_cache_length():
     _shallow_case("llama13b", 2048, cache=2048 + 2 * 64 + 16)
 
 
+def test_llama70b_width_at_the_full_cache_length():
+    """Config 5 at its own cache length: 64 query heads on 8 key/value heads over 4096 cached tokens (the ring attention
+    kernel with grouped heads, in the verify pass and in the draft pass of 4 rows), 2 layers, T = 64."""
+    _shallow_case("llama70b", 4096, cache=4096 + 2 * 64 + 16)
+
+
 def test_llama70b_width_grouped_query_attention():
     _shallow_case("llama70b", 80)
 
