@@ -43,21 +43,23 @@ def _rank0_chain(parent, rank):
         chain.append(cur)
 
 
-def test_llama7b_full_depth_step_against_the_oracle():
-    """Config 3 as the benchmark runs it (32 layers, 512 cached tokens, 64-node tree, k = 3 after layer 24) against
-    the fp64 oracle: prefill state, draft logits, all 64 verify-logit rows (Sec. 3.4.1: a node's logits are those of
+@pytest.mark.parametrize("name", ["llama7b", "llama13b"])
+def test_full_depth_step_against_the_oracle(name):
+    """Configs 3 and 4 as the benchmark runs them (7B: 32 layers, 512 cached tokens; 13B: 40 layers, 2048 cached
+    tokens; 64-node tree, k = 3) against the fp64 oracle: prefill state, draft logits, all 64 verify-logit rows (Sec. 3.4.1: a node's logits are those of
     the causal pass over its path), greedy tokens, acceptance and the caches.  The K cache of every fourth layer
     shows how the rounding of the bf16 activations adds up over the depth; every value is held to the bf16 bound
-    of its depth (`bf16_tol_after`: the one-block tolerance up to three blocks, its random-walk growth beyond) and
+    of its depth (`bf16_tol_after`: the one-block tolerance times sqrt(blocks)) and
     the log gives each error in units of the plain tolerance."""
     from helpers import layerwise_oracle_model
     B, H = _mods()
-    wl = WORKLOADS["llama7b"].with_(max_cache=640)
+    wl = WORKLOADS[name]
+    wl = wl.with_(max_cache=wl.prompt_len + 128)
     L, t = wl.n_layers, wl.transfer_layers[0]
-    say("7B full depth vs oracle: generating weights")
+    say(f"{name} full depth vs oracle: generating weights")
     tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
     cpu_tensors = {k: ([t_.cpu() for t_ in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
-    say("7B full depth vs oracle: oracle prefill of 512 tokens through 32 blocks + GPU prefill")
+    say(f"{name} full depth vs oracle: oracle prefill of {wl.prompt_len} tokens through {L} blocks + GPU prefill")
     sc = H.StepCompare(wl, tensors_gpu=tensors, model=layerwise_oracle_model(wl, cpu_tensors))
     del tensors
     n = sc.ora.n
@@ -66,14 +68,15 @@ def test_llama7b_full_depth_step_against_the_oracle():
         kc = H.cpu(sc.gpu.ht_get_buffer(B.HT_BUF_K_CACHE, layer))[:n]
         ratio = H.within_bf16(kc, sc.ora.K[layer][:n])[1]
         curve.append((layer, ratio))
+    say("  K cache of the prompt, worst row error / plain tolerance, by layer: " + ", ".join(f"{l}: {r:.3f}" for l, r in curve))
+    for layer, ratio in curve:
         # the K rows of block `layer` (0-based) are made from the residual after `layer` blocks, plus their own rounding
         assert ratio * H.BF16_REL_TOL <= H.bf16_tol_after(layer + 1), f"K cache of layer {layer}: {ratio:.2f} x the tolerance"
-    say("  K cache of the prompt, worst row error / plain tolerance, by layer: " + ", ".join(f"{l}: {r:.3f}" for l, r in curve))
     h = H.cpu(sc.gpu.ht_get_buffer(B.HT_BUF_TRANSFER_SRC, 0))
     say(f"  transfer source (layer {t}): {H.within_bf16(h, sc.ora.h_src[t])[1]:.3f} x the plain tolerance")
     sc.tol = H.bf16_tol_after(L)
     sc.check_prefill()
-    say("7B full depth vs oracle: one step (draft pass, 64-node verify pass)")
+    say(f"{name} full depth vs oracle: one step (draft pass, 64-node verify pass)")
     r = sc.step(require_same_tokens=False)
     scale = sc.tol / H.BF16_REL_TOL
     say(f"  emitted {r['emitted']} oracle {r['oracle']['emitted']}; verify passes compared {sc.verify_passes_compared} "
