@@ -18,7 +18,7 @@
 // and rows inside a block too: that is how gate and up rows meet in one wavefront for the fused SiLU epilogue and
 // how a q or k feature meets its rotary partner inside one row block.
 //
-// The activation chunk (M x 64 columns) is staged once per workgroup in LDS (rows padded by 16 bytes:
+// The activation chunk (M x 64 columns) is staged once per workgroup in LDS (rows padded by 32 bytes:
 // conflict-free 128-bit reads) and shared by the four wavefronts; a ring of PD weight chunks per
 // wavefront stays in flight.  Split-K over blockIdx.y writes fp32 partial sums that the consumer adds
 // in a fixed order (deterministic).
@@ -36,6 +36,7 @@ constexpr int kChunkCols = 64;         // K elements per activation chunk (128 f
 constexpr int kRingDepth = 3;          // weight chunks in flight per wavefront
 constexpr int kPadCols = 128;          // packed weights are zero-padded along K to a multiple of this
 constexpr int kTileBlocks = 8;         // row blocks interleaved per K step in the packed layout
+constexpr int kRowPad = 32;            // bytes added to every activation row in LDS, see gemm_packed_kernel
 
 union Frag {
   uint4 raw;
@@ -202,7 +203,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_packed_kernel(const bf16_t* _
                                                                  int KS, void* __restrict__ outp, int nsplit,
                                                                  QkvEpilogue qe, RowScale rs, int row0) {
   constexpr int STEPS = KC / 32;                         // MFMA steps per chunk
-  constexpr int ROWB = KC * 2 + 16;                      // LDS row stride in bytes (padded: conflict-free b128 reads)
+  // LDS row stride in bytes.  A 128-bit operand read is served in four phases of 16 lanes, lanes 8a..8a+7 together
+  // with the eight lanes of a neighbouring 16-lane group, 64 banks of four bytes; with 32 bytes of padding the
+  // sixteen rows of a fragment spread over all banks in every phase (measured with the bank-conflict counter: 4
+  // cycles per read; 16 bytes of padding: 8 cycles, no padding: 16).
+  constexpr int ROWB = KC * 2 + kRowPad;
   constexpr int THREADS = 64 * WAVES;
   constexpr int ROWS = MT * 16;
   constexpr int PIECES = ROWS * (KC / 8);                // 16-byte pieces of the activation chunk
@@ -364,7 +369,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
                                                         int K, int KS, void* __restrict__ outp, QkvEpilogue qe, RowScale rs,
                                                         int n_tiles, int m_tiles) {
   constexpr int KC = 64, STEPS = 2, PD = 2;
-  constexpr int ROWB = KC * 2 + 16, ROWS = MT * 16, STAGE = ROWS * ROWB;
+  constexpr int ROWB = KC * 2 + kRowPad, ROWS = MT * 16, STAGE = ROWS * ROWB;
   constexpr int APASS = ROWS * (KC / 8) / 256;
   static_assert(ROWS * (KC / 8) % 256 == 0 && MT % 4 == 0, "whole passes of pieces; token tiles in groups of four");
   extern __shared__ __attribute__((aligned(16))) unsigned char wide_lds[];
@@ -622,7 +627,7 @@ template <int EPI>
 hipError_t launch_wide(const void* a, const PackedW& w, int M, void* out, const RowScale& rs, hipStream_t s) {
   constexpr int MT = 8, R = 4;                            // 128 tokens x 256 features per workgroup, two workgroups per unit
   const int n_tiles = (w.N / 16 + 4 * R - 1) / (4 * R), m_tiles = (M + MT * 16 - 1) / (MT * 16);
-  const int lds = 2 * MT * 16 * (64 * 2 + 16);
+  const int lds = 2 * MT * 16 * (64 * 2 + kRowPad);
   hipLaunchKernelGGL((gemm_wide_kernel<MT, R, EPI, 1, 2>), dim3(8 * ((n_tiles + 7) / 8) * m_tiles), dim3(256), lds, s,
                      (const bf16_t*)a, w.p, M, w.N, w.K, w.Kp / 32, out, QkvEpilogue{}, rs, n_tiles, m_tiles);
   return hipGetLastError();
