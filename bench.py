@@ -600,6 +600,22 @@ def main():
                                "matrix_frac_of_bf16_peak": round(flops_b / (ms_b * 1e-3) / 2.5e15, 4),
                                "workspace_bytes": ws_bytes.value,
                                "note": "every projection once over all rows (token-tiled kernel), attention 128 rows at a time"}
+        # what the matrix cores of this machine sustain on register operands alone, per instruction form
+        sink_m = torch.zeros(1, dtype=torch.int32, device=dev)
+        rates = {}
+        for form, name in ((0, "v_mfma_f32_16x16x32_bf16"), (1, "v_mfma_f32_32x32x16_bf16"),
+                           (2, "v_mfma_f32_16x16x32_bf16, hashed operand bits"),
+                           (3, "v_mfma_f32_32x32x16_bf16, hashed operand bits")):
+            B.ht_mfma_rate_probe(form, 2000, sink_m)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fl = sum(B.ht_mfma_rate_probe(form, 2000, sink_m) for _ in range(5))
+            e1.record(stream)
+            e1.synchronize()
+            rates[name] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        training["measured_matrix_core_TFLOPs"] = rates
+        training["batched"]["matrix_frac_of_measured_16x16x32_rate"] = round(
+            flops_b / (ms_b * 1e-3) / 1e12 / rates["v_mfma_f32_16x16x32_bf16, hashed operand bits"], 4)
         del ws_tr
         model.ht_prefill(prompt)
 

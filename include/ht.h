@@ -330,6 +330,16 @@ int ht_skinny_gemm_packed_noalloc(const void *a, const void *packed, int32_t M, 
  * read and stored in *bytes_read (host, may be NULL); `sink` is a device word the kernel may write.
  * HT_EINVAL for NULL / misaligned / too small buffers. */
 int ht_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t *bytes_read, void *stream);
+
+/* Measurement aid for the matrix-core roofline of the token-tiled products (the forward pass of the training stage,
+ * Sec. 3.3): 512 workgroups of four wavefronts issue `iters` rounds of independent bf16 matrix-core instructions on
+ * register operands and nothing else: form 0 = 32 accumulators of v_mfma_f32_16x16x32_bf16 per wavefront (the
+ * instruction of the product kernels), form 1 = 8 accumulators of v_mfma_f32_32x32x16_bf16, both on small whole
+ * numbers; forms 2 and 3 = the same two with operands in +-[1, 2) whose sign and mantissa bits are hashed (the
+ * sustained rate depends on the operand bits).  *flops (host, may be NULL) receives the floating-point operations
+ * of the launch; the caller times it.  `sink` is a device word the kernel may write.  HT_EINVAL for a NULL sink,
+ * another form, or iters outside 1 .. 2^20. */
+int ht_mfma_rate_probe(int32_t form, int32_t iters, void *sink, double *flops, void *stream);
 int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
                    void *scratch, size_t scratch_bytes, void *stream);
 

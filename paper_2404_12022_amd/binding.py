@@ -25,7 +25,7 @@ EXPORTS = [
     "ht_tree_verify_step", "ht_accept_and_compact", "ht_cache_len", "ht_last_error", "ht_get_buffer",
     "ht_tree_attention_scratch_bytes", "ht_tree_attention", "ht_padded_rows", "ht_skinny_gemm_scratch_bytes",
     "ht_skinny_gemm", "ht_weight_pack_bytes", "ht_weight_pack", "ht_skinny_gemm_packed", "ht_load_layer",
-    "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_decode_steps",
+    "ht_load_lm_head", "ht_set_fused_nodes", "ht_stream_read_probe", "ht_mfma_rate_probe", "ht_decode_steps",
     "ht_gate_up_pack", "ht_gate_up_silu_packed", "ht_set_dynamic_tree", "ht_candidate_logprobs", "ht_dynamic_tree",
     "ht_training_forward", "ht_kl_divergence_rows", "ht_skinny_gemm_packed_noalloc",
     "ht_training_workspace_bytes", "ht_training_forward_batched",
@@ -78,6 +78,7 @@ def _load() -> C.CDLL:
         "ht_candidate_logprobs": (C.c_int, [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
         "ht_dynamic_tree": (C.c_int, [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp]),
         "ht_stream_read_probe": (C.c_int, [vp, sz, vp, C.POINTER(sz), vp]),
+        "ht_mfma_rate_probe": (C.c_int, [C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), vp]),
         "ht_prefill": (C.c_int, [vp, i32p, C.c_int32, vp]),
         "ht_transfer": (C.c_int, [vp, vp, vp, vp]),
         "ht_tree_verify_step": (C.c_int, [vp, vp, vp, vp, vp]),
@@ -215,6 +216,14 @@ def ht_stream_read_probe(buf, sink, stream=None) -> int:
     got = C.c_size_t(0)
     _check(lib.ht_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), C.byref(got),
                                     _stream_ptr(stream)))
+    return got.value
+
+
+def ht_mfma_rate_probe(form: int, iters: int, sink, stream=None) -> float:
+    """One launch of the matrix-core probe (form 0: 16x16x32, 1: 32x32x16, + 2: hashed operand bits); returns its
+    floating-point operations."""
+    got = C.c_double(0.0)
+    _check(lib.ht_mfma_rate_probe(form, iters, _ptr(sink), C.byref(got), _stream_ptr(stream)))
     return got.value
 
 

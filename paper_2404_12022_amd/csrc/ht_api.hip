@@ -1333,6 +1333,16 @@ int ht_tree_attention(const void* q, const void* k_new, const void* v_new, void*
   return HT_OK;
 }
 
+int ht_mfma_rate_probe(int32_t form, int32_t iters, void* sink, double* flops, void* stream) {
+  if (!sink) return fail(HT_EINVAL, "NULL argument");
+  if (form < 0 || form > 3) return fail(HT_EINVAL, "form %d: 0 / 1 (16x16x32 / 32x32x16), + 2 for hashed operand bits", form);
+  if (iters < 1 || iters > (1 << 20)) return fail(HT_EINVAL, "iters %d outside 1 .. 2^20", iters);
+  const double f = launch_mfma_rate(form, iters, (uint32_t*)sink, (hipStream_t)stream);
+  HT_HIP(hipGetLastError());
+  if (flops) *flops = f;
+  return HT_OK;
+}
+
 int ht_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t* bytes_read, void* stream) {
   if (!buf || !sink) return fail(HT_EINVAL, "NULL argument");
   if ((uintptr_t)buf % 16) return fail(HT_EINVAL, "buffer must be 16-byte aligned");

@@ -157,6 +157,7 @@ hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* s
                                  float* h_src, int last, int d, hipStream_t s);
 // measurement aid: one pass over `buf` with the weight stream's access pattern; returns the bytes actually read
 size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* sink, hipStream_t s);
+double launch_mfma_rate(int form, int iters, uint32_t* sink, hipStream_t s);
 // pseudo[f * row_stride + (i - i0)] = W_i h_f for steps i0 <= i < i0 + steps and F sources
 // h_f = h + (src_rows ? src_rows[f] : f) * d
 hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, int F, const void* const* w_dev,

@@ -1072,6 +1072,72 @@ size_t launch_stream_read(const void* buf, size_t bytes, int groups, uint32_t* s
   return per_group * groups;
 }
 
+// ------------------------------------------------------------------------------------------------ matrix-core probe
+// Nothing but independent matrix-core instructions on register operands, 32 accumulators of 16 x 16 (FORM 0:
+// v_mfma_f32_16x16x32_bf16) or 8 of 32 x 32 (FORM 1: v_mfma_f32_32x32x16_bf16) per wavefront, two wavefronts per
+// SIMD: the rate of this kernel is what a product kernel on that instruction can reach at best on this machine.
+// The rate depends on the operand bits (the clock follows the power drawn), hence two kinds of operands.
+typedef __bf16 probe_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float probe_f32x4_t __attribute__((ext_vector_type(4)));
+typedef float probe_f32x16_t __attribute__((ext_vector_type(16)));
+template <int FORM>
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int random_bits, uint32_t* __restrict__ sink) {
+  // operands: small whole numbers (few bits toggle between lanes and instructions), or values in +-[1, 2) with
+  // hashed sign and mantissa bits (what real activations and weights look like to the multipliers)
+  probe_bf16x8_t a[4], b[8];
+  auto fill = [&](int which, int j) -> __bf16 {
+    if (!random_bits) return (__bf16)(float)((threadIdx.x * (which < 4 ? 1 : 3) + which + j) & 7);
+    uint32_t h = (threadIdx.x * 64u + which * 8u + j) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    const unsigned short bits = (unsigned short)(0x3f80u | (h & 0x7fu) | ((h & 0x100u) << 7));
+    return __builtin_bit_cast(__bf16, bits);
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[i][j] = fill(i, j);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[i][j] = fill(4 + i, j);
+  float total = 0.f;
+  if (FORM == 0) {
+    probe_f32x4_t acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = probe_f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i % 4], b[i / 4], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) total += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  } else {
+    probe_f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i % 2], b[i / 2], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) total += acc[i][j];
+  }
+  if (total == -1.25f) sink[0] = 1;                        // keeps the work alive (sums of whole numbers, or far from -1.25)
+}
+// Returns the floating-point operations of the launch (2 per multiply-add).
+double launch_mfma_rate(int form, int iters, uint32_t* sink, hipStream_t s) {
+  constexpr int kGroups = 512;                             // two workgroups of four wavefronts per compute unit
+  if ((form & 1) == 0)
+    hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(kGroups), dim3(256), 0, s, iters, form >> 1, sink);
+  else
+    hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(kGroups), dim3(256), 0, s, iters, form >> 1, sink);
+  return (double)kGroups * 4 * iters * ((form & 1) == 0 ? 32 * 2.0 * 16 * 16 * 32 : 8 * 2.0 * 32 * 32 * 16);
+}
+
 // ------------------------------------------------------------------------------------------------ generic product
 // out[m][n] = sum_k a[m][k] w[n][k], fp32 accumulation.  One wavefront per output feature n, rows in
 // groups of 4.  Used by the fp32 model path and as the fallback for shapes the MFMA kernel rejects.

@@ -97,6 +97,22 @@ def test_fused_gate_up_product_matches_its_definition(M, f, K):
     assert e.value.code == B.HT_EINVAL
 
 
+def test_matrix_core_probe_counts_its_work_and_rejects_bad_arguments():
+    B, H = _B(), _H()
+    sink = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    # 512 workgroups x 4 wavefronts x iters x (32 instructions of 2 * 16 * 16 * 32 | 8 of 2 * 32 * 32 * 16) operations
+    assert B.ht_mfma_rate_probe(0, 10, sink) == 512 * 4 * 10 * 32 * 16384
+    assert B.ht_mfma_rate_probe(1, 10, sink) == 512 * 4 * 10 * 8 * 32768
+    assert B.ht_mfma_rate_probe(2, 3, sink) == 512 * 4 * 3 * 32 * 16384           # the same with hashed operand bits
+    assert B.ht_mfma_rate_probe(3, 3, sink) == 512 * 4 * 3 * 8 * 32768
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0
+    for form, iters in ((4, 10), (-1, 10), (0, 0), (0, (1 << 20) + 1)):
+        with pytest.raises(B.HTError) as e:
+            B.ht_mfma_rate_probe(form, iters, sink)
+        assert e.value.code == B.HT_EINVAL
+
+
 def test_stream_read_probe_reads_whole_passes_and_rejects_bad_buffers():
     B, H = _B(), _H()
     buf = torch.zeros(40 << 20, dtype=torch.uint8, device=H.DEV)
