@@ -599,7 +599,7 @@ def main():
                                "matrix_TFLOPs": round(flops_b / (ms_b * 1e-3) / 1e12, 1),
                                "matrix_frac_of_bf16_peak": round(flops_b / (ms_b * 1e-3) / 2.5e15, 4),
                                "workspace_bytes": ws_bytes.value,
-                               "note": "every projection once over all rows (token-tiled kernel), attention 128 rows at a time"}
+                               "note": "every projection once over all rows (token-tiled kernel); attention: one causal launch per block for the hidden rows, one for the pseudo rows"}
         # what the matrix cores of this machine sustain on register operands alone, per instruction form
         sink_m = torch.zeros(1, dtype=torch.int32, device=dev)
         rates = {}

@@ -165,15 +165,16 @@ int ht_training_forward(ht_model *m, int32_t step, const int32_t *tokens /*host*
 /* The same forward pass and loss with all positions in one pass per block (Sec. 3.3: the doubled sequence of hidden
  * and pseudo hidden states), for sequences of hundreds or thousands of tokens: every projection runs once over all n
  * (above the transfer layer n + n - step + 1) rows on a kernel tiled over tokens and features, so the matrix cores
- * and not the weight stream set the pace; attention runs 128 rows at a time over the KV cache (hidden rows causally;
- * pseudo rows in passes that hold the hidden rows they may see beyond their chunk's first position).  The pseudo
+ * and not the weight stream set the pace; attention runs as one launch per block for the hidden rows (causal over
+ * the KV cache) and one for the pseudo rows (pseudo row j over the hidden keys 0 .. j + step - 1, merged with its own
+ * key and value, which live in the workspace, not in the cache).  The pseudo
  * states come from a matrix product with bf16-rounded hidden states (ht_training_forward and the decode step feed
  * the transfer map float32 states).  Same outputs and argument meaning as ht_training_forward.
  * train_ws: DEVICE, 256-byte aligned, >= ht_training_workspace_bytes(cfg, n) (activations of all 2 n rows, their
- * logits, the packed transfer map).  Waits for `stream`.  Afterwards the KV cache holds nothing usable (pseudo rows
- * were written over hidden rows' slots): decoding needs a new ht_prefill; the tree set before is kept.
+ * logits, the pseudo rows' keys and values, the packed transfer map).  Waits for `stream`.  The KV cache afterwards
+ * holds the n tokens, but no pending root: decoding needs a new ht_prefill; the tree set before is kept.
  * HT_EUNSUPPORTED unless the model is bf16 on packed weights (widths and vocabulary multiples of 16, heads of 64 or
- * 128); HT_ECAPACITY unless n + 256 <= max_cache; HT_EINVAL / HT_ESTATE as for ht_training_forward. */
+ * 128); HT_ECAPACITY unless n <= max_cache; HT_EINVAL / HT_ESTATE as for ht_training_forward. */
 int ht_training_workspace_bytes(const ht_config *cfg, int32_t n, size_t *out_bytes);
 int ht_training_forward_batched(ht_model *m, int32_t step, const int32_t *tokens /*host*/, int32_t n, float *kl_out /*host*/,
                                 double *loss_out /*host*/, float *logits_hidden_out, float *logits_pseudo_out,

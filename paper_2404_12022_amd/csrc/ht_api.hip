@@ -865,14 +865,13 @@ struct WideBuffers {
   float* ss;           // sums of squares of the rows of u [rows, kNormParts]
   float* logits;       // [rows, V]
   float* cs;           // rotary table of positions 0 .. n [n + 1, hd / 2] (cos, sin), the same for every block
-  void* q_pass;        // queries of one pseudo-row pass [kMaxRows, Hq hd]
-  void* attn_pass;     // its output
-  void* attn_scratch;
+  void* self_k;        // the pseudo rows' own keys [n, Hkv hd] (rotated) and values [Hkv hd, self_cap]
+  void* self_v;
+  int self_cap;
+  void* attn_scratch;  // the two slices of the pseudo rows' attention (cache part, own part)
   void* w_transfer;    // the step's transfer map in the streaming layout
-  TreeTables tail;     // row tables of the last, shorter pseudo-row pass
   size_t total;
 };
-constexpr int kWideChunk = 128;          // rows of an attention launch
 
 WideBuffers carve_wide(const ht_config& c, int n, void* base) {
   Carver cv(base);
@@ -888,39 +887,15 @@ WideBuffers carve_wide(const ht_config& c, int n, void* base) {
   w.ss = cv.take<float>(rows * kNormParts);
   w.logits = cv.take<float>(rows * c.vocab);
   w.cs = cv.take<float>(((size_t)n + 1) * c.head_dim);
-  w.q_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
-  w.attn_pass = cv.take_bytes((size_t)kMaxRows * qd * 2);
-  w.attn_scratch = cv.take_bytes(attn_mfma_scratch_bytes(kMaxRows, c.n_heads, c.head_dim));
+  w.self_cap = (n + 63) / 64 * 64;
+  w.self_k = cv.take_bytes((size_t)n * kvd * 2);
+  w.self_v = cv.take_bytes(kvd * (size_t)w.self_cap * 2);
+  w.attn_scratch = cv.take_bytes(attn_causal_scratch_bytes(n, c.n_heads, c.head_dim));
   w.w_transfer = cv.take_bytes(packed_weight_bytes((int)d, (int)d));
-  w.tail.parent = cv.take<int32_t>(kMaxRows);
-  w.tail.depth = cv.take<int32_t>(kMaxRows);
-  w.tail.rank = cv.take<int32_t>(kMaxRows);
-  w.tail.anc = cv.take<uint64_t>((size_t)kMaxRows * kMaskWords);
   w.total = align_up(cv.off, 256);
   return w;
 }
 
-// Row tables of a pass that holds `look` hidden rows (a chain: row i sees rows 0..i) followed by `cnt` pseudo rows:
-// pseudo row f sees the hidden rows 0 .. f-1 of the pass and itself, and sits f positions past the first row.
-void fill_pseudo_pass_tables(int look, int cnt, int32_t* stage) {
-  int32_t* sp = stage;
-  int32_t* sd = stage + kMaxRows;
-  uint64_t* sa = (uint64_t*)(stage + 3 * kMaxRows);
-  memset(stage, 0, sizeof(int32_t) * kTableInts);
-  auto set_bit = [&](int v, int u) { sa[v * kMaskWords + (u >> 6)] |= 1ull << (u & 63); };
-  for (int i = 0; i < look; ++i) {
-    sp[i] = i - 1;
-    sd[i] = i;
-    for (int u = 0; u <= i; ++u) set_bit(i, u);
-  }
-  for (int f = 0; f < cnt; ++f) {
-    const int v = look + f;
-    sp[v] = f - 1;                       // the hidden row below it (-1: none in this pass)
-    sd[v] = f;
-    for (int u = 0; u < f; ++u) set_bit(v, u);
-    set_bit(v, v);
-  }
-}
 }  // namespace
 
 extern "C" int ht_training_workspace_bytes(const ht_config* cfg, int32_t n, size_t* out_bytes) {
@@ -946,8 +921,7 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
   if (n < step + 2) return fail(HT_EINVAL, "%d tokens give no loss term for step %d (at least %d needed)", n, step, step + 2);
   for (int i = 0; i < n; ++i)
     if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(HT_EINVAL, "token %d at %d outside the vocabulary", tokens[i], i);
-  if (n + 2 * kWideChunk > c.max_cache)
-    return fail(HT_ECAPACITY, "%d tokens + %d rows of a pseudo-row pass exceed max_cache %d", n, 2 * kWideChunk, c.max_cache);
+  if (n > c.max_cache) return fail(HT_ECAPACITY, "%d tokens exceed max_cache %d", n, c.max_cache);
   if ((uintptr_t)train_ws % 256) return fail(HT_EINVAL, "workspace must be 256-byte aligned");
   const WideBuffers w = carve_wide(c, n, train_ws);
   if (train_ws_bytes < w.total) return fail(HT_EINVAL, "workspace has %zu bytes, %zu needed", train_ws_bytes, w.total);
@@ -967,17 +941,6 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
   m->n = 0;
   m->has_prefill = m->transfer_ready = m->verify_done = false;
   m->drafts_of = -1;
-  // row tables of the pseudo-row passes: full ones (127 hidden rows of lookahead + 128 pseudo rows) in b.train, the
-  // last, shorter one in the workspace
-  const int tail_cnt = P % kWideChunk;
-  int rc;
-  fill_pseudo_pass_tables(kWideChunk - 1, kWideChunk, m->h_stage);
-  if ((rc = upload_tables(b.train, m->h_stage, s))) return rc;
-  if (tail_cnt) {
-    fill_pseudo_pass_tables(tail_cnt - 1, tail_cnt, m->h_stage + kTableInts);
-    if ((rc = upload_tables(w.tail, m->h_stage + kTableInts, s))) return rc;
-  }
-  HT_HIP(hipMemsetAsync(w.q_pass, 0, (size_t)kMaxRows * qd * 2, s));      // the lookahead rows' queries are never used
   HT_HIP(launch_repack(WeightSegs{{m->w_transfer[step - 1], nullptr, nullptr}, {d, 0, 0}, 1}, d, 0, 0, w.w_transfer, s));
   const PackedW p_transfer{(const bf16_t*)w.w_transfer, d, d, packed_cols(d)};
 
@@ -999,32 +962,24 @@ extern "C" int ht_training_forward_batched(ht_model* m, int32_t step, const int3
     }
     HT_HIP(launch_add_norm_parts(w.x, w.part, pending, (size_t)rows * d, m->attn_norm[l], w.u, nullptr, w.ss, rows, d, s));
     HT_HIP(launch_gemm_wide(w.u, b.p_qkv[l], rows, w.qkv, s, rs));
-    // hidden rows: rotary at their own position, K/V to their own slot, then causal attention chunk by chunk
+    // hidden rows: rotary at their own position, K/V to their own cache slot
     HT_HIP(launch_rope_append(c.dtype, w.qkv, 1, w.cs, w.q, b.kc[l], b.vc[l], 0, n, c.n_heads, c.n_kv_heads, c.head_dim,
                               c.max_cache, true, s));
-    for (int c0 = 0; c0 < n; c0 += kWideChunk) {
-      const int cnt = n - c0 < kWideChunk ? n - c0 : kWideChunk;
-      HT_HIP(launch_attn_mfma((char*)w.q + (size_t)c0 * qd * 2, b.kc[l], b.vc[l], c.max_cache, c0, cnt, chain, c.n_heads,
-                              c.n_kv_heads, c.head_dim, (char*)w.attn + (size_t)c0 * qd * 2, w.attn_scratch, s));
-    }
     if (l >= t) {
-      // pseudo rows, 128 at a time from the end of the sequence backwards.  A pass over pseudo rows j0 .. j0 + cnt - 1
-      // holds the hidden rows of positions j0 + step .. j0 + step + cnt - 2 (already in the cache: only their keys
-      // matter) and then the pseudo rows, whose K/V land in the cache slots behind those hidden rows and so overwrite
-      // keys of later positions: every pass that needed those has run before.
-      for (int j0 = (P - 1) / kWideChunk * kWideChunk; j0 >= 0; j0 -= kWideChunk) {
-        const int cnt = P - j0 < kWideChunk ? P - j0 : kWideChunk, look = cnt - 1, n0 = j0 + step;
-        const TreeTables& tab = cnt == kWideChunk ? b.train : w.tail;
-        // pseudo row f sits at position n0 + f: its rotary factors are row n0 + f of the table
-        HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)(n + j0) * stride_qkv, 1, w.cs + (size_t)n0 * c.head_dim,
-                                  (char*)w.q_pass + (size_t)look * qd * 2,
-                                  b.kc[l], b.vc[l], n0 + look, cnt, c.n_heads, c.n_kv_heads, c.head_dim, c.max_cache, true, s));
-        HT_HIP(launch_attn_mfma(w.q_pass, b.kc[l], b.vc[l], c.max_cache, n0, look + cnt, tab.dev(), c.n_heads, c.n_kv_heads,
-                                c.head_dim, w.attn_pass, w.attn_scratch, s));
-        HT_HIP(hipMemcpyAsync((char*)w.attn + (size_t)(n + j0) * qd * 2, (char*)w.attn_pass + (size_t)look * qd * 2,
-                              (size_t)cnt * qd * 2, hipMemcpyDeviceToDevice, s));
-      }
+      // Pseudo row j sits at position j + step and sees the hidden keys 0 .. j + step - 1 and itself (Sec. 3.3): as
+      // row j + step - 1 of a causal launch over the hidden keys, with its own key and value, kept in buffers of their
+      // own, as one more slice.  The step - 1 rows in front of pseudo row 0 are computed for nothing (their queries
+      // are the last hidden rows'), and their outputs land on the last hidden rows of w.attn, which the hidden rows'
+      // own launch below writes afterwards.
+      const int lead = step - 1;
+      HT_HIP(launch_rope_append(c.dtype, w.qkv + (size_t)n * stride_qkv, 1, w.cs + (size_t)step * c.head_dim,
+                                (char*)w.q + (size_t)n * qd * 2, w.self_k, w.self_v, lead, P, c.n_heads, c.n_kv_heads,
+                                c.head_dim, w.self_cap, true, s));
+      HT_HIP(launch_attn_causal((char*)w.q + (size_t)(n - lead) * qd * 2, b.kc[l], b.vc[l], c.max_cache, n, chain, c.n_heads,
+                                c.n_kv_heads, c.head_dim, (char*)w.attn + (size_t)(n - lead) * qd * 2, s, w.self_k, w.self_v,
+                                w.self_cap, w.attn_scratch));
     }
+    HT_HIP(launch_attn_causal(w.q, b.kc[l], b.vc[l], c.max_cache, n, chain, c.n_heads, c.n_kv_heads, c.head_dim, w.attn, s));
     HT_HIP(launch_gemm_wide(w.attn, b.p_o[l], rows, w.part, s));
     HT_HIP(launch_add_norm_parts(w.x, w.part, 1, (size_t)rows * d, m->ffn_norm[l], w.u, nullptr, w.ss, rows, d, s));
     HT_HIP(launch_gemm_wide_silu(w.u, b.p_gu[l], rows, w.act, s, rs));

@@ -297,8 +297,24 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
                                                             const uint64_t* __restrict__ anc, int Hq, int Hkv,
                                                             bf16_t* __restrict__ out, float* __restrict__ part_o,
                                                             float* __restrict__ part_ml, int nsplit, float scale_log2,
-                                                            const int32_t* __restrict__ n_dev) {
+                                                            const int32_t* __restrict__ n_dev, int chunk) {
   n = cache_len(n, n_dev);
+  // chunk > 0 (a whole causal sequence in one launch): the M rows come in chunks of `chunk` rows, and a chunk is a
+  // pass of its own that sees the cache up to its first row plus its own rows through `anc` (the same masks for every
+  // chunk).  Every workgroup walks all its keys (no key slices); with nsplit > 1 it leaves its result as slice 0 of
+  // nsplit for a merge with slices that someone else writes.  Workgroups are taken from the last chunk backwards: the
+  // longest key ranges start first.
+  int gy = blockIdx.y, row_base = 0;
+  const int Mtot = M;
+  if (chunk > 0) {
+    gy = gridDim.y - 1 - gy;
+    row_base = gy * (NW * QB * 16) / chunk * chunk;
+    n += row_base;
+    q += (size_t)row_base * Hq * HD;
+    out += (size_t)row_base * Hq * HD;
+    M = M - row_base < chunk ? M - row_base : chunk;
+    gy -= row_base / (NW * QB * 16);
+  }
   constexpr int TK = 64;                 // keys per tile
   constexpr int ES = HD / 32, EB = HD / 16;
   constexpr int THREADS = 64 * NW;
@@ -314,12 +330,12 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, g = lane >> 4;
   const int h = blockIdx.x, hk = h / (Hq / Hkv);
-  const int m0 = (blockIdx.y * NW + wave) * QB * 16;
-  const int split = blockIdx.z;
+  const int m0 = (gy * NW + wave) * QB * 16;
+  const int split = chunk > 0 ? 0 : blockIdx.z;
   const int S = n + M;
   const int tiles = (S + TK - 1) / TK;
   int ts, te;
-  even_share(tiles, nsplit, split, ts, te);
+  even_share(tiles, chunk > 0 ? 1 : nsplit, split, ts, te);
   int tmid = n / TK;                     // tiles below tmid hold cache keys only
   tmid = tmid < ts ? ts : (tmid > te ? te : tmid);
 
@@ -525,12 +541,12 @@ __global__ __launch_bounds__(64 * NW) void attn_tile_kernel(const bf16_t* __rest
         for (int i = 0; i < 4; ++i) ob[i] = float_to_bf16(oacc[qb][eb][i] * inv);
         *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e0) = *(const uint2*)ob;
       } else {
-        float* dst = part_o + (((size_t)h * nsplit + split) * M + m) * HD + e0;
+        float* dst = part_o + (((size_t)h * nsplit + split) * Mtot + row_base + m) * HD + e0;
         *(float4*)dst = make_float4(oacc[qb][eb][0], oacc[qb][eb][1], oacc[qb][eb][2], oacc[qb][eb][3]);
       }
     }
     if (nsplit > 1 && g == 0) {
-      float* ml = part_ml + (((size_t)h * nsplit + split) * M + m) * 2;
+      float* ml = part_ml + (((size_t)h * nsplit + split) * Mtot + row_base + m) * 2;
       ml[0] = mrun[qb];
       ml[1] = lsum;
     }
@@ -813,6 +829,33 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   *(uint2*)(out + (size_t)m * Hq * HD + (size_t)h * HD + e) = pack4_bf16(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
 }
 
+// One more slice for attn_merge_kernel: every row's own key and value, taken from buffers of their own (`ks`
+// [M][Hkv][HD], `vs` [Hkv][HD][cap], as the rotary/append kernel writes them): m = q.k in scaled log2 units, l = 1,
+// O = v.  One wavefront per (row, head), four heads per workgroup.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_self_slice_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ ks,
+                                                              const bf16_t* __restrict__ vs, int cap, int M, int Hq, int Hkv,
+                                                              float scale_log2, float* __restrict__ part_o,
+                                                              float* __restrict__ part_ml, int nsplit, int split) {
+  constexpr int PER = HD / 64;
+  const int m = blockIdx.x, h = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (h >= Hq) return;
+  const int hk = h / (Hq / Hkv), e = lane * PER;
+  float dot = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    dot += bf16_to_float(q[((size_t)m * Hq + h) * HD + e + i]) * bf16_to_float(ks[((size_t)m * Hkv + hk) * HD + e + i]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+  const size_t idx = ((size_t)h * nsplit + split) * M + m;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) part_o[idx * HD + e + i] = bf16_to_float(vs[((size_t)hk * HD + e + i) * cap + m]);
+  if (lane == 0) {
+    part_ml[idx * 2] = dot * scale_log2;
+    part_ml[idx * 2 + 1] = 1.0f;
+  }
+}
+
 // Work split.  M <= 16 rows (decode steps, pseudo rows): one row block, the four wavefronts of a workgroup
 // split the keys of the slice and fragments come straight from global memory.  More rows: the tile kernel,
 // each wavefront owning 16 rows (two row groups of workgroups above 64 rows).
@@ -898,7 +941,7 @@ hipError_t launch_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int ca
   } else if (!p.tiled) {
     hipLaunchKernelGGL((attn_mfma_kernel<HD, 1>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
   } else {
-    hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS);
+    hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, HT_ATTN_ARGS, 0);
   }
 #undef HT_ATTN_ARGS
   if (p.nsplit > 1)
@@ -917,6 +960,56 @@ hipError_t attn_mfma_prepare(int hd) {
   if (hd == 128) return allow_ring_lds<128, 4>();
   if (hd == 64) return allow_ring_lds<64, 4>();
   return hipSuccess;
+}
+
+// A causal sequence of `rows` rows whose K/V are in the cache already (slot = position): row r sees the keys 0 .. r.
+// One launch of the tile kernel, rows attending in chunks of kCausalChunk, a workgroup per (query head, 64 rows), every
+// workgroup over all its keys.  `tree` holds the masks of a chain of at least kCausalChunk rows.
+// With `self_k` / `self_v` ([rows][Hkv][hd] and [Hkv][hd][self_cap]) row r sees the keys 0 .. r of the cache and, on
+// top, the key and value of its own row in those buffers: the cache part and the own part meet in the merge kernel
+// (`scratch`: attn_causal_scratch_bytes).
+namespace {
+constexpr int kCausalChunk = 128;
+template <int HD>
+hipError_t launch_causal_hd(const bf16_t* q, const bf16_t* kc, const bf16_t* vc, int cap, int rows, const uint64_t* anc, int Hq,
+                            int Hkv, bf16_t* out, const bf16_t* self_k, const bf16_t* self_v, int self_cap, void* scratch,
+                            hipStream_t s) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+  const dim3 grid(Hq, (rows + 63) / 64, 1);
+  if (!self_k) {
+    hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, q, kc, vc, cap, 0, rows, anc, Hq, Hkv, out,
+                       nullptr, nullptr, 1, scale_log2, nullptr, kCausalChunk);
+    return hipGetLastError();
+  }
+  float* part_o = (float*)scratch;
+  float* part_ml = part_o + (size_t)Hq * 2 * rows * HD;
+  hipLaunchKernelGGL((attn_tile_kernel<HD, 1, 4>), grid, dim3(256), 0, s, q, kc, vc, cap, 0, rows, anc, Hq, Hkv, out, part_o,
+                     part_ml, 2, scale_log2, nullptr, kCausalChunk);
+  hipLaunchKernelGGL((attn_self_slice_kernel<HD>), dim3(rows, (Hq + 3) / 4), dim3(256), 0, s, q, self_k, self_v, self_cap, rows,
+                     Hq, Hkv, scale_log2, part_o, part_ml, 2, 1);
+  hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((rows + 256 / (HD / 4) - 1) / (256 / (HD / 4)), Hq), dim3(256), 0, s, part_o,
+                     part_ml, 2, rows, Hq, out);
+  return hipGetLastError();
+}
+}  // namespace
+
+size_t attn_causal_scratch_bytes(int rows, int Hq, int hd) {
+  return ((size_t)Hq * 2 * rows * hd + (size_t)Hq * 2 * rows * 2) * sizeof(float) + 256;
+}
+
+hipError_t launch_attn_causal(const void* q, const void* kc, const void* vc, int cap, int rows, TreeDev tree, int Hq, int Hkv,
+                              int hd, void* out, hipStream_t s, const void* self_k, const void* self_v, int self_cap,
+                              void* scratch) {
+  if ((size_t)cap * Hkv * hd >= ((size_t)1 << 31) || rows < 1 || rows > cap) return hipErrorInvalidValue;
+  if ((self_k != nullptr) != (self_v != nullptr) || (self_k && (!scratch || self_cap < rows))) return hipErrorInvalidValue;
+  const bf16_t *qp = (const bf16_t*)q, *kp = (const bf16_t*)kc, *vp = (const bf16_t*)vc;
+  if (hd == 128)
+    return launch_causal_hd<128>(qp, kp, vp, cap, rows, tree.anc, Hq, Hkv, (bf16_t*)out, (const bf16_t*)self_k,
+                                 (const bf16_t*)self_v, self_cap, scratch, s);
+  if (hd == 64)
+    return launch_causal_hd<64>(qp, kp, vp, cap, rows, tree.anc, Hq, Hkv, (bf16_t*)out, (const bf16_t*)self_k,
+                                (const bf16_t*)self_v, self_cap, scratch, s);
+  return hipErrorInvalidValue;
 }
 
 size_t attn_mfma_scratch_bytes(int M, int Hq, int hd) {

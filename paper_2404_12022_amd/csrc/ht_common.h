@@ -215,5 +215,9 @@ size_t attn_mfma_scratch_bytes(int M, int Hq, int hd);
 hipError_t attn_mfma_prepare(int hd);
 hipError_t launch_attn_mfma(const void* q, const void* kc, const void* vc, int cap, int n, int M, TreeDev tree, int Hq,
                             int Hkv, int hd, void* out, void* scratch, hipStream_t s, const int32_t* n_dev = nullptr);
+hipError_t launch_attn_causal(const void* q, const void* kc, const void* vc, int cap, int rows, TreeDev tree, int Hq, int Hkv,
+                              int hd, void* out, hipStream_t s, const void* self_k = nullptr, const void* self_v = nullptr,
+                              int self_cap = 0, void* scratch = nullptr);
+size_t attn_causal_scratch_bytes(int rows, int Hq, int hd);
 
 }  // namespace ht

@@ -227,7 +227,7 @@ def test_batched_training_forward_error_codes():
     f32.close()
     wl = _packed_small(max_cache=320)
     gpu = H.gpu_model(wl, max_tree=16)
-    for step, n, code in ((0, 20, B.HT_EINVAL), (4, 20, B.HT_EINVAL), (2, 3, B.HT_EINVAL), (1, 65, B.HT_ECAPACITY)):
+    for step, n, code in ((0, 20, B.HT_EINVAL), (4, 20, B.HT_EINVAL), (2, 3, B.HT_EINVAL), (1, 321, B.HT_ECAPACITY)):
         with pytest.raises(B.HTError) as e:
             gpu.ht_training_forward_batched(step, prompt_of(wl, n))
         assert e.value.code == code, (step, n)
