@@ -553,9 +553,8 @@ def main():
     # ---- forward pass of the training stage (Sec. 3.3) over N tokens, first transfer step: chunks of
     # (max_tree - 1) / 2 positions; the blocks above the transfer layer and the LM head are walked once per chunk,
     # the blocks below it once per two chunks
-    training = None
-    if args.training_forward:
-        n_tr, step_tr = args.training_forward, 1
+    def time_training_forward(model, n_tr):
+        step_tr = 1
         toks_tr = [int(t) for t in counter_tokens(wl.seed, PROMPT_STREAM, n_tr, wl.vocab)]
         model.ht_training_forward(step_tr, toks_tr)
         reps_tr = 3
@@ -617,6 +616,12 @@ def main():
         training["batched"]["matrix_frac_of_measured_16x16x32_rate"] = round(
             flops_b / (ms_b * 1e-3) / 1e12 / rates["v_mfma_f32_16x16x32_bf16, hashed operand bits"], 4)
         del ws_tr
+        return training
+
+
+    training = None
+    if args.training_forward:
+        training = time_training_forward(model, args.training_forward)
         model.ht_prefill(prompt)
 
     kern = time_dominant_kernel(wl, T, dev, tdt, stream)
@@ -679,7 +684,15 @@ def main():
         res["cpu_baseline"] = cpu_baseline(wl, T, n0, weights)
     if not args.only_main and wl.name == "llama7b":
         model.close()
-        del model, weights
+        del model
+        torch.cuda.empty_cache()
+        if not training:        # the forward pass of the training stage over 2048 tokens, on a model of its own
+            wl_tr = wl.with_(max_cache=2048 + 256)
+            m_tr = B.HTModel(B.make_config(wl_tr, max_tree=128), weights, dev)
+            res["training_forward"] = time_training_forward(m_tr, 2048)
+            m_tr.close()
+            del m_tr
+        del weights
         torch.cuda.empty_cache()
         res["attention_op"] = time_attention_op(dev)
         res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps))
