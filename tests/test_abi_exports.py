@@ -65,3 +65,12 @@ def test_binding_constants_match_the_header():
     m = re.search(r"#define\s+HT_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
     assert B.HT_NOALLOC_SCRATCH_BYTES == int(m.group(1)) << int(m.group(2))
     assert B.lib.ht_padded_rows(129) == 256 and B.lib.ht_padded_rows(256) == 256
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is the whole target: `bench.py --gpus N` with N > 1 exits with a message and prints no result line."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and not r.stdout.strip()
