@@ -963,7 +963,8 @@ hipError_t launch_prefill_finish(StepState* st, const int32_t* g, const float* s
 // when src_rows is NULL).  With several sources a wavefront produces four consecutive output features: the four
 // weight rows are read fully coalesced (16 bytes per lane and row) and every 16-byte piece of a source, which
 // comes from L2, serves all four (one feature per wavefront re-read the sources for every weight row: nine bytes
-// of source per weight byte with four sources, 51 us against 28 us at d = 4096).  Sources go in groups of four;
+// of source per weight byte with four sources, 51 us against 28 us at d = 4096).  Sources go in groups of four (of
+// sixteen from sixteen sources on, which walks the weight rows a quarter as often);
 // one source alone has its own instance with one feature per wavefront.  Every (source,
 // output) sum runs in the same order whatever F is, so one source alone and the same source among several give
 // the same bits.
@@ -1034,8 +1035,11 @@ hipError_t launch_transfer(int dtype, const float* h, const int32_t* src_rows, i
   if (F == 1) {      // one source: its re-reads are cheap and one feature per wavefront spreads the rows wider
     HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 1, 1>), dim3((d + 3) / 4, steps), dim3(256), 0, s, h,
                                                 src_rows, F, w_dev, pseudo, i0, row_stride, d);)
-  } else {
+  } else if (F < 16) {
     HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 4, 4>), dim3((d + 15) / 16, steps), dim3(256), 0, s, h,
+                                                src_rows, F, w_dev, pseudo, i0, row_stride, d);)
+  } else {           // every node of a tree drafts: sixteen sources per walk over the weight rows (same sums, same order)
+    HT_DISPATCH_DTYPE(dtype, hipLaunchKernelGGL((transfer_kernel<T, 16, 4>), dim3((d + 15) / 16, steps), dim3(256), 0, s, h,
                                                 src_rows, F, w_dev, pseudo, i0, row_stride, d);)
   }
   return hipGetLastError();
