@@ -190,7 +190,7 @@ def time_attention_op(dev):
                     "static tree's tables are uploaded once"}
 
 
-def time_second_workload(name, dev, tree_sizes, reps):
+def time_second_workload(name, dev, tree_sizes, reps, also_layers=None):
     """Verify pass of another named workload at its own cache length: one model, a sweep over tree sizes (HIP events
     on the launch stream), the one-token pass, and the whole step at the workload's own tree size in two schedules."""
     import torch
@@ -241,7 +241,7 @@ def time_second_workload(name, dev, tree_sizes, reps):
         e1.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    def step_ms(nodes):
+    def step_ms(nodes, model=model):
         model.ht_set_tree(parent, rank)
         model.ht_set_fused_nodes(nodes)
         for _ in range(3):
@@ -276,7 +276,19 @@ def time_second_workload(name, dev, tree_sizes, reps):
            "one_token_step_ms": round(ms_one, 4), "tree_size_sweep": sweep, "tree_size_of_the_steps": T0,
            "step_ms_draft_after_accept": round(ms_s1, 4), "step_ms_rank0_chain_drafts_in_verify_pass": round(ms_hybrid, 4)}
     model.close()
-    del model, weights
+    del model
+    torch.cuda.empty_cache()
+    if also_layers:        # the same decoder with one transfer layer per step (the 13B setting of Sec. 4.1)
+        wl2 = wl.with_(transfer_layers=tuple(also_layers))
+        m2 = B.HTModel(B.make_config(wl2, max_tree=min(128, rows)), weights, dev)
+        m2.ht_set_tree(parent, rank)
+        m2.ht_prefill(prompt)
+        res["transfer_after_layers_%s" % "_".join(str(t) for t in also_layers)] = {
+            "step_ms_draft_after_accept": round(step_ms([], m2), 4),
+            "step_ms_rank0_chain_drafts_in_verify_pass": round(step_ms(chain, m2), 4)}
+        m2.close()
+        del m2
+    del weights
     torch.cuda.empty_cache()
     return res
 
@@ -695,7 +707,7 @@ def main():
         del weights
         torch.cuda.empty_cache()
         res["attention_op"] = time_attention_op(dev)
-        res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps))
+        res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps), also_layers=(25, 30, 35))
         res["llama70b"] = time_second_workload("llama70b", dev, [1, 64], max(5, args.steps // 3))
     print(json.dumps(res))
 

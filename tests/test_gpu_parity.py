@@ -836,15 +836,15 @@ def test_error_codes():
 
 
 # ------------------------------------------------------------------ large shapes
-def _shallow_case(name, prompt_len, tree_size=None, cache=None, fused_chain=False, steps=1):
-    """Full widths of a named workload (the launch configurations the benchmark uses), depth cut to 2 layers and
-    the prompt shortened so that the fp64 oracle finishes in seconds."""
+def _shallow_case(name, prompt_len, tree_size=None, cache=None, fused_chain=False, steps=1, layers=2, transfer_layers=None):
+    """Full widths of a named workload (the launch configurations the benchmark uses), depth cut to 2 layers (or
+    `layers`) and the prompt shortened so that the fp64 oracle finishes in seconds."""
     H = _H()
     base = WORKLOADS[name]
     T = tree_size or base.tree_size
-    wl = base.with_(n_layers=2, transfer_layers=tuple(1 for _ in range(base.k)), prompt_len=prompt_len,
+    wl = base.with_(n_layers=layers, transfer_layers=transfer_layers or tuple(1 for _ in range(base.k)), prompt_len=prompt_len,
                     max_cache=cache or (prompt_len + 2 * T + 8 + 8 * steps) // 8 * 8, tree_size=T)
-    say(f"{name} width, 2 layers, T={T}, n={prompt_len}: generating weights")
+    say(f"{name} width, {layers} layers, T={T}, n={prompt_len}: generating weights")
     tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
     cpu_tensors = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in tensors.items()}
     say(f"{name}: oracle + gpu")
@@ -881,6 +881,14 @@ def test_llama70b_width_at_the_full_cache_length():
     """Config 5 at its own cache length: 64 query heads on 8 key/value heads over 4096 cached tokens (the ring attention
     kernel with grouped heads, in the verify pass and in the draft pass of 4 rows), 2 layers, T = 64."""
     _shallow_case("llama70b", 4096, cache=4096 + 2 * 64 + 16)
+
+
+@pytest.mark.parametrize("fused_chain", [False, True])
+def test_llama13b_width_with_a_transfer_layer_per_step(fused_chain):
+    """The 13B setting of Sec. 4.1 has one transfer layer per step (25 / 30 / 35 of 40): here the 13B widths at 4 layers
+    with the steps' maps after layers 1 / 2 / 3, so pseudo rows join the draft pass, or the verify pass, at three
+    different blocks; drafting after acceptance and with the rank-0 chain drafting in the pass."""
+    _shallow_case("llama13b_t253035", 96, fused_chain=fused_chain, steps=2, layers=4, transfer_layers=(1, 2, 3))
 
 
 def test_llama70b_width_grouped_query_attention():
