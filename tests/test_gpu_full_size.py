@@ -88,19 +88,48 @@ def test_full_depth_step_against_the_oracle(name):
     sc.gpu.close()
 
 
-def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_accepted():
+def _full_size_model(wl, max_tree):
+    """The model of a workload at its full size; past 100 GB of weights the layers are generated and handed over one
+    at a time (`ht_load_layer`), so that the row-major matrices and the packed copy never sit in memory together."""
     B, H = _mods()
-    wl = WORKLOADS["llama7b"].with_(max_cache=640)
+    param_bytes = 2 * wl.n_layers * (wl.d_model * (wl.n_heads + 2 * wl.n_kv_heads) * wl.head_dim +
+                                     wl.n_heads * wl.head_dim * wl.d_model + 3 * wl.d_model * wl.d_ffn)
+    if param_bytes <= 100e9:
+        return H.gpu_model(wl, make_weights(wl, wl.seed, H.DEV, torch.bfloat16), max_tree=max_tree)
+    from ht_inputs import layer_weights
+    weights = make_weights(wl, wl.seed, H.DEV, torch.bfloat16, layers=[])
+    head = weights["lm_head"]
+    weights["lm_head"] = None
+    model = B.HTModel(B.make_config(wl, max_tree=max_tree), weights, H.DEV)
+    for layer in range(wl.n_layers):
+        lw = layer_weights(wl, wl.seed, layer, H.DEV, torch.bfloat16)
+        model.ht_load_layer(layer, lw)
+        torch.cuda.synchronize()
+        del lw
+    model.ht_load_lm_head(head)
+    torch.cuda.synchronize()
+    return model
+
+
+@pytest.mark.parametrize("name", ["llama7b", "llama70b"])
+def test_full_size_tree_rows_equal_causal_decode_and_greedy_path_is_accepted(name):
+    """Configs 3 and 5 at their full depth, width and cache length (32 blocks over 512 cached tokens; 80 blocks, 64 query
+    on 8 key/value heads, 4096 cached tokens), where no fp64 oracle pass is affordable for the larger one: the
+    invariants of Sec. 3.4.1 and of lossless verification on the library's own passes.  Every node of the rank-0 chain
+    of the 64-node tree, fed the greedy continuation, must give the logits of the one-token pass over the same
+    prefix, and the acceptance walk must follow the chain."""
+    B, H = _mods()
+    wl = WORKLOADS[name]
+    wl = wl.with_(max_cache=wl.prompt_len + 128)
     T = wl.tree_size
     parent, rank = prune_tree(wl.branching, T)
     chain = _rank0_chain(parent, rank)
     assert len(chain) == wl.k + 1
-    say("7B full depth: generating weights")
-    tensors = make_weights(wl, wl.seed, H.DEV, torch.bfloat16)
+    say(f"{name} full size: generating and loading weights")
+    plain = _full_size_model(wl, T)
     prompt = prompt_of(wl)
 
-    say("7B full depth: plain decode, one token per pass")
-    plain = H.gpu_model(wl, tensors, max_tree=T)
+    say(f"{name} full size: plain decode, one token per pass")
     plain.ht_set_tree([-1], [0])
     plain.ht_prefill(prompt)
     z1 = torch.empty(1, wl.vocab, dtype=torch.float32, device=H.DEV)
@@ -115,11 +144,9 @@ def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_acc
         rows.append(z1[0].cpu().numpy().astype(np.float64))
         assert root == int(np.argmax(rows[-1]))
         greedy.append(root)
-    plain.close()
-    del plain
 
-    say("7B full depth: one 64-node verify pass holding the greedy continuation on the rank-0 chain")
-    tree = H.gpu_model(wl, tensors, max_tree=T)
+    say(f"{name} full size: one 64-node verify pass holding the greedy continuation on the rank-0 chain")
+    tree = plain                                         # the same model: a new tree and a new prefill
     tree.ht_set_tree(parent, rank)
     tree.ht_prefill(prompt)
     assert int(tree.ht_get_buffer(B.HT_BUF_ROOT)[0]) == greedy[0]
@@ -139,8 +166,12 @@ def test_llama7b_full_depth_tree_rows_equal_causal_decode_and_greedy_path_is_acc
     assert np.array_equal(g.cpu().numpy(), np.argmax(zc, axis=1))
     worst_diff = 0.0
     for d, v in enumerate(chain):
-        # each bf16 pass may be 3e-2 away from the exact logits, so two passes may differ by twice that
-        ok, ratio = H.within_bf16(zc[v], rows[d], tol=2 * H.BF16_REL_TOL)
+        # Each bf16 pass may be 3e-2 away from the exact logits, so two passes may differ by twice that.  The two
+        # passes share weights and inputs and differ in the order of their sums, block after block: at 32 blocks they
+        # sit at 0.47 of that bound, and the difference grows with the square root of the depth like every other
+        # rounding here, so a model of 80 blocks gets sqrt(80 / 32) of the bound (measured there: 0.54 - 0.61 of it).
+        pass_tol = 2 * H.BF16_REL_TOL * max(1.0, float(np.sqrt(wl.n_layers / 32.0)))
+        ok, ratio = H.within_bf16(zc[v], rows[d], tol=pass_tol)
         diff = float(np.max(np.abs(zc[v] - rows[d])))
         worst_diff = max(worst_diff, diff)
         say(f"  depth {d}: tree row {v} vs plain decode: error / bound {ratio:.3f}, max-abs {diff:.2e}")
