@@ -698,17 +698,30 @@ def main():
         model.close()
         del model
         torch.cuda.empty_cache()
+        # Objects beside the headline: a failure in one of them (say, too little free memory for the 70B model) is
+        # recorded in its place and must not take the result line with it.
+        def optional(key, fn):
+            try:
+                res[key] = fn()
+            except Exception as exc:                 # noqa: BLE001 - reported, not swallowed
+                res[key] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+                torch.cuda.empty_cache()
+
         if not training:        # the forward pass of the training stage over 2048 tokens, on a model of its own
-            wl_tr = wl.with_(max_cache=2048 + 256)
-            m_tr = B.HTModel(B.make_config(wl_tr, max_tree=128), weights, dev)
-            res["training_forward"] = time_training_forward(m_tr, 2048)
-            m_tr.close()
-            del m_tr
+            def train_object():
+                wl_tr = wl.with_(max_cache=2048 + 256)
+                m_tr = B.HTModel(B.make_config(wl_tr, max_tree=128), weights, dev)
+                try:
+                    return time_training_forward(m_tr, 2048)
+                finally:
+                    m_tr.close()
+            optional("training_forward", train_object)
         del weights
         torch.cuda.empty_cache()
-        res["attention_op"] = time_attention_op(dev)
-        res["llama13b"] = time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps), also_layers=(25, 30, 35))
-        res["llama70b"] = time_second_workload("llama70b", dev, [1, 64], max(5, args.steps // 3))
+        optional("attention_op", lambda: time_attention_op(dev))
+        optional("llama13b", lambda: time_second_workload("llama13b", dev, [1, 16, 32, 64, 128], max(5, args.steps),
+                                                          also_layers=(25, 30, 35)))
+        optional("llama70b", lambda: time_second_workload("llama70b", dev, [1, 64], max(5, args.steps // 3)))
     print(json.dumps(res))
 
 
