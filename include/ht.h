@@ -310,6 +310,8 @@ int ht_gate_up_silu_packed(const void *a, const void *packed, int32_t M, int32_t
                            void *stream);
 int ht_skinny_gemm_packed(const void *a, const void *packed, int32_t M, int32_t N, int32_t K, float *out,
                           void *scratch, size_t scratch_bytes, void *stream);
+int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
+                   void *scratch, size_t scratch_bytes, void *stream);
 
 /* For callers that cannot allocate device memory (code under HIP-graph capture, tight serving loops, harnesses
  * that forbid hipMalloc): `ht_skinny_gemm_packed` without a scratch argument.  The split-K partial sums go to a
@@ -341,8 +343,6 @@ int ht_stream_read_probe(const void *buf, size_t bytes, void *sink, size_t *byte
  * of the launch; the caller times it.  `sink` is a device word the kernel may write.  HT_EINVAL for a NULL sink,
  * another form, or iters outside 1 .. 2^20. */
 int ht_mfma_rate_probe(int32_t form, int32_t iters, void *sink, double *flops, void *stream);
-int ht_skinny_gemm(const void *a, const void *w, int32_t M, int32_t N, int32_t K, int32_t dtype, float *out,
-                   void *scratch, size_t scratch_bytes, void *stream);
 
 #ifdef __cplusplus
 }
